@@ -1,0 +1,272 @@
+/*
+ * omnisparse.h -- C ABI of the MI355X (gfx950) OmniSparse hot-path library.
+ *
+ * One transformer layer's sparse attention as defined by arxiv 2511.12201
+ * ("OmniSparse"): lazy/active query classification, KV selection under one
+ * token budget set by the flattest head, sparse prefill attention (forward and
+ * backward) and a decode step that fetches visual KV only for heads whose
+ * decoding query is active.
+ *
+ * General rules (all entry points)
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless the
+ *     comment says "host".  The library allocates and frees no device memory:
+ *     scratch comes from the caller's workspace `ws` of `ws_bytes` bytes, whose
+ *     required size is returned by omni_workspace_bytes().  The workspace
+ *     content is unspecified between calls.  `ws` must be 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on
+ *     that stream and return; results are valid once the stream has been
+ *     synchronised.  Nothing else orders the work.
+ *   - Data-dependent scalars (kept-query counts, the budget b) live in device
+ *     memory and are consumed from there by later calls, so the pipeline needs
+ *     no host synchronisation.
+ *   - Layout: Q, O, dO, dQ are [batch, n_q_heads, n_tokens, head_dim]; K, V,
+ *     dK, dV are [batch, n_kv_heads, n_tokens, head_dim]; head_dim is
+ *     contiguous, the other strides are given in elements in the descriptor.
+ *     Outputs O, dQ, dK, dV use the same strides as Q resp. K.  Query head i
+ *     reads KV head i / (n_q_heads / n_kv_heads).
+ *   - Heads and tokens are 0-based; the paper's "first attention head" is
+ *     head 0 and its "first token" (attention sink) is `sink_index`.
+ *   - Return value: OMNI_OK, or a negative omni_status.  On error nothing has
+ *     been enqueued; omni_last_error() gives a message (thread local).
+ *     Arguments are validated on the host before any launch: null pointers,
+ *     n_q_heads % n_kv_heads, head_dim in {64, 128}, 0 <= vis_begin < vis_end
+ *     <= n_tokens, 0 <= sink_index < n_tokens, strides at least the natural
+ *     ones and multiples of 8 elements, workspace size and alignment.
+ *   - Deterministic: equal inputs give bit-equal outputs (no floating-point
+ *     atomics anywhere).
+ */
+#ifndef OMNISPARSE_H
+#define OMNISPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { OMNI_F32 = 0, OMNI_BF16 = 1 } omni_dtype;
+
+typedef enum {
+  OMNI_OK = 0,
+  OMNI_ERR_INVALID = -1,      /* bad argument value or null pointer            */
+  OMNI_ERR_UNSUPPORTED = -2,  /* shape / dtype outside what the kernels handle */
+  OMNI_ERR_WORKSPACE = -3,    /* workspace too small or misaligned             */
+  OMNI_ERR_HIP = -4           /* a HIP runtime call failed                     */
+} omni_status;
+
+/* Identifiers for omni_workspace_bytes(). */
+typedef enum {
+  OMNI_CALL_SCORE_QUERIES = 0,
+  OMNI_CALL_SELECT_QUERIES = 1,
+  OMNI_CALL_KV_BUDGET = 2,
+  OMNI_CALL_SELECT_KV = 3,
+  OMNI_CALL_SPARSE_ATTN_FWD = 4,
+  OMNI_CALL_SPARSE_ATTN_BWD = 5,
+  OMNI_CALL_SLIM_DECODE = 6,
+  OMNI_CALL_DENSE_ATTN_FWD = 7,
+  OMNI_CALL_DENSE_DECODE = 8
+} omni_call_id;
+
+/* One attention layer during prefill / training.
+ * Visual tokens are [vis_begin, vis_end) (paper Sec. "Overview": X = [X_v, X_t]);
+ * every other token is text. */
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim, n_tokens;
+  int32_t vis_begin, vis_end, sink_index;
+  int32_t causal;              /* 1: token n attends tokens <= n (Sec. "Preliminary") */
+  int32_t dtype;               /* omni_dtype of Q, K, V, O, dO, dQ, dK, dV */
+  float softmax_scale;         /* 1 / sqrt(head_dim) in the paper's attention equation */
+  int64_t q_stride[3];         /* batch, head, token strides of Q-shaped tensors, in elements */
+  int64_t kv_stride[3];        /* same for K/V-shaped tensors */
+} omni_layer_desc;
+
+/* KV cache during decode: rows [0, ctx_len[b]) of each sequence are valid;
+ * [vis_begin, vis_end) is the visual segment K^v, the rest text K^t and
+ * decoded answer K^a (Sec. "KV Cache Slimming"). */
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim, cache_capacity;
+  int32_t vis_begin, vis_end;
+  int32_t dtype;               /* omni_dtype of q, Kcache, Vcache, O */
+  float softmax_scale;
+  float tau;                   /* lazy/active threshold of the query-mask equation */
+  int64_t kv_stride[3];        /* batch, head, token strides of the caches, in elements */
+} omni_decode_desc;
+
+/*
+ * omni_score_queries -- Sec. "Query Selection as Binary Lazy-Active
+ * Classification", probe-softmax equation.
+ * For every KV head: probe_keys[.,.,0,:] = K[sink_index] (lazy reference),
+ * probe_keys[.,.,1,:] = mean of the visual keys (active reference).
+ * For every query head and token: scores = second column of the two-way
+ * softmax of (q . k_lazy, q . k_act) * softmax_scale, i.e. the probability of
+ * the active class.  Accumulation in fp32.
+ *   probe_keys [batch, n_kv_heads, 2, head_dim] f32, out
+ *   scores     [batch, n_q_heads, n_tokens] f32, out (all tokens are scored;
+ *              only the visual ones are classified later)
+ */
+int omni_score_queries(const omni_layer_desc* desc, const void* Q, const void* K,
+                       float* probe_keys, float* scores,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_select_queries -- same section, query-mask equation.
+ * mode 0: a visual query is kept iff scores > param (param = tau, strict).
+ * mode 1: the ceil(param * n_visual) visual queries of highest score are kept
+ *         per head (equal scores: lower token index first); 0 < param <= 1.
+ * Head 0 keeps every query; non-visual queries are always kept.
+ *   q_idx [batch, n_q_heads, n_tokens] i32, out: kept token indices, ascending;
+ *         entries at and beyond the count are unspecified
+ *   q_cnt [batch, n_q_heads] i32, out
+ */
+int omni_select_queries(const omni_layer_desc* desc, const float* scores,
+                        int mode, float param, int32_t* q_idx, int32_t* q_cnt,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_kv_budget -- Sec. "KV Selection with Head-level Dynamic Budget
+ * Allocation" (accumulated key score, kurtosis, budget equation) with the
+ * block-wise probe of the paragraph "Block-wise probing and sparse flash
+ * attention kernel".
+ * key_scores[i,k] = sum over pooled query blocks j (probe_block consecutive
+ * tokens, all queries) of w_j * softmax_k(mean_q(j) . K[k] * scale), w_j = rows
+ * in block j; under the causal mask block j sees keys up to its last token.
+ * kurtosis[i] = m4 / m2^2 - 3 of key_scores[i,:] (fp64; -2 when m2 == 0).
+ * flattest = arg min kurtosis (lowest index on ties).
+ * budget = min { b : sum of the b largest key_scores[flattest] >= recall_p * n_tokens }
+ * (budget_mode 0, the paper's rule) or the maximum over heads of each head's own
+ * such b (budget_mode 1).  recall[i] = mass of head i's b largest scores / n_tokens.
+ *   key_scores [batch, n_q_heads, n_tokens] f32, out
+ *   kurtosis   [batch, n_q_heads] f64, out
+ *   flattest   [batch] i32, out
+ *   budget     [batch] i32, out (device)
+ *   recall     [batch, n_q_heads] f32, out
+ *   budget_host: optional pinned HOST pointer [batch]; if not null the budget is
+ *                also copied there (valid after the stream is synchronised).
+ * 0 < recall_p <= 1, probe_block >= 1.
+ */
+int omni_kv_budget(const omni_layer_desc* desc, const void* Q, const void* K,
+                   float recall_p, int probe_block, int budget_mode,
+                   float* key_scores, double* kurtosis, int32_t* flattest,
+                   int32_t* budget, float* recall, int32_t* budget_host,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_budget_from_scores -- the second half of omni_kv_budget on key scores
+ * the caller already holds (same section: kurtosis, flattest head, budget
+ * equation, per-head recall).  Arguments as in omni_kv_budget; key_scores is an
+ * input here.
+ */
+int omni_budget_from_scores(const omni_layer_desc* desc, const float* key_scores,
+                            float recall_p, int budget_mode,
+                            double* kurtosis, int32_t* flattest, int32_t* budget, float* recall,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_select_kv -- same section, key-mask equation (value mask = key mask).
+ * Per head the min(budget, b_cap) keys of largest key_scores; when several keys
+ * share the cut value those of lower token index are taken.
+ *   kv_idx [batch, n_q_heads, b_cap] i32, out: ascending; entries beyond the
+ *          budget are unspecified
+ */
+int omni_select_kv(const omni_layer_desc* desc, const float* key_scores, const int32_t* budget,
+                   int32_t b_cap, int32_t* kv_idx,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_sparse_attn_fwd -- Sec. "Preliminary" (attention equation restricted by
+ * the masks M^Q, M^K, M^V) for the kept queries and selected keys.
+ * For head i and kept query n: softmax over {k in kv_idx[i] : k <= n} (all of
+ * kv_idx[i] when not causal) of q_n . k_k * scale, times V.  Queries that are
+ * not kept, and kept queries with no admissible key, get an all-zero output row
+ * and lse = -inf.  bf16 inputs: bf16 MFMA with fp32 accumulation and softmax.
+ *   q_idx/q_cnt as written by omni_select_queries, kv_idx/budget as written by
+ *   omni_select_kv / omni_kv_budget (both index lists ascending); the effective
+ *   number of keys per head is min(budget[batch], b_cap).
+ *   O   [batch, n_q_heads, n_tokens, head_dim] dtype, out (fully written)
+ *   lse [batch, n_q_heads, n_tokens] f32, out: natural-log sum of exp of the
+ *       scaled logits over the admissible keys
+ */
+int omni_sparse_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                         const int32_t* q_idx, const int32_t* q_cnt,
+                         const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                         void* O, float* lse,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_sparse_attn_bwd -- gradient of omni_sparse_attn_fwd with the index sets
+ * held constant (the paper trains with the same sparse attention and defines no
+ * gradient through the selection): dV = P^T dO, dP = dO V^T,
+ * dS = P (dP - rowsum(dO O)), dQ = dS K scale, dK = dS^T Q scale, with dK, dV
+ * summed over the query heads of a KV group.
+ *   O, lse: outputs of the forward call on the same inputs
+ *   dQ [like Q], dK, dV [like K], out, fully written (zero rows where nothing
+ *   was kept / selected)
+ */
+int omni_sparse_attn_bwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                         const void* O, const void* dO, const float* lse,
+                         const int32_t* q_idx, const int32_t* q_cnt,
+                         const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                         void* dQ, void* dK, void* dV,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_slim_decode -- Sec. "KV Cache Slimming", decoding-attention equation.
+ * Per head the decoding query is scored against probe_keys as in
+ * omni_score_queries; the head is active iff score > tau or it is head 0.  An
+ * active head attends its stored visual rows vis_idx[i, 0:vis_cnt[i]) (those
+ * below ctx_len), a lazy head none of the visual rows; every head attends all
+ * non-visual rows below ctx_len.
+ *   q       [batch, n_q_heads, head_dim] dtype, contiguous
+ *   Kcache, Vcache [batch, n_kv_heads, cache_capacity, head_dim] dtype (strides in desc)
+ *   ctx_len [batch] i32
+ *   probe_keys [batch, n_kv_heads, 2, head_dim] f32 (from prefill)
+ *   vis_idx [batch, n_q_heads, b_cap] i32, vis_cnt [batch, n_q_heads] i32
+ *   O       [batch, n_q_heads, head_dim] dtype, out
+ *   active  [batch, n_q_heads] u8, out
+ */
+int omni_slim_decode(const omni_decode_desc* desc, const void* q,
+                     const void* Kcache, const void* Vcache, const int32_t* ctx_len,
+                     const float* probe_keys,
+                     const int32_t* vis_idx, const int32_t* vis_cnt, int32_t b_cap,
+                     void* O, uint8_t* active,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_visual_subset -- helper for the hand-over from prefill to decode
+ * (Sec. "KV Cache Slimming": the selected KV pairs are stored at token level).
+ * Copies, per head, the entries of kv_idx that are visual tokens to vis_idx and
+ * writes their number to vis_cnt.
+ *   vis_idx [batch, n_q_heads, b_cap] i32, out; vis_cnt [batch, n_q_heads] i32, out
+ */
+int omni_visual_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget,
+                       int32_t b_cap, int32_t* vis_idx, int32_t* vis_cnt, void* stream);
+
+/*
+ * Baselines used by the reported metric (not part of the method): plain causal
+ * / non-causal attention of the attention equation in Sec. "Preliminary" built
+ * on the same tile engine, and plain decode attention over rows [0, ctx_len).
+ */
+int omni_dense_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                        void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+int omni_dense_decode(const omni_decode_desc* desc, const void* q,
+                      const void* Kcache, const void* Vcache, const int32_t* ctx_len,
+                      void* O, void* ws, size_t ws_bytes, void* stream);
+
+/* Workspace bytes needed by call `call_id` (omni_call_id) for the given
+ * descriptor (omni_layer_desc* for prefill calls, omni_decode_desc* for the two
+ * decode calls).  `param` is the index capacity b_cap for the calls that take
+ * one, the probe block for OMNI_CALL_KV_BUDGET, and ignored otherwise.
+ * Returns 0 on invalid input (a valid call never needs 0 bytes). */
+size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param);
+
+/* Message of the last error on this thread ("" if none). */
+const char* omni_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int omni_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMNISPARSE_H */

@@ -1,0 +1,344 @@
+"""Thin ctypes binding over libomnisparse.so (argument marshalling only).
+
+Function names mirror the C ABI in include/omnisparse.h.  torch is used for
+device memory and the current HIP stream; every step of the computation runs in
+the library's kernels.  There is no CPU fallback: if the shared library is
+missing and cannot be built, importing a function raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libomnisparse.so")
+
+OMNI_F32, OMNI_BF16 = 0, 1
+(CALL_SCORE_QUERIES, CALL_SELECT_QUERIES, CALL_KV_BUDGET, CALL_SELECT_KV, CALL_SPARSE_ATTN_FWD,
+ CALL_SPARSE_ATTN_BWD, CALL_SLIM_DECODE, CALL_DENSE_ATTN_FWD, CALL_DENSE_DECODE) = range(9)
+
+EXPORTED = [
+    "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
+    "omni_sparse_attn_fwd", "omni_sparse_attn_bwd", "omni_slim_decode", "omni_visual_subset",
+    "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
+]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("n_tokens", C.c_int32), ("vis_begin", C.c_int32), ("vis_end", C.c_int32), ("sink_index", C.c_int32),
+        ("causal", C.c_int32), ("dtype", C.c_int32), ("softmax_scale", C.c_float),
+        ("q_stride", C.c_int64 * 3), ("kv_stride", C.c_int64 * 3),
+    ]
+
+
+class DecodeDesc(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("cache_capacity", C.c_int32), ("vis_begin", C.c_int32), ("vis_end", C.c_int32), ("dtype", C.c_int32),
+        ("softmax_scale", C.c_float), ("tau", C.c_float), ("kv_stride", C.c_int64 * 3),
+    ]
+
+
+class OmniError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"omnisparse error {code}: {message}")
+        self.code = code
+        self.message = message
+
+
+_lib = None
+
+
+def load_library(path: str = LIB_PATH) -> C.CDLL:
+    """Loads the built library (builds it first if no build exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build()
+    lib = C.CDLL(path)
+    vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
+    lib.omni_last_error.restype = C.c_char_p
+    lib.omni_version.restype = C.c_int
+    lib.omni_workspace_bytes.restype = sz
+    lib.omni_workspace_bytes.argtypes = [C.c_int, vp, i32]
+    lib.omni_score_queries.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.omni_select_queries.argtypes = [vp, vp, C.c_int, f32, vp, vp, vp, sz, vp]
+    lib.omni_kv_budget.argtypes = [vp, vp, vp, f32, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.omni_budget_from_scores.argtypes = [vp, vp, f32, C.c_int, vp, vp, vp, vp, vp, sz, vp]
+    lib.omni_select_kv.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.omni_visual_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp]
+    lib.omni_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.omni_dense_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.omni_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    for name in EXPORTED:
+        fn = getattr(lib, name)
+        if name not in ("omni_last_error", "omni_version", "omni_workspace_bytes"):
+            fn.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def last_error() -> str:
+    return load_library().omni_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise OmniError(rc, last_error())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return OMNI_BF16
+    if t.dtype == torch.float32:
+        return OMNI_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def make_layer_desc(Q: torch.Tensor, K: torch.Tensor, vis_begin: int, vis_end: int, sink_index: int = 0,
+                    causal: bool = True, softmax_scale: float | None = None) -> LayerDesc:
+    B, Hq, N, D = Q.shape
+    d = LayerDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim, d.n_tokens = B, Hq, K.shape[1], D, N
+    d.vis_begin, d.vis_end, d.sink_index = vis_begin, vis_end, sink_index
+    d.causal = 1 if causal else 0
+    d.dtype = _dtype_code(Q)
+    d.softmax_scale = softmax_scale if softmax_scale is not None else D ** -0.5
+    if Q.stride(3) != 1 or K.stride(3) != 1:
+        raise ValueError("head_dim must be contiguous")
+    d.q_stride = (C.c_int64 * 3)(*Q.stride()[:3])
+    d.kv_stride = (C.c_int64 * 3)(*K.stride()[:3])
+    return d
+
+
+def make_decode_desc(q: torch.Tensor, Kcache: torch.Tensor, vis_begin: int, vis_end: int, tau: float,
+                     softmax_scale: float | None = None) -> DecodeDesc:
+    B, Hq, D = q.shape
+    d = DecodeDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = B, Hq, Kcache.shape[1], D
+    d.cache_capacity = Kcache.shape[2]
+    d.vis_begin, d.vis_end = vis_begin, vis_end
+    d.dtype = _dtype_code(q)
+    d.softmax_scale = softmax_scale if softmax_scale is not None else D ** -0.5
+    d.tau = tau
+    d.kv_stride = (C.c_int64 * 3)(*Kcache.stride()[:3])
+    return d
+
+
+def workspace_bytes(call_id: int, desc, param: int = 0) -> int:
+    n = load_library().omni_workspace_bytes(call_id, C.byref(desc), param)
+    if n == 0:
+        raise OmniError(-1, last_error() or "invalid descriptor")
+    return int(n)
+
+
+class Workspace:
+    """Caller-owned scratch buffers, one per call id, grown on demand and reused."""
+
+    def __init__(self, device="cuda"):
+        self.device = device
+        self.bufs: dict[int, torch.Tensor] = {}
+
+    def get(self, call_id: int, desc, param: int = 0):
+        need = workspace_bytes(call_id, desc, param)
+        buf = self.bufs.get(call_id)
+        if buf is None or buf.numel() < need:
+            buf = torch.empty(need, dtype=torch.uint8, device=self.device)
+            self.bufs[call_id] = buf
+        return buf
+
+
+_default_ws = None
+
+
+def default_workspace() -> Workspace:
+    global _default_ws
+    if _default_ws is None:
+        _default_ws = Workspace()
+    return _default_ws
+
+
+# ------------------------------------------------------------------ entry points
+
+def omni_score_queries(desc: LayerDesc, Q, K, probe_keys=None, scores=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    dev = Q.device
+    if probe_keys is None:
+        probe_keys = torch.empty(desc.batch, desc.n_kv_heads, 2, desc.head_dim, dtype=torch.float32, device=dev)
+    if scores is None:
+        scores = torch.empty(desc.batch, desc.n_q_heads, desc.n_tokens, dtype=torch.float32, device=dev)
+    buf = ws.get(CALL_SCORE_QUERIES, desc)
+    _check(lib.omni_score_queries(C.byref(desc), _ptr(Q), _ptr(K), _ptr(probe_keys), _ptr(scores), _ptr(buf),
+                                  buf.numel(), _stream()))
+    return probe_keys, scores
+
+
+def omni_select_queries(desc: LayerDesc, scores, mode: int, param: float, q_idx=None, q_cnt=None,
+                        ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    dev = scores.device
+    if q_idx is None:
+        q_idx = torch.empty(desc.batch, desc.n_q_heads, desc.n_tokens, dtype=torch.int32, device=dev)
+    if q_cnt is None:
+        q_cnt = torch.empty(desc.batch, desc.n_q_heads, dtype=torch.int32, device=dev)
+    buf = ws.get(CALL_SELECT_QUERIES, desc)
+    _check(lib.omni_select_queries(C.byref(desc), _ptr(scores), mode, param, _ptr(q_idx), _ptr(q_cnt), _ptr(buf),
+                                   buf.numel(), _stream()))
+    return q_idx, q_cnt
+
+
+@dataclass
+class BudgetResult:
+    key_scores: torch.Tensor
+    kurtosis: torch.Tensor
+    flattest: torch.Tensor
+    budget: torch.Tensor
+    recall: torch.Tensor
+
+
+def omni_kv_budget(desc: LayerDesc, Q, K, recall_p: float, probe_block: int = 256, budget_mode: int = 0,
+                   out: BudgetResult | None = None, budget_host=None, ws: Workspace | None = None) -> BudgetResult:
+    lib = load_library()
+    ws = ws or default_workspace()
+    dev = Q.device
+    B, H, N = desc.batch, desc.n_q_heads, desc.n_tokens
+    if out is None:
+        out = BudgetResult(
+            torch.empty(B, H, N, dtype=torch.float32, device=dev), torch.empty(B, H, dtype=torch.float64, device=dev),
+            torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+            torch.empty(B, H, dtype=torch.float32, device=dev))
+    buf = ws.get(CALL_KV_BUDGET, desc, probe_block)
+    _check(lib.omni_kv_budget(C.byref(desc), _ptr(Q), _ptr(K), recall_p, probe_block, budget_mode,
+                              _ptr(out.key_scores), _ptr(out.kurtosis), _ptr(out.flattest), _ptr(out.budget),
+                              _ptr(out.recall), _ptr(budget_host), _ptr(buf), buf.numel(), _stream()))
+    return out
+
+
+def omni_budget_from_scores(desc: LayerDesc, key_scores, recall_p: float, budget_mode: int = 0,
+                            ws: Workspace | None = None) -> BudgetResult:
+    lib = load_library()
+    ws = ws or default_workspace()
+    dev = key_scores.device
+    B, H = desc.batch, desc.n_q_heads
+    out = BudgetResult(key_scores, torch.empty(B, H, dtype=torch.float64, device=dev),
+                       torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+                       torch.empty(B, H, dtype=torch.float32, device=dev))
+    buf = ws.get(CALL_KV_BUDGET, desc, 256)
+    _check(lib.omni_budget_from_scores(C.byref(desc), _ptr(key_scores), recall_p, budget_mode, _ptr(out.kurtosis),
+                                       _ptr(out.flattest), _ptr(out.budget), _ptr(out.recall), _ptr(buf), buf.numel(),
+                                       _stream()))
+    return out
+
+
+def omni_select_kv(desc: LayerDesc, key_scores, budget, b_cap: int, kv_idx=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if kv_idx is None:
+        kv_idx = torch.empty(desc.batch, desc.n_q_heads, b_cap, dtype=torch.int32, device=key_scores.device)
+    buf = ws.get(CALL_SELECT_KV, desc)
+    _check(lib.omni_select_kv(C.byref(desc), _ptr(key_scores), _ptr(budget), b_cap, _ptr(kv_idx), _ptr(buf),
+                              buf.numel(), _stream()))
+    return kv_idx
+
+
+def omni_visual_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, vis_idx=None, vis_cnt=None):
+    lib = load_library()
+    dev = kv_idx.device
+    if vis_idx is None:
+        vis_idx = torch.empty(desc.batch, desc.n_q_heads, b_cap, dtype=torch.int32, device=dev)
+    if vis_cnt is None:
+        vis_cnt = torch.empty(desc.batch, desc.n_q_heads, dtype=torch.int32, device=dev)
+    _check(lib.omni_visual_subset(C.byref(desc), _ptr(kv_idx), _ptr(budget), b_cap, _ptr(vis_idx), _ptr(vis_cnt),
+                                  _stream()))
+    return vis_idx, vis_cnt
+
+
+def omni_sparse_attn_fwd(desc: LayerDesc, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap: int, O=None, lse=None,
+                         ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty(desc.batch, desc.n_q_heads, desc.n_tokens, dtype=torch.float32, device=Q.device)
+    buf = ws.get(CALL_SPARSE_ATTN_FWD, desc, b_cap)
+    _check(lib.omni_sparse_attn_fwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(q_idx), _ptr(q_cnt), _ptr(kv_idx),
+                                    _ptr(budget), b_cap, _ptr(O), _ptr(lse), _ptr(buf), buf.numel(), _stream()))
+    return O, lse
+
+
+def omni_dense_attn_fwd(desc: LayerDesc, Q, K, V, O=None, lse=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty(desc.batch, desc.n_q_heads, desc.n_tokens, dtype=torch.float32, device=Q.device)
+    buf = ws.get(CALL_DENSE_ATTN_FWD, desc)
+    _check(lib.omni_dense_attn_fwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(lse), _ptr(buf),
+                                   buf.numel(), _stream()))
+    return O, lse
+
+
+def omni_sparse_attn_bwd(desc: LayerDesc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap: int,
+                         dQ=None, dK=None, dV=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if dQ is None:
+        dQ = torch.empty_like(Q)
+    if dK is None:
+        dK = torch.empty_like(K)
+    if dV is None:
+        dV = torch.empty_like(V)
+    buf = ws.get(CALL_SPARSE_ATTN_BWD, desc, b_cap)
+    _check(lib.omni_sparse_attn_bwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse),
+                                    _ptr(q_idx), _ptr(q_cnt), _ptr(kv_idx), _ptr(budget), b_cap, _ptr(dQ), _ptr(dK),
+                                    _ptr(dV), _ptr(buf), buf.numel(), _stream()))
+    return dQ, dK, dV
+
+
+def omni_slim_decode(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, vis_idx, vis_cnt, b_cap: int,
+                     O=None, active=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if O is None:
+        O = torch.empty_like(q)
+    if active is None:
+        active = torch.empty(desc.batch, desc.n_q_heads, dtype=torch.uint8, device=q.device)
+    buf = ws.get(CALL_SLIM_DECODE, desc)
+    _check(lib.omni_slim_decode(C.byref(desc), _ptr(q), _ptr(Kcache), _ptr(Vcache), _ptr(ctx_len), _ptr(probe_keys),
+                                _ptr(vis_idx), _ptr(vis_cnt), b_cap, _ptr(O), _ptr(active), _ptr(buf), buf.numel(),
+                                _stream()))
+    return O, active
+
+
+def omni_dense_decode(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, O=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if O is None:
+        O = torch.empty_like(q)
+    buf = ws.get(CALL_DENSE_DECODE, desc)
+    _check(lib.omni_dense_decode(C.byref(desc), _ptr(q), _ptr(Kcache), _ptr(Vcache), _ptr(ctx_len), _ptr(O), _ptr(buf),
+                                 buf.numel(), _stream()))
+    return O

@@ -1,0 +1,306 @@
+// C-ABI entry points: argument validation, workspace carving, dispatch.
+// Everything here runs on the host; no entry point allocates device memory.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace omni {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+void clear_error() { g_err[0] = 0; }
+
+int validate_layer(const omni_layer_desc* d) {
+  if (!d) OMNI_FAIL(OMNI_ERR_INVALID, "descriptor is null");
+  if (d->batch < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_tokens < 1)
+    OMNI_FAIL(OMNI_ERR_INVALID, "batch, head counts and n_tokens must be positive");
+  if (d->n_q_heads % d->n_kv_heads) OMNI_FAIL(OMNI_ERR_INVALID, "n_q_heads must be a multiple of n_kv_heads");
+  if (d->head_dim != 64 && d->head_dim != 128) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+  if (d->dtype != OMNI_F32 && d->dtype != OMNI_BF16) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "dtype must be OMNI_F32 or OMNI_BF16");
+  if (!(d->vis_begin >= 0 && d->vis_begin < d->vis_end && d->vis_end <= d->n_tokens))
+    OMNI_FAIL(OMNI_ERR_INVALID, "need 0 <= vis_begin < vis_end <= n_tokens");
+  if (d->sink_index < 0 || d->sink_index >= d->n_tokens) OMNI_FAIL(OMNI_ERR_INVALID, "sink_index out of range");
+  if (d->causal != 0 && d->causal != 1) OMNI_FAIL(OMNI_ERR_INVALID, "causal must be 0 or 1");
+  if (!(d->softmax_scale > 0.f) || !std::isfinite(d->softmax_scale))
+    OMNI_FAIL(OMNI_ERR_INVALID, "softmax_scale must be positive and finite");
+  if ((long long)d->batch * d->n_q_heads * (long long)d->n_tokens >= (1ll << 31))
+    OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "batch * n_q_heads * n_tokens must be below 2^31");
+  const long long nat_q[3] = {(long long)d->n_q_heads * d->n_tokens * d->head_dim, (long long)d->n_tokens * d->head_dim,
+                              d->head_dim};
+  const long long nat_k[3] = {(long long)d->n_kv_heads * d->n_tokens * d->head_dim,
+                              (long long)d->n_tokens * d->head_dim, d->head_dim};
+  for (int k = 0; k < 3; ++k) {
+    if (d->q_stride[k] % 8 || d->kv_stride[k] % 8) OMNI_FAIL(OMNI_ERR_INVALID, "strides must be multiples of 8 elements");
+  }
+  if (d->q_stride[2] < nat_q[2] || d->kv_stride[2] < nat_k[2]) OMNI_FAIL(OMNI_ERR_INVALID, "token stride below head_dim");
+  if (d->q_stride[1] < nat_q[2] || d->kv_stride[1] < nat_k[2] || d->q_stride[0] < nat_q[2] || d->kv_stride[0] < nat_k[2])
+    OMNI_FAIL(OMNI_ERR_INVALID, "head / batch stride below head_dim");
+  (void)nat_q;
+  (void)nat_k;
+  return OMNI_OK;
+}
+
+int validate_decode(const omni_decode_desc* d) {
+  if (!d) OMNI_FAIL(OMNI_ERR_INVALID, "descriptor is null");
+  if (d->batch < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->cache_capacity < 1)
+    OMNI_FAIL(OMNI_ERR_INVALID, "batch, head counts and cache_capacity must be positive");
+  if (d->n_q_heads % d->n_kv_heads) OMNI_FAIL(OMNI_ERR_INVALID, "n_q_heads must be a multiple of n_kv_heads");
+  if (d->head_dim != 64 && d->head_dim != 128) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+  if (d->dtype != OMNI_F32 && d->dtype != OMNI_BF16) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "dtype must be OMNI_F32 or OMNI_BF16");
+  if (!(d->vis_begin >= 0 && d->vis_begin <= d->vis_end && d->vis_end <= d->cache_capacity))
+    OMNI_FAIL(OMNI_ERR_INVALID, "need 0 <= vis_begin <= vis_end <= cache_capacity");
+  if (!(d->softmax_scale > 0.f) || !std::isfinite(d->softmax_scale))
+    OMNI_FAIL(OMNI_ERR_INVALID, "softmax_scale must be positive and finite");
+  for (int k = 0; k < 3; ++k)
+    if (d->kv_stride[k] % 8 || d->kv_stride[k] < d->head_dim)
+      OMNI_FAIL(OMNI_ERR_INVALID, "cache strides must be multiples of 8 elements and at least head_dim");
+  return OMNI_OK;
+}
+
+int check_ws(const void* ws, size_t have, size_t need) {
+  if (!ws) OMNI_FAIL(OMNI_ERR_INVALID, "workspace pointer is null");
+  if (reinterpret_cast<uintptr_t>(ws) % 256) OMNI_FAIL(OMNI_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (have < need) OMNI_FAIL(OMNI_ERR_WORKSPACE, "workspace too small: have %zu bytes, need %zu", have, need);
+  return OMNI_OK;
+}
+
+Layer make_layer(const omni_layer_desc* d) {
+  Layer L;
+  L.B = d->batch;
+  L.Hq = d->n_q_heads;
+  L.Hkv = d->n_kv_heads;
+  L.G = L.Hq / L.Hkv;
+  L.D = d->head_dim;
+  L.N = d->n_tokens;
+  L.v0 = d->vis_begin;
+  L.v1 = d->vis_end;
+  L.sink = d->sink_index;
+  L.causal = d->causal;
+  L.scale = d->softmax_scale;
+  for (int k = 0; k < 3; ++k) {
+    L.qs[k] = d->q_stride[k];
+    L.ks[k] = d->kv_stride[k];
+  }
+  return L;
+}
+
+static bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
+
+static size_t kv_budget_ws(const Layer& L, int dtype, int pb) {
+  return align_up(probe_ws(L, dtype, pb), 256) + budget_stats_ws(L);
+}
+
+}  // namespace omni
+
+using namespace omni;
+
+#define REQUIRE_PTR(p)                                                     \
+  do {                                                                     \
+    if (!(p)) OMNI_FAIL(OMNI_ERR_INVALID, "argument %s is null", #p);      \
+  } while (0)
+#define REQUIRE_ALIGNED(p)                                                            \
+  do {                                                                                \
+    if (!aligned16(p)) OMNI_FAIL(OMNI_ERR_INVALID, "argument %s must be 16-byte aligned", #p); \
+  } while (0)
+#define CHECK(expr)            \
+  do {                         \
+    int rc__ = (expr);         \
+    if (rc__ != OMNI_OK) return rc__; \
+  } while (0)
+
+extern "C" {
+
+const char* omni_last_error(void) { return g_err; }
+int omni_version(void) { return 100; }
+
+size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param) {
+  clear_error();
+  if (!desc) return 0;
+  if (call_id == OMNI_CALL_SLIM_DECODE || call_id == OMNI_CALL_DENSE_DECODE) {
+    const omni_decode_desc* d = static_cast<const omni_decode_desc*>(desc);
+    if (validate_decode(d) != OMNI_OK) return 0;
+    return decode_ws(d);
+  }
+  const omni_layer_desc* d = static_cast<const omni_layer_desc*>(desc);
+  if (validate_layer(d) != OMNI_OK) return 0;
+  const Layer L = make_layer(d);
+  switch (call_id) {
+    case OMNI_CALL_SCORE_QUERIES: return score_queries_ws(L);
+    case OMNI_CALL_SELECT_QUERIES: return select_ws(L);
+    case OMNI_CALL_SELECT_KV: return select_ws(L);
+    case OMNI_CALL_KV_BUDGET:
+      if (param < 1) { set_error("probe block must be >= 1"); return 0; }
+      return kv_budget_ws(L, d->dtype, param);
+    case OMNI_CALL_SPARSE_ATTN_FWD:
+      if (param < 1) { set_error("b_cap must be >= 1"); return 0; }
+      return attn_fwd_ws(L, d->dtype, param, true);
+    case OMNI_CALL_SPARSE_ATTN_BWD:
+      if (param < 1) { set_error("b_cap must be >= 1"); return 0; }
+      return attn_bwd_ws(L, d->dtype, param);
+    case OMNI_CALL_DENSE_ATTN_FWD: return attn_fwd_ws(L, d->dtype, L.N, false);
+    default: set_error("unknown call id %d", call_id); return 0;
+  }
+}
+
+int omni_score_queries(const omni_layer_desc* desc, const void* Q, const void* K, float* probe_keys, float* scores,
+                       void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(probe_keys); REQUIRE_PTR(scores);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K);
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, score_queries_ws(L)));
+  return run_score_queries(L, desc->dtype, Q, K, probe_keys, scores, ws, static_cast<hipStream_t>(stream));
+}
+
+int omni_select_queries(const omni_layer_desc* desc, const float* scores, int mode, float param, int32_t* q_idx,
+                        int32_t* q_cnt, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(scores); REQUIRE_PTR(q_idx); REQUIRE_PTR(q_cnt);
+  if (mode != 0 && mode != 1) OMNI_FAIL(OMNI_ERR_INVALID, "mode must be 0 (threshold) or 1 (top fraction)");
+  if (!std::isfinite(param)) OMNI_FAIL(OMNI_ERR_INVALID, "param must be finite");
+  if (mode == 1 && !(param > 0.f && param <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "top fraction must be in (0, 1]");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, select_ws(L)));
+  return run_select_queries(L, scores, mode, param, q_idx, q_cnt, ws, static_cast<hipStream_t>(stream));
+}
+
+int omni_kv_budget(const omni_layer_desc* desc, const void* Q, const void* K, float recall_p, int probe_block,
+                   int budget_mode, float* key_scores, double* kurtosis, int32_t* flattest, int32_t* budget,
+                   float* recall, int32_t* budget_host, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(key_scores); REQUIRE_PTR(kurtosis); REQUIRE_PTR(flattest);
+  REQUIRE_PTR(budget); REQUIRE_PTR(recall);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K);
+  if (!(recall_p > 0.f && recall_p <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "recall_p must be in (0, 1]");
+  if (probe_block < 1) OMNI_FAIL(OMNI_ERR_INVALID, "probe_block must be >= 1");
+  if (budget_mode != 0 && budget_mode != 1) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0 or 1");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, kv_budget_ws(L, desc->dtype, probe_block)));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  CHECK(run_probe(L, desc->dtype, Q, K, probe_block, key_scores, ws, st));
+  void* ws2 = static_cast<char*>(ws) + align_up(probe_ws(L, desc->dtype, probe_block), 256);
+  CHECK(run_budget_stats(L, key_scores, recall_p, budget_mode, kurtosis, flattest, budget, recall, ws2, st));
+  if (budget_host)
+    OMNI_HIP_CHECK(hipMemcpyAsync(budget_host, budget, sizeof(int32_t) * L.B, hipMemcpyDeviceToHost, st));
+  return OMNI_OK;
+}
+
+int omni_budget_from_scores(const omni_layer_desc* desc, const float* key_scores, float recall_p, int budget_mode,
+                            double* kurtosis, int32_t* flattest, int32_t* budget, float* recall, void* ws,
+                            size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(key_scores); REQUIRE_PTR(kurtosis); REQUIRE_PTR(flattest); REQUIRE_PTR(budget); REQUIRE_PTR(recall);
+  if (!(recall_p > 0.f && recall_p <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "recall_p must be in (0, 1]");
+  if (budget_mode != 0 && budget_mode != 1) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0 or 1");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, budget_stats_ws(L)));
+  return run_budget_stats(L, key_scores, recall_p, budget_mode, kurtosis, flattest, budget, recall, ws,
+                          static_cast<hipStream_t>(stream));
+}
+
+int omni_select_kv(const omni_layer_desc* desc, const float* key_scores, const int32_t* budget, int32_t b_cap,
+                   int32_t* kv_idx, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(key_scores); REQUIRE_PTR(budget); REQUIRE_PTR(kv_idx);
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, select_ws(L)));
+  return run_select_kv(L, key_scores, budget, b_cap, kv_idx, ws, static_cast<hipStream_t>(stream));
+}
+
+int omni_visual_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                       int32_t* vis_idx, int32_t* vis_cnt, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(kv_idx); REQUIRE_PTR(budget); REQUIRE_PTR(vis_idx); REQUIRE_PTR(vis_cnt);
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  return run_visual_subset(make_layer(desc), kv_idx, budget, b_cap, vis_idx, vis_cnt, static_cast<hipStream_t>(stream));
+}
+
+int omni_sparse_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                         const int32_t* q_idx, const int32_t* q_cnt, const int32_t* kv_idx, const int32_t* budget,
+                         int32_t b_cap, void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(V); REQUIRE_PTR(q_idx); REQUIRE_PTR(q_cnt); REQUIRE_PTR(kv_idx);
+  REQUIRE_PTR(budget); REQUIRE_PTR(O); REQUIRE_PTR(lse);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K); REQUIRE_ALIGNED(V); REQUIRE_ALIGNED(O);
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, attn_fwd_ws(L, desc->dtype, b_cap, true)));
+  return run_attn_fwd(L, desc->dtype, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, true,
+                      static_cast<hipStream_t>(stream));
+}
+
+int omni_dense_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, void* O, float* lse,
+                        void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(V); REQUIRE_PTR(O); REQUIRE_PTR(lse);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K); REQUIRE_ALIGNED(V); REQUIRE_ALIGNED(O);
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, attn_fwd_ws(L, desc->dtype, L.N, false)));
+  return run_attn_fwd(L, desc->dtype, Q, K, V, nullptr, nullptr, nullptr, nullptr, L.N, O, lse, ws, false,
+                      static_cast<hipStream_t>(stream));
+}
+
+int omni_sparse_attn_bwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, const void* O,
+                         const void* dO, const float* lse, const int32_t* q_idx, const int32_t* q_cnt,
+                         const int32_t* kv_idx, const int32_t* budget, int32_t b_cap, void* dQ, void* dK, void* dV,
+                         void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(V); REQUIRE_PTR(O); REQUIRE_PTR(dO); REQUIRE_PTR(lse);
+  REQUIRE_PTR(q_idx); REQUIRE_PTR(q_cnt); REQUIRE_PTR(kv_idx); REQUIRE_PTR(budget);
+  REQUIRE_PTR(dQ); REQUIRE_PTR(dK); REQUIRE_PTR(dV);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K); REQUIRE_ALIGNED(V); REQUIRE_ALIGNED(O); REQUIRE_ALIGNED(dO);
+  REQUIRE_ALIGNED(dQ); REQUIRE_ALIGNED(dK); REQUIRE_ALIGNED(dV);
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, attn_bwd_ws(L, desc->dtype, b_cap)));
+  return run_attn_bwd(L, desc->dtype, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws,
+                      static_cast<hipStream_t>(stream));
+}
+
+int omni_slim_decode(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,
+                     const int32_t* ctx_len, const float* probe_keys, const int32_t* vis_idx, const int32_t* vis_cnt,
+                     int32_t b_cap, void* O, uint8_t* active, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(q); REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(ctx_len); REQUIRE_PTR(probe_keys);
+  REQUIRE_PTR(vis_idx); REQUIRE_PTR(vis_cnt); REQUIRE_PTR(O); REQUIRE_PTR(active);
+  REQUIRE_ALIGNED(q); REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache);
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
+  CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
+  return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, vis_idx, vis_cnt, b_cap, O, active, ws,
+                    static_cast<hipStream_t>(stream));
+}
+
+int omni_dense_decode(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,
+                      const int32_t* ctx_len, void* O, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(q); REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(ctx_len); REQUIRE_PTR(O);
+  REQUIRE_ALIGNED(q); REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache);
+  CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
+  return run_decode(desc, q, Kcache, Vcache, ctx_len, nullptr, nullptr, nullptr, 1, O, nullptr, ws,
+                    static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,478 @@
+// FlashAttention-style forward over kept queries and packed (gathered) keys:
+// omni_sparse_attn_fwd and the dense baseline omni_dense_attn_fwd (paper Sec.
+// "Preliminary", attention equation, restricted by the masks M^Q, M^K, M^V).
+//
+// Design for gfx950:
+//  * A pack kernel gathers each head's selected K rows into a dense row-major
+//    buffer and its V rows into the exact operand order the matrix cores need
+//    (below), zero-padding to whole 64-key tiles and recording the original
+//    token index of every slot.  The dense baseline runs the same pack with
+//    identity indices per KV head.  The main loop is then free of gathers.
+//  * Both GEMMs are computed transposed, S^T = K Q^T and O^T = V^T P^T, with
+//    32x32 MFMA tiles.  Each lane then owns one query column: the softmax row
+//    statistics are per-lane scalars (one exchange with the partner lane that
+//    holds the other half of the keys), and the S^T accumulator registers are
+//    already in the B-operand order of the second GEMM, so P never moves.
+//  * V is packed so that the A operand of O^T = V^T P^T is one 16-byte LDS read:
+//    [16-key group][half h][d][8 keys], key(group,h,j) = 16 group + 8 (j/4) + 4 h + j%4,
+//    which is the order in which the S^T accumulators hold the keys.
+//  * 256 threads = 4 wavefronts x 32 query rows; 64-key K/V tiles are double
+//    buffered in LDS, one barrier per tile; two workgroups fit a CU.
+//  * fp32 inputs take the same path with the fp32 32x32x2 MFMA (accuracy path).
+#include "common.h"
+#include "kernels.h"
+
+namespace omni {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ------------------------------------------------------------------ pack / gather
+
+// grid: (npad/64, BHx).  Slot p of the packed buffers holds source row src_idx[p]
+// (identity when src_idx == nullptr); slots >= nkeys are zero with index kPadKeyIndex.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void pack_kv_kernel(const T* __restrict__ K, const T* __restrict__ V, Layer L,
+                                                          int per_q_head, const int* __restrict__ src_idx,
+                                                          int idx_stride, const int* __restrict__ budget, int b_cap,
+                                                          int npad, T* __restrict__ Kp, T* __restrict__ Vp,
+                                                          int* __restrict__ kidx) {
+  constexpr bool kBf16 = sizeof(T) == 2;
+  constexpr int E = Elem<T>::kPer16B;
+  constexpr int CPR = D / E;                     // 16-byte chunks per row
+  __shared__ int sIdx[kTileN];
+  const int tile = blockIdx.x, bhx = blockIdx.y;
+  const int H = per_q_head ? L.Hq : L.Hkv;
+  const int b = bhx / H, hx = bhx % H;
+  const int g = per_q_head ? hx / L.G : hx;
+  const int nkeys = budget ? min(budget[b], b_cap) : L.N;
+  if (tile * kTileN >= nkeys) return;
+  if (threadIdx.x < kTileN) {
+    const int p = tile * kTileN + threadIdx.x;
+    int id = kPadKeyIndex;
+    if (p < nkeys) id = src_idx ? src_idx[(long long)bhx * idx_stride + p] : p;
+    sIdx[threadIdx.x] = id;
+    kidx[(long long)bhx * npad + p] = id;
+  }
+  __syncthreads();
+  const T* kbase = K + b * L.ks[0] + g * L.ks[1];
+  const T* vbase = V + b * L.ks[0] + g * L.ks[1];
+  T* kdst = Kp + ((long long)bhx * npad + tile * kTileN) * D;
+  T* vdst = Vp + ((long long)bhx * npad + tile * kTileN) * D;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int c = threadIdx.x; c < kTileN * CPR; c += kThreads) {
+    const int row = c / CPR, col = (c % CPR) * E;
+    const int id = sIdx[row];
+    u32x4 kv = zero;
+    if (id != kPadKeyIndex) kv = *reinterpret_cast<const u32x4*>(kbase + (long long)id * L.ks[2] + col);
+    *reinterpret_cast<u32x4*>(kdst + row * D + col) = kv;
+    if constexpr (!kBf16) {
+      u32x4 vv = zero;
+      if (id != kPadKeyIndex) vv = *reinterpret_cast<const u32x4*>(vbase + (long long)id * L.ks[2] + col);
+      *reinterpret_cast<u32x4*>(vdst + row * D + col) = vv;
+    }
+  }
+  if constexpr (kBf16) {
+    // work item = (16-key group, half, 8-wide d chunk): 8x8 transpose in registers
+    constexpr int kItems = (kTileN / 16) * 2 * (D / 8);
+    for (int it = threadIdx.x; it < kItems; it += kThreads) {
+      const int dc = it % (D / 8);
+      const int h = (it / (D / 8)) & 1;
+      const int grp = it / (D / 8) / 2;
+      u32x4 in[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int slot = 16 * grp + 8 * (j >> 2) + 4 * h + (j & 3);
+        const int id = sIdx[slot];
+        in[j] = zero;
+        if (id != kPadKeyIndex) in[j] = *reinterpret_cast<const u32x4*>(vbase + (long long)id * L.ks[2] + dc * 8);
+      }
+      // out[e] = 8 keys (j = 0..7) of column dc*8 + e
+      u16* dst = reinterpret_cast<u16*>(vdst) + ((grp * 2 + h) * D + dc * 8) * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        unsigned w[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const unsigned a = in[2 * jj][e >> 1], bb = in[2 * jj + 1][e >> 1];
+          const unsigned lo = (e & 1) ? (a >> 16) : (a & 0xffffu);
+          const unsigned hi = (e & 1) ? (bb >> 16) : (bb & 0xffffu);
+          w[jj] = lo | (hi << 16);
+        }
+        u32x4 o = {w[0], w[1], w[2], w[3]};
+        *reinterpret_cast<u32x4*>(dst + e * 8) = o;
+      }
+    }
+  }
+}
+
+// O = 0, lse = -inf for every row (kept rows are overwritten by the attention kernel).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void clear_output_kernel(T* __restrict__ O, float* __restrict__ lse, Layer L) {
+  constexpr int E = Elem<T>::kPer16B;
+  const int CPR = L.D / E;
+  const int bh = blockIdx.y, b = bh / L.Hq, i = bh % L.Hq;
+  T* base = O + b * L.qs[0] + i * L.qs[1];
+  const int row0 = blockIdx.x * 64;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int c = threadIdx.x; c < 64 * CPR; c += kThreads) {
+    const int r = row0 + c / CPR;
+    if (r < L.N) *reinterpret_cast<u32x4*>(base + (long long)r * L.qs[2] + (c % CPR) * E) = zero;
+  }
+  if (threadIdx.x < 64 && row0 + (int)threadIdx.x < L.N) lse[(long long)bh * L.N + row0 + threadIdx.x] = -INFINITY;
+}
+
+// ------------------------------------------------------------------ attention
+
+struct FwdParams {
+  const void* Q;
+  void* O;
+  float* lse;
+  Layer L;
+  const int* q_idx;     // [B*Hq, N] kept query rows, ascending; nullptr: all rows
+  const int* q_cnt;     // [B*Hq]; nullptr: N
+  const void* Kp;       // packed keys  [BHx, npad, D]
+  const void* Vp;       // packed values, tile layout (bf16) or row-major (fp32)
+  const int* kidx;      // [BHx, npad] original token index of every slot
+  const int* budget;    // [B] number of packed keys (device); nullptr: N
+  int b_cap;
+  int npad;
+  int per_q_head;       // packed buffers per query head (sparse) or per KV head (dense)
+  int identity_keys;    // kidx[p] == p: causal bounds by arithmetic
+  int ntile_q;          // ceil(N / kTileM)
+};
+
+// number of entries <= v in ascending a[0,n)
+__device__ __forceinline__ int upper_count(const int* __restrict__ a, int n, int v) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (a[mid] <= v) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
+  constexpr bool kBf16 = sizeof(T) == 2;
+  constexpr int KLD = kBf16 ? D + 8 : D + 4;        // K tile row pitch in elements
+  constexpr int VLD = D + 8;                        // fp32 V tile row pitch
+  constexpr int NBUF = kBf16 ? 2 : 1;
+  constexpr int kKBytes = kTileN * KLD * (int)sizeof(T);
+  constexpr int kVBytes = kBf16 ? kTileN * D * 2 : kTileN * VLD * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char sK_raw[NBUF * kKBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char sV_raw[NBUF * kVBytes];
+  __shared__ __attribute__((aligned(16))) int sIdx[NBUF][kTileN];
+  __shared__ int sBound[2];
+
+  const Layer& L = p.L;
+  const int BH = L.B * L.Hq;
+  const int bh = blockIdx.x % BH;
+  const int tq = p.ntile_q - 1 - blockIdx.x / BH;    // long (late) tiles are scheduled first
+  const int b = bh / L.Hq, i = bh % L.Hq, g = i / L.G;
+  const int nq = p.q_cnt ? p.q_cnt[bh] : L.N;
+  if (tq * kTileM >= nq) return;
+  const int nkeys = p.budget ? min(p.budget[b], p.b_cap) : L.N;
+  const int bhx = p.per_q_head ? bh : b * L.Hkv + g;
+  const int* kidx = p.kidx + (long long)bhx * p.npad;
+  const int* qlist = p.q_idx ? p.q_idx + (long long)bh * L.N : nullptr;
+
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int ln = lane & 31, h = lane >> 5;
+
+  // ---- key range of this query tile
+  const int pos_first = tq * kTileM, pos_last = min(pos_first + kTileM, nq) - 1;
+  if (threadIdx.x == 0 || threadIdx.x == 64) {
+    const int which = threadIdx.x ? 1 : 0;
+    const int pos = which ? pos_last : pos_first;
+    const int row = qlist ? qlist[pos] : pos;
+    int cnt;
+    if (!L.causal) cnt = nkeys;
+    else if (p.identity_keys) cnt = min(row + 1, nkeys);
+    else cnt = upper_count(kidx, nkeys, row);
+    sBound[which] = cnt;
+  }
+  __syncthreads();
+  const int n_full_tiles = sBound[0] / kTileN;         // tiles with every key admissible for every row
+  const int ntiles = cdiv(sBound[1], kTileN);
+
+  // ---- this lane's query row
+  const int qpos = pos_first + wave * 32 + ln;
+  const bool qvalid = qpos < nq;
+  const int qpos_c = min(qpos, nq - 1);
+  const int qrow = qlist ? qlist[qpos_c] : qpos_c;
+  const int qcmp = L.causal ? qrow : kPadKeyIndex - 1;  // key admissible iff its index <= qcmp
+  const T* qptr = static_cast<const T*>(p.Q) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+
+  bf16x8 qf16[kBf16 ? D / 16 : 1];
+  f32x4 qf32[kBf16 ? 1 : D / 8];
+  if constexpr (kBf16) {
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) qf16[ks] = *reinterpret_cast<const bf16x8*>(qptr + ks * 16 + h * 8);
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < D / 8; ++ks) qf32[ks] = *reinterpret_cast<const f32x4*>(qptr + ks * 8 + h * 4);
+  }
+
+  f32x16 o[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c2 = L.scale * kLog2e;
+
+  // ---- tile staging
+  constexpr int E = Elem<T>::kPer16B;
+  constexpr int CPR = D / E;
+  constexpr int kChunks = kTileN * CPR / kThreads;   // 16-byte chunks per thread per operand
+  const T* kp = static_cast<const T*>(p.Kp) + (long long)bhx * p.npad * D;
+  const T* vp = static_cast<const T*>(p.Vp) + (long long)bhx * p.npad * D;
+  u32x4 stK[kChunks], stV[kChunks];
+  i32x4 stI;
+
+  auto load_tile = [&](int t) {
+    const T* ks = kp + (long long)t * kTileN * D;
+    const T* vs = vp + (long long)t * kTileN * D;
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      const int ch = threadIdx.x + c * kThreads;
+      stK[c] = *reinterpret_cast<const u32x4*>(ks + ch * E);
+      stV[c] = *reinterpret_cast<const u32x4*>(vs + ch * E);
+    }
+    if (threadIdx.x < kTileN / 4) stI = *reinterpret_cast<const i32x4*>(kidx + t * kTileN + threadIdx.x * 4);
+  };
+  auto store_tile = [&](int buf) {
+    T* sk = reinterpret_cast<T*>(sK_raw + buf * kKBytes);
+    T* sv = reinterpret_cast<T*>(sV_raw + buf * kVBytes);
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      const int ch = threadIdx.x + c * kThreads;
+      const int row = ch / CPR, col = (ch % CPR) * E;
+      *reinterpret_cast<u32x4*>(sk + row * KLD + col) = stK[c];
+      if constexpr (kBf16) *reinterpret_cast<u32x4*>(sv + ch * E) = stV[c];
+      else *reinterpret_cast<u32x4*>(sv + row * VLD + col) = stV[c];
+    }
+    if (threadIdx.x < kTileN / 4) *reinterpret_cast<i32x4*>(&sIdx[buf][threadIdx.x * 4]) = stI;
+  };
+
+  auto compute_tile = [&](int buf, bool masked) {
+    const T* sk = reinterpret_cast<const T*>(sK_raw + buf * kKBytes);
+    const T* sv = reinterpret_cast<const T*>(sV_raw + buf * kVBytes);
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      if constexpr (kBf16) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + ln) * KLD + ks * 16 + h * 8);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf16[ks], s[kb], 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < D / 8; ++ks) {
+          const f32x4 kf = *reinterpret_cast<const f32x4*>(sk + (kb * 32 + ln) * KLD + ks * 8 + h * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[e], qf32[ks][e], s[kb], 0, 0, 0);
+        }
+      }
+    }
+    if (masked) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const i32x4 id = *reinterpret_cast<const i32x4*>(&sIdx[buf][kb * 32 + 8 * q4 + 4 * h]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (id[e] > qcmp) s[kb][q4 * 4 + e] = -INFINITY;
+        }
+    }
+    // online softmax; this lane and lane^32 share the query row
+    float mloc = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[kb][r]);
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    const float m_new = fmaxf(m_run, mloc);
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+    if (__any(m_new > m_run)) {
+      const float alpha = exp2f((m_run - m_ref) * c2);
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+      m_run = m_new;
+    }
+    const float mc = m_ref * c2;
+    float lsum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pv = exp2f(fmaf(s[kb][r], c2, -mc));
+        s[kb][r] = pv;
+        lsum += pv;
+      }
+    l_run += lsum;
+    if constexpr (kBf16) {
+#pragma unroll
+      for (int t16 = 0; t16 < 4; ++t16) {
+        const int kb = t16 >> 1, r0 = (t16 & 1) * 8;
+        union { bf16x8 v; unsigned u[4]; } pf;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) pf.u[jj] = pack_bf16x2(s[kb][r0 + 2 * jj], s[kb][r0 + 2 * jj + 1]);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + ((t16 * 2 + h) * D + db * 32 + ln) * 8);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, o[db], 0, 0, 0);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int slot = kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            const float vf = sv[slot * VLD + db * 32 + ln];
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(vf, s[kb][r], o[db], 0, 0, 0);
+          }
+        }
+    }
+  };
+
+  if (ntiles > 0) {
+    if constexpr (kBf16) {
+      load_tile(0);
+      store_tile(0);
+      __syncthreads();
+      for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles) load_tile(t + 1);
+        compute_tile(t & 1, t >= n_full_tiles);
+        if (t + 1 < ntiles) store_tile((t + 1) & 1);
+        __syncthreads();
+      }
+    } else {
+      for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+        load_tile(t);
+        store_tile(0);
+        __syncthreads();
+        compute_tile(0, t >= n_full_tiles);
+      }
+    }
+  }
+
+  // ---- epilogue
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  if (qvalid) {
+    T* optr = static_cast<T*>(p.O) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int d = db * 32 + 8 * q4 + 4 * h;
+        const float v0 = o[db][q4 * 4 + 0] * inv, v1 = o[db][q4 * 4 + 1] * inv;
+        const float v2 = o[db][q4 * 4 + 2] * inv, v3 = o[db][q4 * 4 + 3] * inv;
+        if constexpr (kBf16) {
+          uint2 w;
+          w.x = pack_bf16x2(v0, v1);
+          w.y = pack_bf16x2(v2, v3);
+          *reinterpret_cast<uint2*>(optr + d) = w;
+        } else {
+          f32x4 w = {v0, v1, v2, v3};
+          *reinterpret_cast<f32x4*>(optr + d) = w;
+        }
+      }
+    if (h == 0)
+      p.lse[(long long)bh * L.N + qrow] = l_tot > 0.f ? (m_run * c2 + log2f(l_tot)) * kLn2 : -INFINITY;
+  }
+}
+
+struct FwdWs {
+  void* Kp;
+  void* Vp;
+  int* kidx;
+};
+
+FwdWs carve_fwd(Arena& a, const Layer& L, int dtype, int heads, int npad) {
+  FwdWs w;
+  const size_t es = dtype == OMNI_BF16 ? 2 : 4;
+  const size_t rows = (size_t)L.B * heads * npad;
+  w.Kp = a.take<unsigned char>(rows * L.D * es);
+  w.Vp = a.take<unsigned char>(rows * L.D * es);
+  w.kidx = a.take<int>(rows);
+  return w;
+}
+
+template <typename T, int D>
+int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, const int* q_idx, const int* q_cnt,
+               const int* kv_idx, const int* budget, int b_cap, void* O, float* lse, void* ws, bool sparse,
+               hipStream_t st) {
+  Arena a(ws);
+  const int heads = sparse ? L.Hq : L.Hkv;
+  const int npad = (int)align_up(sparse ? b_cap : L.N, kTileN);
+  FwdWs w = carve_fwd(a, L, sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32, heads, npad);
+  hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kTileN, L.B * heads), dim3(kThreads), 0, st,
+                     static_cast<const T*>(K), static_cast<const T*>(V), L, sparse ? 1 : 0, kv_idx, b_cap, budget,
+                     b_cap, npad, static_cast<T*>(w.Kp), static_cast<T*>(w.Vp), w.kidx);
+  OMNI_LAUNCH_CHECK();
+  if (sparse) {
+    hipLaunchKernelGGL((clear_output_kernel<T>), dim3(cdiv(L.N, 64), L.B * L.Hq), dim3(kThreads), 0, st,
+                       static_cast<T*>(O), lse, L);
+    OMNI_LAUNCH_CHECK();
+  }
+  FwdParams p;
+  p.Q = Q;
+  p.O = O;
+  p.lse = lse;
+  p.L = L;
+  p.q_idx = q_idx;
+  p.q_cnt = q_cnt;
+  p.Kp = w.Kp;
+  p.Vp = w.Vp;
+  p.kidx = w.kidx;
+  p.budget = budget;
+  p.b_cap = b_cap;
+  p.npad = npad;
+  p.per_q_head = sparse ? 1 : 0;
+  p.identity_keys = sparse ? 0 : 1;
+  p.ntile_q = cdiv(L.N, kTileM);
+  hipLaunchKernelGGL((attn_fwd_kernel<T, D>), dim3(p.ntile_q * L.B * L.Hq), dim3(kThreads), 0, st, p);
+  OMNI_LAUNCH_CHECK();
+  return OMNI_OK;
+}
+
+}  // namespace
+
+size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse) {
+  Arena a(nullptr);
+  carve_fwd(a, L, dtype, sparse ? L.Hq : L.Hkv, (int)align_up(sparse ? b_cap : L.N, kTileN));
+  return a.used();
+}
+
+int run_attn_fwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const int* q_idx,
+                 const int* q_cnt, const int* kv_idx, const int* budget, int b_cap, void* O, float* lse, void* ws,
+                 bool sparse, hipStream_t st) {
+  if (dtype == OMNI_BF16) {
+    if (L.D == 128)
+      return launch_fwd<u16, 128>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st);
+    return launch_fwd<u16, 64>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st);
+  }
+  if (L.D == 128)
+    return launch_fwd<float, 128>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st);
+  return launch_fwd<float, 64>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st);
+}
+
+}  // namespace omni

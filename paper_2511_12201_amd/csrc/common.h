@@ -1,0 +1,146 @@
+// Shared host/device helpers of the gfx950 OmniSparse library (internal).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/omnisparse.h"
+
+namespace omni {
+
+// ---------------------------------------------------------------- host side
+
+void set_error(const char* fmt, ...);
+void clear_error();
+
+#define OMNI_FAIL(code, ...)        \
+  do {                              \
+    ::omni::set_error(__VA_ARGS__); \
+    return (code);                  \
+  } while (0)
+
+#define OMNI_HIP_CHECK(expr)                                                          \
+  do {                                                                                \
+    hipError_t e__ = (expr);                                                          \
+    if (e__ != hipSuccess) OMNI_FAIL(OMNI_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+#define OMNI_LAUNCH_CHECK() OMNI_HIP_CHECK(hipGetLastError())
+
+__host__ __device__ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+__host__ __device__ static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Bump allocator over the caller's workspace.
+struct Arena {
+  char* base;
+  size_t off;
+  explicit Arena(void* p) : base(static_cast<char*>(p)), off(0) {}
+  template <typename T>
+  T* take(size_t n) {
+    off = align_up(off, 256);
+    T* r = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += n * sizeof(T);
+    return r;
+  }
+  size_t used() const { return align_up(off, 256); }
+};
+
+int validate_layer(const omni_layer_desc* d);
+int validate_decode(const omni_decode_desc* d);
+int check_ws(const void* ws, size_t have, size_t need);
+
+// Plain-data copy of the descriptor with derived fields, passed to kernels by value.
+struct Layer {
+  int B, Hq, Hkv, G, D, N;
+  int v0, v1, sink;
+  int causal;
+  float scale;
+  long long qs[3];
+  long long ks[3];
+};
+Layer make_layer(const omni_layer_desc* d);
+
+constexpr int kTileM = 128;   // query rows per attention workgroup
+constexpr int kTileN = 64;    // keys per attention tile
+constexpr int kPadKeyIndex = 0x7fffffff;
+
+// ---------------------------------------------------------------- device side
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16;
+
+__device__ __forceinline__ float bf16_bits_to_f32(u16 h) {
+  return __uint_as_float(((unsigned)h) << 16);
+}
+// round-to-nearest-even; inputs are finite in every use here
+__device__ __forceinline__ u16 f32_to_bf16_bits(float f) {
+  unsigned u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (u16)(u >> 16);
+}
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+  return (unsigned)f32_to_bf16_bits(lo) | ((unsigned)f32_to_bf16_bits(hi) << 16);
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr int kPer16B = 4;
+  __device__ static __forceinline__ float load(const float* p) { return *p; }
+  __device__ static __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <>
+struct Elem<u16> {
+  static constexpr int kPer16B = 8;
+  __device__ static __forceinline__ float load(const u16* p) { return bf16_bits_to_f32(*p); }
+  __device__ static __forceinline__ void store(u16* p, float v) { *p = f32_to_bf16_bits(v); }
+};
+
+// 16-byte chunk -> floats
+__device__ __forceinline__ void unpack16(const u32x4& raw, float (&out)[4], const float*) {
+  out[0] = __uint_as_float(raw.x);
+  out[1] = __uint_as_float(raw.y);
+  out[2] = __uint_as_float(raw.z);
+  out[3] = __uint_as_float(raw.w);
+}
+__device__ __forceinline__ void unpack16(const u32x4& raw, float (&out)[8], const u16*) {
+  out[0] = __uint_as_float(raw.x << 16);
+  out[1] = __uint_as_float(raw.x & 0xffff0000u);
+  out[2] = __uint_as_float(raw.y << 16);
+  out[3] = __uint_as_float(raw.y & 0xffff0000u);
+  out[4] = __uint_as_float(raw.z << 16);
+  out[5] = __uint_as_float(raw.z & 0xffff0000u);
+  out[6] = __uint_as_float(raw.w << 16);
+  out[7] = __uint_as_float(raw.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// order-preserving map float bits -> unsigned (larger float <=> larger key)
+__device__ __forceinline__ unsigned float_key(float f) {
+  unsigned u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+}  // namespace omni

@@ -1,0 +1,48 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel files.
+#pragma once
+
+#include "common.h"
+
+namespace omni {
+
+// score.hip
+size_t score_queries_ws(const Layer& L);
+int run_score_queries(const Layer& L, int dtype, const void* Q, const void* K, float* probe, float* scores, void* ws,
+                      hipStream_t st);
+
+// select.hip
+size_t select_ws(const Layer& L);
+int run_select_queries(const Layer& L, const float* scores, int mode, float param, int* q_idx, int* q_cnt, void* ws,
+                       hipStream_t st);
+int run_select_kv(const Layer& L, const float* key_scores, const int* budget, int b_cap, int* kv_idx, void* ws,
+                  hipStream_t st);
+size_t budget_stats_ws(const Layer& L);
+int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, int budget_mode, double* kurt,
+                     int* flattest, int* budget, float* recall, void* ws, hipStream_t st);
+int run_visual_subset(const Layer& L, const int* kv_idx, const int* budget, int b_cap, int* vis_idx, int* vis_cnt,
+                      hipStream_t st);
+
+// probe.hip
+size_t probe_ws(const Layer& L, int dtype, int pb);
+int run_probe(const Layer& L, int dtype, const void* Q, const void* K, int pb, float* key_scores, void* ws,
+              hipStream_t st);
+
+// attn_fwd.hip
+size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse);
+int run_attn_fwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const int* q_idx,
+                 const int* q_cnt, const int* kv_idx, const int* budget, int b_cap, void* O, float* lse, void* ws,
+                 bool sparse, hipStream_t st);
+
+// attn_bwd.hip
+size_t attn_bwd_ws(const Layer& L, int dtype, int b_cap);
+int run_attn_bwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const void* O,
+                 const void* dO, const float* lse, const int* q_idx, const int* q_cnt, const int* kv_idx,
+                 const int* budget, int b_cap, void* dQ, void* dK, void* dV, void* ws, hipStream_t st);
+
+// decode.hip
+size_t decode_ws(const omni_decode_desc* d);
+int run_decode(const omni_decode_desc* d, const void* q, const void* K, const void* V, const int* ctx_len,
+               const float* probe, const int* vis_idx, const int* vis_cnt, int b_cap, void* O,
+               unsigned char* active, void* ws, hipStream_t st);
+
+}  // namespace omni

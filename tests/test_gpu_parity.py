@@ -1,0 +1,346 @@
+"""GPU parity: every C-ABI call against the CPU oracle on the same seeded inputs (run with -m gpu)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import omni_oracle as oc
+from paper_2511_12201_amd import binding as ob
+from paper_2511_12201_amd import synth
+from tests.helpers import lists_to_padded, near_cut_only, padded_to_lists, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL_OUT = {"f32": 1e-4, "bf16": 2e-2}          # max-abs bar for attention outputs and gradients
+
+# shapes: several 128-row query tiles and 64-key tiles with ragged tails, all dtype / head_dim variants
+CFG_BF16 = synth.C2_16K.scaled(name="bf16_d128", frames=7, tok_per_frame=252, n_text=95, n_q_heads=8, n_kv_heads=2)
+CFG_BF16_64 = synth.C2_16K.scaled(name="bf16_d64", frames=5, tok_per_frame=100, n_text=37, n_q_heads=4, n_kv_heads=2,
+                                  head_dim=64, seed=11)
+CFG_F32 = synth.C1_TINY
+CFG_F32_128 = synth.C1_TINY.scaled(name="f32_d128", head_dim=128, frames=3, tok_per_frame=150, n_text=29,
+                                   n_q_heads=4, n_kv_heads=2, seed=12)
+ALL_CFGS = [CFG_BF16, CFG_BF16_64, CFG_F32, CFG_F32_128]
+
+
+class Case:
+    """Inputs on host and device plus the oracle's results for one configuration (cached per test session)."""
+    _cache = {}
+
+    def __init__(self, cfg, tau=0.08, recall_p=0.95, probe_block=256, q_mode=0, q_param=0.08):
+        self.cfg = cfg
+        L = synth.make_layer(cfg)
+        self.Q, self.K, self.V = L["Q"], L["K"], L["V"]
+        self.side = L["side"]
+        self.dQ, self.dK, self.dV = (to_device(x, cfg.dtype) for x in (self.Q, self.K, self.V))
+        self.desc = ob.make_layer_desc(self.dQ, self.dK, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+        self.recall_p, self.probe_block, self.q_mode, self.q_param = recall_p, probe_block, q_mode, q_param
+        # oracle pipeline
+        self.o_probe = oc.probe_keys(self.K, cfg.vis_begin, cfg.vis_end, cfg.sink_index)
+        self.o_scores = oc.score_queries(self.Q, self.o_probe, cfg.scale)
+        self.o_scores32 = self.o_scores.astype(np.float32)
+        self.o_qidx = oc.select_queries(self.o_scores32, q_mode, q_param, cfg.vis_begin, cfg.vis_end)
+        self.o_a = oc.pooled_key_scores(self.Q, self.K, probe_block, cfg.causal, cfg.scale)
+        self.o_a32 = self.o_a.astype(np.float32)
+        self.o_bud = oc.kv_budget(self.o_a32, recall_p, 0)
+        self.o_kvidx = oc.select_kv(self.o_a32, self.o_bud["budget"])
+
+    @classmethod
+    def get(cls, cfg, **kw):
+        key = (cfg, tuple(sorted(kw.items())))
+        if key not in cls._cache:
+            cls._cache[key] = cls(cfg, **kw)
+        return cls._cache[key]
+
+
+def case_for(cfg):
+    if cfg.structured:
+        return Case.get(cfg)
+    return Case.get(cfg, q_mode=1, q_param=0.25, probe_block=64)
+
+
+# ------------------------------------------------------------------ query scoring and selection
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+def test_score_queries(cfg):
+    c = case_for(cfg)
+    probe, scores = ob.omni_score_queries(c.desc, c.dQ, c.dK)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_host(probe), c.o_probe, rtol=2e-5, atol=2e-5)
+    np.testing.assert_allclose(to_host(scores), c.o_scores, rtol=0, atol=1e-5)
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("mode,param", [(0, 0.08), (0, 0.5), (1, 0.25), (1, 1.0), (0, -1.0), (0, 2.0)])
+def test_select_queries_is_bit_exact_on_given_scores(cfg, mode, param):
+    c = case_for(cfg)
+    scores = torch.from_numpy(c.o_scores32).cuda()
+    q_idx, q_cnt = ob.omni_select_queries(c.desc, scores, mode, param)
+    torch.cuda.synchronize()
+    want = oc.select_queries(c.o_scores32, mode, param, cfg.vis_begin, cfg.vis_end)
+    got = padded_to_lists(q_idx, q_cnt)
+    for b in range(cfg.batch):
+        for h in range(cfg.n_q_heads):
+            np.testing.assert_array_equal(got[b][h], want[b][h], err_msg=f"batch {b} head {h}")
+
+
+def test_select_queries_with_tied_scores():
+    cfg = CFG_BF16_64
+    c = case_for(cfg)
+    rng = np.random.default_rng(5)
+    tied = (rng.integers(0, 6, c.o_scores32.shape) / 8.0).astype(np.float32)      # heavy ties, includes 0.0
+    scores = torch.from_numpy(tied).cuda()
+    for mode, param in [(1, 0.3), (1, 0.01), (0, 0.25)]:
+        q_idx, q_cnt = ob.omni_select_queries(c.desc, scores, mode, param)
+        torch.cuda.synchronize()
+        want = oc.select_queries(tied, mode, param, cfg.vis_begin, cfg.vis_end)
+        got = padded_to_lists(q_idx, q_cnt)
+        for h in range(cfg.n_q_heads):
+            np.testing.assert_array_equal(got[0][h], want[0][h])
+
+
+# ------------------------------------------------------------------ key scores, budget, KV selection
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+def test_kv_budget_key_scores_and_statistics(cfg):
+    c = case_for(cfg)
+    r = ob.omni_kv_budget(c.desc, c.dQ, c.dK, c.recall_p, c.probe_block, 0)
+    torch.cuda.synchronize()
+    a = to_host(r.key_scores).astype(np.float64)
+    amax = c.o_a.max()
+    np.testing.assert_allclose(a, c.o_a, rtol=0, atol=1e-4 * amax)
+    np.testing.assert_allclose(a.sum(-1), cfg.n_tokens, rtol=1e-5)
+    np.testing.assert_allclose(to_host(r.kurtosis), c.o_bud["kurtosis"], rtol=1e-3)
+    k_sorted = np.sort(c.o_bud["kurtosis"], axis=-1)
+    if np.all((k_sorted[:, 1] - k_sorted[:, 0]) > 1e-3 * np.abs(k_sorted[:, 0])):
+        np.testing.assert_array_equal(to_host(r.flattest), c.o_bud["flattest"])
+        # budget: minimal under the oracle's own score array up to the probe's numeric error
+        for b in range(cfg.batch):
+            srt = np.sort(c.o_a32[b, c.o_bud["flattest"][b]].astype(np.float64))[::-1]
+            cum = np.cumsum(srt)
+            target = float(np.float32(c.recall_p)) * cfg.n_tokens
+            bb = int(to_host(r.budget)[b])
+            assert cum[bb - 1] >= target * (1 - 1e-4)
+            assert bb == 1 or cum[bb - 2] < target * (1 + 1e-4)
+    np.testing.assert_allclose(to_host(r.recall), c.o_bud["recall"], atol=2e-4)
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("p,mode", [(0.95, 0), (0.5, 0), (0.82, 1), (1.0, 0)])
+def test_budget_from_given_scores_is_exact(cfg, p, mode):
+    c = case_for(cfg)
+    a = torch.from_numpy(c.o_a32).cuda()
+    r = ob.omni_budget_from_scores(c.desc, a, p, mode)
+    torch.cuda.synchronize()
+    want = oc.kv_budget(c.o_a32, p, mode)
+    np.testing.assert_allclose(to_host(r.kurtosis), want["kurtosis"], rtol=1e-9)
+    np.testing.assert_array_equal(to_host(r.flattest), want["flattest"])
+    np.testing.assert_array_equal(to_host(r.budget), want["budget"])
+    np.testing.assert_allclose(to_host(r.recall), want["recall"], atol=1e-6)
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+def test_select_kv_is_bit_exact_on_given_scores(cfg):
+    c = case_for(cfg)
+    a = torch.from_numpy(c.o_a32).cuda()
+    N = cfg.n_tokens
+    for budget in (int(c.o_bud["budget"][0]), 1, 63, N - 1, N):
+        bud = torch.full((cfg.batch,), budget, dtype=torch.int32, device="cuda")
+        kv_idx = ob.omni_select_kv(c.desc, a, bud, N)
+        torch.cuda.synchronize()
+        want = oc.select_kv(c.o_a32, [budget] * cfg.batch)
+        got = to_host(kv_idx)
+        for b in range(cfg.batch):
+            np.testing.assert_array_equal(got[b, :, :budget], want[b], err_msg=f"budget {budget}")
+
+
+def test_select_kv_ties_and_capacity_clamp():
+    cfg = CFG_BF16_64
+    c = case_for(cfg)
+    rng = np.random.default_rng(6)
+    a_np = (rng.integers(0, 4, c.o_a32.shape) / 4.0).astype(np.float32)
+    a = torch.from_numpy(a_np).cuda()
+    bud = torch.full((cfg.batch,), 200, dtype=torch.int32, device="cuda")
+    got = to_host(ob.omni_select_kv(c.desc, a, bud, 256))
+    want = oc.select_kv(a_np, [200])
+    np.testing.assert_array_equal(got[0, :, :200], want[0])
+    # capacity below the budget: the effective budget is b_cap
+    got = to_host(ob.omni_select_kv(c.desc, a, bud, 96))
+    want = oc.select_kv(a_np, [96])
+    np.testing.assert_array_equal(got[0], want[0])
+
+
+# ------------------------------------------------------------------ attention forward
+
+def _run_sparse_fwd(c, q_lists, kv_lists):
+    cfg = c.cfg
+    N = cfg.n_tokens
+    q_idx, q_cnt = lists_to_padded(q_lists, cfg.n_q_heads, N)
+    b = max(len(x) for x in kv_lists[0])
+    kv_idx, _ = lists_to_padded(kv_lists, cfg.n_q_heads, b)
+    budget = torch.tensor([len(kv_lists[bb][0]) for bb in range(cfg.batch)], dtype=torch.int32, device="cuda")
+    O, lse = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, budget, b)
+    torch.cuda.synchronize()
+    return to_host(O), to_host(lse)
+
+
+def _check_fwd(c, O, lse, Oo, Lo):
+    tol = TOL_OUT[c.cfg.dtype]
+    assert np.max(np.abs(O - Oo)) <= tol
+    fin = np.isfinite(Lo)
+    np.testing.assert_array_equal(np.isfinite(lse), fin)
+    assert np.all(lse[~fin] == -np.inf)
+    assert np.max(np.abs(lse[fin] - Lo[fin])) <= (1e-4 if c.cfg.dtype == "f32" else 2e-3)
+    assert np.all(O[~fin] == 0)
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+def test_sparse_attn_fwd_on_oracle_selection(cfg):
+    c = case_for(cfg)
+    kv_lists = [list(c.o_kvidx[b]) for b in range(cfg.batch)]
+    O, lse = _run_sparse_fwd(c, c.o_qidx, kv_lists)
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+    _check_fwd(c, O, lse, Oo, Lo)
+
+
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
+def test_sparse_attn_fwd_edge_sets(cfg):
+    """Tiny budgets, a head with no kept query past the first keys, a head whose queries precede all its keys."""
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    rng = np.random.default_rng(9)
+    q_lists = [[np.arange(N, dtype=np.int32)] + [np.sort(rng.choice(N, int(rng.integers(1, 200)), replace=False)).astype(np.int32)
+                                                for _ in range(H - 1)]]
+    q_lists[0][1] = np.arange(0, 5, dtype=np.int32)                     # precedes every key of head 1
+    for b_sel in (1, 65, 130):
+        kv_lists = [[np.sort(rng.choice(np.arange(8, N), b_sel, replace=False)).astype(np.int32) for _ in range(H)]]
+        O, lse = _run_sparse_fwd(c, q_lists, kv_lists)
+        Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, q_lists, kv_lists, cfg.causal, cfg.scale)
+        _check_fwd(c, O, lse, Oo, Lo)
+        assert np.all(lse[0, 1] == -np.inf)
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("causal", [True, False])
+def test_dense_attn_fwd_and_full_budget_sparse_equal_dense_definition(cfg, causal):
+    c = case_for(cfg)
+    desc = ob.make_layer_desc(c.dQ, c.dK, cfg.vis_begin, cfg.vis_end, cfg.sink_index, causal)
+    O, lse = ob.omni_dense_attn_fwd(desc, c.dQ, c.dK, c.dV)
+    torch.cuda.synchronize()
+    Oo, Lo = oc.dense_attention(c.Q, c.K, c.V, causal, cfg.scale)
+    tol = TOL_OUT[cfg.dtype]
+    assert np.max(np.abs(to_host(O) - Oo)) <= tol
+    assert np.max(np.abs(to_host(lse) - Lo)) <= (1e-4 if cfg.dtype == "f32" else 2e-3)
+    # sparse call with every query kept and b = N is the same function
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    full = [[np.arange(N, dtype=np.int32) for _ in range(H)] for _ in range(cfg.batch)]
+    q_idx, q_cnt = lists_to_padded(full, H, N)
+    budget = torch.full((cfg.batch,), N, dtype=torch.int32, device="cuda")
+    O2, lse2 = ob.omni_sparse_attn_fwd(desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, q_idx, budget, N)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(to_host(O2) - Oo)) <= tol
+
+
+# ------------------------------------------------------------------ decode
+
+def _decode_case(cfg, batch, n_ans=9):
+    c = case_for(cfg)
+    N = cfg.n_tokens
+    cap = N + 16
+    steps = synth.make_decode_steps(cfg, dict(side=c.side), n_ans + 1, batch=batch)
+    Kc = np.zeros((batch, cfg.n_kv_heads, cap, cfg.head_dim), dtype=np.float32)
+    Vc = np.zeros_like(Kc)
+    for b in range(batch):
+        Kc[b, :, :N], Vc[b, :, :N] = c.K[0], c.V[0]
+        Kc[b, :, N:N + n_ans] = steps["k_new"][:n_ans, b].transpose(1, 0, 2)
+        Vc[b, :, N:N + n_ans] = steps["v_new"][:n_ans, b].transpose(1, 0, 2)
+    ctx = np.array([N + n_ans - (b % 3) for b in range(batch)], dtype=np.int32)
+    q = steps["q"][n_ans]
+    vis = oc.visual_subset([list(c.o_kvidx[0])] * batch, cfg.vis_begin, cfg.vis_end)
+    probe = np.repeat(c.o_probe, batch, axis=0)
+    return c, q, Kc, Vc, ctx, probe, vis
+
+
+@pytest.mark.parametrize("cfg,batch", [(CFG_BF16, 1), (CFG_BF16, 3), (CFG_BF16_64, 2), (CFG_F32, 2), (CFG_F32_128, 1)],
+                         ids=lambda x: getattr(x, "name", str(x)))
+def test_slim_decode_and_dense_decode(cfg, batch):
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    tau = 0.08
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    dctx = torch.from_numpy(ctx).cuda()
+    b_cap = max(len(v) for per in vis for v in per)
+    vis_idx, vis_cnt = lists_to_padded(vis, cfg.n_q_heads, b_cap)
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    desc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau)
+    O, act = ob.omni_slim_decode(desc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap)
+    torch.cuda.synchronize()
+    Oo, acto, sc = oc.slim_decode(q, Kc, Vc, ctx, probe.astype(np.float32), vis, tau, cfg.vis_begin, cfg.vis_end, cfg.scale)
+    act = to_host(act)
+    clear = np.abs(sc - tau) > 1e-5          # heads whose score is not at the threshold must agree
+    np.testing.assert_array_equal(act[clear], acto[clear])
+    same = act == acto
+    tol = TOL_OUT[cfg.dtype]
+    assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= tol
+    assert 0 < acto.sum() and (not cfg.structured or acto.sum() < acto.size)
+    Od = ob.omni_dense_decode(desc, dq, dKc, dVc, dctx)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(to_host(Od) - oc.dense_decode(q, Kc, Vc, ctx, cfg.scale))) <= tol
+
+
+def test_visual_subset_matches_oracle():
+    cfg = CFG_BF16
+    c = case_for(cfg)
+    b = int(c.o_bud["budget"][0])
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])], cfg.n_q_heads, b)
+    budget = torch.tensor([b], dtype=torch.int32, device="cuda")
+    vis_idx, vis_cnt = ob.omni_visual_subset(c.desc, kv_idx, budget, b)
+    torch.cuda.synchronize()
+    want = oc.visual_subset([list(c.o_kvidx[0])], cfg.vis_begin, cfg.vis_end)
+    got = padded_to_lists(vis_idx, vis_cnt)
+    for h in range(cfg.n_q_heads):
+        np.testing.assert_array_equal(got[0][h], want[0][h])
+
+
+# ------------------------------------------------------------------ whole pipeline, free running
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+def test_free_running_pipeline_matches_oracle_up_to_ties_at_the_cut(cfg):
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    probe, scores = ob.omni_score_queries(c.desc, c.dQ, c.dK)
+    q_idx, q_cnt = ob.omni_select_queries(c.desc, scores, c.q_mode, c.q_param)
+    r = ob.omni_kv_budget(c.desc, c.dQ, c.dK, c.recall_p, c.probe_block, 0)
+    kv_idx = ob.omni_select_kv(c.desc, r.key_scores, r.budget, N)
+    O, lse = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, r.budget, N)
+    torch.cuda.synchronize()
+    got_q = padded_to_lists(q_idx, q_cnt)
+    rel = 1e-4          # numeric error of the GPU score arrays relative to the fp64 oracle
+    for h in range(H):
+        if c.q_mode == 0:
+            cut = c.q_param
+        else:
+            vis = np.sort(c.o_scores32[0, h, cfg.vis_begin:cfg.vis_end])[::-1]
+            cut = float(vis[math.ceil(c.q_param * cfg.n_vis) - 1])
+        assert near_cut_only(got_q[0][h], c.o_qidx[0][h], c.o_scores32[0, h], cut, rel), f"query set, head {h}"
+    bg, bo = int(to_host(r.budget)[0]), int(c.o_bud["budget"][0])
+    assert abs(bg - bo) <= max(2, int(2e-3 * bo))
+    got_kv = to_host(kv_idx)[0, :, :bg]
+    worst = 0
+    for h in range(H):
+        cut = float(np.sort(c.o_a32[0, h])[::-1][bo - 1])
+        diff = np.setxor1d(got_kv[h], c.o_kvidx[0][h])
+        worst = max(worst, diff.size)
+        assert np.all(np.abs(c.o_a32[0, h, diff] - cut) <= 5e-3 * cut + 1e-12), f"kv set, head {h}"
+    assert worst <= max(4, int(0.01 * bo) + abs(bg - bo))
+    # attention output: compared with the oracle's own pipeline wherever both selected the same sets
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, [list(c.o_kvidx[0])], cfg.causal, cfg.scale)
+    Og, Lg = to_host(O), to_host(lse)
+    compared = 0
+    for h in range(H):
+        if bg != bo or not np.array_equal(got_kv[h], c.o_kvidx[0][h]):
+            continue
+        rows = np.intersect1d(got_q[0][h], c.o_qidx[0][h])
+        assert np.max(np.abs(Og[0, h, rows] - Oo[0, h, rows])) <= TOL_OUT[cfg.dtype]
+        compared += 1
+    assert compared >= H // 2
