@@ -260,6 +260,21 @@ int omni_dense_decode(const omni_decode_desc* desc, const void* q,
  * Returns 0 on invalid input (a valid call never needs 0 bytes). */
 size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param);
 
+/*
+ * Kernel timing for benchmarks (not part of the method).  While enabled, the
+ * library records a HIP event pair on the call's stream around each launch of
+ * the kernels listed below (at most 64 launches per kernel; later ones are not
+ * recorded).  omni_profile_enable() resets the records; omni_profile_read()
+ * waits for the recorded launches and returns their summed duration in
+ * milliseconds and their number.  Not thread safe.  kernel_id: 0 attention
+ * forward main kernel, 1 K/V pack (gather), 2 output clear, 3 query pooling,
+ * 4 probe pass 1 (row log-sum-exp), 5 probe pass 2 (column sums), 6 query
+ * scoring, 7 backward dK/dV kernel, 8 backward dQ kernel, 9 backward
+ * scatter-reduce, 10 decode partial kernel, 11 selection kernels.
+ */
+int omni_profile_enable(int on);
+int omni_profile_read(int kernel_id, float* total_ms /* host */, int* launches /* host */);
+
 /* Message of the last error on this thread ("" if none). */
 const char* omni_last_error(void);
 

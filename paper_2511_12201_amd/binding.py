@@ -24,7 +24,11 @@ EXPORTED = [
     "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
     "omni_sparse_attn_fwd", "omni_sparse_attn_bwd", "omni_slim_decode", "omni_visual_subset",
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
+    "omni_profile_enable", "omni_profile_read",
 ]
+
+PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
+                "score": 6, "bwd_dkdv": 7, "bwd_dq": 8, "bwd_reduce": 9, "decode": 10, "select": 11}
 
 
 class LayerDesc(C.Structure):
@@ -79,6 +83,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.omni_profile_enable.argtypes = [C.c_int]
+    lib.omni_profile_read.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
     for name in EXPORTED:
         fn = getattr(lib, name)
         if name not in ("omni_last_error", "omni_version", "omni_workspace_bytes"):
@@ -142,6 +148,17 @@ def make_decode_desc(q: torch.Tensor, Kcache: torch.Tensor, vis_begin: int, vis_
     d.tau = tau
     d.kv_stride = (C.c_int64 * 3)(*Kcache.stride()[:3])
     return d
+
+
+def profile_enable(on: bool):
+    _check(load_library().omni_profile_enable(1 if on else 0))
+
+
+def profile_read(kernel: str):
+    """(total milliseconds, launches) recorded for one kernel since profile_enable(True)."""
+    ms, n = C.c_float(0), C.c_int(0)
+    _check(load_library().omni_profile_read(PROF_KERNELS[kernel], C.byref(ms), C.byref(n)))
+    return float(ms.value), int(n.value)
 
 
 def workspace_bytes(call_id: int, desc, param: int = 0) -> int:

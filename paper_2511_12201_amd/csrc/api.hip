@@ -94,6 +94,33 @@ Layer make_layer(const omni_layer_desc* d) {
   return L;
 }
 
+// ---- kernel timing with HIP events (off by default)
+constexpr int kProfSlots = 64;
+struct ProfEntry {
+  hipEvent_t start[kProfSlots], stop[kProfSlots];
+  int created, used;
+};
+static ProfEntry g_prof[kProfCount];
+static bool g_prof_on = false;
+
+void prof_begin(int id, hipStream_t st) {
+  if (!g_prof_on) return;
+  ProfEntry& e = g_prof[id];
+  if (e.used >= kProfSlots) return;
+  if (e.used >= e.created) {
+    if (hipEventCreate(&e.start[e.created]) != hipSuccess || hipEventCreate(&e.stop[e.created]) != hipSuccess) return;
+    e.created++;
+  }
+  (void)hipEventRecord(e.start[e.used], st);
+}
+void prof_end(int id, hipStream_t st) {
+  if (!g_prof_on) return;
+  ProfEntry& e = g_prof[id];
+  if (e.used >= e.created || e.used >= kProfSlots) return;
+  (void)hipEventRecord(e.stop[e.used], st);
+  e.used++;
+}
+
 static bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
 static size_t kv_budget_ws(const Layer& L, int dtype, int pb) {
@@ -108,6 +135,7 @@ using namespace omni;
   do {                                                                     \
     if (!(p)) OMNI_FAIL(OMNI_ERR_INVALID, "argument %s is null", #p);      \
   } while (0)
+#define REQUIRE_PTR_EARLY(p) REQUIRE_PTR(p)
 #define REQUIRE_ALIGNED(p)                                                            \
   do {                                                                                \
     if (!aligned16(p)) OMNI_FAIL(OMNI_ERR_INVALID, "argument %s must be 16-byte aligned", #p); \
@@ -121,6 +149,31 @@ using namespace omni;
 extern "C" {
 
 const char* omni_last_error(void) { return g_err; }
+
+int omni_profile_enable(int on) {
+  clear_error();
+  g_prof_on = on != 0;
+  for (int i = 0; i < kProfCount; ++i) g_prof[i].used = 0;
+  return OMNI_OK;
+}
+
+int omni_profile_read(int kernel_id, float* total_ms, int* launches) {
+  clear_error();
+  if (kernel_id < 0 || kernel_id >= kProfCount) OMNI_FAIL(OMNI_ERR_INVALID, "kernel_id out of range");
+  REQUIRE_PTR_EARLY(total_ms);
+  REQUIRE_PTR_EARLY(launches);
+  ProfEntry& e = g_prof[kernel_id];
+  float sum = 0.f;
+  for (int i = 0; i < e.used; ++i) {
+    OMNI_HIP_CHECK(hipEventSynchronize(e.stop[i]));
+    float ms = 0.f;
+    OMNI_HIP_CHECK(hipEventElapsedTime(&ms, e.start[i], e.stop[i]));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = e.used;
+  return OMNI_OK;
+}
 int omni_version(void) { return 100; }
 
 size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param) {

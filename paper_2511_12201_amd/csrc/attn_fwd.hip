@@ -424,14 +424,20 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   const int heads = sparse ? L.Hq : L.Hkv;
   const int npad = (int)align_up(sparse ? b_cap : L.N, kTileN);
   FwdWs w = carve_fwd(a, L, sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32, heads, npad);
-  hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kTileN, L.B * heads), dim3(kThreads), 0, st,
-                     static_cast<const T*>(K), static_cast<const T*>(V), L, sparse ? 1 : 0, kv_idx, b_cap, budget,
-                     b_cap, npad, static_cast<T*>(w.Kp), static_cast<T*>(w.Vp), w.kidx);
-  OMNI_LAUNCH_CHECK();
-  if (sparse) {
-    hipLaunchKernelGGL((clear_output_kernel<T>), dim3(cdiv(L.N, 64), L.B * L.Hq), dim3(kThreads), 0, st,
-                       static_cast<T*>(O), lse, L);
+  {
+    ProfScope prof__(kProfPack, st);
+    hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kTileN, L.B * heads), dim3(kThreads), 0, st,
+                       static_cast<const T*>(K), static_cast<const T*>(V), L, sparse ? 1 : 0, kv_idx, b_cap, budget,
+                       b_cap, npad, static_cast<T*>(w.Kp), static_cast<T*>(w.Vp), w.kidx);
     OMNI_LAUNCH_CHECK();
+  }
+  if (sparse) {
+    {
+      ProfScope prof__(kProfClear, st);
+      hipLaunchKernelGGL((clear_output_kernel<T>), dim3(cdiv(L.N, 64), L.B * L.Hq), dim3(kThreads), 0, st,
+                         static_cast<T*>(O), lse, L);
+      OMNI_LAUNCH_CHECK();
+    }
   }
   FwdParams p;
   p.Q = Q;
@@ -449,8 +455,11 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.per_q_head = sparse ? 1 : 0;
   p.identity_keys = sparse ? 0 : 1;
   p.ntile_q = cdiv(L.N, kTileM);
-  hipLaunchKernelGGL((attn_fwd_kernel<T, D>), dim3(p.ntile_q * L.B * L.Hq), dim3(kThreads), 0, st, p);
-  OMNI_LAUNCH_CHECK();
+  {
+    ProfScope prof__(kProfAttnFwd, st);
+    hipLaunchKernelGGL((attn_fwd_kernel<T, D>), dim3(p.ntile_q * L.B * L.Hq), dim3(kThreads), 0, st, p);
+    OMNI_LAUNCH_CHECK();
+  }
   return OMNI_OK;
 }
 

@@ -61,6 +61,21 @@ struct Layer {
 };
 Layer make_layer(const omni_layer_desc* d);
 
+// Optional HIP-event timing of individual kernels (omni_profile_* in the C ABI).
+enum ProfId {
+  kProfAttnFwd = 0, kProfPack = 1, kProfClear = 2, kProfPool = 3, kProfProbeLse = 4, kProfProbeSum = 5,
+  kProfScore = 6, kProfBwdDkDv = 7, kProfBwdDq = 8, kProfBwdReduce = 9, kProfDecode = 10, kProfSelect = 11,
+  kProfCount = 12
+};
+void prof_begin(int id, hipStream_t st);
+void prof_end(int id, hipStream_t st);
+struct ProfScope {
+  int id;
+  hipStream_t st;
+  ProfScope(int i, hipStream_t s) : id(i), st(s) { prof_begin(id, st); }
+  ~ProfScope() { prof_end(id, st); }
+};
+
 constexpr int kTileM = 128;   // query rows per attention workgroup
 constexpr int kTileN = 64;    // keys per attention tile
 constexpr int kPadKeyIndex = 0x7fffffff;

@@ -170,8 +170,11 @@ __global__ void decode_combine_kernel(DecodeParams p) {
 
 template <typename T, int D>
 int launch_decode(const DecodeParams& p, hipStream_t st) {
-  hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3(p.nsplit, p.B * p.Hq), dim3(kThreads), 0, st, p);
-  OMNI_LAUNCH_CHECK();
+  {
+    ProfScope prof__(kProfDecode, st);
+    hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3(p.nsplit, p.B * p.Hq), dim3(kThreads), 0, st, p);
+    OMNI_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(p.B * p.Hq), dim3(128), 0, st, p);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;

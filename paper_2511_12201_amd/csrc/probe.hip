@@ -324,18 +324,27 @@ int launch_probe(const Layer& L, const void* Q, const void* K, int pb, float* ke
   constexpr int KPG = probe_keys_per_wg<T>();
   const int nchunk = cdiv(L.N, KPG);
   const int BH = L.B * L.Hq;
-  hipLaunchKernelGGL((pool_queries_kernel<T, D>), dim3(nblk, BH), dim3(kThreads), 0, st, static_cast<const T*>(Q), L,
-                     pb, nblk, w.qbar);
-  OMNI_LAUNCH_CHECK();
-  hipLaunchKernelGGL((probe_kernel<T, D, 1>), dim3(nchunk, BH), dim3(kThreads), 0, st, static_cast<const T*>(K), L, pb,
-                     nblk, nchunk, w.qbar, w.part_m, w.part_l, (const float*)nullptr, (float*)nullptr);
-  OMNI_LAUNCH_CHECK();
+  {
+    ProfScope prof__(kProfPool, st);
+    hipLaunchKernelGGL((pool_queries_kernel<T, D>), dim3(nblk, BH), dim3(kThreads), 0, st, static_cast<const T*>(Q), L,
+                       pb, nblk, w.qbar);
+    OMNI_LAUNCH_CHECK();
+  }
+  {
+    ProfScope prof__(kProfProbeLse, st);
+    hipLaunchKernelGGL((probe_kernel<T, D, 1>), dim3(nchunk, BH), dim3(kThreads), 0, st, static_cast<const T*>(K), L, pb,
+                       nblk, nchunk, w.qbar, w.part_m, w.part_l, (const float*)nullptr, (float*)nullptr);
+    OMNI_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL(probe_lse_kernel, dim3(cdiv(nblk, 4), BH), dim3(kThreads), 0, st, L, pb, nblk, nchunk, KPG,
                      w.part_m, w.part_l, w.lse2w);
   OMNI_LAUNCH_CHECK();
-  hipLaunchKernelGGL((probe_kernel<T, D, 2>), dim3(nchunk, BH), dim3(kThreads), 0, st, static_cast<const T*>(K), L, pb,
-                     nblk, nchunk, w.qbar, (float*)nullptr, (float*)nullptr, w.lse2w, key_scores);
-  OMNI_LAUNCH_CHECK();
+  {
+    ProfScope prof__(kProfProbeSum, st);
+    hipLaunchKernelGGL((probe_kernel<T, D, 2>), dim3(nchunk, BH), dim3(kThreads), 0, st, static_cast<const T*>(K), L, pb,
+                       nblk, nchunk, w.qbar, (float*)nullptr, (float*)nullptr, w.lse2w, key_scores);
+    OMNI_LAUNCH_CHECK();
+  }
   return OMNI_OK;
 }
 

@@ -113,9 +113,12 @@ int launch_score(const Layer& L, const void* Q, const void* K, float* probe, flo
                      probe);
   OMNI_LAUNCH_CHECK();
   const int rows_per_block = 256;
-  hipLaunchKernelGGL((score_queries_kernel<T, D>), dim3(cdiv(L.N, rows_per_block), L.B * L.Hq), dim3(kThreads), 0, st,
-                     q, L, probe, scores, rows_per_block);
-  OMNI_LAUNCH_CHECK();
+  {
+    ProfScope prof__(kProfScore, st);
+    hipLaunchKernelGGL((score_queries_kernel<T, D>), dim3(cdiv(L.N, rows_per_block), L.B * L.Hq), dim3(kThreads), 0, st,
+                       q, L, probe, scores, rows_per_block);
+    OMNI_LAUNCH_CHECK();
+  }
   return OMNI_OK;
 }
 

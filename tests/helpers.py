@@ -15,7 +15,9 @@ def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
 
 
 def to_host(t: torch.Tensor) -> np.ndarray:
-    return t.detach().float().cpu().numpy() if t.is_floating_point() else t.detach().cpu().numpy()
+    if t.dtype == torch.bfloat16:
+        return t.detach().float().cpu().numpy()
+    return t.detach().cpu().numpy()
 
 
 def lists_to_padded(lists, n_heads: int, width: int):
