@@ -27,7 +27,7 @@ Recipe (all draws from numpy's PCG64 seeded with `seed`):
     (c) Each visual query is "lazy" with probability 0.7 and then becomes
     0.25 q + lambda u_sink + beta phi(n), where u_sink is the unit sink key and
     lambda puts the sink logit at +5; the other queries stay broad.  Finally
-    the queries of head i are multiplied by t_i: t_0 = 1 and t_1..t_{H-1} on a
+    the queries of head i are multiplied by t_i: t_0 = 0.5 and t_1..t_{H-1} on a
     geometric ramp 1.3 .. 3, so head 0 is clearly the flattest by design.
   * bf16 configurations round Q, K, V to the bf16 grid (nearest-even); arrays
     stay float32 so the oracle reads exactly the values the GPU reads.
@@ -94,7 +94,7 @@ WINDOW = 64.0
 SINK_LOGIT = 5.0
 LOCAL_GAIN = 6.0          # beta^2 / sqrt(d)
 CLUSTER_VAR = 0.5
-SHARP_FLAT, SHARP_LO, SHARP_HI = 1.0, 1.3, 3.0
+SHARP_FLAT, SHARP_LO, SHARP_HI = 0.5, 1.3, 3.0
 SALIENCE_GAIN = 8.4       # gamma^2 / sqrt(d)
 
 
