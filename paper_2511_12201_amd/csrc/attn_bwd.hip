@@ -1,14 +1,716 @@
-// Backward of the sparse attention (placeholder until the kernels land).
+// Backward of the sparse attention (omni_sparse_attn_bwd): gradients of
+// O = softmax(Q K^T scale) V over kept queries x selected keys with the index
+// sets held constant (the paper trains with the same sparse attention and gives
+// no gradient through the selection):
+//   P = exp(S - lse), dV = P^T dO, dP = dO V^T, dS = P (dP - delta),
+//   delta = rowsum(dO O), dQ = scale dS K, dK = scale dS^T Q.
+//
+// Deterministic two-kernel scheme, no floating-point atomics:
+//  * dkdv kernel: a workgroup owns 128 packed keys of one query head (32 per
+//    wavefront, K and V fragments resident in registers) and streams 64-query
+//    tiles of the kept rows through LDS.  S = Q K^T and dP = dO V^T are computed
+//    with queries on the accumulator rows, so that P and dS are already the B
+//    operands of dV^T = dO^T P and dK^T = Q^T dS; the A operands dO^T and Q^T come
+//    from the k-packed copies made by the pack pass.
+//  * dq kernel: a workgroup owns 128 kept queries (32 per wavefront) and streams
+//    64-key tiles, exactly like the forward: S^T = K Q^T, dP^T = V dO^T, and
+//    dQ^T = K^T dS^T with K^T from the k-packed copy of K.
+//  * a reduce kernel adds the per-query-head dK', dV' rows of a KV group into
+//    dK, dV in head order (position found by binary search in the ascending
+//    index list) and writes zeros for unselected tokens.
+// fp32 inputs run the same kernels on the fp32 32x32x2 MFMA with natural layouts.
 #include "common.h"
 #include "kernels.h"
 
 namespace omni {
 
-size_t attn_bwd_ws(const Layer&, int, int) { return 256; }
+namespace {
 
-int run_attn_bwd(const Layer&, int, const void*, const void*, const void*, const void*, const void*, const float*,
-                 const int*, const int*, const int*, const int*, int, void*, void*, void*, void*, hipStream_t) {
-  OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "omni_sparse_attn_bwd is not implemented yet");
+constexpr int kThreads = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kBwdKeys = 128;     // keys per dkdv workgroup
+constexpr int kBwdQ = 64;         // queries per dkdv iteration
+
+struct BwdParams {
+  const void* Q;
+  const void* dO;
+  Layer L;
+  const int* q_idx;
+  const int* q_cnt;
+  const int* budget;
+  int b_cap, npad, nqpad;
+  const void* Kn;       // packed natural K, V
+  const void* Vn;
+  const void* Kt;       // k-packed K (bf16 only)
+  const int* kidx;
+  const void* Qt;       // k-packed kept Q, dO (bf16 only)
+  const void* dOt;
+  const float* lse2c;   // per kept position: lse * log2e (+inf: contributes nothing)
+  const float* deltac;
+  float* dKp;           // [B*Hq, npad, D] fp32 per-query-head partial gradients
+  float* dVp;
+  void* dQ;
+};
+
+// first position in ascending a[0,n) with a[pos] >= v
+__device__ __forceinline__ int lower_pos(const int* __restrict__ a, int n, int v) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (a[mid] < v) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+// number of entries <= v
+__device__ __forceinline__ int upper_cnt(const int* __restrict__ a, int n, int v) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (a[mid] <= v) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int r0) {
+  union { bf16x8 v; unsigned u[4]; } o;
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) o.u[jj] = pack_bf16x2(v[r0 + 2 * jj], v[r0 + 2 * jj + 1]);
+  return o.v;
+}
+
+// ------------------------------------------------------------------ dK', dV'
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(BwdParams p) {
+  constexpr bool kBf16 = sizeof(T) == 2;
+  constexpr int LD = D + 8;                               // row pitch of natural tiles (elements)
+  constexpr int NBUF = kBf16 ? 2 : 1;
+  constexpr int kNatBytes = kBwdQ * LD * (int)sizeof(T);
+  constexpr int kPackBytes = kBf16 ? kBwdQ * D * 2 : 16;
+  __shared__ __attribute__((aligned(16))) unsigned char sQn_raw[NBUF * kNatBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char sGn_raw[NBUF * kNatBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char sQt_raw[NBUF * kPackBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char sGt_raw[NBUF * kPackBytes];
+  __shared__ __attribute__((aligned(16))) float sLse[NBUF][kBwdQ];
+  __shared__ __attribute__((aligned(16))) float sDel[NBUF][kBwdQ];
+  __shared__ __attribute__((aligned(16))) int sQi[NBUF][kBwdQ];
+  __shared__ int sBound[2];
+
+  const Layer& L = p.L;
+  const int ktile = blockIdx.x, bh = blockIdx.y;
+  const int b = bh / L.Hq, i = bh % L.Hq;
+  const int nkeys = min(p.budget[b], p.b_cap);
+  if (ktile * kBwdKeys >= nkeys) return;
+  const int nq = p.q_cnt[bh];
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int ln = lane & 31, h = lane >> 5;
+  const int* kidx = p.kidx + (long long)bh * p.npad;
+  const int* qlist = p.q_idx + (long long)bh * L.N;
+  const int slot0 = ktile * kBwdKeys;
+  const int slot = slot0 + wave * 32 + ln;                  // this lane's key slot (< npad by construction)
+  const int my_kidx = kidx[slot];
+  const float c2 = L.scale * kLog2e;
+
+  // query range that can see this key tile, and the part of it that sees every key of the tile
+  if (threadIdx.x == 0 || threadIdx.x == 64) {
+    const int which = threadIdx.x ? 1 : 0;
+    const int last_slot = min(slot0 + kBwdKeys, nkeys) - 1;
+    int v;
+    if (!L.causal) v = 0;
+    else v = lower_pos(qlist, nq, which ? kidx[last_slot] : kidx[slot0]);
+    sBound[which] = v;
+  }
+  __syncthreads();
+  const bool has_pad = slot0 + kBwdKeys > nkeys;
+  const int q_begin = sBound[0] / kBwdQ;                    // first query tile with an admissible pair
+  const int q_full_pos = has_pad ? 0x7fffffff : sBound[1];  // tiles starting at or after this position need no mask
+  const int n_qtiles = cdiv(nq, kBwdQ);
+
+  // resident K, V fragments (B operands: lane = key column)
+  const T* krow = static_cast<const T*>(p.Kn) + ((long long)bh * p.npad + slot) * D;
+  const T* vrow = static_cast<const T*>(p.Vn) + ((long long)bh * p.npad + slot) * D;
+  bf16x8 kf16[kBf16 ? D / 16 : 1], vf16[kBf16 ? D / 16 : 1];
+  f32x4 kf32[kBf16 ? 1 : D / 8], vf32[kBf16 ? 1 : D / 8];
+  if constexpr (kBf16) {
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      kf16[ks] = *reinterpret_cast<const bf16x8*>(krow + ks * 16 + h * 8);
+      vf16[ks] = *reinterpret_cast<const bf16x8*>(vrow + ks * 16 + h * 8);
+    }
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < D / 8; ++ks) {
+      kf32[ks] = *reinterpret_cast<const f32x4*>(krow + ks * 8 + h * 4);
+      vf32[ks] = *reinterpret_cast<const f32x4*>(vrow + ks * 8 + h * 4);
+    }
+  }
+
+  f32x16 dk[D / 32], dv[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      dk[db][r] = 0.f;
+      dv[db][r] = 0.f;
+    }
+
+  // ---- staging of a 64-query tile
+  constexpr int E = Elem<T>::kPer16B;
+  constexpr int CPR = D / E;
+  constexpr int kChunks = kBwdQ * CPR / kThreads;
+  const T* qbase = static_cast<const T*>(p.Q) + b * L.qs[0] + i * L.qs[1];
+  const T* gbase = static_cast<const T*>(p.dO) + b * L.qs[0] + i * L.qs[1];
+  const T* qt = static_cast<const T*>(p.Qt) + (long long)bh * p.nqpad * D;
+  const T* gt = static_cast<const T*>(p.dOt) + (long long)bh * p.nqpad * D;
+  const float* lsec = p.lse2c + (long long)bh * p.nqpad;
+  const float* delc = p.deltac + (long long)bh * p.nqpad;
+  u32x4 stQ[kChunks], stG[kChunks], stQt[kBf16 ? kChunks : 1], stGt[kBf16 ? kChunks : 1];
+  float stL = 0.f, stD = 0.f;
+  int stI = -1;
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+  auto load_tile = [&](int t) {
+    const int pos0 = t * kBwdQ;
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      const int ch = threadIdx.x + c * kThreads;
+      const int row = ch / CPR, col = (ch % CPR) * E;
+      const int pos = pos0 + row;
+      stQ[c] = zero4;
+      stG[c] = zero4;
+      if (pos < nq) {
+        const long long qrow = qlist[pos];
+        stQ[c] = *reinterpret_cast<const u32x4*>(qbase + qrow * L.qs[2] + col);
+        stG[c] = *reinterpret_cast<const u32x4*>(gbase + qrow * L.qs[2] + col);
+      }
+      if constexpr (kBf16) {
+        stQt[c] = *reinterpret_cast<const u32x4*>(qt + (long long)pos0 * D + ch * E);
+        stGt[c] = *reinterpret_cast<const u32x4*>(gt + (long long)pos0 * D + ch * E);
+      }
+    }
+    if (threadIdx.x < kBwdQ) {
+      const int pos = pos0 + threadIdx.x;
+      stL = lsec[pos];
+      stD = delc[pos];
+      stI = pos < nq ? qlist[pos] : -1;
+    }
+  };
+  auto store_tile = [&](int buf) {
+    T* sq = reinterpret_cast<T*>(sQn_raw + buf * kNatBytes);
+    T* sg = reinterpret_cast<T*>(sGn_raw + buf * kNatBytes);
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      const int ch = threadIdx.x + c * kThreads;
+      const int row = ch / CPR, col = (ch % CPR) * E;
+      *reinterpret_cast<u32x4*>(sq + row * LD + col) = stQ[c];
+      *reinterpret_cast<u32x4*>(sg + row * LD + col) = stG[c];
+      if constexpr (kBf16) {
+        *reinterpret_cast<u32x4*>(reinterpret_cast<T*>(sQt_raw + buf * kPackBytes) + ch * E) = stQt[c];
+        *reinterpret_cast<u32x4*>(reinterpret_cast<T*>(sGt_raw + buf * kPackBytes) + ch * E) = stGt[c];
+      }
+    }
+    if (threadIdx.x < kBwdQ) {
+      sLse[buf][threadIdx.x] = stL;
+      sDel[buf][threadIdx.x] = stD;
+      sQi[buf][threadIdx.x] = stI;
+    }
+  };
+
+  auto compute_tile = [&](int buf, bool masked) {
+    const T* sq = reinterpret_cast<const T*>(sQn_raw + buf * kNatBytes);
+    const T* sg = reinterpret_cast<const T*>(sGn_raw + buf * kNatBytes);
+#pragma unroll
+    for (int qb = 0; qb < kBwdQ / 32; ++qb) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        s[r] = 0.f;
+        dp[r] = 0.f;
+      }
+      if constexpr (kBf16) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(sq + (qb * 32 + ln) * LD + ks * 16 + h * 8);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf16[ks], s, 0, 0, 0);
+          const bf16x8 ga = *reinterpret_cast<const bf16x8*>(sg + (qb * 32 + ln) * LD + ks * 16 + h * 8);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vf16[ks], dp, 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < D / 8; ++ks) {
+          const f32x4 qa = *reinterpret_cast<const f32x4*>(sq + (qb * 32 + ln) * LD + ks * 8 + h * 4);
+          const f32x4 ga = *reinterpret_cast<const f32x4*>(sg + (qb * 32 + ln) * LD + ks * 8 + h * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            s = __builtin_amdgcn_mfma_f32_32x32x2f32(qa[e], kf32[ks][e], s, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x2f32(ga[e], vf32[ks][e], dp, 0, 0, 0);
+          }
+        }
+      }
+      // accumulator rows are queries 8 (r/4) + 4 h + r%4 of this block, the column is this lane's key
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int qo = qb * 32 + 8 * q4 + 4 * h;
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sLse[buf][qo]);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sDel[buf][qo]);
+        i32x4 qi4 = {0, 0, 0, 0};
+        if (masked) qi4 = *reinterpret_cast<const i32x4*>(&sQi[buf][qo]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = q4 * 4 + e;
+          float pv = exp2f(fmaf(s[r], c2, -l4[e]));
+          if (masked) {
+            const int qcmp = L.causal ? qi4[e] : kPadKeyIndex - 1;
+            if (my_kidx > qcmp) pv = 0.f;
+          }
+          s[r] = pv;
+          dp[r] = pv * (dp[r] - d4[e]);
+        }
+      }
+      if constexpr (kBf16) {
+        const T* sqt = reinterpret_cast<const T*>(sQt_raw + buf * kPackBytes);
+        const T* sgt = reinterpret_cast<const T*>(sGt_raw + buf * kPackBytes);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int t16 = qb * 2 + u;
+          const bf16x8 pf = pack8(s, u * 8);
+          const bf16x8 dsf = pack8(dp, u * 8);
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            const bf16x8 ga = *reinterpret_cast<const bf16x8*>(sgt + ((t16 * 2 + h) * D + db * 32 + ln) * 8);
+            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, pf, dv[db], 0, 0, 0);
+            const bf16x8 qa = *reinterpret_cast<const bf16x8*>(sqt + ((t16 * 2 + h) * D + db * 32 + ln) * 8);
+            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, dsf, dk[db], 0, 0, 0);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qrow = qb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            dv[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(sg[qrow * LD + db * 32 + ln], s[r], dv[db], 0, 0, 0);
+            dk[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(sq[qrow * LD + db * 32 + ln], dp[r], dk[db], 0, 0, 0);
+          }
+        }
+      }
+    }
+  };
+
+  if (q_begin < n_qtiles) {
+    if constexpr (kBf16) {
+      load_tile(q_begin);
+      store_tile(0);
+      __syncthreads();
+      for (int t = q_begin; t < n_qtiles; ++t) {
+        const int buf = (t - q_begin) & 1;
+        if (t + 1 < n_qtiles) load_tile(t + 1);
+        compute_tile(buf, t * kBwdQ < q_full_pos || (t + 1) * kBwdQ > nq);
+        if (t + 1 < n_qtiles) store_tile(buf ^ 1);
+        __syncthreads();
+      }
+    } else {
+      for (int t = q_begin; t < n_qtiles; ++t) {
+        __syncthreads();
+        load_tile(t);
+        store_tile(0);
+        __syncthreads();
+        compute_tile(0, t * kBwdQ < q_full_pos || (t + 1) * kBwdQ > nq);
+      }
+    }
+  }
+
+  // ---- write dK' (scaled) and dV' for this lane's key slot; accumulator rows are d
+  float* dkrow = p.dKp + ((long long)bh * p.npad + slot) * D;
+  float* dvrow = p.dVp + ((long long)bh * p.npad + slot) * D;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int d = db * 32 + 8 * q4 + 4 * h;
+      f32x4 a = {dk[db][q4 * 4] * L.scale, dk[db][q4 * 4 + 1] * L.scale, dk[db][q4 * 4 + 2] * L.scale,
+                 dk[db][q4 * 4 + 3] * L.scale};
+      f32x4 c = {dv[db][q4 * 4], dv[db][q4 * 4 + 1], dv[db][q4 * 4 + 2], dv[db][q4 * 4 + 3]};
+      *reinterpret_cast<f32x4*>(dkrow + d) = a;
+      *reinterpret_cast<f32x4*>(dvrow + d) = c;
+    }
+}
+
+// ------------------------------------------------------------------ dQ
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p, int ntile_q) {
+  constexpr bool kBf16 = sizeof(T) == 2;
+  constexpr int LD = D + 8;
+  constexpr int NBUF = kBf16 ? 2 : 1;
+  constexpr int kNatBytes = kTileN * LD * (int)sizeof(T);
+  constexpr int kPackBytes = kBf16 ? kTileN * D * 2 : 16;
+  __shared__ __attribute__((aligned(16))) unsigned char sK_raw[NBUF * kNatBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char sV_raw[NBUF * kNatBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char sKt_raw[NBUF * kPackBytes];
+  __shared__ __attribute__((aligned(16))) int sIdx[NBUF][kTileN];
+  __shared__ int sBound[2];
+
+  const Layer& L = p.L;
+  const int BH = L.B * L.Hq;
+  const int bh = blockIdx.x % BH;
+  const int tq = ntile_q - 1 - blockIdx.x / BH;
+  const int b = bh / L.Hq, i = bh % L.Hq;
+  const int nq = p.q_cnt[bh];
+  if (tq * kTileM >= nq) return;
+  const int nkeys = min(p.budget[b], p.b_cap);
+  const int* kidx = p.kidx + (long long)bh * p.npad;
+  const int* qlist = p.q_idx + (long long)bh * L.N;
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int ln = lane & 31, h = lane >> 5;
+
+  const int pos_first = tq * kTileM, pos_last = min(pos_first + kTileM, nq) - 1;
+  if (threadIdx.x == 0 || threadIdx.x == 64) {
+    const int which = threadIdx.x ? 1 : 0;
+    const int row = qlist[which ? pos_last : pos_first];
+    sBound[which] = L.causal ? upper_cnt(kidx, nkeys, row) : nkeys;
+  }
+  __syncthreads();
+  const int n_full_tiles = sBound[0] / kTileN;
+  const int ntiles = cdiv(sBound[1], kTileN);
+
+  const int qpos = pos_first + wave * 32 + ln;
+  const bool qvalid = qpos < nq;
+  const int qpos_c = min(qpos, nq - 1);
+  const int qrow = qlist[qpos_c];
+  const int qcmp = L.causal ? qrow : kPadKeyIndex - 1;
+  const float lse2 = p.lse2c[(long long)bh * p.nqpad + qpos_c];
+  const float delta = p.deltac[(long long)bh * p.nqpad + qpos_c];
+  const float c2 = L.scale * kLog2e;
+  const T* qptr = static_cast<const T*>(p.Q) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+  const T* gptr = static_cast<const T*>(p.dO) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+  bf16x8 qf16[kBf16 ? D / 16 : 1], gf16[kBf16 ? D / 16 : 1];
+  f32x4 qf32[kBf16 ? 1 : D / 8], gf32[kBf16 ? 1 : D / 8];
+  if constexpr (kBf16) {
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      qf16[ks] = *reinterpret_cast<const bf16x8*>(qptr + ks * 16 + h * 8);
+      gf16[ks] = *reinterpret_cast<const bf16x8*>(gptr + ks * 16 + h * 8);
+    }
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < D / 8; ++ks) {
+      qf32[ks] = *reinterpret_cast<const f32x4*>(qptr + ks * 8 + h * 4);
+      gf32[ks] = *reinterpret_cast<const f32x4*>(gptr + ks * 8 + h * 4);
+    }
+  }
+  f32x16 dq[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
+
+  constexpr int E = Elem<T>::kPer16B;
+  constexpr int CPR = D / E;
+  constexpr int kChunks = kTileN * CPR / kThreads;
+  const T* kn = static_cast<const T*>(p.Kn) + (long long)bh * p.npad * D;
+  const T* vn = static_cast<const T*>(p.Vn) + (long long)bh * p.npad * D;
+  const T* kt = static_cast<const T*>(p.Kt) + (long long)bh * p.npad * D;
+  u32x4 stK[kChunks], stV[kChunks], stKt[kBf16 ? kChunks : 1];
+  i32x4 stI;
+
+  auto load_tile = [&](int t) {
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      const int ch = threadIdx.x + c * kThreads;
+      stK[c] = *reinterpret_cast<const u32x4*>(kn + (long long)t * kTileN * D + ch * E);
+      stV[c] = *reinterpret_cast<const u32x4*>(vn + (long long)t * kTileN * D + ch * E);
+      if constexpr (kBf16) stKt[c] = *reinterpret_cast<const u32x4*>(kt + (long long)t * kTileN * D + ch * E);
+    }
+    if (threadIdx.x < kTileN / 4) stI = *reinterpret_cast<const i32x4*>(kidx + t * kTileN + threadIdx.x * 4);
+  };
+  auto store_tile = [&](int buf) {
+    T* sk = reinterpret_cast<T*>(sK_raw + buf * kNatBytes);
+    T* sv = reinterpret_cast<T*>(sV_raw + buf * kNatBytes);
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      const int ch = threadIdx.x + c * kThreads;
+      const int row = ch / CPR, col = (ch % CPR) * E;
+      *reinterpret_cast<u32x4*>(sk + row * LD + col) = stK[c];
+      *reinterpret_cast<u32x4*>(sv + row * LD + col) = stV[c];
+      if constexpr (kBf16) *reinterpret_cast<u32x4*>(reinterpret_cast<T*>(sKt_raw + buf * kPackBytes) + ch * E) = stKt[c];
+    }
+    if (threadIdx.x < kTileN / 4) *reinterpret_cast<i32x4*>(&sIdx[buf][threadIdx.x * 4]) = stI;
+  };
+  auto compute_tile = [&](int buf, bool masked) {
+    const T* sk = reinterpret_cast<const T*>(sK_raw + buf * kNatBytes);
+    const T* sv = reinterpret_cast<const T*>(sV_raw + buf * kNatBytes);
+    f32x16 s[2], dp[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        s[kb][r] = 0.f;
+        dp[kb][r] = 0.f;
+      }
+      if constexpr (kBf16) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+          const bf16x8 ka = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + ln) * LD + ks * 16 + h * 8);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf16[ks], s[kb], 0, 0, 0);
+          const bf16x8 va = *reinterpret_cast<const bf16x8*>(sv + (kb * 32 + ln) * LD + ks * 16 + h * 8);
+          dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, gf16[ks], dp[kb], 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < D / 8; ++ks) {
+          const f32x4 ka = *reinterpret_cast<const f32x4*>(sk + (kb * 32 + ln) * LD + ks * 8 + h * 4);
+          const f32x4 va = *reinterpret_cast<const f32x4*>(sv + (kb * 32 + ln) * LD + ks * 8 + h * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ka[e], qf32[ks][e], s[kb], 0, 0, 0);
+            dp[kb] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], gf32[ks][e], dp[kb], 0, 0, 0);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        i32x4 id = {0, 0, 0, 0};
+        if (masked) id = *reinterpret_cast<const i32x4*>(&sIdx[buf][kb * 32 + 8 * q4 + 4 * h]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = q4 * 4 + e;
+          float pv = exp2f(fmaf(s[kb][r], c2, -lse2));
+          if (masked && id[e] > qcmp) pv = 0.f;
+          dp[kb][r] = pv * (dp[kb][r] - delta);
+        }
+      }
+    if constexpr (kBf16) {
+      const T* skt = reinterpret_cast<const T*>(sKt_raw + buf * kPackBytes);
+#pragma unroll
+      for (int t16 = 0; t16 < 4; ++t16) {
+        const bf16x8 dsf = pack8(dp[t16 >> 1], (t16 & 1) * 8);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+          const bf16x8 ka = *reinterpret_cast<const bf16x8*>(skt + ((t16 * 2 + h) * D + db * 32 + ln) * 8);
+          dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, dsf, dq[db], 0, 0, 0);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int ks_slot = kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db)
+            dq[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(sk[ks_slot * LD + db * 32 + ln], dp[kb][r], dq[db], 0, 0, 0);
+        }
+    }
+  };
+
+  if (ntiles > 0) {
+    if constexpr (kBf16) {
+      load_tile(0);
+      store_tile(0);
+      __syncthreads();
+      for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles) load_tile(t + 1);
+        compute_tile(t & 1, t >= n_full_tiles);
+        if (t + 1 < ntiles) store_tile((t + 1) & 1);
+        __syncthreads();
+      }
+    } else {
+      for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+        load_tile(t);
+        store_tile(0);
+        __syncthreads();
+        compute_tile(0, t >= n_full_tiles);
+      }
+    }
+  }
+  if (qvalid) {
+    T* optr = static_cast<T*>(p.dQ) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int d = db * 32 + 8 * q4 + 4 * h;
+        const float v0 = dq[db][q4 * 4 + 0] * L.scale, v1 = dq[db][q4 * 4 + 1] * L.scale;
+        const float v2 = dq[db][q4 * 4 + 2] * L.scale, v3 = dq[db][q4 * 4 + 3] * L.scale;
+        if constexpr (kBf16) {
+          uint2 w;
+          w.x = pack_bf16x2(v0, v1);
+          w.y = pack_bf16x2(v2, v3);
+          *reinterpret_cast<uint2*>(optr + d) = w;
+        } else {
+          f32x4 w = {v0, v1, v2, v3};
+          *reinterpret_cast<f32x4*>(optr + d) = w;
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------ dK, dV = sum over the heads of a KV group
+
+// grid: (ceil(N / rows_per_block), B*Hkv); one token row per D/4 lanes.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void attn_bwd_reduce_kernel(BwdParams p, const int* __restrict__ kv_idx,
+                                                                  T* __restrict__ dK, T* __restrict__ dV) {
+  constexpr int LPR = D / 4;
+  constexpr int RPB = kThreads / LPR;
+  const Layer& L = p.L;
+  const int bg = blockIdx.y, b = bg / L.Hkv, g = bg % L.Hkv;
+  const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
+  const int n = blockIdx.x * RPB + r0;
+  if (n >= L.N) return;
+  const int nkeys = min(p.budget[b], p.b_cap);
+  f32x4 ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < L.G; ++j) {
+    const int bh = b * L.Hq + g * L.G + j;
+    const int* list = kv_idx + (long long)bh * p.b_cap;
+    const int pos = lower_pos(list, nkeys, n);
+    if (pos < nkeys && list[pos] == n) {
+      const long long o = ((long long)bh * p.npad + pos) * D + c * 4;
+      const f32x4 k4 = *reinterpret_cast<const f32x4*>(p.dKp + o);
+      const f32x4 v4 = *reinterpret_cast<const f32x4*>(p.dVp + o);
+      ak += k4;
+      av += v4;
+    }
+  }
+  const long long o = b * L.ks[0] + g * L.ks[1] + (long long)n * L.ks[2] + c * 4;
+  if constexpr (sizeof(T) == 2) {
+    uint2 wk, wv;
+    wk.x = pack_bf16x2(ak[0], ak[1]);
+    wk.y = pack_bf16x2(ak[2], ak[3]);
+    wv.x = pack_bf16x2(av[0], av[1]);
+    wv.y = pack_bf16x2(av[2], av[3]);
+    *reinterpret_cast<uint2*>(dK + o) = wk;
+    *reinterpret_cast<uint2*>(dV + o) = wv;
+  } else {
+    *reinterpret_cast<f32x4*>(dK + o) = ak;
+    *reinterpret_cast<f32x4*>(dV + o) = av;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void clear_rows_kernel(T* __restrict__ X, Layer L) {
+  constexpr int E = Elem<T>::kPer16B;
+  const int CPR = L.D / E;
+  const int bh = blockIdx.y, b = bh / L.Hq, i = bh % L.Hq;
+  T* base = X + b * L.qs[0] + i * L.qs[1];
+  const int row0 = blockIdx.x * 64;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int c = threadIdx.x; c < 64 * CPR; c += kThreads) {
+    const int r = row0 + c / CPR;
+    if (r < L.N) *reinterpret_cast<u32x4*>(base + (long long)r * L.qs[2] + (c % CPR) * E) = zero;
+  }
+}
+
+struct BwdWs {
+  void *Kn, *Vn, *Kt, *Qt, *dOt;
+  int* kidx;
+  float *lse2c, *deltac, *dKp, *dVp;
+};
+
+BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
+  BwdWs w;
+  const size_t es = dtype == OMNI_BF16 ? 2 : 4;
+  const size_t BH = (size_t)L.B * L.Hq;
+  const size_t krows = BH * npad, qrows = BH * nqpad;
+  w.Kn = a.take<unsigned char>(krows * L.D * es);
+  w.Vn = a.take<unsigned char>(krows * L.D * es);
+  w.Kt = a.take<unsigned char>(dtype == OMNI_BF16 ? krows * L.D * es : 16);
+  w.Qt = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
+  w.dOt = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
+  w.kidx = a.take<int>(krows);
+  w.lse2c = a.take<float>(qrows);
+  w.deltac = a.take<float>(qrows);
+  w.dKp = a.take<float>(krows * L.D);
+  w.dVp = a.take<float>(krows * L.D);
+  return w;
+}
+
+int bwd_npad(int b_cap) { return (int)align_up(b_cap, kBwdKeys); }
+int bwd_nqpad(const Layer& L) { return (int)align_up(L.N, kTileM); }
+
+template <typename T, int D>
+int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+               const float* lse, const int* q_idx, const int* q_cnt, const int* kv_idx, const int* budget, int b_cap,
+               void* dQ, void* dK, void* dV, void* ws, hipStream_t st) {
+  constexpr int dt = sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32;
+  Arena a(ws);
+  const int npad = bwd_npad(b_cap), nqpad = bwd_nqpad(L);
+  BwdWs w = carve_bwd(a, L, dt, npad, nqpad);
+  int rc = run_pack_kv(L, dt, K, V, 1, kv_idx, b_cap, budget, b_cap, npad, kBwdKeys, w.Kn, w.Vn,
+                       dt == OMNI_BF16 ? w.Kt : nullptr,
+                       nullptr, w.kidx, st);
+  if (rc != OMNI_OK) return rc;
+  rc = run_pack_q(L, dt, Q, O, dO, lse, q_idx, q_cnt, nqpad, w.Qt, w.dOt, w.lse2c, w.deltac, st);
+  if (rc != OMNI_OK) return rc;
+  hipLaunchKernelGGL((clear_rows_kernel<T>), dim3(cdiv(L.N, 64), L.B * L.Hq), dim3(kThreads), 0, st,
+                     static_cast<T*>(dQ), L);
+  OMNI_LAUNCH_CHECK();
+  BwdParams p;
+  p.Q = Q;
+  p.dO = dO;
+  p.L = L;
+  p.q_idx = q_idx;
+  p.q_cnt = q_cnt;
+  p.budget = budget;
+  p.b_cap = b_cap;
+  p.npad = npad;
+  p.nqpad = nqpad;
+  p.Kn = w.Kn;
+  p.Vn = w.Vn;
+  p.Kt = w.Kt;
+  p.kidx = w.kidx;
+  p.Qt = w.Qt;
+  p.dOt = w.dOt;
+  p.lse2c = w.lse2c;
+  p.deltac = w.deltac;
+  p.dKp = w.dKp;
+  p.dVp = w.dVp;
+  p.dQ = dQ;
+  {
+    ProfScope prof__(kProfBwdDkDv, st);
+    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<T, D>), dim3(npad / kBwdKeys, L.B * L.Hq), dim3(kThreads), 0, st, p);
+    OMNI_LAUNCH_CHECK();
+  }
+  {
+    ProfScope prof__(kProfBwdDq, st);
+    const int ntile_q = cdiv(L.N, kTileM);
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<T, D>), dim3(ntile_q * L.B * L.Hq), dim3(kThreads), 0, st, p, ntile_q);
+    OMNI_LAUNCH_CHECK();
+  }
+  {
+    ProfScope prof__(kProfBwdReduce, st);
+    constexpr int RPB = kThreads / (D / 4);
+    hipLaunchKernelGGL((attn_bwd_reduce_kernel<T, D>), dim3(cdiv(L.N, RPB), L.B * L.Hkv), dim3(kThreads), 0, st, p,
+                       kv_idx, static_cast<T*>(dK), static_cast<T*>(dV));
+    OMNI_LAUNCH_CHECK();
+  }
+  return OMNI_OK;
+}
+
+}  // namespace
+
+size_t attn_bwd_ws(const Layer& L, int dtype, int b_cap) {
+  Arena a(nullptr);
+  carve_bwd(a, L, dtype, bwd_npad(b_cap), bwd_nqpad(L));
+  return a.used();
+}
+
+int run_attn_bwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const void* O,
+                 const void* dO, const float* lse, const int* q_idx, const int* q_cnt, const int* kv_idx,
+                 const int* budget, int b_cap, void* dQ, void* dK, void* dV, void* ws, hipStream_t st) {
+  if (dtype == OMNI_BF16) {
+    if (L.D == 128)
+      return launch_bwd<u16, 128>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
+    return launch_bwd<u16, 64>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
+  }
+  if (L.D == 128)
+    return launch_bwd<float, 128>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
+  return launch_bwd<float, 64>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
 }
 
 }  // namespace omni

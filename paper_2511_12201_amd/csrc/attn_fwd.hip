@@ -3,11 +3,11 @@
 // "Preliminary", attention equation, restricted by the masks M^Q, M^K, M^V).
 //
 // Design for gfx950:
-//  * A pack kernel gathers each head's selected K rows into a dense row-major
-//    buffer and its V rows into the exact operand order the matrix cores need
-//    (below), zero-padding to whole 64-key tiles and recording the original
-//    token index of every slot.  The dense baseline runs the same pack with
-//    identity indices per KV head.  The main loop is then free of gathers.
+//  * A pack pass (pack.hip) gathers each head's selected K rows into a dense
+//    row-major buffer and its V rows into the exact operand order the matrix
+//    cores need (below), zero-padding to whole 64-key tiles and recording the
+//    original token index of every slot.  The dense baseline runs the same pack
+//    with identity indices per KV head.  The main loop is then free of gathers.
 //  * Both GEMMs are computed transposed, S^T = K Q^T and O^T = V^T P^T, with
 //    32x32 MFMA tiles.  Each lane then owns one query column: the softmax row
 //    statistics are per-lane scalars (one exchange with the partner lane that
@@ -29,85 +29,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-
-// ------------------------------------------------------------------ pack / gather
-
-// grid: (npad/64, BHx).  Slot p of the packed buffers holds source row src_idx[p]
-// (identity when src_idx == nullptr); slots >= nkeys are zero with index kPadKeyIndex.
-template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void pack_kv_kernel(const T* __restrict__ K, const T* __restrict__ V, Layer L,
-                                                          int per_q_head, const int* __restrict__ src_idx,
-                                                          int idx_stride, const int* __restrict__ budget, int b_cap,
-                                                          int npad, T* __restrict__ Kp, T* __restrict__ Vp,
-                                                          int* __restrict__ kidx) {
-  constexpr bool kBf16 = sizeof(T) == 2;
-  constexpr int E = Elem<T>::kPer16B;
-  constexpr int CPR = D / E;                     // 16-byte chunks per row
-  __shared__ int sIdx[kTileN];
-  const int tile = blockIdx.x, bhx = blockIdx.y;
-  const int H = per_q_head ? L.Hq : L.Hkv;
-  const int b = bhx / H, hx = bhx % H;
-  const int g = per_q_head ? hx / L.G : hx;
-  const int nkeys = budget ? min(budget[b], b_cap) : L.N;
-  if (tile * kTileN >= nkeys) return;
-  if (threadIdx.x < kTileN) {
-    const int p = tile * kTileN + threadIdx.x;
-    int id = kPadKeyIndex;
-    if (p < nkeys) id = src_idx ? src_idx[(long long)bhx * idx_stride + p] : p;
-    sIdx[threadIdx.x] = id;
-    kidx[(long long)bhx * npad + p] = id;
-  }
-  __syncthreads();
-  const T* kbase = K + b * L.ks[0] + g * L.ks[1];
-  const T* vbase = V + b * L.ks[0] + g * L.ks[1];
-  T* kdst = Kp + ((long long)bhx * npad + tile * kTileN) * D;
-  T* vdst = Vp + ((long long)bhx * npad + tile * kTileN) * D;
-  const u32x4 zero = {0u, 0u, 0u, 0u};
-  for (int c = threadIdx.x; c < kTileN * CPR; c += kThreads) {
-    const int row = c / CPR, col = (c % CPR) * E;
-    const int id = sIdx[row];
-    u32x4 kv = zero;
-    if (id != kPadKeyIndex) kv = *reinterpret_cast<const u32x4*>(kbase + (long long)id * L.ks[2] + col);
-    *reinterpret_cast<u32x4*>(kdst + row * D + col) = kv;
-    if constexpr (!kBf16) {
-      u32x4 vv = zero;
-      if (id != kPadKeyIndex) vv = *reinterpret_cast<const u32x4*>(vbase + (long long)id * L.ks[2] + col);
-      *reinterpret_cast<u32x4*>(vdst + row * D + col) = vv;
-    }
-  }
-  if constexpr (kBf16) {
-    // work item = (16-key group, half, 8-wide d chunk): 8x8 transpose in registers
-    constexpr int kItems = (kTileN / 16) * 2 * (D / 8);
-    for (int it = threadIdx.x; it < kItems; it += kThreads) {
-      const int dc = it % (D / 8);
-      const int h = (it / (D / 8)) & 1;
-      const int grp = it / (D / 8) / 2;
-      u32x4 in[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int slot = 16 * grp + 8 * (j >> 2) + 4 * h + (j & 3);
-        const int id = sIdx[slot];
-        in[j] = zero;
-        if (id != kPadKeyIndex) in[j] = *reinterpret_cast<const u32x4*>(vbase + (long long)id * L.ks[2] + dc * 8);
-      }
-      // out[e] = 8 keys (j = 0..7) of column dc*8 + e
-      u16* dst = reinterpret_cast<u16*>(vdst) + ((grp * 2 + h) * D + dc * 8) * 8;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        unsigned w[4];
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const unsigned a = in[2 * jj][e >> 1], bb = in[2 * jj + 1][e >> 1];
-          const unsigned lo = (e & 1) ? (a >> 16) : (a & 0xffffu);
-          const unsigned hi = (e & 1) ? (bb >> 16) : (bb & 0xffffu);
-          w[jj] = lo | (hi << 16);
-        }
-        u32x4 o = {w[0], w[1], w[2], w[3]};
-        *reinterpret_cast<u32x4*>(dst + e * 8) = o;
-      }
-    }
-  }
-}
 
 // O = 0, lse = -inf for every row (kept rows are overwritten by the attention kernel).
 template <typename T>
@@ -425,11 +346,11 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   const int npad = (int)align_up(sparse ? b_cap : L.N, kTileN);
   FwdWs w = carve_fwd(a, L, sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32, heads, npad);
   {
-    ProfScope prof__(kProfPack, st);
-    hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kTileN, L.B * heads), dim3(kThreads), 0, st,
-                       static_cast<const T*>(K), static_cast<const T*>(V), L, sparse ? 1 : 0, kv_idx, b_cap, budget,
-                       b_cap, npad, static_cast<T*>(w.Kp), static_cast<T*>(w.Vp), w.kidx);
-    OMNI_LAUNCH_CHECK();
+    const int dt = sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32;
+    // bf16: K natural + V k-packed; fp32: both natural
+    int rc = run_pack_kv(L, dt, K, V, sparse ? 1 : 0, kv_idx, b_cap, budget, b_cap, npad, kTileN, w.Kp,
+                         dt == OMNI_BF16 ? nullptr : w.Vp, nullptr, dt == OMNI_BF16 ? w.Vp : nullptr, w.kidx, st);
+    if (rc != OMNI_OK) return rc;
   }
   if (sparse) {
     {

@@ -27,6 +27,14 @@ size_t probe_ws(const Layer& L, int dtype, int pb);
 int run_probe(const Layer& L, int dtype, const void* Q, const void* K, int pb, float* key_scores, void* ws,
               hipStream_t st);
 
+// pack.hip (outputs that are nullptr are skipped; Kt / Vt / Qt / dOt exist for bf16 only)
+int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per_q_head, const int* src_idx,
+                int idx_stride, const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt,
+                void* Vt, int* kidx, hipStream_t st);
+int run_pack_q(const Layer& L, int dtype, const void* Q, const void* O, const void* dO, const float* lse,
+               const int* q_idx, const int* q_cnt, int nqpad, void* Qt, void* dOt, float* lse2c, float* deltac,
+               hipStream_t st);
+
 // attn_fwd.hip
 size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse);
 int run_attn_fwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const int* q_idx,

@@ -1,0 +1,239 @@
+// Gather / re-layout passes that feed the attention kernels (HBM-bound copies).
+//
+// pack_kv: per head, the selected K/V rows are gathered into dense buffers,
+// padded with zero rows to whole 64-key tiles, and the original token index of
+// every slot is recorded (pad slots: kPadKeyIndex).  Two layouts are produced on
+// request: "natural" [slot][d], and "k-packed" [16-slot group][half h][d][8 slots]
+// with slot(group,h,j) = 16 group + 8 (j/4) + 4 h + j%4 -- the order in which a
+// 32x32 MFMA accumulator holds its rows -- so that the operand of a GEMM that
+// contracts over the slots is one 16-byte LDS read per lane.  fp32 inputs only
+// use the natural layout (the fp32 MFMA takes one element per lane).
+//
+// pack_q: for the backward pass, the kept rows of Q and dO in the k-packed
+// layout (contraction over queries), plus per kept row lse * log2(e) and
+// delta = rowsum(dO * O).
+#include "common.h"
+#include "kernels.h"
+
+namespace omni {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// 8 rows x 8 bf16 (one 16-byte chunk per row) -> 8 columns x 8 rows, written as 8 x 16 bytes
+__device__ __forceinline__ void transpose8x8_store(const u32x4 (&in)[8], u16* dst) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    unsigned w[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const unsigned a = in[2 * jj][e >> 1], b = in[2 * jj + 1][e >> 1];
+      const unsigned lo = (e & 1) ? (a >> 16) : (a & 0xffffu);
+      const unsigned hi = (e & 1) ? (b >> 16) : (b & 0xffffu);
+      w[jj] = lo | (hi << 16);
+    }
+    u32x4 o = {w[0], w[1], w[2], w[3]};
+    *reinterpret_cast<u32x4*>(dst + e * 8) = o;
+  }
+}
+
+// grid: (npad/64, BHx)
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void pack_kv_kernel(const T* __restrict__ K, const T* __restrict__ V, Layer L,
+                                                          int per_q_head, const int* __restrict__ src_idx,
+                                                          int idx_stride, const int* __restrict__ budget, int b_cap,
+                                                          int npad, int pad_to, T* __restrict__ Kn, T* __restrict__ Vn,
+                                                          T* __restrict__ Kt, T* __restrict__ Vt,
+                                                          int* __restrict__ kidx) {
+  constexpr bool kBf16 = sizeof(T) == 2;
+  constexpr int E = Elem<T>::kPer16B;
+  constexpr int CPR = D / E;
+  __shared__ int sIdx[kTileN];
+  const int tile = blockIdx.x, bhx = blockIdx.y;
+  const int H = per_q_head ? L.Hq : L.Hkv;
+  const int b = bhx / H, hx = bhx % H;
+  const int g = per_q_head ? hx / L.G : hx;
+  const int nkeys = budget ? min(budget[b], b_cap) : L.N;
+  if (tile * kTileN >= (int)align_up((size_t)max(nkeys, 0), (size_t)pad_to)) return;   // consumers read whole pad_to-slot groups
+  if (threadIdx.x < kTileN) {
+    const int p = tile * kTileN + threadIdx.x;
+    int id = kPadKeyIndex;
+    if (p < nkeys) id = src_idx ? src_idx[(long long)bhx * idx_stride + p] : p;
+    sIdx[threadIdx.x] = id;
+    kidx[(long long)bhx * npad + p] = id;
+  }
+  __syncthreads();
+  const T* kbase = K + b * L.ks[0] + g * L.ks[1];
+  const T* vbase = V + b * L.ks[0] + g * L.ks[1];
+  const long long tile_off = ((long long)bhx * npad + tile * kTileN) * D;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  if (Kn || Vn) {
+    for (int c = threadIdx.x; c < kTileN * CPR; c += kThreads) {
+      const int row = c / CPR, col = (c % CPR) * E;
+      const int id = sIdx[row];
+      if (Kn) {
+        u32x4 v = zero;
+        if (id != kPadKeyIndex) v = *reinterpret_cast<const u32x4*>(kbase + (long long)id * L.ks[2] + col);
+        *reinterpret_cast<u32x4*>(Kn + tile_off + row * D + col) = v;
+      }
+      if (Vn) {
+        u32x4 v = zero;
+        if (id != kPadKeyIndex) v = *reinterpret_cast<const u32x4*>(vbase + (long long)id * L.ks[2] + col);
+        *reinterpret_cast<u32x4*>(Vn + tile_off + row * D + col) = v;
+      }
+    }
+  }
+  if constexpr (kBf16) {
+    // work item = (tensor, 16-slot group, half, 8-wide d chunk): 8x8 transpose in registers
+    constexpr int kItems = (kTileN / 16) * 2 * (D / 8);
+    for (int it0 = threadIdx.x; it0 < 2 * kItems; it0 += kThreads) {
+      const int which = it0 / kItems, it = it0 % kItems;
+      T* dst_t = which ? Vt : Kt;
+      if (!dst_t) continue;
+      const T* src = which ? vbase : kbase;
+      const int dc = it % (D / 8);
+      const int h = (it / (D / 8)) & 1;
+      const int grp = it / (D / 8) / 2;
+      u32x4 in[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int id = sIdx[16 * grp + 8 * (j >> 2) + 4 * h + (j & 3)];
+        in[j] = zero;
+        if (id != kPadKeyIndex) in[j] = *reinterpret_cast<const u32x4*>(src + (long long)id * L.ks[2] + dc * 8);
+      }
+      transpose8x8_store(in, reinterpret_cast<u16*>(dst_t) + tile_off + ((grp * 2 + h) * D + dc * 8) * 8);
+    }
+  }
+}
+
+// grid: (ceil(N/64), B*Hq).  Tile t covers kept positions [64 t, 64 t + 64).
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void pack_q_kernel(const T* __restrict__ Q, const T* __restrict__ O,
+                                                         const T* __restrict__ dO, const float* __restrict__ lse,
+                                                         Layer L, const int* __restrict__ q_idx,
+                                                         const int* __restrict__ q_cnt, int nqpad,
+                                                         T* __restrict__ Qt, T* __restrict__ dOt,
+                                                         float* __restrict__ lse2c, float* __restrict__ deltac) {
+  constexpr bool kBf16 = sizeof(T) == 2;
+  constexpr int E = Elem<T>::kPer16B;
+  constexpr int LPR = D / E;
+  constexpr int RPP = kThreads / LPR;
+  __shared__ int sIdx[64];
+  const int tile = blockIdx.x, bh = blockIdx.y;
+  const int b = bh / L.Hq, i = bh % L.Hq;
+  const int nq = q_cnt[bh];
+  if (tile * 64 >= nq) return;
+  if (threadIdx.x < 64) {
+    const int p = tile * 64 + threadIdx.x;
+    sIdx[threadIdx.x] = p < nq ? q_idx[(long long)bh * L.N + p] : -1;
+  }
+  __syncthreads();
+  const long long head_off = b * L.qs[0] + i * L.qs[1];
+  // delta = rowsum(dO * O), lse in log2 units; rows that contribute nothing get lse = +inf (P = 0)
+  const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
+  for (int rb = 0; rb < 64; rb += RPP) {
+    const int r = rb + r0;
+    const int row = sIdx[r];
+    float dot = 0.f;
+    if (row >= 0) {
+      const u32x4 a = *reinterpret_cast<const u32x4*>(O + head_off + (long long)row * L.qs[2] + c * E);
+      const u32x4 g = *reinterpret_cast<const u32x4*>(dO + head_off + (long long)row * L.qs[2] + c * E);
+      float av[E], gv[E];
+      unpack16(a, av, (const T*)nullptr);
+      unpack16(g, gv, (const T*)nullptr);
+#pragma unroll
+      for (int e = 0; e < E; ++e) dot = fmaf(av[e], gv[e], dot);
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+    if (c == 0) {
+      const long long o = (long long)bh * nqpad + tile * 64 + r;
+      float l2 = INFINITY;
+      if (row >= 0) {
+        const float lv = lse[(long long)bh * L.N + row];
+        l2 = lv == -INFINITY ? INFINITY : lv * kLog2e;
+      }
+      lse2c[o] = l2;
+      deltac[o] = row >= 0 ? dot : 0.f;
+    }
+  }
+  if constexpr (kBf16) {
+    constexpr int kItems = (64 / 16) * 2 * (D / 8);
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    const long long tile_off = ((long long)bh * nqpad + tile * 64) * D;
+    for (int it0 = threadIdx.x; it0 < 2 * kItems; it0 += kThreads) {
+      const int which = it0 / kItems, it = it0 % kItems;
+      const T* src = (which ? dO : Q) + head_off;
+      T* dst_t = which ? dOt : Qt;
+      const int dc = it % (D / 8);
+      const int h = (it / (D / 8)) & 1;
+      const int grp = it / (D / 8) / 2;
+      u32x4 in[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = sIdx[16 * grp + 8 * (j >> 2) + 4 * h + (j & 3)];
+        in[j] = zero;
+        if (row >= 0) in[j] = *reinterpret_cast<const u32x4*>(src + (long long)row * L.qs[2] + dc * 8);
+      }
+      transpose8x8_store(in, reinterpret_cast<u16*>(dst_t) + tile_off + ((grp * 2 + h) * D + dc * 8) * 8);
+    }
+  }
+}
+
+template <typename T, int D>
+int launch_pack_kv(const Layer& L, const void* K, const void* V, int per_q_head, const int* src_idx, int idx_stride,
+                   const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt, void* Vt,
+                   int* kidx, hipStream_t st) {
+  const int heads = per_q_head ? L.Hq : L.Hkv;
+  ProfScope prof__(kProfPack, st);
+  hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kTileN, L.B * heads), dim3(kThreads), 0, st,
+                     static_cast<const T*>(K), static_cast<const T*>(V), L, per_q_head, src_idx, idx_stride, budget,
+                     b_cap, npad, pad_to, static_cast<T*>(Kn), static_cast<T*>(Vn), static_cast<T*>(Kt), static_cast<T*>(Vt),
+                     kidx);
+  OMNI_LAUNCH_CHECK();
+  return OMNI_OK;
+}
+
+template <typename T, int D>
+int launch_pack_q(const Layer& L, const void* Q, const void* O, const void* dO, const float* lse, const int* q_idx,
+                  const int* q_cnt, int nqpad, void* Qt, void* dOt, float* lse2c, float* deltac, hipStream_t st) {
+  hipLaunchKernelGGL((pack_q_kernel<T, D>), dim3(nqpad / 64, L.B * L.Hq), dim3(kThreads), 0, st,
+                     static_cast<const T*>(Q), static_cast<const T*>(O), static_cast<const T*>(dO), lse, L, q_idx,
+                     q_cnt, nqpad, static_cast<T*>(Qt), static_cast<T*>(dOt), lse2c, deltac);
+  OMNI_LAUNCH_CHECK();
+  return OMNI_OK;
+}
+
+}  // namespace
+
+int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per_q_head, const int* src_idx,
+                int idx_stride, const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt,
+                void* Vt, int* kidx, hipStream_t st) {
+  if (dtype == OMNI_BF16) {
+    if (L.D == 128)
+      return launch_pack_kv<u16, 128>(L, K, V, per_q_head, src_idx, idx_stride, budget, b_cap, npad, pad_to, Kn, Vn, Kt,
+                                      Vt, kidx, st);
+    return launch_pack_kv<u16, 64>(L, K, V, per_q_head, src_idx, idx_stride, budget, b_cap, npad, pad_to, Kn, Vn, Kt, Vt,
+                                   kidx, st);
+  }
+  if (L.D == 128)
+    return launch_pack_kv<float, 128>(L, K, V, per_q_head, src_idx, idx_stride, budget, b_cap, npad, pad_to, Kn, Vn,
+                                      nullptr, nullptr, kidx, st);
+  return launch_pack_kv<float, 64>(L, K, V, per_q_head, src_idx, idx_stride, budget, b_cap, npad, pad_to, Kn, Vn,
+                                   nullptr, nullptr, kidx, st);
+}
+
+int run_pack_q(const Layer& L, int dtype, const void* Q, const void* O, const void* dO, const float* lse,
+               const int* q_idx, const int* q_cnt, int nqpad, void* Qt, void* dOt, float* lse2c, float* deltac,
+               hipStream_t st) {
+  if (dtype == OMNI_BF16) {
+    if (L.D == 128) return launch_pack_q<u16, 128>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, lse2c, deltac, st);
+    return launch_pack_q<u16, 64>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, lse2c, deltac, st);
+  }
+  if (L.D == 128) return launch_pack_q<float, 128>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, lse2c, deltac, st);
+  return launch_pack_q<float, 64>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, lse2c, deltac, st);
+}
+
+}  // namespace omni

@@ -344,3 +344,73 @@ def test_free_running_pipeline_matches_oracle_up_to_ties_at_the_cut(cfg):
         assert np.max(np.abs(Og[0, h, rows] - Oo[0, h, rows])) <= TOL_OUT[cfg.dtype]
         compared += 1
     assert compared >= H // 2
+
+
+# ------------------------------------------------------------------ attention backward
+
+def _run_fwd_bwd(c, q_lists, kv_lists, dO_np, desc=None):
+    cfg = c.cfg
+    N = cfg.n_tokens
+    desc = desc or c.desc
+    q_idx, q_cnt = lists_to_padded(q_lists, cfg.n_q_heads, N)
+    b = max(len(x) for x in kv_lists[0])
+    kv_idx, _ = lists_to_padded(kv_lists, cfg.n_q_heads, b)
+    budget = torch.tensor([len(kv_lists[bb][0]) for bb in range(cfg.batch)], dtype=torch.int32, device="cuda")
+    dO = to_device(dO_np, cfg.dtype)
+    O, lse = ob.omni_sparse_attn_fwd(desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, budget, b)
+    dQ, dK, dV = ob.omni_sparse_attn_bwd(desc, c.dQ, c.dK, c.dV, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b)
+    torch.cuda.synchronize()
+    return dQ, dK, dV
+
+
+def _check_grads(cfg, got, want):
+    tol = TOL_OUT[cfg.dtype]
+    for name, g, w in zip(("dQ", "dK", "dV"), got, want):
+        g = to_host(g)
+        err = np.max(np.abs(g - w))
+        assert err <= tol, f"{name}: max abs err {err}"
+        assert np.all(g[w == 0] == 0), f"{name}: rows outside the sets must be exactly zero"
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+def test_sparse_attn_bwd_on_oracle_selection(cfg):
+    c = case_for(cfg)
+    dO = synth.make_grad_output(cfg)
+    kv_lists = [list(c.o_kvidx[b]) for b in range(cfg.batch)]
+    got = _run_fwd_bwd(c, c.o_qidx, kv_lists, dO)
+    want = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+    _check_grads(cfg, got, want)
+    # bitwise reproducible
+    again = _run_fwd_bwd(c, c.o_qidx, kv_lists, dO)
+    for x, y in zip(got, again):
+        assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32_128], ids=lambda c: c.name)
+@pytest.mark.parametrize("causal", [True, False])
+def test_sparse_attn_bwd_full_sets_is_dense_attention_gradient(cfg, causal):
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    desc = ob.make_layer_desc(c.dQ, c.dK, cfg.vis_begin, cfg.vis_end, cfg.sink_index, causal)
+    full = [[np.arange(N, dtype=np.int32) for _ in range(H)] for _ in range(cfg.batch)]
+    dO = synth.make_grad_output(cfg)
+    got = _run_fwd_bwd(c, full, full, dO, desc)
+    want = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO, full, full, causal, cfg.scale)
+    _check_grads(cfg, got, want)
+
+
+@pytest.mark.parametrize("cfg", [CFG_BF16_64, CFG_F32], ids=lambda c: c.name)
+def test_sparse_attn_bwd_edge_sets(cfg):
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    rng = np.random.default_rng(19)
+    dO = synth.make_grad_output(cfg)
+    q_lists = [[np.arange(N, dtype=np.int32)] + [np.sort(rng.choice(N, int(rng.integers(1, 150)), replace=False)).astype(np.int32)
+                                                for _ in range(H - 1)]]
+    q_lists[0][1] = np.arange(0, 5, dtype=np.int32)            # precedes every key of head 1: no gradient at all
+    for b_sel in (1, 64, 129, 200):
+        kv_lists = [[np.sort(rng.choice(np.arange(8, N), b_sel, replace=False)).astype(np.int32) for _ in range(H)]]
+        got = _run_fwd_bwd(c, q_lists, kv_lists, dO)
+        want = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO, q_lists, kv_lists, cfg.causal, cfg.scale)
+        _check_grads(cfg, got, want)
+        assert np.all(to_host(got[0])[0, 1] == 0)
