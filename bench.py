@@ -193,8 +193,150 @@ def main():
         out["speedup_vs_dense"] = round(dense_ms / ms_per_step, 3)
         del Od
         out["cpu_baseline"] = cpu_baseline(cfg, layer, q_lists, kv_lists, valid, ms_per_step)
+        del Q, K, V, O, dev, layer
+        torch.cuda.empty_cache()
+        for name, fn in (("train_step_32k", bench_train), ("decode_131k", bench_decode)):
+            try:
+                t0 = time.time()
+                out[name] = fn(torch, ob, synth)
+                log(f"[bench] {name} done in {time.time() - t0:.1f}s")
+            except Exception as e:      # the headline line must survive a failing extra
+                out[name] = {"error": repr(e)}
 
     print(json.dumps(out), flush=True)
+
+
+def _upload(torch, synth, x):
+    return torch.from_numpy(synth.bf16_bits(x)).view(torch.bfloat16).cuda()
+
+
+def bench_train(torch, ob, synth, steps: int = 5):
+    """Training step of one layer at N=32768: selection recomputed, sparse forward, sparse backward."""
+    cfg = synth.C4_TRAIN_32K
+    layer = synth.make_layer(cfg)
+    Q, K, V = (_upload(torch, synth, layer[k]) for k in "QKV")
+    dO = _upload(torch, synth, synth.make_grad_output(cfg))
+    N, Hq, D = cfg.n_tokens, cfg.n_q_heads, cfg.head_dim
+    desc = ob.make_layer_desc(Q, K, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    f32, i32 = torch.float32, torch.int32
+    probe = torch.empty(1, cfg.n_kv_heads, 2, D, dtype=f32, device="cuda")
+    scores = torch.empty(1, Hq, N, dtype=f32, device="cuda")
+    q_idx = torch.empty(1, Hq, N, dtype=i32, device="cuda")
+    q_cnt = torch.empty(1, Hq, dtype=i32, device="cuda")
+    kv_idx = torch.empty(1, Hq, N, dtype=i32, device="cuda")
+    O, dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    lse = torch.empty(1, Hq, N, dtype=f32, device="cuda")
+    bud = None
+
+    def step():
+        nonlocal bud
+        ob.omni_score_queries(desc, Q, K, probe, scores)
+        ob.omni_select_queries(desc, scores, 0, TAU, q_idx, q_cnt)
+        bud = ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 0, out=bud)
+        ob.omni_select_kv(desc, bud.key_scores, bud.budget, N, kv_idx)
+        ob.omni_sparse_attn_fwd(desc, Q, K, V, q_idx, q_cnt, kv_idx, bud.budget, N, O, lse)
+        ob.omni_sparse_attn_bwd(desc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, bud.budget, N, dQ, dK, dV)
+
+    step()
+    step()
+    torch.cuda.synchronize()
+    ob.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    kern = {}
+    for name in ("attn_fwd", "bwd_dkdv", "bwd_dq", "bwd_reduce", "pack_kv"):
+        t, n = ob.profile_read(name)
+        if n:
+            kern[name] = round(t / n, 4)
+    ob.profile_enable(False)
+    cnt = q_cnt.cpu().numpy()[0]
+    b = int(bud.budget.cpu()[0])
+    qi, ki = q_idx.cpu().numpy()[0], kv_idx.cpu().numpy()[0]
+    valid, _ = pair_counts([qi[h, : cnt[h]] for h in range(Hq)], [ki[h, :b] for h in range(Hq)], cfg.causal)
+    bwd_ms = kern.get("bwd_dkdv", 0) + kern.get("bwd_dq", 0)
+    res = {"workload": f"{cfg.name}: N={N}, bf16, selection + sparse fwd + sparse bwd", "ms_per_step": round(ms, 4),
+           "kernel_ms": kern, "kept_query_fraction": round(float(cnt.sum()) / (Hq * N), 4),
+           "budget_fraction": round(b / N, 4),
+           "bwd_algorithmic_tflops": round(10.0 * D * valid / (bwd_ms * 1e-3) / 1e12, 2) if bwd_ms else None,
+           "bwd_issued_gemm_tflops": round(14.0 * D * valid / (bwd_ms * 1e-3) / 1e12, 2) if bwd_ms else None,
+           "fwd_algorithmic_tflops": round(4.0 * D * valid / (kern["attn_fwd"] * 1e-3) / 1e12, 2)}
+    return res
+
+
+def bench_decode(torch, ob, synth, n_steps: int = 256):
+    """Decode with KV cache slimming on a 131072-token cache, batch 1..8, 256 steps each."""
+    cfg = synth.C5_DECODE_131K
+    layer = synth.make_layer(cfg)
+    Q, K, V = (_upload(torch, synth, layer[k]) for k in "QKV")
+    N, Hq, Hkv, D = cfg.n_tokens, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    desc = ob.make_layer_desc(Q, K, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    probe, _ = ob.omni_score_queries(desc, Q, K)
+    bud = ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 0)
+    b = int(bud.budget.cpu()[0])
+    kv_idx = ob.omni_select_kv(desc, bud.key_scores, bud.budget, b)
+    vis_idx1, vis_cnt1 = ob.omni_visual_subset(desc, kv_idx, bud.budget, b)
+    torch.cuda.synchronize()
+    del Q, bud
+    cap = N + n_steps
+    res = {"workload": f"{cfg.name}: cache {N} tokens + {n_steps} decoded, bf16, tau={TAU}", "budget_fraction": round(b / N, 4),
+           "per_batch": {}}
+    vis_cnt_host = vis_cnt1.cpu().numpy()[0]
+    for B in (1, 2, 4, 8):
+        steps = synth.make_decode_steps(cfg, layer, n_steps, batch=B)
+        q_all = _upload(torch, synth, steps["q"])                      # [S,B,Hq,D]
+        k_new = _upload(torch, synth, steps["k_new"])
+        v_new = _upload(torch, synth, steps["v_new"])
+        Kc = torch.zeros(B, Hkv, cap, D, dtype=torch.bfloat16, device="cuda")
+        Vc = torch.zeros_like(Kc)
+        Kc[:, :, :N] = K
+        Vc[:, :, :N] = V
+        vis_idx = vis_idx1.expand(B, -1, -1).contiguous()
+        vis_cnt = vis_cnt1.expand(B, -1).contiguous()
+        probe_b = probe.expand(B, -1, -1, -1).contiguous()
+        ctx = torch.full((B,), N, dtype=torch.int32, device="cuda")
+        O = torch.empty(B, Hq, D, dtype=torch.bfloat16, device="cuda")
+        act = torch.empty(B, Hq, dtype=torch.uint8, device="cuda")
+        ddesc = ob.make_decode_desc(q_all[0], Kc, cfg.vis_begin, cfg.vis_end, TAU)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        timing = {}
+        for mode in ("slim", "dense"):
+            ctx.fill_(N + 1)
+            for _ in range(3):                                    # untimed warm-up of both entry points
+                ob.omni_slim_decode(ddesc, q_all[0], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
+                ob.omni_dense_decode(ddesc, q_all[0], Kc, Vc, ctx, O)
+            ctx.fill_(N)
+            torch.cuda.synchronize()
+            ev0.record()
+            for s in range(n_steps):
+                Kc[:, :, N + s] = k_new[s]
+                Vc[:, :, N + s] = v_new[s]
+                ctx += 1
+                if mode == "slim":
+                    ob.omni_slim_decode(ddesc, q_all[s], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
+                else:
+                    ob.omni_dense_decode(ddesc, q_all[s], Kc, Vc, ctx, O)
+            ev1.record()
+            torch.cuda.synchronize()
+            timing[mode] = ev0.elapsed_time(ev1) * 1e3 / n_steps          # us per decode step
+        # bytes of K/V rows fetched in the last step (algorithmic): per head its own rows
+        a = act.cpu().numpy()
+        n_text = (N - cfg.vis_end) + cfg.vis_begin + n_steps
+        rows_slim = sum(int(a[bb, h]) * int(vis_cnt_host[h]) + n_text for bb in range(B) for h in range(Hq))
+        rows_dense = B * Hq * (N + n_steps)
+        res["per_batch"][str(B)] = {
+            "slim_us_per_token": round(timing["slim"], 2), "dense_us_per_token": round(timing["dense"], 2),
+            "speedup": round(timing["dense"] / timing["slim"], 3),
+            "active_head_fraction_last_step": round(float(a.mean()), 4),
+            "kv_row_fetches_slim_vs_dense": round(rows_slim / rows_dense, 4),
+            "slim_GBps_row_fetches": round(rows_slim * 2 * D * 2 / (timing["slim"] * 1e-6) / 1e9, 1),
+            "dense_GBps_row_fetches": round(rows_dense * 2 * D * 2 / (timing["dense"] * 1e-6) / 1e9, 1),
+            "dense_GBps_unique_cache": round(B * Hkv * (N + n_steps) * 2 * D * 2 / (timing["dense"] * 1e-6) / 1e9, 1)}
+        del Kc, Vc
+        torch.cuda.empty_cache()
+    return res
 
 
 def cpu_baseline(cfg, layer, q_lists, kv_lists, total_pairs, gpu_ms):

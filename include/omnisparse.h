@@ -275,6 +275,20 @@ size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param);
 int omni_profile_enable(int on);
 int omni_profile_read(int kernel_id, float* total_ms /* host */, int* launches /* host */);
 
+/*
+ * Diagnostic, host only: the work list the query-tile kernels (attention forward,
+ * backward dQ) build on the device, computed by the same code on the host.  Work
+ * item = one 128-row tile of a head's kept queries; items are ordered head by
+ * head, longest tile first, and cut into 8 segments of similar cost (one per
+ * XCD).  All pointers are HOST pointers.  q_cnt [batch * n_q_heads] (null: every
+ * head keeps n_tokens rows), budget [batch] (null: n_tokens), seg_begin [9] out,
+ * item_head / item_tile [capacity] out, n_items out.  OMNI_ERR_WORKSPACE if
+ * capacity is too small (n_items is still written).
+ */
+int omni_debug_work_list(const omni_layer_desc* desc, const int32_t* q_cnt, const int32_t* budget,
+                         int32_t b_cap, int32_t* seg_begin, int32_t* item_head, int32_t* item_tile,
+                         int32_t capacity, int32_t* n_items);
+
 /* Message of the last error on this thread ("" if none). */
 const char* omni_last_error(void);
 

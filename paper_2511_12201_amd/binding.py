@@ -24,7 +24,7 @@ EXPORTED = [
     "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
     "omni_sparse_attn_fwd", "omni_sparse_attn_bwd", "omni_slim_decode", "omni_visual_subset",
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
-    "omni_profile_enable", "omni_profile_read",
+    "omni_profile_enable", "omni_profile_read", "omni_debug_work_list",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -84,6 +84,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_profile_enable.argtypes = [C.c_int]
+    lib.omni_debug_work_list.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp]
     lib.omni_profile_read.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
     for name in EXPORTED:
         fn = getattr(lib, name)
@@ -148,6 +149,23 @@ def make_decode_desc(q: torch.Tensor, Kcache: torch.Tensor, vis_begin: int, vis_
     d.tau = tau
     d.kv_stride = (C.c_int64 * 3)(*Kcache.stride()[:3])
     return d
+
+
+def debug_work_list(desc: LayerDesc, q_cnt=None, budget=None, b_cap: int = 1):
+    """Host mirror of the device work list: (seg_begin[9], item_head[n], item_tile[n]) as numpy arrays."""
+    import numpy as np
+    lib = load_library()
+    cap = desc.batch * desc.n_q_heads * ((desc.n_tokens + 127) // 128)
+    seg = np.zeros(9, dtype=np.int32)
+    head = np.zeros(cap, dtype=np.int32)
+    tile = np.zeros(cap, dtype=np.int32)
+    n = C.c_int32(0)
+    qc = None if q_cnt is None else np.ascontiguousarray(q_cnt, dtype=np.int32)
+    bd = None if budget is None else np.ascontiguousarray(budget, dtype=np.int32)
+    _check(lib.omni_debug_work_list(C.byref(desc), None if qc is None else qc.ctypes.data,
+                                    None if bd is None else bd.ctypes.data, b_cap, seg.ctypes.data,
+                                    head.ctypes.data, tile.ctypes.data, cap, C.byref(n)))
+    return seg, head[: n.value], tile[: n.value]
 
 
 def profile_enable(on: bool):

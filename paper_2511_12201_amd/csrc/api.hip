@@ -4,9 +4,11 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "common.h"
 #include "kernels.h"
+#include "sched.h"
 
 namespace omni {
 
@@ -149,6 +151,29 @@ using namespace omni;
 extern "C" {
 
 const char* omni_last_error(void) { return g_err; }
+
+int omni_debug_work_list(const omni_layer_desc* desc, const int32_t* q_cnt, const int32_t* budget, int32_t b_cap,
+                         int32_t* seg_begin, int32_t* item_head, int32_t* item_tile, int32_t capacity,
+                         int32_t* n_items) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(seg_begin); REQUIRE_PTR(item_head); REQUIRE_PTR(item_tile); REQUIRE_PTR(n_items);
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  const int BH = desc->batch * desc->n_q_heads;
+  std::vector<int> sched(sched_ints(BH));
+  sched_build(q_cnt, budget, desc->batch, desc->n_q_heads, desc->n_tokens, b_cap, desc->causal, sched.data());
+  const int items = sched[kSchedTotal];
+  *n_items = items;
+  for (int x = 0; x <= kNumXcd; ++x) seg_begin[x] = sched[kSchedSeg + x];
+  if (items > capacity) OMNI_FAIL(OMNI_ERR_WORKSPACE, "work list has %d items, capacity is %d", items, capacity);
+  for (int it = 0; it < items; ++it) {
+    int bh, tq;
+    sched_decode(sched.data(), BH, it, bh, tq);
+    item_head[it] = bh;
+    item_tile[it] = tq;
+  }
+  return OMNI_OK;
+}
 
 int omni_profile_enable(int on) {
   clear_error();

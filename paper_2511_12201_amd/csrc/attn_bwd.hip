@@ -21,6 +21,7 @@
 // fp32 inputs run the same kernels on the fp32 32x32x2 MFMA with natural layouts.
 #include "common.h"
 #include "kernels.h"
+#include "sched.h"
 
 namespace omni {
 
@@ -50,6 +51,7 @@ struct BwdParams {
   float* dKp;           // [B*Hq, npad, D] fp32 per-query-head partial gradients
   float* dVp;
   void* dQ;
+  int* sched;           // work list of the dQ kernel (sched.h)
 };
 
 // first position in ascending a[0,n) with a[pos] >= v
@@ -339,7 +341,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(BwdParams p)
 // ------------------------------------------------------------------ dQ
 
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p, int ntile_q) {
+__global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p) {
   constexpr bool kBf16 = sizeof(T) == 2;
   constexpr int LD = D + 8;
   constexpr int NBUF = kBf16 ? 2 : 1;
@@ -351,18 +353,26 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p, i
   __shared__ __attribute__((aligned(16))) int sIdx[NBUF][kTileN];
   __shared__ int sBound[2];
 
+  __shared__ int sItem;
   const Layer& L = p.L;
   const int BH = L.B * L.Hq;
-  const int bh = blockIdx.x % BH;
-  const int tq = ntile_q - 1 - blockIdx.x / BH;
+  const int xcd = xcc_id();
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int ln = lane & 31, h = lane >> 5;
+
+  for (;;) {                                 // persistent: one (head, query tile) per iteration
+  __syncthreads();
+  if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
+  __syncthreads();
+  const int item = sItem;
+  if (item < 0) break;
+  int bh, tq;
+  sched_decode(p.sched, BH, item, bh, tq);
   const int b = bh / L.Hq, i = bh % L.Hq;
   const int nq = p.q_cnt[bh];
-  if (tq * kTileM >= nq) return;
   const int nkeys = min(p.budget[b], p.b_cap);
   const int* kidx = p.kidx + (long long)bh * p.npad;
   const int* qlist = p.q_idx + (long long)bh * L.N;
-  const int lane = lane_id(), wave = threadIdx.x >> 6;
-  const int ln = lane & 31, h = lane >> 5;
 
   const int pos_first = tq * kTileM, pos_last = min(pos_first + kTileM, nq) - 1;
   if (threadIdx.x == 0 || threadIdx.x == 64) {
@@ -548,6 +558,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p, i
         }
       }
   }
+  }  // work-item loop
 }
 
 // ------------------------------------------------------------------ dK, dV = sum over the heads of a KV group
@@ -610,6 +621,7 @@ struct BwdWs {
   void *Kn, *Vn, *Kt, *Qt, *dOt;
   int* kidx;
   float *lse2c, *deltac, *dKp, *dVp;
+  int* sched;
 };
 
 BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
@@ -627,6 +639,7 @@ BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   w.deltac = a.take<float>(qrows);
   w.dKp = a.take<float>(krows * L.D);
   w.dVp = a.take<float>(krows * L.D);
+  w.sched = a.take<int>(sched_ints(L.B * L.Hq));
   return w;
 }
 
@@ -671,6 +684,9 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.dKp = w.dKp;
   p.dVp = w.dVp;
   p.dQ = dQ;
+  p.sched = w.sched;
+  rc = run_schedule(L, q_cnt, budget, b_cap, w.sched, st);
+  if (rc != OMNI_OK) return rc;
   {
     ProfScope prof__(kProfBwdDkDv, st);
     hipLaunchKernelGGL((attn_bwd_dkdv_kernel<T, D>), dim3(npad / kBwdKeys, L.B * L.Hq), dim3(kThreads), 0, st, p);
@@ -678,8 +694,7 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   }
   {
     ProfScope prof__(kProfBwdDq, st);
-    const int ntile_q = cdiv(L.N, kTileM);
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<T, D>), dim3(ntile_q * L.B * L.Hq), dim3(kThreads), 0, st, p, ntile_q);
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<T, D>), dim3(persistent_grid() / 2), dim3(kThreads), 0, st, p);
     OMNI_LAUNCH_CHECK();
   }
   {

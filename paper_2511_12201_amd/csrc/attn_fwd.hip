@@ -21,6 +21,7 @@
 //  * fp32 inputs take the same path with the fp32 32x32x2 MFMA (accuracy path).
 #include "common.h"
 #include "kernels.h"
+#include "sched.h"
 
 namespace omni {
 
@@ -63,7 +64,7 @@ struct FwdParams {
   int npad;
   int per_q_head;       // packed buffers per query head (sparse) or per KV head (dense)
   int identity_keys;    // kidx[p] == p: causal bounds by arithmetic
-  int ntile_q;          // ceil(N / kTileM)
+  int* sched;           // work list (sched.h)
 };
 
 // number of entries <= v in ascending a[0,n)
@@ -89,20 +90,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
   __shared__ __attribute__((aligned(16))) int sIdx[NBUF][kTileN];
   __shared__ int sBound[2];
 
+  __shared__ int sItem;
   const Layer& L = p.L;
   const int BH = L.B * L.Hq;
-  const int bh = blockIdx.x % BH;
-  const int tq = p.ntile_q - 1 - blockIdx.x / BH;    // long (late) tiles are scheduled first
+  const int xcd = xcc_id();
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int ln = lane & 31, h = lane >> 5;
+  const float c2 = L.scale * kLog2e;
+
+  for (;;) {                                 // persistent: one work item (head, query tile) per iteration
+  __syncthreads();                           // LDS of the previous item is no longer read
+  if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
+  __syncthreads();
+  const int item = sItem;
+  if (item < 0) break;
+  int bh, tq;
+  sched_decode(p.sched, BH, item, bh, tq);
   const int b = bh / L.Hq, i = bh % L.Hq, g = i / L.G;
   const int nq = p.q_cnt ? p.q_cnt[bh] : L.N;
-  if (tq * kTileM >= nq) return;
   const int nkeys = p.budget ? min(p.budget[b], p.b_cap) : L.N;
   const int bhx = p.per_q_head ? bh : b * L.Hkv + g;
   const int* kidx = p.kidx + (long long)bhx * p.npad;
   const int* qlist = p.q_idx ? p.q_idx + (long long)bh * L.N : nullptr;
-
-  const int lane = lane_id(), wave = threadIdx.x >> 6;
-  const int ln = lane & 31, h = lane >> 5;
 
   // ---- key range of this query tile
   const int pos_first = tq * kTileM, pos_last = min(pos_first + kTileM, nq) - 1;
@@ -144,7 +153,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
-  const float c2 = L.scale * kLog2e;
 
   // ---- tile staging
   constexpr int E = Elem<T>::kPer16B;
@@ -319,12 +327,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
     if (h == 0)
       p.lse[(long long)bh * L.N + qrow] = l_tot > 0.f ? (m_run * c2 + log2f(l_tot)) * kLn2 : -INFINITY;
   }
+  }  // work-item loop
 }
 
 struct FwdWs {
   void* Kp;
   void* Vp;
   int* kidx;
+  int* sched;
 };
 
 FwdWs carve_fwd(Arena& a, const Layer& L, int dtype, int heads, int npad) {
@@ -334,6 +344,7 @@ FwdWs carve_fwd(Arena& a, const Layer& L, int dtype, int heads, int npad) {
   w.Kp = a.take<unsigned char>(rows * L.D * es);
   w.Vp = a.take<unsigned char>(rows * L.D * es);
   w.kidx = a.take<int>(rows);
+  w.sched = a.take<int>(sched_ints(L.B * L.Hq));
   return w;
 }
 
@@ -375,10 +386,14 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.npad = npad;
   p.per_q_head = sparse ? 1 : 0;
   p.identity_keys = sparse ? 0 : 1;
-  p.ntile_q = cdiv(L.N, kTileM);
+  p.sched = w.sched;
+  {
+    int rc = run_schedule(L, q_cnt, budget, b_cap, w.sched, st);
+    if (rc != OMNI_OK) return rc;
+  }
   {
     ProfScope prof__(kProfAttnFwd, st);
-    hipLaunchKernelGGL((attn_fwd_kernel<T, D>), dim3(p.ntile_q * L.B * L.Hq), dim3(kThreads), 0, st, p);
+    hipLaunchKernelGGL((attn_fwd_kernel<T, D>), dim3(persistent_grid()), dim3(kThreads), 0, st, p);
     OMNI_LAUNCH_CHECK();
   }
   return OMNI_OK;

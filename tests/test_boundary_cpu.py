@@ -110,3 +110,29 @@ def test_argument_errors(lib):
     # a successful validation path clears the message
     assert ob.workspace_bytes(ob.CALL_SELECT_KV, d) > 0
     assert ob.last_error() == ""
+
+
+@pytest.mark.parametrize("q_cnt,budget,n_heads,n_tokens,causal", [
+    ([1859, 500, 300, 0, 20, 129, 128, 1], [700], 8, 1859, 1),
+    (None, None, 8, 1859, 1),
+    ([65536] + [17000 + 13 * i for i in range(27)], [35000], 28, 65536, 1),
+    ([0, 0, 5, 0], [3], 4, 537, 0),
+    ([0, 0, 0, 0], [3], 4, 537, 1),
+])
+def test_device_work_list_covers_every_query_tile_exactly_once(lib, q_cnt, budget, n_heads, n_tokens, causal):
+    import numpy as np
+    d = _desc(n_q_heads=n_heads, n_kv_heads=n_heads, n_tokens=n_tokens, vis_end=min(256, n_tokens), causal=causal)
+    seg, head, tile = ob.debug_work_list(d, q_cnt, budget, n_tokens)
+    counts = q_cnt if q_cnt is not None else [n_tokens] * n_heads
+    want = {(h, t) for h in range(n_heads) for t in range((counts[h] + 127) // 128)}
+    got = list(zip(head.tolist(), tile.tolist()))
+    assert len(got) == len(want) and set(got) == want
+    assert seg[0] == 0 and seg[8] == len(got) and np.all(np.diff(seg) >= 0)
+    # heads in order, tiles of a head from the last (longest under the causal mask) to the first
+    for a, b in zip(got, got[1:]):
+        assert b[0] > a[0] or (b[0] == a[0] and b[1] == a[1] - 1)
+    if len(got) >= 64 and causal:
+        # segments carry similar numbers of keys to visit
+        cost = np.array([(t + 1) / ((counts[h] + 127) // 128) for h, t in got])
+        per_seg = np.array([cost[seg[x]:seg[x + 1]].sum() for x in range(8)])
+        assert per_seg.max() <= 1.25 * per_seg.mean() + 2
