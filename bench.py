@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3_64k", choices=["c3_64k", "c2_16k"])
     ap.add_argument("--no-extras", action="store_true", help="skip dense baseline / oracle timing")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known HBM traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (the path is a single-GPU kernel library); "
@@ -106,6 +108,12 @@ def main():
         selection()
         ob.omni_sparse_attn_fwd(desc, Q, K, V, q_idx, q_cnt, kv_idx, bud.budget, b_cap, O, lse)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -260,7 +260,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(BwdParams p)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = q4 * 4 + e;
-          float pv = exp2f(fmaf(s[r], c2, -l4[e]));
+          float pv = fast_exp2(fmaf(s[r], c2, -l4[e]));
           if (masked) {
             const int qcmp = L.causal ? qi4[e] : kPadKeyIndex - 1;
             if (my_kidx > qcmp) pv = 0.f;
@@ -488,7 +488,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = q4 * 4 + e;
-          float pv = exp2f(fmaf(s[kb][r], c2, -lse2));
+          float pv = fast_exp2(fmaf(s[kb][r], c2, -lse2));
           if (masked && id[e] > qcmp) pv = 0.f;
           dp[kb][r] = pv * (dp[kb][r] - delta);
         }

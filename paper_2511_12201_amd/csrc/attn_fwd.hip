@@ -229,11 +229,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[kb][r]);
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    mloc = pair_max(mloc);
     const float m_new = fmaxf(m_run, mloc);
     const float m_ref = m_new == -INFINITY ? 0.f : m_new;
     if (__any(m_new > m_run)) {
-      const float alpha = exp2f((m_run - m_ref) * c2);
+      const float alpha = fast_exp2((m_run - m_ref) * c2);
       l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float pv = exp2f(fmaf(s[kb][r], c2, -mc));
+        const float pv = fast_exp2(fmaf(s[kb][r], c2, -mc));
         s[kb][r] = pv;
         lsum += pv;
       }
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
   }
 
   // ---- epilogue
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = pair_sum(l_run);
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   if (qvalid) {
     T* optr = static_cast<T*>(p.O) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];

@@ -28,7 +28,14 @@ __device__ __forceinline__ unsigned long long to_fixed(float a) {
   return a > 0.f ? (unsigned long long)((double)a * kFixScale) : 0ull;
 }
 
+constexpr int kRep = 32;     // replicas per histogram bin
+
 struct RadixShared {
+  // Every bin is replicated kRep times and a lane updates replica lane % kRep, so the lanes of one
+  // LDS atomic never collide on an address (scores cluster in a few exponent bins, which would
+  // otherwise serialise 64 ways) and each replica row maps to distinct banks.
+  unsigned rcnt[256 * kRep];
+  unsigned long long rsum[256 * kRep];
   unsigned cnt[256];
   unsigned long long sum[256];
   unsigned prefix, mask;
@@ -42,22 +49,81 @@ struct RadixShared {
 // among elements of x[lo,hi) whose key matches (prefix, mask).
 __device__ __forceinline__ void radix_histogram(const float* __restrict__ x, int lo, int hi, int shift,
                                                 RadixShared& sh, bool with_sum) {
-  for (int t = threadIdx.x; t < 256; t += blockDim.x) {
-    sh.cnt[t] = 0;
-    sh.sum[t] = 0;
+  for (int t = threadIdx.x; t < 256 * kRep; t += blockDim.x) {
+    sh.rcnt[t] = 0;
+    if (with_sum) sh.rsum[t] = 0;
   }
   __syncthreads();
   const unsigned prefix = sh.prefix, mask = sh.mask;
+  const int rep = threadIdx.x & (kRep - 1);
   for (int n = lo + threadIdx.x; n < hi; n += blockDim.x) {
     const float v = x[n];
     const unsigned key = float_key(v);
     if ((key & mask) == prefix) {
       const unsigned d = (key >> shift) & 255u;
-      atomicAdd(&sh.cnt[d], 1u);
-      if (with_sum) atomicAdd(&sh.sum[d], to_fixed(v));
+      atomicAdd(&sh.rcnt[d * kRep + rep], 1u);
+      if (with_sum) atomicAdd(&sh.rsum[d * kRep + rep], to_fixed(v));
     }
   }
   __syncthreads();
+  if (threadIdx.x < 256) {
+    unsigned c = 0;
+    unsigned long long m = 0;
+    for (int r = 0; r < kRep; ++r) {
+      const int o = threadIdx.x * kRep + ((r + threadIdx.x) & (kRep - 1));   // rotate: spread banks across lanes
+      c += sh.rcnt[o];
+      if (with_sum) m += sh.rsum[o];
+    }
+    sh.cnt[threadIdx.x] = c;
+    sh.sum[threadIdx.x] = m;
+  }
+  __syncthreads();
+}
+
+// Run by the first wavefront after a histogram pass.  Walks the 256 bins from the top and finds the
+// first bin at which the running total (of counts, or of fixed-point mass when by_sum) reaches
+// sh.remaining; updates prefix / mask / remaining / cnt_above / sum_above.  Returns false (all lanes)
+// when even the whole histogram falls short.  Each lane owns 4 consecutive bins; totals are combined
+// with a wavefront prefix scan.
+__device__ __forceinline__ bool radix_pick_bin(RadixShared& sh, int shift, bool by_sum) {
+  const int lane = threadIdx.x;
+  const int base = 255 - 4 * lane;
+  unsigned long long c[4], m[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    c[j] = sh.cnt[base - j];
+    m[j] = sh.sum[base - j];
+  }
+  const unsigned long long ctot = c[0] + c[1] + c[2] + c[3], mtot = m[0] + m[1] + m[2] + m[3];
+  unsigned long long cs = ctot, ms = mtot;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned long long tc = __shfl_up(cs, o, 64), tm = __shfl_up(ms, o, 64);
+    if (lane >= o) {
+      cs += tc;
+      ms += tm;
+    }
+  }
+  const long long rem = sh.remaining;
+  const bool cross = (long long)(by_sum ? ms : cs) >= rem;
+  const unsigned long long hit = __ballot(cross);
+  if (hit == 0) return false;
+  const int leader = __ffsll((long long)hit) - 1;
+  if (lane == leader) {
+    unsigned long long cb = cs - ctot, mb = ms - mtot;      // totals of the bins above this lane's
+    int j = 0;
+    for (; j < 3; ++j) {
+      if ((long long)((by_sum ? mb + m[j] : cb + c[j])) >= rem) break;
+      cb += c[j];
+      mb += m[j];
+    }
+    sh.remaining = rem - (long long)(by_sum ? mb : cb);
+    sh.cnt_above += cb;
+    sh.sum_above += mb;
+    sh.prefix |= (unsigned)(base - j) << shift;
+    sh.mask |= 255u << shift;
+  }
+  return true;
 }
 
 // k-th largest element of x[lo,hi): writes its key, the number of elements that
@@ -73,7 +139,8 @@ __device__ void radix_select_block(const float* __restrict__ x, int lo, int hi, 
       __syncthreads();
       unsigned long long local = 0;
       for (int j = lo + threadIdx.x; j < hi; j += blockDim.x) local += to_fixed(x[j]);
-      atomicAdd(&sh.sum_above, local);
+      local = wave_sum(local);
+      if (lane_id() == 0) atomicAdd(&sh.sum_above, local);
       __syncthreads();
       total = sh.sum_above;
     }
@@ -96,19 +163,7 @@ __device__ void radix_select_block(const float* __restrict__ x, int lo, int hi, 
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     radix_histogram(x, lo, hi, shift, sh, with_sum);
-    if (threadIdx.x == 0) {
-      long long rem = sh.remaining;
-      int d = 255;
-      for (; d > 0; --d) {
-        if ((long long)sh.cnt[d] >= rem) break;
-        rem -= sh.cnt[d];
-        sh.cnt_above += sh.cnt[d];
-        sh.sum_above += sh.sum[d];
-      }
-      sh.remaining = rem;
-      sh.prefix |= (unsigned)d << shift;
-      sh.mask |= 255u << shift;
-    }
+    if (threadIdx.x < 64) radix_pick_bin(sh, shift, false);     // k <= matching count: always found
     __syncthreads();
   }
   if (threadIdx.x == 0) {
@@ -138,26 +193,11 @@ __device__ int radix_budget_block(const float* __restrict__ x, int n, unsigned l
   __syncthreads();
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
+    if (sh.done) break;                   // uniform: written before the barrier below
     radix_histogram(x, 0, n, shift, sh, true);
-    if (threadIdx.x == 0 && !sh.done) {
-      long long rem = sh.remaining;
-      int d = 255;
-      bool found = false;
-      for (; d >= 0; --d) {
-        if (sh.cnt[d] && (long long)sh.sum[d] >= rem) {
-          found = true;
-          break;
-        }
-        rem -= (long long)sh.sum[d];
-        sh.cnt_above += sh.cnt[d];
-      }
-      if (!found) {
-        sh.done = 1;          // the matching elements do not reach the target: take them all
-      } else {
-        sh.remaining = rem;
-        sh.prefix |= (unsigned)d << shift;
-        sh.mask |= 255u << shift;
-      }
+    if (threadIdx.x < 64) {
+      const bool found = radix_pick_bin(sh, shift, true);
+      if (!found && threadIdx.x == 0) sh.done = 1;   // even all matching elements fall short: take everything
     }
     __syncthreads();
   }
