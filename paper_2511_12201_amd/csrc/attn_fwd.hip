@@ -163,45 +163,68 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
   u32x4 stK[kChunks], stV[kChunks];
   i32x4 stI;
 
-  auto load_tile = [&](int t) {
+  auto load_k = [&](int t) {
     const T* ks = kp + (long long)t * kTileN * D;
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) stK[c] = *reinterpret_cast<const u32x4*>(ks + (threadIdx.x + c * kThreads) * E);
+  };
+  auto load_v = [&](int t) {
     const T* vs = vp + (long long)t * kTileN * D;
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) stV[c] = *reinterpret_cast<const u32x4*>(vs + (threadIdx.x + c * kThreads) * E);
+    if (threadIdx.x < kTileN / 4) stI = *reinterpret_cast<const i32x4*>(kidx + t * kTileN + threadIdx.x * 4);
+  };
+  auto store_k = [&](int buf) {
+    T* sk = reinterpret_cast<T*>(sK_raw + buf * kKBytes);
 #pragma unroll
     for (int c = 0; c < kChunks; ++c) {
       const int ch = threadIdx.x + c * kThreads;
-      stK[c] = *reinterpret_cast<const u32x4*>(ks + ch * E);
-      stV[c] = *reinterpret_cast<const u32x4*>(vs + ch * E);
+      *reinterpret_cast<u32x4*>(sk + (ch / CPR) * KLD + (ch % CPR) * E) = stK[c];
     }
-    if (threadIdx.x < kTileN / 4) stI = *reinterpret_cast<const i32x4*>(kidx + t * kTileN + threadIdx.x * 4);
   };
-  auto store_tile = [&](int buf) {
-    T* sk = reinterpret_cast<T*>(sK_raw + buf * kKBytes);
+  auto store_v = [&](int buf) {          // the slot indices travel with the V tile
     T* sv = reinterpret_cast<T*>(sV_raw + buf * kVBytes);
 #pragma unroll
     for (int c = 0; c < kChunks; ++c) {
       const int ch = threadIdx.x + c * kThreads;
-      const int row = ch / CPR, col = (ch % CPR) * E;
-      *reinterpret_cast<u32x4*>(sk + row * KLD + col) = stK[c];
       if constexpr (kBf16) *reinterpret_cast<u32x4*>(sv + ch * E) = stV[c];
-      else *reinterpret_cast<u32x4*>(sv + row * VLD + col) = stV[c];
+      else *reinterpret_cast<u32x4*>(sv + (ch / CPR) * VLD + (ch % CPR) * E) = stV[c];
     }
     if (threadIdx.x < kTileN / 4) *reinterpret_cast<i32x4*>(&sIdx[buf][threadIdx.x * 4]) = stI;
   };
 
-  auto compute_tile = [&](int buf, bool masked) {
+  // S^T tile = K tile . Q^T (64 keys x 32 queries per wavefront)
+  auto qk_tile = [&](int buf, f32x16 (&s)[2]) {
     const T* sk = reinterpret_cast<const T*>(sK_raw + buf * kKBytes);
-    const T* sv = reinterpret_cast<const T*>(sV_raw + buf * kVBytes);
-    f32x16 s[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
       if constexpr (kBf16) {
+        // LDS fragment reads are issued one group of 4 ahead of the MFMAs that consume them; the
+        // scheduling fences keep the compiler from pulling each read back next to its MFMA
+        // (which would expose the full LDS latency 16 times per tile).
+        constexpr int NG = D / 64;          // groups of 4 k-steps
+        bf16x8 ka[4], kb4[4];
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + ln) * KLD + ks * 16 + h * 8);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf16[ks], s[kb], 0, 0, 0);
+        for (int j = 0; j < 4; ++j)
+          ka[j] = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + ln) * KLD + j * 16 + h * 8);
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+          __builtin_amdgcn_sched_barrier(0);
+          if (gi + 1 < NG) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              kb4[j] = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + ln) * KLD + ((gi + 1) * 4 + j) * 16 + h * 8);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qf16[gi * 4 + j], s[kb], 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) ka[j] = kb4[j];
         }
+        __builtin_amdgcn_sched_barrier(0);
       } else {
 #pragma unroll
         for (int ks = 0; ks < D / 8; ++ks) {
@@ -212,6 +235,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
         }
       }
     }
+  };
+
+  // mask + online softmax on a finished S^T tile; leaves P in s
+  auto softmax_tile = [&](int buf, bool masked, f32x16 (&s)[2]) {
     if (masked) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -223,7 +250,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
             if (id[e] > qcmp) s[kb][q4 * 4 + e] = -INFINITY;
         }
     }
-    // online softmax; this lane and lane^32 share the query row
+    // this lane and lane^32 share the query row
     float mloc = s[0][0];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -252,19 +279,37 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
         lsum += pv;
       }
     l_run += lsum;
+  };
+
+  // O^T += V^T . P^T
+  auto pv_tile = [&](int buf, const f32x16 (&s)[2]) {
+    const T* sv = reinterpret_cast<const T*>(sV_raw + buf * kVBytes);
     if constexpr (kBf16) {
+      constexpr int NB = D / 32;
+      bf16x8 va[NB], vb[NB];
+#pragma unroll
+      for (int db = 0; db < NB; ++db)
+        va[db] = *reinterpret_cast<const bf16x8*>(sv + ((0 * 2 + h) * D + db * 32 + ln) * 8);
 #pragma unroll
       for (int t16 = 0; t16 < 4; ++t16) {
         const int kb = t16 >> 1, r0 = (t16 & 1) * 8;
+        __builtin_amdgcn_sched_barrier(0);
+        if (t16 + 1 < 4) {
+#pragma unroll
+          for (int db = 0; db < NB; ++db)
+            vb[db] = *reinterpret_cast<const bf16x8*>(sv + (((t16 + 1) * 2 + h) * D + db * 32 + ln) * 8);
+        }
         union { bf16x8 v; unsigned u[4]; } pf;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) pf.u[jj] = pack_bf16x2(s[kb][r0 + 2 * jj], s[kb][r0 + 2 * jj + 1]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + ((t16 * 2 + h) * D + db * 32 + ln) * 8);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, o[db], 0, 0, 0);
-        }
+        for (int db = 0; db < NB; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], pf.v, o[db], 0, 0, 0);
+#pragma unroll
+        for (int db = 0; db < NB; ++db) va[db] = vb[db];
       }
+      __builtin_amdgcn_sched_barrier(0);
     } else {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -282,22 +327,38 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
 
   if (ntiles > 0) {
     if constexpr (kBf16) {
-      load_tile(0);
-      store_tile(0);
+      f32x16 s[2];
+      load_k(0);
+      load_v(0);
+      store_k(0);
+      store_v(0);
       __syncthreads();
       for (int t = 0; t < ntiles; ++t) {
-        if (t + 1 < ntiles) load_tile(t + 1);
-        compute_tile(t & 1, t >= n_full_tiles);
-        if (t + 1 < ntiles) store_tile((t + 1) & 1);
+        if (t + 1 < ntiles) {
+          load_k(t + 1);
+          load_v(t + 1);
+        }
+        qk_tile(t & 1, s);
+        softmax_tile(t & 1, t >= n_full_tiles, s);
+        pv_tile(t & 1, s);
+        if (t + 1 < ntiles) {
+          store_k((t + 1) & 1);
+          store_v((t + 1) & 1);
+        }
         __syncthreads();
       }
     } else {
+      f32x16 s[2];
       for (int t = 0; t < ntiles; ++t) {
         __syncthreads();
-        load_tile(t);
-        store_tile(0);
+        load_k(t);
+        load_v(t);
+        store_k(0);
+        store_v(0);
         __syncthreads();
-        compute_tile(0, t >= n_full_tiles);
+        qk_tile(0, s);
+        softmax_tile(0, t >= n_full_tiles, s);
+        pv_tile(0, s);
       }
     }
   }
