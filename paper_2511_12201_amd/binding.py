@@ -84,7 +84,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_profile_enable.argtypes = [C.c_int]
-    lib.omni_debug_work_list.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp]
+    lib.omni_debug_work_list.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, i32, vp]
     lib.omni_profile_read.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
     for name in EXPORTED:
         fn = getattr(lib, name)
@@ -151,7 +151,7 @@ def make_decode_desc(q: torch.Tensor, Kcache: torch.Tensor, vis_begin: int, vis_
     return d
 
 
-def debug_work_list(desc: LayerDesc, q_cnt=None, budget=None, b_cap: int = 1):
+def debug_work_list(desc: LayerDesc, q_cnt=None, budget=None, b_cap: int = 1, tile_rows: int = 128):
     """Host mirror of the device work list: (seg_begin[9], item_head[n], item_tile[n]) as numpy arrays."""
     import numpy as np
     lib = load_library()
@@ -163,7 +163,7 @@ def debug_work_list(desc: LayerDesc, q_cnt=None, budget=None, b_cap: int = 1):
     qc = None if q_cnt is None else np.ascontiguousarray(q_cnt, dtype=np.int32)
     bd = None if budget is None else np.ascontiguousarray(budget, dtype=np.int32)
     _check(lib.omni_debug_work_list(C.byref(desc), None if qc is None else qc.ctypes.data,
-                                    None if bd is None else bd.ctypes.data, b_cap, seg.ctypes.data,
+                                    None if bd is None else bd.ctypes.data, b_cap, tile_rows, seg.ctypes.data,
                                     head.ctypes.data, tile.ctypes.data, cap, C.byref(n)))
     return seg, head[: n.value], tile[: n.value]
 

@@ -685,7 +685,7 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.dVp = w.dVp;
   p.dQ = dQ;
   p.sched = w.sched;
-  rc = run_schedule(L, q_cnt, budget, b_cap, w.sched, st);
+  rc = run_schedule(L, q_cnt, budget, b_cap, kTileM, w.sched, st);
   if (rc != OMNI_OK) return rc;
   {
     ProfScope prof__(kProfBwdDkDv, st);

@@ -19,6 +19,7 @@
 //  * 256 threads = 4 wavefronts x 32 query rows; 64-key K/V tiles are double
 //    buffered in LDS, one barrier per tile; two workgroups fit a CU.
 //  * fp32 inputs take the same path with the fp32 32x32x2 MFMA (accuracy path).
+
 #include "common.h"
 #include "kernels.h"
 #include "sched.h"
@@ -391,6 +392,296 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
   }  // work-item loop
 }
 
+// ------------------------------------------------------------------ bf16 fast path
+//
+// 512 threads = 8 wavefronts x 32 query rows (256-row work items, one workgroup per CU).
+// K/V tiles go from global memory straight into LDS (global_load_lds, no VGPR staging) into a
+// ring of kStages buffers, so up to kStages - 1 tiles are in flight while one is computed and a
+// single barrier per tile is enough.  The loads are inline assembly with hand-placed
+// s_waitcnt vmcnt(n): the compiler would wait for *every* outstanding LDS-DMA load before the
+// first LDS read, which collapses the ring to one tile of prefetch.
+// A wavefront's LDS-DMA instruction writes 64 x 16 contiguous bytes, so the K tile cannot be
+// row-padded; it is stored unpadded with an XOR swizzle of the 16-byte chunk index
+// (chunk ^ row % chunks_per_row), applied on the global-address side of the copy, which keeps
+// the 16 rows a ds_read_b128 touches on distinct banks.  V is already in operand order.
+
+constexpr int kFastWaves = 8;
+constexpr int kFastThreads = kFastWaves * 64;
+constexpr int kFastTileM = kFastWaves * 32;
+constexpr int kStages = 4;
+
+// 16 bytes per lane, global -> LDS at lds_addr + lane * 16 (lds_addr wave-uniform).  M0 is saved and restored.
+__device__ __forceinline__ void gload_lds16(const void* gptr, unsigned lds_addr) {
+  unsigned saved;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, off\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved)
+      : "v"(gptr), "s"(lds_addr)
+      : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int D>
+__global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParams p) {
+  typedef u16 T;
+  constexpr int CH = D / 8;                          // 16-byte chunks per K row
+  constexpr int kKBytes = kTileN * D * 2;
+  constexpr int kStageBytes = 2 * kKBytes;           // K tile then V tile
+  constexpr int LPH = kKBytes / 1024 / kFastWaves;   // load instructions per operand per wavefront per tile
+  constexpr int LPT = 2 * LPH;
+  static_assert(LPH >= 1, "tile too small for the copy scheme");
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kStages * kStageBytes];
+  __shared__ int sBound[2];
+  __shared__ int sItem;
+
+  const Layer& L = p.L;
+  const int BH = L.B * L.Hq;
+  const int xcd = xcc_id();
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int ln = lane & 31, h = lane >> 5;
+  const float c2 = L.scale * kLog2e;
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+  // per-lane pieces of the copy: which global chunk lands in this lane's LDS slot
+  int kgoff[LPH], vgoff[LPH];
+#pragma unroll
+  for (int j = 0; j < LPH; ++j) {
+    const int pchunk = (j * kFastWaves + wave) * 64 + lane;   // physical 16-byte slot in the K tile
+    const int row = pchunk / CH, pc = pchunk % CH;
+    kgoff[j] = row * D + ((pc ^ (row % CH)) << 3);             // elements
+    vgoff[j] = pchunk << 3;
+  }
+  // per-lane pieces of the fragment reads
+  const int krow_b = ln * (CH * 16);                           // byte offset of row ln in a 32-row block
+  const int khx = (h << 4) ^ ((ln % CH) << 4);                 // (chunk ^ swizzle) << 4 = (ks << 5) ^ khx
+  const int vlane_b = (h * D + ln) * 16;
+
+  for (;;) {
+  __syncthreads();
+  if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
+  __syncthreads();
+  const int item = sItem;
+  if (item < 0) break;
+  int bh, tq;
+  sched_decode(p.sched, BH, item, bh, tq);
+  const int b = bh / L.Hq, i = bh % L.Hq, g = i / L.G;
+  const int nq = p.q_cnt ? p.q_cnt[bh] : L.N;
+  const int nkeys = p.budget ? min(p.budget[b], p.b_cap) : L.N;
+  const int bhx = p.per_q_head ? bh : b * L.Hkv + g;
+  const int* kidx = p.kidx + (long long)bhx * p.npad;
+  const int* qlist = p.q_idx ? p.q_idx + (long long)bh * L.N : nullptr;
+
+  const int pos_first = tq * kFastTileM, pos_last = min(pos_first + kFastTileM, nq) - 1;
+  if (threadIdx.x == 0 || threadIdx.x == 64) {
+    const int which = threadIdx.x ? 1 : 0;
+    const int pos = which ? pos_last : pos_first;
+    const int row = qlist ? qlist[pos] : pos;
+    int cnt;
+    if (!L.causal) cnt = nkeys;
+    else if (p.identity_keys) cnt = min(row + 1, nkeys);
+    else cnt = upper_count(kidx, nkeys, row);
+    sBound[which] = cnt;
+  }
+  __syncthreads();
+  const int n_full_tiles = sBound[0] / kTileN;
+  const int ntiles = cdiv(sBound[1], kTileN);
+
+  const int qpos = pos_first + wave * 32 + ln;
+  const bool qvalid = qpos < nq;
+  const int qpos_c = min(qpos, nq - 1);
+  const int qrow = qlist ? qlist[qpos_c] : qpos_c;
+  const int qcmp = L.causal ? qrow : kPadKeyIndex - 1;
+  const T* qptr = static_cast<const T*>(p.Q) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+  bf16x8 qf[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qptr + ks * 16 + h * 8);
+  // Make the compiler finish these loads here.  Otherwise it places their s_waitcnt vmcnt at the first
+  // use inside the tile loop, where it would also drain the K/V prefetch ring on every iteration.
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(qf[ks]));
+
+  f32x16 o[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const T* kp = static_cast<const T*>(p.Kp) + (long long)bhx * p.npad * D;
+  const T* vp = static_cast<const T*>(p.Vp) + (long long)bhx * p.npad * D;
+
+  // one load instruction of tile t: part < LPH is a K part, the rest are V parts
+  auto issue_part = [&](int t, int part) {
+    const unsigned dst = lds_base + (unsigned)(t % kStages) * kStageBytes;
+    if (part < LPH) {
+      gload_lds16(kp + (long long)t * kTileN * D + kgoff[part], dst + (part * kFastWaves + wave) * 1024);
+    } else {
+      const int j = part - LPH;
+      gload_lds16(vp + (long long)t * kTileN * D + vgoff[j], dst + kKBytes + (j * kFastWaves + wave) * 1024);
+    }
+  };
+  auto issue_tile = [&](int t) {
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) issue_part(t, j);
+  };
+
+  f32x16 s[2];
+
+  // S^T = K tile . Q^T.  Fragments are read from LDS one group of four ahead of the MFMAs that use
+  // them (ping-pong registers); the scheduling fences stop the compiler from pairing every read with
+  // its MFMA, which would expose the LDS latency once per MFMA.
+  auto qk_tile = [&](int t, int pre) {
+    const unsigned char* sk = smem + (t % kStages) * kStageBytes;
+    constexpr int NG = 2 * (D / 64);        // groups of 4 k-steps over both 32-key blocks
+    bf16x8 ka[4], kn[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ka[j] = *reinterpret_cast<const bf16x8*>(sk + krow_b + ((j << 5) ^ khx));
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+      const int kb = gi / (D / 64), g4 = gi % (D / 64);
+      if (g4 == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (gi + 1 < NG) {
+        const int kb2 = (gi + 1) / (D / 64), g42 = (gi + 1) % (D / 64);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          kn[j] = *reinterpret_cast<const bf16x8*>(sk + kb2 * (32 * CH * 16) + krow_b + (((g42 * 4 + j) << 5) ^ khx));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qf[g4 * 4 + j], s[kb], 0, 0, 0);
+      if (gi * LPH % NG == 0 && pre >= 0) issue_part(pre, gi * LPH / NG);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) ka[j] = kn[j];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // mask, online softmax (leaves P in s), then O^T += V^T . P^T
+  auto softmax_pv_tile = [&](int t, bool masked, int pre) {
+    const unsigned char* sv = smem + (t % kStages) * kStageBytes + kKBytes;
+    if (masked) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const i32x4 id = *reinterpret_cast<const i32x4*>(kidx + t * kTileN + kb * 32 + 8 * q4 + 4 * h);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (id[e] > qcmp) s[kb][q4 * 4 + e] = -INFINITY;
+        }
+    }
+    float mloc = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[kb][r]);
+    mloc = pair_max(mloc);
+    const float m_new = fmaxf(m_run, mloc);
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+    if (__any(m_new > m_run)) {
+      const float alpha = fast_exp2((m_run - m_ref) * c2);
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+      m_run = m_new;
+    }
+    const float mc = m_ref * c2;
+    float lsum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pv = fast_exp2(fmaf(s[kb][r], c2, -mc));
+        s[kb][r] = pv;
+        lsum += pv;
+      }
+    l_run += lsum;
+    constexpr int NB = D / 32;
+    const unsigned char* vbase = sv + vlane_b;
+    bf16x8 va[NB], vn[NB];
+#pragma unroll
+    for (int db = 0; db < NB; ++db) va[db] = *reinterpret_cast<const bf16x8*>(vbase + db * 32 * 16);
+#pragma unroll
+    for (int t16 = 0; t16 < 4; ++t16) {
+      const int kb = t16 >> 1, r0 = (t16 & 1) * 8;
+      __builtin_amdgcn_sched_barrier(0);
+      if (t16 + 1 < 4) {
+#pragma unroll
+        for (int db = 0; db < NB; ++db)
+          vn[db] = *reinterpret_cast<const bf16x8*>(vbase + ((t16 + 1) * 2 * D + db * 32) * 16);
+      }
+      union { bf16x8 v; unsigned u[4]; } pf;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) pf.u[jj] = pack_bf16x2(s[kb][r0 + 2 * jj], s[kb][r0 + 2 * jj + 1]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int db = 0; db < NB; ++db)
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], pf.v, o[db], 0, 0, 0);
+      if (t16 * LPH % 4 == 0 && pre >= 0) issue_part(pre, LPH + t16 * LPH / 4);
+#pragma unroll
+      for (int db = 0; db < NB; ++db) va[db] = vn[db];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // Ring of kStages buffers, one barrier per tile.  At the top of iteration t the tiles up to t+2 have
+  // been issued; after its barrier everyone is done with tile t-1, whose buffer takes tile t+3.  The
+  // loads of tile t+3 are spread over the MFMA groups of tile t instead of being issued in one burst:
+  // the CU moves about 64 bytes per clock from memory into LDS, so a burst of all eight wavefronts
+  // backs the queue up and stalls the issuing wavefronts for hundreds of cycles.
+  static_assert(kStages == 4, "the wait counts below assume three tiles of prefetch");
+  if (ntiles > 0) {
+    wait_vmcnt<0>();                        // nothing of the previous item (its output stores) is counted below
+    issue_tile(0);
+    if (ntiles > 1) issue_tile(1);
+    if (ntiles > 2) issue_tile(2);
+    for (int t = 0; t < ntiles; ++t) {
+      const int ahead = min(ntiles - 1, t + 2) - t;   // tiles issued after tile t
+      if (ahead == 2) wait_vmcnt<2 * LPT>();           // this wavefront's share of tile t has landed
+      else if (ahead == 1) wait_vmcnt<LPT>();
+      else wait_vmcnt<0>();
+      __syncthreads();                      // ... and everyone else's; tile t-1 is retired
+      const int pre = t + 3 < ntiles ? t + 3 : -1;
+      qk_tile(t, pre);
+      softmax_pv_tile(t, t >= n_full_tiles, pre);
+    }
+  }
+
+  const float l_tot = pair_sum(l_run);
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  if (qvalid) {
+    T* optr = static_cast<T*>(p.O) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int d = db * 32 + 8 * q4 + 4 * h;
+        uint2 w;
+        w.x = pack_bf16x2(o[db][q4 * 4 + 0] * inv, o[db][q4 * 4 + 1] * inv);
+        w.y = pack_bf16x2(o[db][q4 * 4 + 2] * inv, o[db][q4 * 4 + 3] * inv);
+        *reinterpret_cast<uint2*>(optr + d) = w;
+      }
+    if (h == 0)
+      p.lse[(long long)bh * L.N + qrow] = l_tot > 0.f ? (m_run * c2 + log2f(l_tot)) * kLn2 : -INFINITY;
+  }
+  }  // work-item loop
+}
+
 struct FwdWs {
   void* Kp;
   void* Vp;
@@ -448,13 +739,18 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.per_q_head = sparse ? 1 : 0;
   p.identity_keys = sparse ? 0 : 1;
   p.sched = w.sched;
+  constexpr bool kFast = sizeof(T) == 2;
   {
-    int rc = run_schedule(L, q_cnt, budget, b_cap, w.sched, st);
+    int rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kFastTileM : kTileM, w.sched, st);
     if (rc != OMNI_OK) return rc;
   }
   {
     ProfScope prof__(kProfAttnFwd, st);
-    hipLaunchKernelGGL((attn_fwd_kernel<T, D>), dim3(persistent_grid()), dim3(kThreads), 0, st, p);
+    if constexpr (kFast) {
+      hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), dim3(persistent_grid() / 2), dim3(kFastThreads), 0, st, p);
+    } else {
+      hipLaunchKernelGGL((attn_fwd_kernel<T, D>), dim3(persistent_grid()), dim3(kThreads), 0, st, p);
+    }
     OMNI_LAUNCH_CHECK();
   }
   return OMNI_OK;

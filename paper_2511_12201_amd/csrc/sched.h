@@ -1,6 +1,6 @@
 // Device-side work list for the query-tile kernels (attention forward, backward dQ).
 //
-// Work item = one 128-row tile of a head's kept queries.  Items are ordered head
+// Work item = one tile (tile_m rows, 128 or 256) of a head's kept queries.  Items are ordered head
 // by head, longest tile first (under the causal mask the last tile of a head
 // sees the most keys), and cut into 8 contiguous segments of about equal cost,
 // one per XCD.  The kernels are persistent: every workgroup reads the id of the
@@ -26,7 +26,8 @@ constexpr int kNumXcd = 8;
 
 inline size_t sched_ints(int BH) { return (size_t)kSchedPrefix + BH + 1; }
 
-int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap, int* sched, hipStream_t st);
+int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap, int tile_m, int* sched,
+                 hipStream_t st);
 int persistent_grid();      // workgroups that fill the device at two per CU
 
 // XCC_ID hardware register (id 20), bits [3:0]
@@ -67,14 +68,14 @@ __host__ __device__ inline double sched_head_cost(int m, int nt, int nk, int cau
 
 // Fills the whole array (run by one device thread, or on the host by the diagnostic entry point).
 __host__ __device__ inline void sched_build(const int* q_cnt, const int* budget, int B, int Hq, int N, int b_cap,
-                                            int causal, int* sched) {
+                                            int causal, int tile_m, int* sched) {
   const int BH = B * Hq;
   int* prefix = sched + kSchedPrefix;
   int items = 0;
   double total = 0.0;
   for (int bh = 0; bh < BH; ++bh) {
     const int nq = q_cnt ? q_cnt[bh] : N;
-    const int nt = nq > 0 ? (nq + kTileM - 1) / kTileM : 0;
+    const int nt = nq > 0 ? (nq + tile_m - 1) / tile_m : 0;
     int nk = budget ? budget[bh / Hq] : N;
     nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
     prefix[bh] = items;
@@ -93,7 +94,7 @@ __host__ __device__ inline void sched_build(const int* q_cnt, const int* budget,
     int cut = items;
     while (bh < BH) {
       const int nq = q_cnt ? q_cnt[bh] : N;
-      const int nt = nq > 0 ? (nq + kTileM - 1) / kTileM : 0;
+      const int nt = nq > 0 ? (nq + tile_m - 1) / tile_m : 0;
       int nk = budget ? budget[bh / Hq] : N;
       nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
       const double hc = nt ? sched_head_cost(nt, nt, nk, causal) : 0.0;

@@ -119,12 +119,13 @@ def test_argument_errors(lib):
     ([0, 0, 5, 0], [3], 4, 537, 0),
     ([0, 0, 0, 0], [3], 4, 537, 1),
 ])
-def test_device_work_list_covers_every_query_tile_exactly_once(lib, q_cnt, budget, n_heads, n_tokens, causal):
+@pytest.mark.parametrize("tile_rows", [128, 256])
+def test_device_work_list_covers_every_query_tile_exactly_once(lib, q_cnt, budget, n_heads, n_tokens, causal, tile_rows):
     import numpy as np
     d = _desc(n_q_heads=n_heads, n_kv_heads=n_heads, n_tokens=n_tokens, vis_end=min(256, n_tokens), causal=causal)
-    seg, head, tile = ob.debug_work_list(d, q_cnt, budget, n_tokens)
+    seg, head, tile = ob.debug_work_list(d, q_cnt, budget, n_tokens, tile_rows)
     counts = q_cnt if q_cnt is not None else [n_tokens] * n_heads
-    want = {(h, t) for h in range(n_heads) for t in range((counts[h] + 127) // 128)}
+    want = {(h, t) for h in range(n_heads) for t in range((counts[h] + tile_rows - 1) // tile_rows)}
     got = list(zip(head.tolist(), tile.tolist()))
     assert len(got) == len(want) and set(got) == want
     assert seg[0] == 0 and seg[8] == len(got) and np.all(np.diff(seg) >= 0)
@@ -133,6 +134,6 @@ def test_device_work_list_covers_every_query_tile_exactly_once(lib, q_cnt, budge
         assert b[0] > a[0] or (b[0] == a[0] and b[1] == a[1] - 1)
     if len(got) >= 64 and causal:
         # segments carry similar numbers of keys to visit
-        cost = np.array([(t + 1) / ((counts[h] + 127) // 128) for h, t in got])
+        cost = np.array([(t + 1) / ((counts[h] + tile_rows - 1) // tile_rows) for h, t in got])
         per_seg = np.array([cost[seg[x]:seg[x + 1]].sum() for x in range(8)])
         assert per_seg.max() <= 1.25 * per_seg.mean() + 2
