@@ -20,6 +20,8 @@
 //    buffered in LDS, one barrier per tile; two workgroups fit a CU.
 //  * fp32 inputs take the same path with the fp32 32x32x2 MFMA (accuracy path).
 
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 #include "sched.h"
@@ -533,61 +535,49 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
     for (int j = 0; j < LPT; ++j) issue_part(t, j);
   };
 
-  f32x16 s[2];
+  // Software pipeline over key tiles.  While the matrix cores compute S(t+1)^T = K(t+1) . Q^T the
+  // same wavefront turns S(t) into P(t) on the vector ALU (exp2, row sum, bf16 pack); while they
+  // accumulate O^T += V(t)^T . P(t)^T it scans S(t+1) for the running maximum.  Each MFMA is followed
+  // in program order by its share of the vector work and a scheduling fence, so the hardware always
+  // has independent vector instructions to issue under a running MFMA.  Without this the two
+  // wavefronts of a SIMD, which the per-tile barrier keeps in step, are in their softmax phases at
+  // the same time and the matrix cores idle for that long.
+  constexpr int NQK = 2 * (D / 16);          // MFMAs of one S tile: 2 key blocks x D/16 k-steps
+  constexpr int NPV = 4 * (D / 32);          // MFMAs of one P.V tile: 4 key steps x D/32 row blocks
+  constexpr int NB = D / 32;
+  constexpr int kAhead = 2;                  // fragment reads run this many MFMAs ahead
+  static_assert(32 % NQK == 0 && 32 % NPV == 0 && 16 % NPV == 0, "chunking of the vector work");
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  union PFrag { bf16x8 v[4]; bf16x2 h[16]; };
 
-  // S^T = K tile . Q^T.  Fragments are read from LDS one group of four ahead of the MFMAs that use
-  // them (ping-pong registers); the scheduling fences stop the compiler from pairing every read with
-  // its MFMA, which would expose the LDS latency once per MFMA.
-  auto qk_tile = [&](int t, int pre) {
+  auto kfrag = [&](const unsigned char* sk, int c) {
+    const int kb = c % 2, ks = c / 2;
+    return *reinterpret_cast<const bf16x8*>(sk + kb * (32 * CH * 16) + krow_b + ((ks << 5) ^ khx));
+  };
+  auto vfrag = [&](const unsigned char* sv, int c) {
+    const int t16 = c / NB, db = c % NB;
+    return *reinterpret_cast<const bf16x8*>(sv + vlane_b + (t16 * 2 * D + db * 32) * 16);
+  };
+
+  // S^T of tile t alone (first tile of an item)
+  auto qk_only = [&](f32x16 (&sn)[2], int t) {
     const unsigned char* sk = smem + (t % kStages) * kStageBytes;
-    constexpr int NG = 2 * (D / 64);        // groups of 4 k-steps over both 32-key blocks
-    bf16x8 ka[4], kn[4];
+    bf16x8 kf[kAhead];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ka[j] = *reinterpret_cast<const bf16x8*>(sk + krow_b + ((j << 5) ^ khx));
+    for (int c = 0; c < kAhead; ++c) kf[c] = kfrag(sk, c);
 #pragma unroll
-    for (int gi = 0; gi < NG; ++gi) {
-      const int kb = gi / (D / 64), g4 = gi % (D / 64);
-      if (g4 == 0) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-      }
+    for (int c = 0; c < NQK; ++c) {
+      const int kb = c % 2, ks = c / 2;
       __builtin_amdgcn_sched_barrier(0);
-      if (gi + 1 < NG) {
-        const int kb2 = (gi + 1) / (D / 64), g42 = (gi + 1) % (D / 64);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          kn[j] = *reinterpret_cast<const bf16x8*>(sk + kb2 * (32 * CH * 16) + krow_b + (((g42 * 4 + j) << 5) ^ khx));
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qf[g4 * 4 + j], s[kb], 0, 0, 0);
-      if (gi * LPH % NG == 0 && pre >= 0) issue_part(pre, gi * LPH / NG);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) ka[j] = kn[j];
+      sn[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c % kAhead], qf[ks], ks == 0 ? zero16 : sn[kb], 0, 0, 0);
+      if (c + kAhead < NQK) kf[c % kAhead] = kfrag(sk, c + kAhead);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  // mask, online softmax (leaves P in s), then O^T += V^T . P^T
-  auto softmax_pv_tile = [&](int t, bool masked, int pre) {
-    const unsigned char* sv = smem + (t % kStages) * kStageBytes + kKBytes;
-    if (masked) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const i32x4 id = *reinterpret_cast<const i32x4*>(kidx + t * kTileN + kb * 32 + 8 * q4 + 4 * h);
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (id[e] > qcmp) s[kb][q4 * 4 + e] = -INFINITY;
-        }
-    }
-    float mloc = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[kb][r]);
+  // running maximum from a finished S tile, rescale of the accumulators if it grew
+  float mc = 0.f;                              // (running maximum, 0 if none yet) * c2
+  auto update_max = [&](float mloc) {
     mloc = pair_max(mloc);
     const float m_new = fmaxf(m_run, mloc);
     const float m_ref = m_new == -INFINITY ? 0.f : m_new;
@@ -595,70 +585,144 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
       const float alpha = fast_exp2((m_run - m_ref) * c2);
       l_run *= alpha;
 #pragma unroll
-      for (int db = 0; db < D / 32; ++db)
+      for (int db = 0; db < NB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
       m_run = m_new;
     }
-    const float mc = m_ref * c2;
-    float lsum = 0.f;
+    mc = m_ref * c2;
+  };
+  auto mask_tile = [&](f32x16 (&sn)[2], int t) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pv = fast_exp2(fmaf(s[kb][r], c2, -mc));
-        s[kb][r] = pv;
-        lsum += pv;
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const i32x4 id = *reinterpret_cast<const i32x4*>(kidx + t * kTileN + kb * 32 + 8 * q4 + 4 * h);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (id[e] > qcmp) sn[kb][q4 * 4 + e] = -INFINITY;
+        __builtin_amdgcn_sched_barrier(0);     // one index quad in registers at a time
       }
-    l_run += lsum;
-    constexpr int NB = D / 32;
-    const unsigned char* vbase = sv + vlane_b;
-    bf16x8 va[NB], vn[NB];
+    float mloc = sn[0][0];
 #pragma unroll
-    for (int db = 0; db < NB; ++db) va[db] = *reinterpret_cast<const bf16x8*>(vbase + db * 32 * 16);
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-    for (int t16 = 0; t16 < 4; ++t16) {
-      const int kb = t16 >> 1, r0 = (t16 & 1) * 8;
-      __builtin_amdgcn_sched_barrier(0);
-      if (t16 + 1 < 4) {
-#pragma unroll
-        for (int db = 0; db < NB; ++db)
-          vn[db] = *reinterpret_cast<const bf16x8*>(vbase + ((t16 + 1) * 2 * D + db * 32) * 16);
-      }
-      union { bf16x8 v; unsigned u[4]; } pf;
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) pf.u[jj] = pack_bf16x2(s[kb][r0 + 2 * jj], s[kb][r0 + 2 * jj + 1]);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int db = 0; db < NB; ++db)
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], pf.v, o[db], 0, 0, 0);
-      if (t16 * LPH % 4 == 0 && pre >= 0) issue_part(pre, LPH + t16 * LPH / 4);
-#pragma unroll
-      for (int db = 0; db < NB; ++db) va[db] = vn[db];
-    }
-    __builtin_amdgcn_sched_barrier(0);
+      for (int r = 0; r < 16; r += 2) mloc = fmaxf(fmaxf(sn[kb][r], sn[kb][r + 1]), mloc);
+    return mloc;
   };
 
-  // Ring of kStages buffers, one barrier per tile.  At the top of iteration t the tiles up to t+2 have
-  // been issued; after its barrier everyone is done with tile t-1, whose buffer takes tile t+3.  The
-  // loads of tile t+3 are spread over the MFMA groups of tile t instead of being issued in one burst:
-  // the CU moves about 64 bytes per clock from memory into LDS, so a burst of all eight wavefronts
-  // backs the queue up and stalls the issuing wavefronts for hundreds of cycles.
-  static_assert(kStages == 4, "the wait counts below assume three tiles of prefetch");
+  // One pipeline step: P(t) from sc, O += V(t) P(t); if there is a tile t+1: S(t+1) into sn and its maximum.
+  // `steady` steps are the ones with t + 3 < ntiles: they always have a next tile and always prefetch,
+  // so the step is straight-line code and the fences keep the interleaving as written.
+  auto step = [&](auto steady, f32x16 (&sc)[2], f32x16 (&sn)[2], int t) {
+    constexpr bool kSteady = decltype(steady)::value;
+    const bool has_next = kSteady || t + 1 < ntiles;
+    const int pre = (kSteady || t + 3 < ntiles) ? t + 3 : -1;
+    const unsigned char* sk = smem + ((t + 1) % kStages) * kStageBytes;
+    const unsigned char* sv = smem + (t % kStages) * kStageBytes + kKBytes;
+    PFrag pf;
+    float lsum = 0.f;
+    bf16x8 vf[kAhead];
+    constexpr int EQ = 32 / NQK;             // S elements turned into P per QK MFMA
+    auto softmax_chunk = [&](int c) {
+#pragma unroll
+      for (int e = 0; e < EQ; e += 2) {
+        const int r = c * EQ + e;
+        f32x2 pv;
+        pv[0] = fast_exp2(fmaf(sc[r / 16][r % 16], c2, -mc));
+        pv[1] = fast_exp2(fmaf(sc[r / 16][r % 16 + 1], c2, -mc));
+        const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
+        pf.h[r / 2] = pk;
+        lsum += pv[0] + pv[1];                 // fp32 sum of the unrounded weights: lse stays exact to fp32
+      }
+    };
+    if (has_next) {
+      if (kSteady || t + 2 < ntiles) wait_vmcnt<LPT>();   // this wavefront's share of tile t+1 has landed
+      else wait_vmcnt<0>();
+      __syncthreads();                        // ... and everyone else's; tile t-1 is retired
+      __builtin_amdgcn_sched_barrier(0);
+      bf16x8 kf[kAhead];
+#pragma unroll
+      for (int c = 0; c < kAhead; ++c) kf[c] = kfrag(sk, c);
+#pragma unroll
+      for (int c = 0; c < NQK; ++c) {
+        const int kb = c % 2, ks = c / 2;
+        __builtin_amdgcn_sched_barrier(0);
+        sn[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c % kAhead], qf[ks], ks == 0 ? zero16 : sn[kb], 0, 0, 0);
+        if (c + kAhead < NQK) kf[c % kAhead] = kfrag(sk, c + kAhead);
+        else vf[c + kAhead - NQK] = vfrag(sv, c + kAhead - NQK);
+        softmax_chunk(c);
+        if (c * LPH % NQK == 0 && (kSteady || pre >= 0)) issue_part(pre, c * LPH / NQK);
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < kAhead; ++c) vf[c] = vfrag(sv, c);
+#pragma unroll
+      for (int c = 0; c < NQK; ++c) softmax_chunk(c);
+    }
+    l_run += lsum;
+    float mloc = -INFINITY;
+    constexpr int EV = 32 / NPV;             // S(t+1) elements scanned per P.V MFMA
+#pragma unroll
+    for (int c = 0; c < NPV; ++c) {
+      const int t16 = c / NB, db = c % NB;
+      __builtin_amdgcn_sched_barrier(0);
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c % kAhead], pf.v[t16], o[db], 0, 0, 0);
+      if (c + kAhead < NPV) vf[c % kAhead] = vfrag(sv, c + kAhead);
+#pragma unroll
+      for (int e = 0; e < EV; e += 2) {
+        const int r = c * EV + e;
+        mloc = fmaxf(fmaxf(sn[r / 16][r % 16], sn[r / 16][r % 16 + 1]), mloc);
+      }
+      if (c * LPH % NPV == 0 && (kSteady || pre >= 0)) issue_part(pre, LPH + c * LPH / NPV);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (has_next) {
+      if (t + 1 >= n_full_tiles) mloc = mask_tile(sn, t + 1);
+      update_max(mloc);
+    }
+  };
+
+  // Ring of kStages buffers, one barrier per tile.  At the top of step t the tiles up to t+2 have been
+  // issued; after its barrier everyone is done with tile t-1, whose buffer takes tile t+3.  The loads of
+  // tile t+3 are spread over the MFMAs of the step instead of being issued in one burst: the CU moves
+  // about 64 bytes per clock from memory into LDS, so a burst of all eight wavefronts backs the queue
+  // up and stalls the issuing wavefronts for hundreds of cycles.
+  static_assert(kStages == 4, "the wait counts assume this ring depth");
   if (ntiles > 0) {
+    f32x16 sa[2], sb[2];
+    sb[0] = zero16;
+    sb[1] = zero16;
     wait_vmcnt<0>();                        // nothing of the previous item (its output stores) is counted below
     issue_tile(0);
     if (ntiles > 1) issue_tile(1);
     if (ntiles > 2) issue_tile(2);
-    for (int t = 0; t < ntiles; ++t) {
-      const int ahead = min(ntiles - 1, t + 2) - t;   // tiles issued after tile t
-      if (ahead == 2) wait_vmcnt<2 * LPT>();           // this wavefront's share of tile t has landed
-      else if (ahead == 1) wait_vmcnt<LPT>();
-      else wait_vmcnt<0>();
-      __syncthreads();                      // ... and everyone else's; tile t-1 is retired
-      const int pre = t + 3 < ntiles ? t + 3 : -1;
-      qk_tile(t, pre);
-      softmax_pv_tile(t, t >= n_full_tiles, pre);
+    if (ntiles > 2) wait_vmcnt<2 * LPT>();
+    else if (ntiles > 1) wait_vmcnt<LPT>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+    qk_only(sa, 0);
+    {
+      float mloc;
+      if (0 >= n_full_tiles) {
+        mloc = mask_tile(sa, 0);
+      } else {
+        mloc = sa[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) mloc = fmaxf(fmaxf(sa[kb][r], sa[kb][r + 1]), mloc);
+      }
+      update_max(mloc);
+    }
+    int t = 0;
+    for (; t + 4 < ntiles; t += 2) {
+      step(std::true_type{}, sa, sb, t);
+      step(std::true_type{}, sb, sa, t + 1);
+    }
+    for (; t < ntiles; t += 2) {
+      step(std::false_type{}, sa, sb, t);
+      if (t + 1 < ntiles) step(std::false_type{}, sb, sa, t + 1);
     }
   }
 
