@@ -24,6 +24,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the sparse forward kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# file, scaled by the calibration copy (profiles/attn_fwd_c3_64k_hbm_traffic.txt); None where not profiled.
+MEASURED_TRAFFIC = {"c3_64k": 8.174e9}
+
 TAU = 0.08
 RECALL_P = 0.95
 PROBE_BLOCK = 256
@@ -34,7 +38,7 @@ def log(*a):
 
 
 def pair_counts(q_lists, kv_lists, causal: bool, tile_m: int = 128, tile_n: int = 64):
-    """Valid (query, key) pairs and pairs covered by launched 128x64 tiles."""
+    """Valid (query, key) pairs and pairs covered by the launched tile_m x tile_n tiles."""
     valid = issued = 0
     for qi, ki in zip(q_lists, kv_lists):
         if qi.size == 0 or ki.size == 0:
@@ -111,7 +115,7 @@ def main():
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
-        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        ob.debug_copy(src, dst)             # calibration_copy_kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
@@ -147,7 +151,7 @@ def main():
     ki = kv_idx.cpu().numpy()[0]
     q_lists = [qi[h, : cnt[h]] for h in range(Hq)]
     kv_lists = [ki[h, :b] for h in range(Hq)]
-    valid, issued = pair_counts(q_lists, kv_lists, cfg.causal)
+    valid, issued = pair_counts(q_lists, kv_lists, cfg.causal, tile_m=256)
     dense_pairs = Hq * N * (N + 1) // 2
     flops_alg = 4.0 * D * valid
     flops_issued = 4.0 * D * issued
@@ -164,9 +168,9 @@ def main():
                                f"N={N} ({cfg.frames} frames x {cfg.tok_per_frame} visual + {cfg.n_text} text), causal, "
                                f"tau={TAU}, recall p={RECALL_P}, probe block {PROBE_BLOCK}",
                    "step": "score_queries + select_queries + kv_budget + select_kv + sparse_attn_fwd"},
-        "roofline": {"bound": "mfma", "kernel": "attn_fwd_kernel (sparse)", "achieved": round(ach, 2),
+        "roofline": {"bound": "mfma", "kernel": "attn_fwd_bf16_kernel<128> (sparse)", "achieved": round(ach, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "kernel_ms": round(attn_ms, 4),
+                     "traffic": MEASURED_TRAFFIC.get(cfg.name), "kernel_ms": round(attn_ms, 4),
                      "achieved_on_issued_tiles": round(ach_issued, 2),
                      "frac_on_issued_tiles": round(ach_issued / PEAK_BF16_TFLOPS, 4)},
         "selection_ms": round(sel_ms, 4),
@@ -200,6 +204,13 @@ def main():
         out["dense_tflops"] = round(4.0 * D * dense_pairs / (dense_ms * 1e-3) / 1e12, 2)
         out["speedup_vs_dense"] = round(dense_ms / ms_per_step, 3)
         del Od
+        # what the matrix cores sustain with nothing else running: nominal (constant operands) and with
+        # operands that toggle like data, where the clock is held down by the power limit
+        tf_c, mhz_c = ob.debug_mfma_rate(False)
+        tf_r, mhz_r = ob.debug_mfma_rate(True)
+        out["mfma_only_probe"] = {"constant_operands": {"TFLOP/s": round(tf_c, 1), "shader_MHz": round(mhz_c)},
+                                  "random_operands": {"TFLOP/s": round(tf_r, 1), "shader_MHz": round(mhz_r)}}
+        out["roofline"]["frac_of_sustained_random_operand_rate"] = round(ach / tf_r, 4)
         out["cpu_baseline"] = cpu_baseline(cfg, layer, q_lists, kv_lists, valid, ms_per_step)
         del Q, K, V, O, dev, layer
         torch.cuda.empty_cache()

@@ -289,6 +289,23 @@ int omni_debug_work_list(const omni_layer_desc* desc, const int32_t* q_cnt, cons
                          int32_t b_cap, int32_t tile_rows, int32_t* seg_begin, int32_t* item_head, int32_t* item_tile,
                          int32_t capacity, int32_t* n_items);
 
+/*
+ * Diagnostic: copy `bytes` (a positive multiple of 16) from src to dst, both DEVICE pointers
+ * to 16-byte aligned, non-overlapping buffers, with a plain copy kernel
+ * (calibration_copy_kernel) on `stream`.  A launch of known HBM traffic: a profiler's
+ * byte counters are scaled by what they report for it.
+ */
+int omni_debug_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/*
+ * Diagnostic: sustained rate of register-resident bf16 32x32x16 MFMAs on all compute units,
+ * with constant operands (random_operands = 0) or pseudo-random ones (1); the second is
+ * what power management leaves of the nominal matrix-core peak for operands that toggle
+ * like real data.  Runs on the default stream and synchronises; allocates and frees a few
+ * MiB.  Outputs are HOST pointers: TFLOP/s and the mean shader clock in MHz.
+ */
+int omni_debug_mfma_rate(int random_operands, int iters, double* tflops /* host */, double* shader_mhz /* host */);
+
 /* Message of the last error on this thread ("" if none). */
 const char* omni_last_error(void);
 

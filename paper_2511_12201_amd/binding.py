@@ -24,7 +24,7 @@ EXPORTED = [
     "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
     "omni_sparse_attn_fwd", "omni_sparse_attn_bwd", "omni_slim_decode", "omni_visual_subset",
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
-    "omni_profile_enable", "omni_profile_read", "omni_debug_work_list",
+    "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -84,6 +84,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_profile_enable.argtypes = [C.c_int]
+    lib.omni_debug_copy.argtypes = [vp, vp, sz, vp]
+    lib.omni_debug_mfma_rate.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.omni_debug_work_list.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, i32, vp]
     lib.omni_profile_read.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
     for name in EXPORTED:
@@ -166,6 +168,20 @@ def debug_work_list(desc: LayerDesc, q_cnt=None, budget=None, b_cap: int = 1, ti
                                     None if bd is None else bd.ctypes.data, b_cap, tile_rows, seg.ctypes.data,
                                     head.ctypes.data, tile.ctypes.data, cap, C.byref(n)))
     return seg, head[: n.value], tile[: n.value]
+
+
+def debug_copy(src, dst):
+    """Copy src into dst (same byte size, a multiple of 16) with the library's calibration copy kernel."""
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(load_library().omni_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream()))
+
+
+def debug_mfma_rate(random_operands: bool, iters: int = 40000):
+    """(TFLOP/s, shader MHz) of register-resident bf16 MFMAs with constant or pseudo-random operands."""
+    tf, mhz = C.c_double(0), C.c_double(0)
+    _check(load_library().omni_debug_mfma_rate(1 if random_operands else 0, iters, C.byref(tf), C.byref(mhz)))
+    return tf.value, mhz.value
 
 
 def profile_enable(on: bool):

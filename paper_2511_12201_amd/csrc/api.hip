@@ -177,6 +177,20 @@ int omni_debug_work_list(const omni_layer_desc* desc, const int32_t* q_cnt, cons
   return OMNI_OK;
 }
 
+int omni_debug_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  clear_error();
+  REQUIRE_PTR(src); REQUIRE_PTR(dst);
+  if (bytes == 0 || bytes % 16) OMNI_FAIL(OMNI_ERR_INVALID, "bytes must be a positive multiple of 16");
+  return run_calibration_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
+}
+
+int omni_debug_mfma_rate(int random_operands, int iters, double* tflops, double* shader_mhz) {
+  clear_error();
+  REQUIRE_PTR(tflops); REQUIRE_PTR(shader_mhz);
+  if (iters < 1 || iters > (1 << 22)) OMNI_FAIL(OMNI_ERR_INVALID, "iters must be in [1, 2^22]");
+  return run_mfma_rate(random_operands ? 1 : 0, iters, tflops, shader_mhz);
+}
+
 int omni_profile_enable(int on) {
   clear_error();
   g_prof_on = on != 0;

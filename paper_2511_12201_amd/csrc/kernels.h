@@ -53,4 +53,8 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
                const float* probe, const int* vis_idx, const int* vis_cnt, int b_cap, void* O,
                unsigned char* active, void* ws, hipStream_t st);
 
+// diag.hip
+int run_calibration_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+int run_mfma_rate(int random_operands, int iters, double* tflops, double* shader_mhz);
+
 }  // namespace omni
