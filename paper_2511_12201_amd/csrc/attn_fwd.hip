@@ -66,7 +66,8 @@ struct FwdParams {
   int b_cap;
   int npad;
   int per_q_head;       // packed buffers per query head (sparse) or per KV head (dense)
-  int identity_keys;    // kidx[p] == p: causal bounds by arithmetic
+  int identity_keys;
+  const int* qvis;       // [B*Hq, N] visible packed keys per kept-query position (sparse bf16 path), else nullptr    // kidx[p] == p: causal bounds by arithmetic
   int* sched;           // work list (sched.h)
 };
 
@@ -407,6 +408,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
 // (chunk ^ row % chunks_per_row), applied on the global-address side of the copy, which keeps
 // the 16 rows a ds_read_b128 touches on distinct banks.  V is already in operand order.
 
+// Number of packed keys visible to every kept query: the packed list is ascending in token index, so the
+// keys a causal query may see are a prefix of it, and the mask of a tile is a comparison of the key's
+// position with this count -- no index loads inside the tile loop.
+__global__ __launch_bounds__(256) void visible_counts_kernel(const int* __restrict__ q_idx, const int* __restrict__ q_cnt,
+                                                             const int* __restrict__ kidx, const int* __restrict__ budget,
+                                                             int b_cap, int npad, int N, int Hq, int causal,
+                                                             int* __restrict__ qvis) {
+  const int bh = blockIdx.y, b = bh / Hq;
+  const int nq = q_cnt[bh], nkeys = min(budget[b], b_cap);
+  const int pos = blockIdx.x * blockDim.x + threadIdx.x;
+  if (pos >= nq) return;
+  const int row = q_idx[(long long)bh * N + pos];
+  qvis[(long long)bh * N + pos] = causal ? upper_count(kidx + (long long)bh * npad, nkeys, row) : nkeys;
+}
+
 constexpr int kFastWaves = 8;
 constexpr int kFastThreads = kFastWaves * 64;
 constexpr int kFastTileM = kFastWaves * 32;
@@ -482,15 +498,17 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   const int* qlist = p.q_idx ? p.q_idx + (long long)bh * L.N : nullptr;
 
   const int pos_first = tq * kFastTileM, pos_last = min(pos_first + kFastTileM, nq) - 1;
+  const int* qvis = p.qvis ? p.qvis + (long long)bh * L.N : nullptr;
+  // visible prefix length of the packed key list for a kept-query position
+  auto visible = [&](int pos, int row) {
+    if (!L.causal) return nkeys;
+    if (p.identity_keys) return min(row + 1, nkeys);
+    return qvis ? qvis[pos] : upper_count(kidx, nkeys, row);
+  };
   if (threadIdx.x == 0 || threadIdx.x == 64) {
     const int which = threadIdx.x ? 1 : 0;
     const int pos = which ? pos_last : pos_first;
-    const int row = qlist ? qlist[pos] : pos;
-    int cnt;
-    if (!L.causal) cnt = nkeys;
-    else if (p.identity_keys) cnt = min(row + 1, nkeys);
-    else cnt = upper_count(kidx, nkeys, row);
-    sBound[which] = cnt;
+    sBound[which] = visible(pos, qlist ? qlist[pos] : pos);
   }
   __syncthreads();
   const int n_full_tiles = sBound[0] / kTileN;
@@ -500,7 +518,7 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   const bool qvalid = qpos < nq;
   const int qpos_c = min(qpos, nq - 1);
   const int qrow = qlist ? qlist[qpos_c] : qpos_c;
-  const int qcmp = L.causal ? qrow : kPadKeyIndex - 1;
+  const int qvisible = visible(qpos_c, qrow) - 4 * h;          // compared with key positions that leave out 4 * h
   const T* qptr = static_cast<const T*>(p.Q) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
   bf16x8 qf[D / 16];
 #pragma unroll
@@ -593,16 +611,14 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
     mc = m_ref * c2;
   };
   auto mask_tile = [&](f32x16 (&sn)[2], int t) {
+    const int rel = qvisible - t * kTileN;     // keys of this tile at positions >= rel are hidden (pad rows too)
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const i32x4 id = *reinterpret_cast<const i32x4*>(kidx + t * kTileN + kb * 32 + 8 * q4 + 4 * h);
+      for (int q4 = 0; q4 < 4; ++q4)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (id[e] > qcmp) sn[kb][q4 * 4 + e] = -INFINITY;
-        __builtin_amdgcn_sched_barrier(0);     // one index quad in registers at a time
-      }
+          if (kb * 32 + 8 * q4 + e >= rel) sn[kb][q4 * 4 + e] = -INFINITY;   // register r holds key 8 (r/4) + 4 h + r%4
     float mloc = sn[0][0];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -661,6 +677,7 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
       for (int c = 0; c < NQK; ++c) softmax_chunk(c);
     }
     l_run += lsum;
+    __builtin_amdgcn_s_setprio(0);
     float mloc = -INFINITY;
     constexpr int EV = 32 / NPV;             // S(t+1) elements scanned per P.V MFMA
 #pragma unroll
@@ -677,6 +694,9 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
       if (c * LPH % NPV == 0 && (kSteady || pre >= 0)) issue_part(pre, LPH + c * LPH / NPV);
     }
     __builtin_amdgcn_sched_barrier(0);
+    // The mixed MFMA + vector block and the bookkeeping run at raised priority, the pure MFMA block at the
+    // base one: the wavefront with vector work to issue wins the arbiter, the other one's MFMAs fill in.
+    __builtin_amdgcn_s_setprio(1);
     if (has_next) {
       if (t + 1 >= n_full_tiles) mloc = mask_tile(sn, t + 1);
       update_max(mloc);
@@ -751,9 +771,10 @@ struct FwdWs {
   void* Vp;
   int* kidx;
   int* sched;
+  int* qvis;
 };
 
-FwdWs carve_fwd(Arena& a, const Layer& L, int dtype, int heads, int npad) {
+FwdWs carve_fwd(Arena& a, const Layer& L, int dtype, int heads, int npad, bool sparse) {
   FwdWs w;
   const size_t es = dtype == OMNI_BF16 ? 2 : 4;
   const size_t rows = (size_t)L.B * heads * npad;
@@ -761,6 +782,7 @@ FwdWs carve_fwd(Arena& a, const Layer& L, int dtype, int heads, int npad) {
   w.Vp = a.take<unsigned char>(rows * L.D * es);
   w.kidx = a.take<int>(rows);
   w.sched = a.take<int>(sched_ints(L.B * L.Hq));
+  w.qvis = (sparse && dtype == OMNI_BF16) ? a.take<int>((size_t)L.B * L.Hq * L.N) : nullptr;
   return w;
 }
 
@@ -771,7 +793,7 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   Arena a(ws);
   const int heads = sparse ? L.Hq : L.Hkv;
   const int npad = (int)align_up(sparse ? b_cap : L.N, kTileN);
-  FwdWs w = carve_fwd(a, L, sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32, heads, npad);
+  FwdWs w = carve_fwd(a, L, sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32, heads, npad, sparse);
   {
     const int dt = sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32;
     // bf16: K natural + V k-packed; fp32: both natural
@@ -803,6 +825,12 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.per_q_head = sparse ? 1 : 0;
   p.identity_keys = sparse ? 0 : 1;
   p.sched = w.sched;
+  p.qvis = w.qvis;
+  if (w.qvis) {
+    hipLaunchKernelGGL(visible_counts_kernel, dim3(cdiv(L.N, 256), L.B * L.Hq), dim3(256), 0, st, q_idx, q_cnt, w.kidx,
+                       budget, b_cap, npad, L.N, L.Hq, L.causal, w.qvis);
+    OMNI_LAUNCH_CHECK();
+  }
   constexpr bool kFast = sizeof(T) == 2;
   {
     int rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kFastTileM : kTileM, w.sched, st);
@@ -824,7 +852,7 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
 
 size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse) {
   Arena a(nullptr);
-  carve_fwd(a, L, dtype, sparse ? L.Hq : L.Hkv, (int)align_up(sparse ? b_cap : L.N, kTileN));
+  carve_fwd(a, L, dtype, sparse ? L.Hq : L.Hkv, (int)align_up(sparse ? b_cap : L.N, kTileN), sparse);
   return a.used();
 }
 
