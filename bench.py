@@ -297,12 +297,19 @@ def bench_decode(torch, ob, synth, n_steps: int = 256):
     b = int(bud.budget.cpu()[0])
     kv_idx = ob.omni_select_kv(desc, bud.key_scores, bud.budget, b)
     vis_idx1, vis_cnt1 = ob.omni_visual_subset(desc, kv_idx, bud.budget, b)
+    grp_idx1, grp_mask1, grp_cnt1 = ob.omni_group_subset(desc, kv_idx, bud.budget, b)
     torch.cuda.synchronize()
     del Q, bud
     cap = N + n_steps
     res = {"workload": f"{cfg.name}: cache {N} tokens + {n_steps} decoded, bf16, tau={TAU}", "budget_fraction": round(b / N, 4),
+           "timing": "us_per_token = GPU time of the decode call's kernels (HIP events, first 64 steps); the Python loop "
+                     "around it (cache append, ctypes launches) is host-bound and listed separately",
            "per_batch": {}}
     vis_cnt_host = vis_cnt1.cpu().numpy()[0]
+    vis_idx_host = vis_idx1.cpu().numpy()[0]
+    member = np.zeros((Hq, N), dtype=bool)            # member[h, n]: head h stores visual row n
+    for h in range(Hq):
+        member[h, vis_idx_host[h, : vis_cnt_host[h]]] = True
     for B in (1, 2, 4, 8):
         steps = synth.make_decode_steps(cfg, layer, n_steps, batch=B)
         q_all = _upload(torch, synth, steps["q"])                      # [S,B,Hq,D]
@@ -314,20 +321,24 @@ def bench_decode(torch, ob, synth, n_steps: int = 256):
         Vc[:, :, :N] = V
         vis_idx = vis_idx1.expand(B, -1, -1).contiguous()
         vis_cnt = vis_cnt1.expand(B, -1).contiguous()
+        grp_idx, grp_mask = grp_idx1.expand(B, -1, -1).contiguous(), grp_mask1.expand(B, -1, -1).contiguous()
+        grp_cnt = grp_cnt1.expand(B, -1).contiguous()
         probe_b = probe.expand(B, -1, -1, -1).contiguous()
         ctx = torch.full((B,), N, dtype=torch.int32, device="cuda")
         O = torch.empty(B, Hq, D, dtype=torch.bfloat16, device="cuda")
         act = torch.empty(B, Hq, dtype=torch.uint8, device="cuda")
         ddesc = ob.make_decode_desc(q_all[0], Kc, cfg.vis_begin, cfg.vis_end, TAU)
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        timing = {}
-        for mode in ("slim", "dense"):
+        timing, ktime = {}, {}
+        for mode in ("slim", "slim_grouped", "dense"):
             ctx.fill_(N + 1)
             for _ in range(3):                                    # untimed warm-up of both entry points
+                ob.omni_slim_decode_grouped(ddesc, q_all[0], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act)
                 ob.omni_slim_decode(ddesc, q_all[0], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
                 ob.omni_dense_decode(ddesc, q_all[0], Kc, Vc, ctx, O)
             ctx.fill_(N)
             torch.cuda.synchronize()
+            ob.profile_enable(True)
             ev0.record()
             for s in range(n_steps):
                 Kc[:, :, N + s] = k_new[s]
@@ -335,24 +346,45 @@ def bench_decode(torch, ob, synth, n_steps: int = 256):
                 ctx += 1
                 if mode == "slim":
                     ob.omni_slim_decode(ddesc, q_all[s], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
+                elif mode == "slim_grouped":
+                    ob.omni_slim_decode_grouped(ddesc, q_all[s], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act)
                 else:
                     ob.omni_dense_decode(ddesc, q_all[s], Kc, Vc, ctx, O)
             ev1.record()
             torch.cuda.synchronize()
             timing[mode] = ev0.elapsed_time(ev1) * 1e3 / n_steps          # us per decode step
-        # bytes of K/V rows fetched in the last step (algorithmic): per head its own rows
+            kms, kn = ob.profile_read("decode")                               # last 64 launches: row-streaming kernels only
+            ktime[mode] = kms * 1e3 / max(1, kn)
+            ob.profile_enable(False)
+        # K/V rows a step asks for (last step's activity).  Plain decode: every row once per KV group.  Slimmed
+        # decode with per-head lists: every active head its own stored visual rows (heads of a group that store
+        # the same row both ask for it), plus the non-visual rows once per group.  Grouped lists: the union over
+        # the active heads of a group instead.
         a = act.cpu().numpy()
+        G = Hq // Hkv
         n_text = (N - cfg.vis_end) + cfg.vis_begin + n_steps
-        rows_slim = sum(int(a[bb, h]) * int(vis_cnt_host[h]) + n_text for bb in range(B) for h in range(Hq))
-        rows_dense = B * Hq * (N + n_steps)
+        rows_head = rows_union = 0
+        for bb in range(B):
+            for g in range(Hkv):
+                heads = [h for h in range(g * G, (g + 1) * G) if a[bb, h]]
+                if heads:
+                    rows_union += int(np.any(member[heads], axis=0).sum())
+                    rows_head += int(member[heads].sum())
+                rows_union += n_text
+                rows_head += n_text
+        rows_dense = B * Hkv * (N + n_steps)
+        row_bytes = 2 * D * 2
+        gbps = lambda rows, us: round(rows * row_bytes / (us * 1e-6) / 1e9, 1)
         res["per_batch"][str(B)] = {
-            "slim_us_per_token": round(timing["slim"], 2), "dense_us_per_token": round(timing["dense"], 2),
-            "speedup": round(timing["dense"] / timing["slim"], 3),
+            "slim_us_per_token": round(ktime["slim"], 2), "dense_us_per_token": round(ktime["dense"], 2),
+            "speedup": round(ktime["dense"] / ktime["slim"], 3),
+            "slim_grouped_us_per_token": round(ktime["slim_grouped"], 2),
+            "python_loop_us_per_token": {k: round(v, 1) for k, v in timing.items()},
             "active_head_fraction_last_step": round(float(a.mean()), 4),
-            "kv_row_fetches_slim_vs_dense": round(rows_slim / rows_dense, 4),
-            "slim_GBps_row_fetches": round(rows_slim * 2 * D * 2 / (timing["slim"] * 1e-6) / 1e9, 1),
-            "dense_GBps_row_fetches": round(rows_dense * 2 * D * 2 / (timing["dense"] * 1e-6) / 1e9, 1),
-            "dense_GBps_unique_cache": round(B * Hkv * (N + n_steps) * 2 * D * 2 / (timing["dense"] * 1e-6) / 1e9, 1)}
+            "rows_requested_vs_dense": {"slim": round(rows_head / rows_dense, 4), "slim_grouped": round(rows_union / rows_dense, 4)},
+            "GBps_of_requested_rows": {"slim": gbps(rows_head, ktime["slim"]), "slim_grouped": gbps(rows_union, ktime["slim_grouped"]),
+                                       "dense": gbps(rows_dense, ktime["dense"])},
+            "dense_frac_of_hbm_peak": round(rows_dense * row_bytes / (ktime["dense"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)}
         del Kc, Vc
         torch.cuda.empty_cache()
     return res

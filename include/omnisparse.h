@@ -65,7 +65,8 @@ typedef enum {
   OMNI_CALL_SPARSE_ATTN_BWD = 5,
   OMNI_CALL_SLIM_DECODE = 6,
   OMNI_CALL_DENSE_ATTN_FWD = 7,
-  OMNI_CALL_DENSE_DECODE = 8
+  OMNI_CALL_DENSE_DECODE = 8,
+  OMNI_CALL_GROUP_SUBSET = 9
 } omni_call_id;
 
 /* One attention layer during prefill / training.
@@ -241,6 +242,32 @@ int omni_slim_decode(const omni_decode_desc* desc, const void* q,
  */
 int omni_visual_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget,
                        int32_t b_cap, int32_t* vis_idx, int32_t* vis_cnt, void* stream);
+
+/*
+ * omni_group_subset / omni_slim_decode_grouped -- the same decode step (Sec. "KV
+ * Cache Slimming", decoding-attention equation) with the stored visual rows kept
+ * per KV group instead of per query head.  Under grouped-query attention the heads
+ * of a group index one shared cache; the group list is the ascending union of the
+ * visual entries of its heads' kv_idx lists, with bit j of grp_mask set iff query
+ * head (group * G + j) selected that token (G = n_q_heads / n_kv_heads <= 32).  A
+ * decode step loads a listed row once if any ACTIVE head of the group stores it and
+ * lets exactly the heads that store it attend it, so the output equals
+ * omni_slim_decode on the per-head lists.
+ *   grp_idx  [batch, n_kv_heads, u_cap] i32, grp_mask [batch, n_kv_heads, u_cap] u32,
+ *   grp_cnt  [batch, n_kv_heads] i32 (the true union size; entries beyond u_cap are
+ *   dropped, so pass u_cap >= vis_end - vis_begin to be safe)
+ * omni_group_subset needs a workspace (OMNI_CALL_GROUP_SUBSET);
+ * omni_slim_decode_grouped the one of OMNI_CALL_SLIM_DECODE.
+ */
+int omni_group_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget,
+                      int32_t b_cap, int32_t* grp_idx, uint32_t* grp_mask, int32_t* grp_cnt,
+                      int32_t u_cap, void* ws, size_t ws_bytes, void* stream);
+int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q,
+                             const void* Kcache, const void* Vcache, const int32_t* ctx_len,
+                             const float* probe_keys,
+                             const int32_t* grp_idx, const uint32_t* grp_mask, const int32_t* grp_cnt,
+                             int32_t u_cap, void* O, uint8_t* active,
+                             void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Baselines used by the reported metric (not part of the method): plain causal

@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(_HERE, "libomnisparse.so")
 
 OMNI_F32, OMNI_BF16 = 0, 1
 (CALL_SCORE_QUERIES, CALL_SELECT_QUERIES, CALL_KV_BUDGET, CALL_SELECT_KV, CALL_SPARSE_ATTN_FWD,
- CALL_SPARSE_ATTN_BWD, CALL_SLIM_DECODE, CALL_DENSE_ATTN_FWD, CALL_DENSE_DECODE) = range(9)
+ CALL_SPARSE_ATTN_BWD, CALL_SLIM_DECODE, CALL_DENSE_ATTN_FWD, CALL_DENSE_DECODE, CALL_GROUP_SUBSET) = range(10)
 
 EXPORTED = [
     "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
     "omni_sparse_attn_fwd", "omni_sparse_attn_bwd", "omni_slim_decode", "omni_visual_subset",
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
     "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
+    "omni_group_subset", "omni_slim_decode_grouped",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -83,6 +84,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.omni_group_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
+    lib.omni_slim_decode_grouped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_profile_enable.argtypes = [C.c_int]
     lib.omni_debug_copy.argtypes = [vp, vp, sz, vp]
     lib.omni_debug_mfma_rate.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -381,6 +384,38 @@ def omni_slim_decode(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, v
     _check(lib.omni_slim_decode(C.byref(desc), _ptr(q), _ptr(Kcache), _ptr(Vcache), _ptr(ctx_len), _ptr(probe_keys),
                                 _ptr(vis_idx), _ptr(vis_cnt), b_cap, _ptr(O), _ptr(active), _ptr(buf), buf.numel(),
                                 _stream()))
+    return O, active
+
+
+def omni_group_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, u_cap: int | None = None,
+                      ws: Workspace | None = None):
+    """(grp_idx [B,Hkv,u_cap] i32, grp_mask [B,Hkv,u_cap] i32 holding the u32 bits, grp_cnt [B,Hkv] i32)."""
+    lib = load_library()
+    ws = ws or default_workspace()
+    if u_cap is None:
+        u_cap = desc.vis_end - desc.vis_begin
+    dev = kv_idx.device
+    grp_idx = torch.empty(desc.batch, desc.n_kv_heads, u_cap, dtype=torch.int32, device=dev)
+    grp_mask = torch.empty(desc.batch, desc.n_kv_heads, u_cap, dtype=torch.int32, device=dev)
+    grp_cnt = torch.empty(desc.batch, desc.n_kv_heads, dtype=torch.int32, device=dev)
+    buf = ws.get(CALL_GROUP_SUBSET, desc)
+    _check(lib.omni_group_subset(C.byref(desc), _ptr(kv_idx), _ptr(budget), b_cap, _ptr(grp_idx), _ptr(grp_mask),
+                                 _ptr(grp_cnt), u_cap, _ptr(buf), buf.numel(), _stream()))
+    return grp_idx, grp_mask, grp_cnt
+
+
+def omni_slim_decode_grouped(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_mask, grp_cnt,
+                             O=None, active=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if O is None:
+        O = torch.empty_like(q)
+    if active is None:
+        active = torch.empty(desc.batch, desc.n_q_heads, dtype=torch.uint8, device=q.device)
+    buf = ws.get(CALL_SLIM_DECODE, desc)
+    _check(lib.omni_slim_decode_grouped(C.byref(desc), _ptr(q), _ptr(Kcache), _ptr(Vcache), _ptr(ctx_len),
+                                        _ptr(probe_keys), _ptr(grp_idx), _ptr(grp_mask), _ptr(grp_cnt),
+                                        grp_idx.shape[-1], _ptr(O), _ptr(active), _ptr(buf), buf.numel(), _stream()))
     return O, active
 
 

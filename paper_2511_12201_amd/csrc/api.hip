@@ -242,6 +242,7 @@ size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param) {
       if (param < 1) { set_error("b_cap must be >= 1"); return 0; }
       return attn_bwd_ws(L, d->dtype, param);
     case OMNI_CALL_DENSE_ATTN_FWD: return attn_fwd_ws(L, d->dtype, L.N, false);
+    case OMNI_CALL_GROUP_SUBSET: return group_subset_ws(L);
     default: set_error("unknown call id %d", call_id); return 0;
   }
 }
@@ -326,6 +327,19 @@ int omni_visual_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const
   return run_visual_subset(make_layer(desc), kv_idx, budget, b_cap, vis_idx, vis_cnt, static_cast<hipStream_t>(stream));
 }
 
+int omni_group_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                      int32_t* grp_idx, uint32_t* grp_mask, int32_t* grp_cnt, int32_t u_cap, void* ws, size_t ws_bytes,
+                      void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(kv_idx); REQUIRE_PTR(budget); REQUIRE_PTR(grp_idx); REQUIRE_PTR(grp_mask); REQUIRE_PTR(grp_cnt);
+  if (b_cap < 1 || u_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap and u_cap must be >= 1");
+  if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, group_subset_ws(L)));
+  return run_group_subset(L, kv_idx, budget, b_cap, grp_idx, grp_mask, grp_cnt, u_cap, ws, static_cast<hipStream_t>(stream));
+}
+
 int omni_sparse_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
                          const int32_t* q_idx, const int32_t* q_cnt, const int32_t* kv_idx, const int32_t* budget,
                          int32_t b_cap, void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
@@ -382,7 +396,24 @@ int omni_slim_decode(const omni_decode_desc* desc, const void* q, const void* Kc
   if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
   if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
-  return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, vis_idx, vis_cnt, b_cap, O, active, ws,
+  return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, vis_idx, vis_cnt, nullptr, b_cap, O, active, ws,
+                    static_cast<hipStream_t>(stream));
+}
+
+int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,
+                             const int32_t* ctx_len, const float* probe_keys, const int32_t* grp_idx,
+                             const uint32_t* grp_mask, const int32_t* grp_cnt, int32_t u_cap, void* O, uint8_t* active,
+                             void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(q); REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(ctx_len); REQUIRE_PTR(probe_keys);
+  REQUIRE_PTR(grp_idx); REQUIRE_PTR(grp_mask); REQUIRE_PTR(grp_cnt); REQUIRE_PTR(O); REQUIRE_PTR(active);
+  REQUIRE_ALIGNED(q); REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache);
+  if (u_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "u_cap must be >= 1");
+  if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
+  if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
+  CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
+  return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
                     static_cast<hipStream_t>(stream));
 }
 
@@ -393,7 +424,7 @@ int omni_dense_decode(const omni_decode_desc* desc, const void* q, const void* K
   REQUIRE_PTR(q); REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(ctx_len); REQUIRE_PTR(O);
   REQUIRE_ALIGNED(q); REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache);
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
-  return run_decode(desc, q, Kcache, Vcache, ctx_len, nullptr, nullptr, nullptr, 1, O, nullptr, ws,
+  return run_decode(desc, q, Kcache, Vcache, ctx_len, nullptr, nullptr, nullptr, nullptr, 1, O, nullptr, ws,
                     static_cast<hipStream_t>(stream));
 }
 

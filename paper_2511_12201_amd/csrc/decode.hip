@@ -1,12 +1,25 @@
 // Decode step with KV cache slimming (paper Sec. "KV Cache Slimming",
 // decoding-attention equation) and the plain decode baseline.
 //
-// HBM-bound: one query row per head, so no matrix cores.  The row list of a head
-// (its stored visual rows if the decoding query is active, then every
-// non-visual row below ctx_len) is split over `nsplit` workgroups; a cache row
-// is read by D*sizeof(T)/16 lanes with one 16-byte load each for K and for V.
-// Every lane group keeps an online-softmax state; groups, then splits, are
-// merged with the usual (max, sum, weighted output) rule in a fixed order.
+// HBM-bound: one query row per head, so the job is to stream cache rows at memory speed and read
+// each of them as few times as possible.  Two kinds of workgroups write partial softmax states:
+//
+//  * shared rows -- rows that every head of a KV group attends (the whole context for the plain
+//    decode, the non-visual rows for the slimmed one).  One workgroup handles a slice of these
+//    rows for ALL heads of the group: a row's K and V are loaded once and used for every head.
+//  * per-head rows -- the stored visual rows of one query head, read through its index list, only
+//    if the head's decoding query is active (omni_slim_decode).
+//  * group rows -- the union of the stored visual rows of the heads of a KV group with a membership
+//    bit per head (omni_slim_decode_grouped): a row is loaded once if any ACTIVE head of the group
+//    stores it, and only the heads that store it see it.  Under grouped-query attention this is
+//    what turns fewer rows per head into fewer bytes from HBM, since the plain decode already
+//    shares every row between the heads of a group.
+//
+// A cache row is read by D*sizeof(T)/16 lanes with one 16-byte load each for K and for V; a lane
+// group has kUnroll rows in flight per iteration.  bf16 dot products use the packed dot
+// instruction on the raw 16-byte chunks (products of bf16 pairs are exact in fp32).  Every lane
+// group keeps an online-softmax state per head; groups, then slices, are merged with the usual
+// (max, sum, weighted output) rule in a fixed order, so results are bitwise reproducible.
 #include "common.h"
 #include "kernels.h"
 
@@ -15,7 +28,10 @@ namespace omni {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kRowsPerSlice = 512;   // target rows of one workgroup
+constexpr int kMaxSlices = 256;
 
 struct DecodeParams {
   const void* q;
@@ -23,181 +39,420 @@ struct DecodeParams {
   const void* V;
   const int* ctx_len;
   const float* probe;      // nullptr: plain decode (every head attends every row)
-  const int* vis_idx;
+  const int* vis_idx;      // per-head lists [B*Hq, b_cap], or group lists [B*Hkv, b_cap] (grouped call)
   const int* vis_cnt;
+  const unsigned* grp_mask; // membership bits of the group lists, nullptr for the per-head call
   int b_cap;
   void* O;
   unsigned char* active;
-  float* part;             // [B*Hq, nsplit, D + 2]
-  int B, Hq, Hkv, G, D, cap, v0, v1, nsplit;
+  float* part;             // [B*Hq, n_shared + n_head, D + 2]
+  int B, Hq, Hkv, G, D, cap, v0, v1;
+  int n_shared, n_head;    // slices of the shared rows / of a head's own rows
   float scale, tau;
   long long ks[3];
 };
 
-template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeParams p) {
+// dot of a lane's chunk of q with its chunk of a key row
+__device__ __forceinline__ float chunk_dot(const u32x4& qraw, const u32x4& kraw, const u16*) {
+  float qv[8], kv[8];
+  unpack16(qraw, qv, (const u16*)nullptr);
+  unpack16(kraw, kv, (const u16*)nullptr);
+  float acc = qv[0] * kv[0];
+#pragma unroll
+  for (int e = 1; e < 8; ++e) acc = fmaf(qv[e], kv[e], acc);
+  return acc;
+}
+__device__ __forceinline__ float chunk_dot(const u32x4& qraw, const u32x4& kraw, const float*) {
+  float acc = __uint_as_float(qraw.x) * __uint_as_float(kraw.x);
+  acc = fmaf(__uint_as_float(qraw.y), __uint_as_float(kraw.y), acc);
+  acc = fmaf(__uint_as_float(qraw.z), __uint_as_float(kraw.z), acc);
+  acc = fmaf(__uint_as_float(qraw.w), __uint_as_float(kraw.w), acc);
+  return acc;
+}
+
+// Sum over the LPR (a power of two) lanes that share a cache row; every lane gets the total.  Within
+// a row of 16 lanes the exchanges are DPP modifiers of the add itself (no LDS traffic).
+template <int LPR>
+__device__ __forceinline__ float row_group_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // lane ^ 2
+  if (LPR >= 8) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // 7 - lane in a half row
+  if (LPR >= 16) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true)); // 15 - lane in a row
+#pragma unroll
+  for (int o = 16; o < LPR; o <<= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Streams the rows [begin, end) of a virtual row list for GT heads at once and leaves the merged
+// partial state of the workgroup in part[head][slot].  row_of maps a list position to a cache row
+// or -1.  Every thread of the workgroup must call it (it contains barriers).
+// mask_of gives the heads (bit h = head0 + h) that attend the row; heads outside head_bits are skipped
+// altogether (a wave-uniform decision) and get an empty partial state.
+template <typename T, int D, int GT, typename RowOf, typename MaskOf>
+__device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g, int head0, int begin, int end,
+                                            RowOf row_of, MaskOf mask_of, unsigned head_bits, int slot) {
   constexpr int E = Elem<T>::kPer16B;
-  constexpr int LPR = D / E;
-  constexpr int RPP = kThreads / LPR;
-  __shared__ float sM[RPP], sL[RPP];
+  constexpr int LPR = D / E;              // lanes per row
+  constexpr int RPP = kThreads / LPR;     // lane groups = rows per pass
+  __shared__ float sM[GT][RPP], sL[GT][RPP];
   __shared__ float sO[RPP][D];
-  __shared__ int sActive;
-  const int split = blockIdx.x, bh = blockIdx.y;
-  const int b = bh / p.Hq, i = bh % p.Hq, g = i / p.G;
   const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
-  const T* qptr = static_cast<const T*>(p.q) + (long long)bh * D;
-  float qv[E];
-  {
-    u32x4 raw = *reinterpret_cast<const u32x4*>(qptr + c * E);
-    unpack16(raw, qv, (const T*)nullptr);
-  }
-  // lazy/active classification of the decoding query (every workgroup of the head repeats it)
-  int act = 1;
-  if (p.probe) {
-    if (threadIdx.x < 64) {
-      const float* pk = p.probe + ((long long)(b * p.Hkv + g) * 2) * D;
-      float dot = 0.f;
-      for (int d = threadIdx.x; d < D; d += 64) dot = fmaf(Elem<T>::load(qptr + d), pk[D + d] - pk[d], dot);
-      dot = wave_sum(dot);
-      if (threadIdx.x == 0) {
-        const float score = 1.0f / (1.0f + expf(-dot * p.scale));
-        sActive = (i == 0 || score > p.tau) ? 1 : 0;
-      }
-    }
-    __syncthreads();
-    act = sActive;
-    if (split == 0 && threadIdx.x == 0 && p.active) p.active[bh] = (unsigned char)act;
-  }
-  const int ctx = min(p.ctx_len[b], p.cap);
-  const int n_vis = (p.probe && act) ? min(p.vis_cnt[bh], p.b_cap) : 0;
-  const int n_lo = p.probe ? min(p.v0, ctx) : ctx;
-  const int hi0 = min(p.v1, ctx);
-  const int n_hi = p.probe ? ctx - hi0 : 0;
-  const int total = n_vis + n_lo + n_hi;
-  int per = cdiv(total, p.nsplit);
-  per = cdiv(per, RPP) * RPP;
-  const int begin = split * per, end = min(total, begin + per);
-  const int* vlist = p.vis_idx ? p.vis_idx + (long long)bh * p.b_cap : nullptr;
-  const T* kbase = static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1];
-  const T* vbase = static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1];
+  const T* kbase = static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1] + c * E;
+  const T* vbase = static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1] + c * E;
   const float c2 = p.scale * kLog2e;
 
-  float m = -INFINITY, l = 0.f, acc[E];
+  u32x4 qraw[GT];
 #pragma unroll
-  for (int e = 0; e < E; ++e) acc[e] = 0.f;
-  for (int it0 = begin; it0 < end; it0 += RPP) {     // uniform trip count over the workgroup
-    const int it = it0 + grp;
-    int row = -1;
-    if (it < end) {
-      if (it < n_vis) {
-        row = vlist[it];
-        if (row >= ctx) row = -1;                       // stored rows beyond the context are ignored
-      } else if (it < n_vis + n_lo) {
-        row = it - n_vis;
-      } else {
-        row = hi0 + (it - n_vis - n_lo);
+  for (int h = 0; h < GT; ++h)
+    qraw[h] = *reinterpret_cast<const u32x4*>(static_cast<const T*>(p.q) + (long long)(b * p.Hq + head0 + h) * D + c * E);
+  float m[GT], l[GT], acc[GT][E];
+#pragma unroll
+  for (int h = 0; h < GT; ++h) {
+    m[h] = -INFINITY;
+    l[h] = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[h][e] = 0.f;
+  }
+
+  for (int it0 = begin; it0 < end; it0 += RPP * kUnroll) {      // uniform trip count over the workgroup
+    int row[kUnroll];
+    unsigned member[kUnroll];
+    u32x4 kraw[kUnroll], vraw[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int it = it0 + u * RPP + grp;
+      row[u] = it < end ? row_of(it) : -1;
+      member[u] = (it < end && row[u] >= 0) ? (mask_of(it) & head_bits) : 0u;
+      if (member[u] == 0u) row[u] = -1;                     // nobody wants it: not loaded
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      kraw[u] = u32x4{0u, 0u, 0u, 0u};
+      vraw[u] = u32x4{0u, 0u, 0u, 0u};
+      if (row[u] >= 0) {
+        const long long off = (long long)row[u] * p.ks[2];
+        kraw[u] = *reinterpret_cast<const u32x4*>(kbase + off);
+        vraw[u] = *reinterpret_cast<const u32x4*>(vbase + off);
       }
     }
-    float dot = 0.f;
-    u32x4 vraw = {0u, 0u, 0u, 0u};
-    if (row >= 0) {
-      const u32x4 kraw = *reinterpret_cast<const u32x4*>(kbase + (long long)row * p.ks[2] + c * E);
-      vraw = *reinterpret_cast<const u32x4*>(vbase + (long long)row * p.ks[2] + c * E);
-      float kv[E];
-      unpack16(kraw, kv, (const T*)nullptr);
+    float s[GT][kUnroll];
 #pragma unroll
-      for (int e = 0; e < E; ++e) dot = fmaf(qv[e], kv[e], dot);
+    for (int h = 0; h < GT; ++h) {
+      if (!((head_bits >> h) & 1u)) continue;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) s[h][u] = row_group_sum<LPR>(chunk_dot(qraw[h], kraw[u], (const T*)nullptr));
     }
+    float vv[kUnroll][E];
 #pragma unroll
-    for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
-    if (row >= 0) {
-      const float s2 = dot * c2;
-      const float m_new = fmaxf(m, s2);
-      const float alpha = exp2f(m - m_new);          // m = -inf -> 0
-      const float pw = exp2f(s2 - m_new);
-      float vv[E];
-      unpack16(vraw, vv, (const T*)nullptr);
-      l = l * alpha + pw;
+    for (int u = 0; u < kUnroll; ++u) unpack16(vraw[u], vv[u], (const T*)nullptr);
 #pragma unroll
-      for (int e = 0; e < E; ++e) acc[e] = fmaf(acc[e], alpha, pw * vv[e]);
-      m = m_new;
+    for (int h = 0; h < GT; ++h) {
+      if (!((head_bits >> h) & 1u)) continue;
+      float mx = m[h];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        s[h][u] = ((member[u] >> h) & 1u) ? s[h][u] * c2 : -INFINITY;
+        mx = fmaxf(mx, s[h][u]);
+      }
+      const float mref = mx == -INFINITY ? 0.f : mx;
+      const float alpha = fast_exp2(m[h] - mref);               // m = -inf -> 0
+      float pw[kUnroll], ps = 0.f;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        pw[u] = fast_exp2(s[h][u] - mref);
+        ps += pw[u];
+      }
+      l[h] = fmaf(l[h], alpha, ps);
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        float a = acc[h][e] * alpha;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) a = fmaf(pw[u], vv[u][e], a);
+        acc[h][e] = a;
+      }
+      m[h] = mx;
     }
   }
-  // merge the lane groups of the workgroup in group order
-  if (c == 0) {
-    sM[grp] = m;
-    sL[grp] = l;
-  }
-#pragma unroll
-  for (int e = 0; e < E; ++e) sO[grp][c * E + e] = acc[e];
-  __syncthreads();
-  if (threadIdx.x < D) {
-    float M = -INFINITY;
-    for (int r = 0; r < RPP; ++r) M = fmaxf(M, sM[r]);
-    const float Mr = M == -INFINITY ? 0.f : M;
-    float Ls = 0.f, Os = 0.f;
-    for (int r = 0; r < RPP; ++r) {
-      const float w = sM[r] == -INFINITY ? 0.f : exp2f(sM[r] - Mr);
-      Ls = fmaf(sL[r], w, Ls);
-      Os = fmaf(sO[r][threadIdx.x], w, Os);
+
+  if (begin >= end) {                       // empty slice: mark it, the combine pass skips its output row
+    if (threadIdx.x < GT) {
+      float* dst = p.part + ((long long)(b * p.Hq + head0 + threadIdx.x) * (p.n_shared + p.n_head) + slot) * (D + 2);
+      dst[D] = -INFINITY;
+      dst[D + 1] = 0.f;
     }
-    float* dst = p.part + ((long long)bh * p.nsplit + split) * (D + 2);
-    dst[threadIdx.x] = Os;
-    if (threadIdx.x == 0) {
-      dst[D] = M;
-      dst[D + 1] = Ls;
+    return;
+  }
+  // merge the lane groups of the workgroup in group order, one head at a time
+#pragma unroll
+  for (int h = 0; h < GT; ++h) {
+    __syncthreads();
+    if (c == 0) {
+      sM[h][grp] = m[h];
+      sL[h][grp] = l[h];
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) sO[grp][c * E + e] = acc[h][e];
+    __syncthreads();
+    if (threadIdx.x < D) {
+      float M = -INFINITY;
+      for (int r = 0; r < RPP; ++r) M = fmaxf(M, sM[h][r]);
+      const float Mr = M == -INFINITY ? 0.f : M;
+      float Ls = 0.f, Os = 0.f;
+      for (int r = 0; r < RPP; ++r) {
+        const float w = sM[h][r] == -INFINITY ? 0.f : exp2f(sM[h][r] - Mr);
+        Ls = fmaf(sL[h][r], w, Ls);
+        Os = fmaf(sO[r][threadIdx.x], w, Os);
+      }
+      float* dst = p.part + ((long long)(b * p.Hq + head0 + h) * (p.n_shared + p.n_head) + slot) * (D + 2);
+      dst[threadIdx.x] = Os;
+      if (threadIdx.x == 0) {
+        dst[D] = M;
+        dst[D + 1] = Ls;
+      }
     }
   }
 }
 
+// Shared rows of one KV group, GT heads per workgroup.  grid = (n_shared, B * Hkv * (G / GT)).
+template <typename T, int D, int GT>
+__global__ __launch_bounds__(kThreads) void decode_shared_kernel(DecodeParams p) {
+  constexpr int RPP = kThreads / (D / Elem<T>::kPer16B);
+  const int slice = blockIdx.x;
+  const int chunks = p.G / GT;
+  const int unit = blockIdx.y, chunk = unit % chunks, bg = unit / chunks;
+  const int b = bg / p.Hkv, g = bg % p.Hkv;
+  const int ctx = min(p.ctx_len[b], p.cap);
+  const int n_lo = p.probe ? min(p.v0, ctx) : ctx;       // rows below the visual segment (all rows if plain)
+  const int hi0 = min(p.v1, ctx);
+  const int n_hi = p.probe ? ctx - hi0 : 0;              // rows above it
+  const int total = n_lo + n_hi;
+  int per = cdiv(total, p.n_shared);
+  per = cdiv(per, RPP * kUnroll) * (RPP * kUnroll);
+  const int begin = min(total, slice * per), end = min(total, begin + per);
+  stream_rows<T, D, GT>(p, b, g, g * p.G + chunk * GT, begin, end,
+                        [&](int it) { return it < n_lo ? it : hi0 + (it - n_lo); }, [](int) { return ~0u; },
+                        (1u << GT) - 1u, slice);
+}
+
+// A head's own (stored visual) rows.  grid = (n_head, B * Hq).  Also classifies the decoding query.
 template <typename T, int D>
-__global__ void decode_combine_kernel(DecodeParams p) {
-  const int bh = blockIdx.x, d = threadIdx.x;
-  if (d >= D) return;
-  const float* src = p.part + (long long)bh * p.nsplit * (D + 2);
-  float M = -INFINITY;
-  for (int s = 0; s < p.nsplit; ++s) M = fmaxf(M, src[s * (D + 2) + D]);
-  const float Mr = M == -INFINITY ? 0.f : M;
-  float Ls = 0.f, Os = 0.f;
-  for (int s = 0; s < p.nsplit; ++s) {
-    const float ms = src[s * (D + 2) + D];
-    const float w = ms == -INFINITY ? 0.f : exp2f(ms - Mr);
-    Ls = fmaf(src[s * (D + 2) + D + 1], w, Ls);
-    Os = fmaf(src[s * (D + 2) + d], w, Os);
+__global__ __launch_bounds__(kThreads) void decode_head_kernel(DecodeParams p) {
+  constexpr int RPP = kThreads / (D / Elem<T>::kPer16B);
+  __shared__ int sActive;
+  const int slice = blockIdx.x, bh = blockIdx.y;
+  const int b = bh / p.Hq, i = bh % p.Hq, g = i / p.G;
+  if (threadIdx.x < 64) {
+    const T* qptr = static_cast<const T*>(p.q) + (long long)bh * D;
+    const float* pk = p.probe + ((long long)(b * p.Hkv + g) * 2) * D;
+    float dot = 0.f;
+    for (int d = threadIdx.x; d < D; d += 64) dot = fmaf(Elem<T>::load(qptr + d), pk[D + d] - pk[d], dot);
+    dot = wave_sum(dot);
+    if (threadIdx.x == 0) {
+      const float score = 1.0f / (1.0f + expf(-dot * p.scale));
+      sActive = (i == 0 || score > p.tau) ? 1 : 0;
+    }
   }
-  Elem<T>::store(static_cast<T*>(p.O) + (long long)bh * D + d, Ls > 0.f ? Os / Ls : 0.f);
+  __syncthreads();
+  const int act = sActive;
+  if (slice == 0 && threadIdx.x == 0 && p.active) p.active[bh] = (unsigned char)act;
+  const int ctx = min(p.ctx_len[b], p.cap);
+  const int total = act ? min(p.vis_cnt[bh], p.b_cap) : 0;
+  int per = cdiv(total, p.n_head);
+  per = cdiv(per, RPP * kUnroll) * (RPP * kUnroll);
+  const int begin = min(total, slice * per), end = min(total, begin + per);
+  const int* vlist = p.vis_idx + (long long)bh * p.b_cap;
+  stream_rows<T, D, 1>(p, b, g, i, begin, end,
+                       [&](int it) {
+                         const int r = vlist[it];
+                         return r < ctx ? r : -1;          // stored rows beyond the context are ignored
+                       },
+                       [](int) { return 1u; }, 1u, p.n_shared + slice);
+}
+
+// The union list of a KV group, GT heads per workgroup.  grid = (n_head, B * Hkv * (G / GT)).  Classifies the
+// decoding queries of its heads first: only active heads take part.
+template <typename T, int D, int GT>
+__global__ __launch_bounds__(kThreads) void decode_group_kernel(DecodeParams p) {
+  constexpr int RPP = kThreads / (D / Elem<T>::kPer16B);
+  __shared__ unsigned sBits;
+  const int slice = blockIdx.x;
+  const int chunks = p.G / GT;
+  const int unit = blockIdx.y, chunk = unit % chunks, bg = unit / chunks;
+  const int b = bg / p.Hkv, g = bg % p.Hkv;
+  const int head0 = g * p.G + chunk * GT;
+  if (threadIdx.x == 0) sBits = 0u;
+  __syncthreads();
+  {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float* pk = p.probe + ((long long)(b * p.Hkv + g) * 2) * D;
+    for (int h = wave; h < GT; h += kThreads / 64) {
+      const int i = head0 + h;
+      const T* qptr = static_cast<const T*>(p.q) + (long long)(b * p.Hq + i) * D;
+      float dot = 0.f;
+      for (int d = lane; d < D; d += 64) dot = fmaf(Elem<T>::load(qptr + d), pk[D + d] - pk[d], dot);
+      dot = wave_sum(dot);
+      if (lane == 0) {
+        const float score = 1.0f / (1.0f + expf(-dot * p.scale));
+        const int act = (i == 0 || score > p.tau) ? 1 : 0;
+        if (act) atomicOr(&sBits, 1u << h);
+        if (slice == 0 && p.active) p.active[b * p.Hq + i] = (unsigned char)act;
+      }
+    }
+  }
+  __syncthreads();
+  const unsigned bits = sBits;
+  const int ctx = min(p.ctx_len[b], p.cap);
+  const int total = bits ? min(p.vis_cnt[bg], p.b_cap) : 0;
+  int per = cdiv(total, p.n_head);
+  per = cdiv(per, RPP * kUnroll) * (RPP * kUnroll);
+  const int begin = min(total, slice * per), end = min(total, begin + per);
+  const int* vlist = p.vis_idx + (long long)bg * p.b_cap;
+  const unsigned* mlist = p.grp_mask + (long long)bg * p.b_cap;
+  const int shift = chunk * GT;
+  stream_rows<T, D, GT>(p, b, g, head0, begin, end,
+                        [&](int it) {
+                          const int r = vlist[it];
+                          return r < ctx ? r : -1;
+                        },
+                        [&](int it) { return mlist[it] >> shift; }, bits, p.n_shared + slice);
+}
+
+// Merges the slices of one head.  grid = B * Hq, kCombineThreads threads: lane groups of D/2 threads (two
+// output elements each) take the slices round-robin with many independent loads in flight, then the
+// groups are summed in group order.
+constexpr int kCombineThreads = 1024;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(DecodeParams p) {
+  constexpr int LG = D / 2;                        // threads per slice
+  constexpr int NG = kCombineThreads / LG;         // slices in flight per pass
+  __shared__ float sRed[kCombineThreads / 64];
+  __shared__ float sMax;
+  __shared__ float sL[NG];
+  __shared__ float sO[NG][D];
+  const int bh = blockIdx.x;
+  const int n = p.n_shared + p.n_head;
+  const float* src = p.part + (long long)bh * n * (D + 2);
+  // global maximum over the slices
+  float M = -INFINITY;
+  for (int s = threadIdx.x; s < n; s += kCombineThreads) M = fmaxf(M, src[s * (D + 2) + D]);
+  M = wave_max(M);
+  if ((threadIdx.x & 63) == 0) sRed[threadIdx.x >> 6] = M;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float m = -INFINITY;
+    for (int w = 0; w < kCombineThreads / 64; ++w) m = fmaxf(m, sRed[w]);
+    sMax = m;
+  }
+  __syncthreads();
+  const float Mr = sMax == -INFINITY ? 0.f : sMax;
+  const int grp = threadIdx.x / LG, c = threadIdx.x % LG;
+  float Ls = 0.f, O0 = 0.f, O1 = 0.f;
+  for (int s = grp; s < n; s += NG) {
+    const float* row = src + s * (D + 2);
+    const float ms = row[D];
+    if (ms == -INFINITY) continue;                 // empty slice or nothing visible in it: its output row may be unwritten
+    const float w = exp2f(ms - Mr);
+    const float2 o = *reinterpret_cast<const float2*>(row + 2 * c);
+    Ls = fmaf(row[D + 1], w, Ls);
+    O0 = fmaf(o.x, w, O0);
+    O1 = fmaf(o.y, w, O1);
+  }
+  if (c == 0) sL[grp] = Ls;
+  sO[grp][2 * c] = O0;
+  sO[grp][2 * c + 1] = O1;
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float Lt = 0.f, Ot = 0.f;
+    for (int g2 = 0; g2 < NG; ++g2) {
+      Lt += sL[g2];
+      Ot += sO[g2][threadIdx.x];
+    }
+    Elem<T>::store(static_cast<T*>(p.O) + (long long)bh * D + threadIdx.x, Lt > 0.f ? Ot / Lt : 0.f);
+  }
+}
+
+// heads of a KV group handled by one workgroup of the shared-row kernel: the largest supported divisor of G
+int group_tile(int G) {
+  if (G % 8 == 0) return 8;
+  if (G % 7 == 0) return 7;
+  if (G % 4 == 0) return 4;
+  if (G % 2 == 0) return 2;
+  return 1;
+}
+
+template <typename T, int D, int GT>
+void launch_shared(const DecodeParams& p, hipStream_t st) {
+  hipLaunchKernelGGL((decode_shared_kernel<T, D, GT>), dim3(p.n_shared, p.B * p.Hkv * (p.G / GT)), dim3(kThreads), 0,
+                     st, p);
+  if (p.grp_mask && p.n_head > 0)
+    hipLaunchKernelGGL((decode_group_kernel<T, D, GT>), dim3(p.n_head, p.B * p.Hkv * (p.G / GT)), dim3(kThreads), 0,
+                       st, p);
 }
 
 template <typename T, int D>
 int launch_decode(const DecodeParams& p, hipStream_t st) {
   {
     ProfScope prof__(kProfDecode, st);
-    hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3(p.nsplit, p.B * p.Hq), dim3(kThreads), 0, st, p);
+    switch (group_tile(p.G)) {
+      case 8: launch_shared<T, D, 8>(p, st); break;
+      case 7: launch_shared<T, D, 7>(p, st); break;
+      case 4: launch_shared<T, D, 4>(p, st); break;
+      case 2: launch_shared<T, D, 2>(p, st); break;
+      default: launch_shared<T, D, 1>(p, st); break;
+    }
+    OMNI_LAUNCH_CHECK();
+    if (!p.grp_mask && p.n_head > 0) {
+      hipLaunchKernelGGL((decode_head_kernel<T, D>), dim3(p.n_head, p.B * p.Hq), dim3(kThreads), 0, st, p);
+      OMNI_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(p.B * p.Hq), dim3(kCombineThreads), 0, st, p);
     OMNI_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(p.B * p.Hq), dim3(128), 0, st, p);
-  OMNI_LAUNCH_CHECK();
   return OMNI_OK;
+}
+
+int slices_for(long long rows, int units, int target_blocks) {
+  // enough workgroups to fill the chip a few times over, but no slice much below kRowsPerSlice rows
+  long long s = cdiv(rows, (long long)kRowsPerSlice);
+  const long long want = cdiv(target_blocks, units);
+  if (s > want) s = want;
+  if (s < 1) s = 1;
+  if (s > kMaxSlices) s = kMaxSlices;
+  return (int)s;
+}
+
+struct Slices {
+  int n_shared, n_head;
+};
+
+// Slice counts depend on the descriptor only (not on device-side counts), so the workspace size is static.
+Slices decode_slices(const omni_decode_desc* d, bool slim) {
+  Slices s;
+  const int G = d->n_q_heads / d->n_kv_heads;
+  const int units = d->batch * d->n_kv_heads * (G / group_tile(G));
+  const long long shared_rows = slim ? (long long)d->cache_capacity - (d->vis_end - d->vis_begin) : d->cache_capacity;
+  s.n_shared = slices_for(shared_rows, units, 2048);
+  // only the active heads (typically a quarter) have rows to read, so aim higher
+  s.n_head = slim ? slices_for(d->vis_end - d->vis_begin, d->batch * d->n_q_heads, 8192) : 0;
+  return s;
 }
 
 }  // namespace
 
-int decode_splits(int batch, int n_q_heads) {
-  int s = cdiv(2048, batch * n_q_heads);
-  if (s < 1) s = 1;
-  if (s > 64) s = 64;
-  return s;
-}
-
 size_t decode_ws(const omni_decode_desc* d) {
   Arena a(nullptr);
-  a.take<float>((size_t)d->batch * d->n_q_heads * decode_splits(d->batch, d->n_q_heads) * (d->head_dim + 2));
+  // one size for both calls: the larger of the slimmed and the plain slice counts
+  const Slices s1 = decode_slices(d, true);
+  const Slices s0 = decode_slices(d, false);
+  const int n = s1.n_shared + s1.n_head > s0.n_shared ? s1.n_shared + s1.n_head : s0.n_shared;
+  a.take<float>((size_t)d->batch * d->n_q_heads * n * (d->head_dim + 2));
   return a.used();
 }
 
 int run_decode(const omni_decode_desc* d, const void* q, const void* K, const void* V, const int* ctx_len,
-               const float* probe, const int* vis_idx, const int* vis_cnt, int b_cap, void* O,
-               unsigned char* active, void* ws, hipStream_t st) {
+               const float* probe, const int* vis_idx, const int* vis_cnt, const unsigned* grp_mask, int b_cap,
+               void* O, unsigned char* active, void* ws, hipStream_t st) {
   Arena a(ws);
   DecodeParams p;
   p.q = q;
@@ -207,6 +462,7 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
   p.probe = probe;
   p.vis_idx = vis_idx;
   p.vis_cnt = vis_cnt;
+  p.grp_mask = grp_mask;
   p.b_cap = b_cap;
   p.O = O;
   p.active = active;
@@ -218,11 +474,13 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
   p.cap = d->cache_capacity;
   p.v0 = d->vis_begin;
   p.v1 = d->vis_end;
-  p.nsplit = decode_splits(p.B, p.Hq);
+  const Slices s = decode_slices(d, probe != nullptr);
+  p.n_shared = s.n_shared;
+  p.n_head = s.n_head;
   p.scale = d->softmax_scale;
   p.tau = d->tau;
   for (int k = 0; k < 3; ++k) p.ks[k] = d->kv_stride[k];
-  p.part = a.take<float>((size_t)p.B * p.Hq * p.nsplit * (p.D + 2));
+  p.part = a.take<float>((size_t)p.B * p.Hq * (p.n_shared + p.n_head) * (p.D + 2));
   if (d->dtype == OMNI_BF16) {
     if (p.D == 128) return launch_decode<u16, 128>(p, st);
     return launch_decode<u16, 64>(p, st);

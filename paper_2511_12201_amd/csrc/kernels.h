@@ -21,6 +21,9 @@ int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, in
                      int* flattest, int* budget, float* recall, void* ws, hipStream_t st);
 int run_visual_subset(const Layer& L, const int* kv_idx, const int* budget, int b_cap, int* vis_idx, int* vis_cnt,
                       hipStream_t st);
+size_t group_subset_ws(const Layer& L);
+int run_group_subset(const Layer& L, const int* kv_idx, const int* budget, int b_cap, int* grp_idx, unsigned* grp_mask,
+                     int* grp_cnt, int u_cap, void* ws, hipStream_t st);
 
 // probe.hip
 size_t probe_ws(const Layer& L, int dtype, int pb);
@@ -49,9 +52,10 @@ int run_attn_bwd(const Layer& L, int dtype, const void* Q, const void* K, const 
 
 // decode.hip
 size_t decode_ws(const omni_decode_desc* d);
+// grp_mask == nullptr: vis_idx / vis_cnt are per query head; otherwise per KV group with membership bits
 int run_decode(const omni_decode_desc* d, const void* q, const void* K, const void* V, const int* ctx_len,
-               const float* probe, const int* vis_idx, const int* vis_cnt, int b_cap, void* O,
-               unsigned char* active, void* ws, hipStream_t st);
+               const float* probe, const int* vis_idx, const int* vis_cnt, const unsigned* grp_mask, int b_cap,
+               void* O, unsigned char* active, void* ws, hipStream_t st);
 
 // diag.hip
 int run_calibration_copy(const void* src, void* dst, size_t bytes, hipStream_t st);

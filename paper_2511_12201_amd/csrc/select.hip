@@ -11,6 +11,8 @@
 #include <cmath>
 #include <cstring>
 
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -622,6 +624,86 @@ int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, in
   }
   hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, 0, L.N, 0, budget,
                      L.N, 0, thr, need, recall, (float)L.N);
+  OMNI_LAUNCH_CHECK();
+  return OMNI_OK;
+}
+
+// ---- union of the stored visual rows over the heads of a KV group, with a membership bit per head
+// (paper Sec. "KV Cache Slimming": per-head token-level storage; under grouped-query attention the heads
+// of a group index one shared cache, so the group's union is what a decode step can touch at all)
+
+__global__ void fill_u32_kernel(unsigned* p, long long n, unsigned v) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+
+// grid: (cdiv(b_cap, 256), B*Hq)
+__global__ void group_mark_kernel(const int* __restrict__ kv_idx, const int* __restrict__ budget, int Hq, int Hkv, int b_cap,
+                                  int v0, int v1, unsigned* __restrict__ umask) {
+  const int bh = blockIdx.y, b = bh / Hq, i = bh % Hq, G = Hq / Hkv, g = i / G;
+  const int n = min(budget[b], b_cap);
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  const int tok = kv_idx[(long long)bh * b_cap + t];
+  if (tok < v0 || tok >= v1) return;
+  atomicOr(&umask[(long long)(b * Hkv + g) * (v1 - v0) + (tok - v0)], 1u << (i % G));
+}
+
+// grid: B*Hkv, 1024 threads.  Ordered compaction of the marked tokens.
+__global__ __launch_bounds__(1024) void group_compact_kernel(const unsigned* __restrict__ umask, int nv, int v0, int u_cap,
+                                                             int* __restrict__ grp_idx, unsigned* __restrict__ grp_mask,
+                                                             int* __restrict__ grp_cnt) {
+  __shared__ int wave_cnt[16];
+  __shared__ int base;
+  const int bg = blockIdx.x;
+  const unsigned* src = umask + (long long)bg * nv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  for (int c0 = 0; c0 < nv; c0 += 1024) {
+    const int t = c0 + threadIdx.x;
+    const unsigned m = t < nv ? src[t] : 0u;
+    const unsigned long long bal = __ballot(m != 0u);
+    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    __syncthreads();
+    int off = base;
+    for (int w = 0; w < wave; ++w) off += wave_cnt[w];
+    off += __popcll(bal & ((1ull << lane) - 1ull));
+    if (m != 0u && off < u_cap) {
+      grp_idx[(long long)bg * u_cap + off] = v0 + t;
+      grp_mask[(long long)bg * u_cap + off] = m;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int tot = 0;
+      for (int w = 0; w < 16; ++w) tot += wave_cnt[w];
+      base += tot;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) grp_cnt[bg] = base;
+}
+
+size_t group_subset_ws(const Layer& L) {
+  Arena a(nullptr);
+  a.take<unsigned>((size_t)L.B * L.Hkv * (L.v1 - L.v0));
+  return a.used();
+}
+
+int run_group_subset(const Layer& L, const int* kv_idx, const int* budget, int b_cap, int* grp_idx, unsigned* grp_mask,
+                     int* grp_cnt, int u_cap, void* ws, hipStream_t st) {
+  Arena a(ws);
+  const int nv = L.v1 - L.v0;
+  const long long n = (long long)L.B * L.Hkv * nv;
+  unsigned* umask = a.take<unsigned>((size_t)n);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<long long>(cdiv(n, 256LL), 4096)), dim3(256), 0, st, umask, n,
+                     0u);
+  OMNI_LAUNCH_CHECK();
+  hipLaunchKernelGGL(group_mark_kernel, dim3(cdiv(b_cap, 256), L.B * L.Hq), dim3(256), 0, st, kv_idx, budget, L.Hq, L.Hkv,
+                     b_cap, L.v0, L.v1, umask);
+  OMNI_LAUNCH_CHECK();
+  hipLaunchKernelGGL(group_compact_kernel, dim3(L.B * L.Hkv), dim3(1024), 0, st, umask, nv, L.v0, u_cap, grp_idx, grp_mask,
+                     grp_cnt);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
 }

@@ -288,6 +288,46 @@ def test_slim_decode_and_dense_decode(cfg, batch):
     assert np.max(np.abs(to_host(Od) - oc.dense_decode(q, Kc, Vc, ctx, cfg.scale))) <= tol
 
 
+@pytest.mark.parametrize("cfg,batch", [(CFG_BF16, 1), (CFG_BF16, 3), (CFG_BF16_64, 2), (CFG_F32, 2), (CFG_F32_128, 1)],
+                         ids=lambda x: getattr(x, "name", str(x)))
+def test_grouped_slim_decode(cfg, batch):
+    """Group-union storage of the visual rows: the structure is the union of the per-head sets with the
+    right membership bits, and the decode step on it gives the oracle's per-head result."""
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    tau = 0.08
+    H, Hkv = cfg.n_q_heads, cfg.n_kv_heads
+    G = H // Hkv
+    b = len(c.o_kvidx[0][0])
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])] * batch, H, b)
+    budget = torch.full((batch,), b, dtype=torch.int32, device="cuda")
+    ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                               cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset(ldesc, kv_idx, budget, b)
+    torch.cuda.synchronize()
+    gi, gm, gc = to_host(grp_idx), to_host(grp_mask).view(np.uint32), to_host(grp_cnt)
+    for bb in range(batch):
+        for g in range(Hkv):
+            sets = [set(int(x) for x in vis[bb][g * G + j]) for j in range(G)]
+            union = sorted(set().union(*sets))
+            n = int(gc[bb, g])
+            assert n == len(union)
+            np.testing.assert_array_equal(gi[bb, g, :n], np.array(union, dtype=np.int32))
+            want = np.array([sum((1 << j) for j in range(G) if t in sets[j]) for t in union], dtype=np.uint32)
+            np.testing.assert_array_equal(gm[bb, g, :n], want)
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    dctx = torch.from_numpy(ctx).cuda()
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    desc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau)
+    O, act = ob.omni_slim_decode_grouped(desc, dq, dKc, dVc, dctx, dprobe, grp_idx, grp_mask, grp_cnt)
+    torch.cuda.synchronize()
+    Oo, acto, sc = oc.slim_decode(q, Kc, Vc, ctx, probe.astype(np.float32), vis, tau, cfg.vis_begin, cfg.vis_end, cfg.scale)
+    act = to_host(act)
+    clear = np.abs(sc - tau) > 1e-5
+    np.testing.assert_array_equal(act[clear], acto[clear])
+    same = act == acto
+    assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
+
+
 def test_visual_subset_matches_oracle():
     cfg = CFG_BF16
     c = case_for(cfg)
