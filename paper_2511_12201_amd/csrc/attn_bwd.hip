@@ -52,6 +52,8 @@ struct BwdParams {
   float* dVp;
   void* dQ;
   int* sched;           // work list of the dQ kernel (sched.h)
+  const int* qvis;      // [B*Hq, N] visible packed keys per kept-query position (bf16 fast path)
+  const int* kfirst;    // [B*Hq, npad] first kept-query position that sees a packed key
 };
 
 // first position in ascending a[0,n) with a[pos] >= v
@@ -561,6 +563,210 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p) {
   }  // work-item loop
 }
 
+// ------------------------------------------------------------------ dQ, bf16 fast path
+//
+// Same organisation as the bf16 forward kernel: 512 threads = 8 wavefronts x 32 kept queries (256-row work
+// items from the XCD-aware persistent list), K / V / K^T tiles of 64 keys streamed memory -> LDS with
+// LDS-DMA loads into a ring of kDqStages buffers (natural tiles unpadded with the XOR chunk swizzle), one
+// barrier per tile, the loads of tile t+2 spread over the MFMAs of tile t, causal mask from the per-query
+// visible-prefix count.  Per tile and wavefront: S^T = K Q^T and dP^T = V dO^T (32 MFMAs), dS^T on the
+// vector ALU, dQ^T += K^T dS^T (16 MFMAs).
+
+constexpr int kDqWaves = 8;
+constexpr int kDqThreads = kDqWaves * 64;
+constexpr int kDqTileM = kDqWaves * 32;
+constexpr int kDqStages = 3;
+
+template <int D>
+__global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdParams p) {
+  typedef u16 T;
+  constexpr int CH = D / 8;                          // 16-byte chunks per natural row
+  constexpr int kOpBytes = kTileN * D * 2;           // one operand tile
+  constexpr int kStageBytes = 3 * kOpBytes;          // K natural, V natural, K k-packed
+  constexpr int LPH = kOpBytes / 1024 / kDqWaves;    // load instructions per operand per wavefront per tile
+  constexpr int LPT = 3 * LPH;
+  constexpr int NB = D / 32;
+  static_assert(LPH >= 1, "tile too small for the copy scheme");
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kDqStages * kStageBytes];
+  __shared__ int sBound[2];
+  __shared__ int sItem;
+
+  const Layer& L = p.L;
+  const int BH = L.B * L.Hq;
+  const int xcd = xcc_id();
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int ln = lane & 31, h = lane >> 5;
+  const float c2 = L.scale * kLog2e;
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+  int ngoff[LPH], pgoff[LPH];                        // element offsets of this lane's 16-byte chunk: natural (swizzled), packed
+#pragma unroll
+  for (int j = 0; j < LPH; ++j) {
+    const int pchunk = (j * kDqWaves + wave) * 64 + lane;
+    const int row = pchunk / CH, pc = pchunk % CH;
+    ngoff[j] = row * D + ((pc ^ (row % CH)) << 3);
+    pgoff[j] = pchunk << 3;
+  }
+  const int krow_b = ln * (CH * 16);
+  const int khx = (h << 4) ^ ((ln % CH) << 4);
+  const int plane_b = (h * D + ln) * 16;
+
+  for (;;) {
+  __syncthreads();
+  if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
+  __syncthreads();
+  const int item = sItem;
+  if (item < 0) break;
+  int bh, tq;
+  sched_decode(p.sched, BH, item, bh, tq);
+  const int b = bh / L.Hq, i = bh % L.Hq;
+  const int nq = p.q_cnt[bh];
+  const int* qlist = p.q_idx + (long long)bh * L.N;
+  const int* qvis = p.qvis + (long long)bh * L.N;
+
+  const int pos_first = tq * kDqTileM, pos_last = min(pos_first + kDqTileM, nq) - 1;
+  if (threadIdx.x == 0 || threadIdx.x == 64) sBound[threadIdx.x ? 1 : 0] = qvis[threadIdx.x ? pos_last : pos_first];
+  __syncthreads();
+  const int n_full_tiles = sBound[0] / kTileN;
+  const int ntiles = cdiv(sBound[1], kTileN);
+
+  const int qpos = pos_first + wave * 32 + ln;
+  const bool qvalid = qpos < nq;
+  const int qpos_c = min(qpos, nq - 1);
+  const int qrow = qlist[qpos_c];
+  const int qvisible = qvis[qpos_c] - 4 * h;
+  const float lse2 = p.lse2c[(long long)bh * p.nqpad + qpos_c];
+  const float delta = p.deltac[(long long)bh * p.nqpad + qpos_c];
+  const T* qptr = static_cast<const T*>(p.Q) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+  const T* gptr = static_cast<const T*>(p.dO) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+  bf16x8 qf[D / 16], gf[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    qf[ks] = *reinterpret_cast<const bf16x8*>(qptr + ks * 16 + h * 8);
+    gf[ks] = *reinterpret_cast<const bf16x8*>(gptr + ks * 16 + h * 8);
+  }
+  float lse2r = lse2, deltar = delta;
+  // finish every ordinary load here: a compiler-placed wait inside the tile loop would drain the ring
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    asm volatile("" : "+v"(qf[ks]));
+    asm volatile("" : "+v"(gf[ks]));
+  }
+  asm volatile("" : "+v"(lse2r), "+v"(deltar));
+
+  f32x16 dq[NB];
+#pragma unroll
+  for (int db = 0; db < NB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
+
+  const T* kn = static_cast<const T*>(p.Kn) + (long long)bh * p.npad * D;
+  const T* vn = static_cast<const T*>(p.Vn) + (long long)bh * p.npad * D;
+  const T* kt = static_cast<const T*>(p.Kt) + (long long)bh * p.npad * D;
+  auto issue_part = [&](int t, int part) {
+    const int op = part / LPH, j = part % LPH;
+    const unsigned dst = lds_base + (unsigned)(t % kDqStages) * kStageBytes + op * kOpBytes + (j * kDqWaves + wave) * 1024;
+    const long long tile_off = (long long)t * kTileN * D;
+    if (op == 0) gload_lds16(kn + tile_off + ngoff[j], dst);
+    else if (op == 1) gload_lds16(vn + tile_off + ngoff[j], dst);
+    else gload_lds16(kt + tile_off + pgoff[j], dst);
+  };
+  auto issue_tile = [&](int t) {
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) issue_part(t, j);
+  };
+
+  constexpr int NA = 4 * (D / 16);           // MFMAs of the S^T and dP^T tiles: 2 key blocks x D/16 k-steps x 2
+  constexpr int NC = 4 * NB;                 // MFMAs of the dQ^T update: 4 key steps x D/32 row blocks
+  constexpr int kAhead = 2;
+  static_assert(NA % (2 * LPH) == 0 && NC % LPH == 0, "loads are spread evenly over the MFMAs");
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  auto compute_tile = [&](int t, int pre, bool masked) {
+    const unsigned char* st = smem + (t % kDqStages) * kStageBytes;
+    // chunk c of phase A: key block kb, k-step ks, operand (0: K for S, 1: V for dP)
+    auto afrag = [&](int c) {
+      const int which = c % 2, ks = (c / 2) % (D / 16), kb = c / (D / 8);
+      return *reinterpret_cast<const bf16x8*>(st + which * kOpBytes + kb * (32 * CH * 16) + krow_b + ((ks << 5) ^ khx));
+    };
+    auto cfrag = [&](int c) {
+      const int t16 = c / NB, db = c % NB;
+      return *reinterpret_cast<const bf16x8*>(st + 2 * kOpBytes + plane_b + (t16 * 2 * D + db * 32) * 16);
+    };
+    f32x16 s[2], dp[2];
+    bf16x8 fa[kAhead];
+#pragma unroll
+    for (int c = 0; c < kAhead; ++c) fa[c] = afrag(c);
+#pragma unroll
+    for (int c = 0; c < NA; ++c) {
+      const int which = c % 2, ks = (c / 2) % (D / 16), kb = c / (D / 8);
+      __builtin_amdgcn_sched_barrier(0);
+      if (which == 0) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c % kAhead], qf[ks], ks == 0 ? zero16 : s[kb], 0, 0, 0);
+      else dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c % kAhead], gf[ks], ks == 0 ? zero16 : dp[kb], 0, 0, 0);
+      if (c + kAhead < NA) fa[c % kAhead] = afrag(c + kAhead);
+      if (c % (NA / (2 * LPH)) == 0 && pre >= 0) issue_part(pre, c / (NA / (2 * LPH)));      // K and V parts of tile t+2
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // dS^T = P^T (dP^T - delta); the lane's query fixes lse and delta, the register fixes the key
+    const int rel = masked ? qvisible - t * kTileN : 0x7fffffff;
+    bf16x8 fc[kAhead];
+#pragma unroll
+    for (int c = 0; c < kAhead; ++c) fc[c] = cfrag(c);
+    bf16x8 dsf[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float pv = fast_exp2(fmaf(s[kb][r], c2, -lse2r));
+        if (kb * 32 + 8 * (r >> 2) + (r & 3) >= rel) pv = 0.f;
+        dp[kb][r] = pv * (dp[kb][r] - deltar);
+      }
+      dsf[kb * 2] = pack8(dp[kb], 0);
+      dsf[kb * 2 + 1] = pack8(dp[kb], 8);
+    }
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int t16 = c / NB, db = c % NB;
+      __builtin_amdgcn_sched_barrier(0);
+      dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[c % kAhead], dsf[t16], dq[db], 0, 0, 0);
+      if (c + kAhead < NC) fc[c % kAhead] = cfrag(c + kAhead);
+      if (c % (NC / LPH) == 0 && pre >= 0) issue_part(pre, 2 * LPH + c / (NC / LPH));            // K^T parts
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // Ring of kDqStages buffers, one barrier per tile: at the top of step t the tiles up to t+1 have been
+  // issued; after its barrier everyone is done with tile t-1, whose buffer takes tile t+2.
+  static_assert(kDqStages == 3, "the wait counts assume this ring depth");
+  if (ntiles > 0) {
+    wait_vmcnt<0>();
+    issue_tile(0);
+    if (ntiles > 1) issue_tile(1);
+    for (int t = 0; t < ntiles; ++t) {
+      if (t + 1 < ntiles) wait_vmcnt<LPT>();
+      else wait_vmcnt<0>();
+      __syncthreads();
+      compute_tile(t, t + 2 < ntiles ? t + 2 : -1, t >= n_full_tiles);
+    }
+  }
+
+  if (qvalid) {
+    T* optr = static_cast<T*>(p.dQ) + b * L.qs[0] + i * L.qs[1] + (long long)qrow * L.qs[2];
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int d = db * 32 + 8 * q4 + 4 * h;
+        uint2 w;
+        w.x = pack_bf16x2(dq[db][q4 * 4 + 0] * L.scale, dq[db][q4 * 4 + 1] * L.scale);
+        w.y = pack_bf16x2(dq[db][q4 * 4 + 2] * L.scale, dq[db][q4 * 4 + 3] * L.scale);
+        *reinterpret_cast<uint2*>(optr + d) = w;
+      }
+  }
+  }  // work-item loop
+}
+
 // ------------------------------------------------------------------ dK, dV = sum over the heads of a KV group
 
 // grid: (ceil(N / rows_per_block), B*Hkv); one token row per D/4 lanes.
@@ -622,6 +828,7 @@ struct BwdWs {
   int* kidx;
   float *lse2c, *deltac, *dKp, *dVp;
   int* sched;
+  int *qvis, *kfirst;
 };
 
 BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
@@ -640,6 +847,8 @@ BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   w.dKp = a.take<float>(krows * L.D);
   w.dVp = a.take<float>(krows * L.D);
   w.sched = a.take<int>(sched_ints(L.B * L.Hq));
+  w.qvis = a.take<int>(dtype == OMNI_BF16 ? BH * L.N : 4);
+  w.kfirst = a.take<int>(dtype == OMNI_BF16 ? krows : 4);
   return w;
 }
 
@@ -685,7 +894,14 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.dVp = w.dVp;
   p.dQ = dQ;
   p.sched = w.sched;
-  rc = run_schedule(L, q_cnt, budget, b_cap, kTileM, w.sched, st);
+  p.qvis = w.qvis;
+  p.kfirst = w.kfirst;
+  constexpr bool kFast = sizeof(T) == 2;
+  if constexpr (kFast) {
+    rc = run_visible_counts(L, q_idx, q_cnt, w.kidx, budget, b_cap, npad, w.qvis, w.kfirst, st);
+    if (rc != OMNI_OK) return rc;
+  }
+  rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kDqTileM : kTileM, w.sched, st);
   if (rc != OMNI_OK) return rc;
   {
     ProfScope prof__(kProfBwdDkDv, st);
@@ -694,7 +910,10 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   }
   {
     ProfScope prof__(kProfBwdDq, st);
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<T, D>), dim3(persistent_grid() / 2), dim3(kThreads), 0, st, p);
+    if constexpr (kFast)
+      hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), dim3(persistent_grid() / 2), dim3(kDqThreads), 0, st, p);
+    else
+      hipLaunchKernelGGL((attn_bwd_dq_kernel<T, D>), dim3(persistent_grid() / 2), dim3(kThreads), 0, st, p);
     OMNI_LAUNCH_CHECK();
   }
   {

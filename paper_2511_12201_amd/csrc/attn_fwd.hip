@@ -72,15 +72,6 @@ struct FwdParams {
 };
 
 // number of entries <= v in ascending a[0,n)
-__device__ __forceinline__ int upper_count(const int* __restrict__ a, int n, int v) {
-  int lo = 0, hi = n;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (a[mid] <= v) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
-
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
   constexpr bool kBf16 = sizeof(T) == 2;
@@ -408,43 +399,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
 // (chunk ^ row % chunks_per_row), applied on the global-address side of the copy, which keeps
 // the 16 rows a ds_read_b128 touches on distinct banks.  V is already in operand order.
 
-// Number of packed keys visible to every kept query: the packed list is ascending in token index, so the
-// keys a causal query may see are a prefix of it, and the mask of a tile is a comparison of the key's
-// position with this count -- no index loads inside the tile loop.
-__global__ __launch_bounds__(256) void visible_counts_kernel(const int* __restrict__ q_idx, const int* __restrict__ q_cnt,
-                                                             const int* __restrict__ kidx, const int* __restrict__ budget,
-                                                             int b_cap, int npad, int N, int Hq, int causal,
-                                                             int* __restrict__ qvis) {
-  const int bh = blockIdx.y, b = bh / Hq;
-  const int nq = q_cnt[bh], nkeys = min(budget[b], b_cap);
-  const int pos = blockIdx.x * blockDim.x + threadIdx.x;
-  if (pos >= nq) return;
-  const int row = q_idx[(long long)bh * N + pos];
-  qvis[(long long)bh * N + pos] = causal ? upper_count(kidx + (long long)bh * npad, nkeys, row) : nkeys;
-}
-
 constexpr int kFastWaves = 8;
 constexpr int kFastThreads = kFastWaves * 64;
 constexpr int kFastTileM = kFastWaves * 32;
 constexpr int kStages = 4;
-
-// 16 bytes per lane, global -> LDS at lds_addr + lane * 16 (lds_addr wave-uniform).  M0 is saved and restored.
-__device__ __forceinline__ void gload_lds16(const void* gptr, unsigned lds_addr) {
-  unsigned saved;
-  asm volatile(
-      "s_mov_b32 %0, m0\n\t"
-      "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, off\n\t"
-      "s_mov_b32 m0, %0"
-      : "=&s"(saved)
-      : "v"(gptr), "s"(lds_addr)
-      : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
 
 template <int D>
 __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParams p) {
@@ -827,9 +785,8 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.sched = w.sched;
   p.qvis = w.qvis;
   if (w.qvis) {
-    hipLaunchKernelGGL(visible_counts_kernel, dim3(cdiv(L.N, 256), L.B * L.Hq), dim3(256), 0, st, q_idx, q_cnt, w.kidx,
-                       budget, b_cap, npad, L.N, L.Hq, L.causal, w.qvis);
-    OMNI_LAUNCH_CHECK();
+    int rc = run_visible_counts(L, q_idx, q_cnt, w.kidx, budget, b_cap, npad, w.qvis, nullptr, st);
+    if (rc != OMNI_OK) return rc;
   }
   constexpr bool kFast = sizeof(T) == 2;
   {

@@ -149,6 +149,33 @@ __device__ __forceinline__ void unpack16(const u32x4& raw, float (&out)[8], cons
   out[7] = __uint_as_float(raw.w & 0xffff0000u);
 }
 
+// 16 bytes per lane, global -> LDS at lds_addr + lane * 16 (lds_addr wave-uniform).  M0 is saved and restored.
+__device__ __forceinline__ void gload_lds16(const void* gptr, unsigned lds_addr) {
+  unsigned saved;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, off\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved)
+      : "v"(gptr), "s"(lds_addr)
+      : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ int upper_count(const int* __restrict__ a, int n, int v) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (a[mid] <= v) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
 template <typename T>

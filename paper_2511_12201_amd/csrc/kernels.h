@@ -38,6 +38,11 @@ int run_pack_q(const Layer& L, int dtype, const void* Q, const void* O, const vo
                const int* q_idx, const int* q_cnt, int nqpad, void* Qt, void* dOt, float* lse2c, float* deltac,
                hipStream_t st);
 
+// qvis [B*Hq, N] / kfirst [B*Hq, npad] (either may be nullptr): visibility bounds of the causal mask on the
+// packed, ascending key and kept-query lists of every query head
+int run_visible_counts(const Layer& L, const int* q_idx, const int* q_cnt, const int* kidx, const int* budget,
+                       int b_cap, int npad, int* qvis, int* kfirst, hipStream_t st);
+
 // attn_fwd.hip
 size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse);
 int run_attn_fwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const int* q_idx,

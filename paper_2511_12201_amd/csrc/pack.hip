@@ -206,7 +206,50 @@ int launch_pack_q(const Layer& L, const void* Q, const void* O, const void* dO, 
   return OMNI_OK;
 }
 
+// Visibility bounds of the causal mask on the packed lists.  The packed key list and the kept-query list
+// are both ascending in token index, so the keys a query may see are a prefix of the key list and the
+// queries that may see a key are a suffix of the query list; the masks of the tile loops are then
+// comparisons of positions with these counts -- no index loads inside the loops.
+//   qvis[bh, pos]    = number of packed keys with token index <= that of kept query `pos`
+//   kfirst[bh, slot] = first kept-query position whose token index is >= that of packed key `slot`
+// grid: (cdiv(max(N, npad), 256), B*Hq)
+__global__ __launch_bounds__(256) void visibility_kernel(const int* __restrict__ q_idx, const int* __restrict__ q_cnt,
+                                                         const int* __restrict__ kidx, const int* __restrict__ budget,
+                                                         int b_cap, int npad, int N, int Hq, int causal,
+                                                         int* __restrict__ qvis, int* __restrict__ kfirst) {
+  const int bh = blockIdx.y, b = bh / Hq;
+  const int nq = q_cnt[bh], nkeys = min(budget[b], b_cap);
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int* qlist = q_idx + (long long)bh * N;
+  const int* klist = kidx + (long long)bh * npad;
+  if (qvis && t < nq) qvis[(long long)bh * N + t] = causal ? upper_count(klist, nkeys, qlist[t]) : nkeys;
+  if (kfirst && t < npad) {
+    int v = 0;
+    if (t >= nkeys) {
+      v = nq;                                  // pad slot: nobody sees it
+    } else if (causal) {
+      const int key = klist[t];
+      int lo = 0, hi = nq;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (qlist[mid] < key) lo = mid + 1; else hi = mid;
+      }
+      v = lo;
+    }
+    kfirst[(long long)bh * npad + t] = v;
+  }
+}
+
 }  // namespace
+
+int run_visible_counts(const Layer& L, const int* q_idx, const int* q_cnt, const int* kidx, const int* budget,
+                       int b_cap, int npad, int* qvis, int* kfirst, hipStream_t st) {
+  const int n = kfirst ? max(L.N, npad) : L.N;
+  hipLaunchKernelGGL(visibility_kernel, dim3(cdiv(n, 256), L.B * L.Hq), dim3(256), 0, st, q_idx, q_cnt, kidx, budget,
+                     b_cap, npad, L.N, L.Hq, L.causal, qvis, kfirst);
+  OMNI_LAUNCH_CHECK();
+  return OMNI_OK;
+}
 
 int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per_q_head, const int* src_idx,
                 int idx_stride, const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt,
