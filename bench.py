@@ -280,7 +280,8 @@ def bench_train(torch, ob, synth, steps: int = 5):
            "kernel_ms": kern, "kept_query_fraction": round(float(cnt.sum()) / (Hq * N), 4),
            "budget_fraction": round(b / N, 4),
            "bwd_algorithmic_tflops": round(10.0 * D * valid / (bwd_ms * 1e-3) / 1e12, 2) if bwd_ms else None,
-           "bwd_issued_gemm_tflops": round(14.0 * D * valid / (bwd_ms * 1e-3) / 1e12, 2) if bwd_ms else None,
+           # 8 GEMMs per pair are issued (S is recomputed by the dK, dV and dQ kernels), 5 are the algorithm's
+           "bwd_issued_gemm_tflops": round(16.0 * D * valid / (bwd_ms * 1e-3) / 1e12, 2) if bwd_ms else None,
            "fwd_algorithmic_tflops": round(4.0 * D * valid / (kern["attn_fwd"] * 1e-3) / 1e12, 2)}
     return res
 

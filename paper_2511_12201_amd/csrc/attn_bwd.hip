@@ -46,6 +46,8 @@ struct BwdParams {
   const int* kidx;
   const void* Qt;       // k-packed kept Q, dO (bf16 only)
   const void* dOt;
+  const void* Qn;       // kept Q, dO rows in kept order, contiguous (bf16 only)
+  const void* dOn;
   const float* lse2c;   // per kept position: lse * log2e (+inf: contributes nothing)
   const float* deltac;
   float* dKp;           // [B*Hq, npad, D] fp32 per-query-head partial gradients
@@ -767,6 +769,242 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
   }  // work-item loop
 }
 
+// ------------------------------------------------------------------ dK' and dV', bf16 fast path
+//
+// Two kernels of the same shape as the dQ kernel with the roles of keys and queries swapped: a workgroup
+// of 8 wavefronts owns 256 packed keys of one query head (32 per wavefront, K and V fragments resident in
+// registers) and streams 64-query tiles of the packed kept rows memory -> LDS with LDS-DMA loads into a
+// ring.  Keeping dK and dV in one kernel needs 192 registers for the resident fragments and the two
+// accumulators alone, which does not fit two wavefronts per SIMD; split, each kernel does, and the price
+// is that S = Q K^T is computed twice (8 GEMMs per pair in the whole backward instead of 7).
+//   MODE 0 (dK): streams Q, dO (natural) and Q (k-packed):  S, dP -> dS;  dK'^T += Q^T dS
+//   MODE 1 (dV): streams Q (natural) and dO (k-packed):     S -> P;       dV'^T += dO^T P
+// lse * log2e and delta of the tile's queries come with the tile (LDS-DMA of 4 bytes per lane); the causal
+// mask is a comparison of the query position with the first position that sees the lane's key.
+
+constexpr int kKeyWaves = 8;
+constexpr int kKeyThreads = kKeyWaves * 64;
+constexpr int kKeyTile = kKeyWaves * 32;     // packed keys per workgroup
+constexpr int kKeyQ = 64;                    // queries per streamed tile
+
+template <int D, int MODE>
+__global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdParams p) {
+  typedef u16 T;
+  constexpr int CH = D / 8;
+  constexpr int NB = D / 32;
+  constexpr int NOPS = MODE == 0 ? 3 : 2;            // streamed operand tiles
+  constexpr int kStages = MODE == 0 ? 3 : 4;
+  constexpr int kAheadTiles = kStages - 1;
+  constexpr int NSMALL = MODE == 0 ? 2 : 1;          // wavefronts that also bring a 256-byte per-query array
+  constexpr int kOpBytes = kKeyQ * D * 2;
+  constexpr int kSmallOff = NOPS * kOpBytes;
+  constexpr int kStageBytes = kSmallOff + 1024;
+  constexpr int LPH = kOpBytes / 1024 / kKeyWaves;
+  constexpr int LPT = NOPS * LPH;
+  static_assert(LPH >= 1, "tile too small for the copy scheme");
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kStages * kStageBytes];
+  __shared__ int sBound[2];
+
+  const Layer& L = p.L;
+  const int ktile = blockIdx.x, bh = blockIdx.y;
+  const int b = bh / L.Hq;
+  const int nkeys = min(p.budget[b], p.b_cap);
+  if (ktile * kKeyTile >= nkeys) return;
+  const int nq = p.q_cnt[bh];
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int ln = lane & 31, h = lane >> 5;
+  const float c2 = L.scale * kLog2e;
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const int slot0 = ktile * kKeyTile;
+  const int slot = slot0 + wave * 32 + ln;                  // this lane's key slot (< npad by construction)
+  const int* kfirst = p.kfirst + (long long)bh * p.npad;
+  if (threadIdx.x == 0 || threadIdx.x == 64) {
+    const int last_slot = min(slot0 + kKeyTile, nkeys) - 1;
+    sBound[threadIdx.x ? 1 : 0] = kfirst[threadIdx.x ? last_slot : slot0];
+  }
+  int my_first = kfirst[slot];
+  __syncthreads();
+  const bool has_pad = slot0 + kKeyTile > nkeys;
+  const int q_begin = sBound[0] / kKeyQ;                    // first query tile with an admissible pair
+  const int q_full_pos = has_pad ? 0x7fffffff : sBound[1];  // tiles starting at or after this position need no mask
+  const int n_qtiles = cdiv(nq, kKeyQ);
+
+  // resident K (and V) fragments: B operands, lane = key column
+  const T* krow = static_cast<const T*>(p.Kn) + ((long long)bh * p.npad + slot) * D;
+  const T* vrow = static_cast<const T*>(p.Vn) + ((long long)bh * p.npad + slot) * D;
+  bf16x8 kf[D / 16], vf[MODE == 0 ? D / 16 : 1];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    kf[ks] = *reinterpret_cast<const bf16x8*>(krow + ks * 16 + h * 8);
+    if (MODE == 0) vf[ks] = *reinterpret_cast<const bf16x8*>(vrow + ks * 16 + h * 8);
+  }
+  // finish every ordinary load here: a compiler-placed wait inside the tile loop would drain the ring
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    asm volatile("" : "+v"(kf[ks]));
+    if (MODE == 0) asm volatile("" : "+v"(vf[ks]));
+  }
+  asm volatile("" : "+v"(my_first));
+  const int first_h = my_first - 4 * h;
+
+  f32x16 acc[NB];
+#pragma unroll
+  for (int db = 0; db < NB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+  unsigned ngoff[LPH], pgoff[LPH];                          // byte offsets of this lane's chunk: natural (swizzled), packed
+#pragma unroll
+  for (int j = 0; j < LPH; ++j) {
+    const int pchunk = (j * kKeyWaves + wave) * 64 + lane;
+    const int row = pchunk / CH, pc = pchunk % CH;
+    ngoff[j] = (row * D + ((pc ^ (row % CH)) << 3)) * 2;      // bytes
+    pgoff[j] = pchunk << 4;
+  }
+  const int krow_b = ln * (CH * 16);
+  const int khx = (h << 4) ^ ((ln % CH) << 4);
+  const int plane_b = (h * D + ln) * 16;
+
+  const T* qn = static_cast<const T*>(p.Qn) + (long long)bh * p.nqpad * D;
+  const T* gn = static_cast<const T*>(p.dOn) + (long long)bh * p.nqpad * D;
+  const T* qt = static_cast<const T*>(p.Qt) + (long long)bh * p.nqpad * D;
+  const T* gt = static_cast<const T*>(p.dOt) + (long long)bh * p.nqpad * D;
+  const float* lsec = p.lse2c + (long long)bh * p.nqpad;
+  const float* delc = p.deltac + (long long)bh * p.nqpad;
+  const bool has_small = wave < NSMALL;
+
+  // u = tile index relative to q_begin (ring position); operand order: MODE 0: Q nat, dO nat, Q packed; MODE 1: Q nat, dO packed
+  auto issue_part = [&](int u, int part) {
+    const int op = part / LPH, j = part % LPH;
+    const unsigned dst = lds_base + (unsigned)(u % kStages) * kStageBytes + op * kOpBytes + (j * kKeyWaves + wave) * 1024;
+    const long long tile_off = (long long)(q_begin + u) * kKeyQ * D;
+    if (op == 0) gload_lds16(qn + tile_off, ngoff[j], dst);
+    else if (MODE == 0 && op == 1) gload_lds16(gn + tile_off, ngoff[j], dst);
+    else if (MODE == 0) gload_lds16(qt + tile_off, pgoff[j], dst);
+    else gload_lds16(gt + tile_off, pgoff[j], dst);
+  };
+  auto issue_small = [&](int u) {
+    if (!has_small) return;
+    const unsigned dst = lds_base + (unsigned)(u % kStages) * kStageBytes + kSmallOff + wave * 256;
+    const float* src = (wave == 0 ? lsec : delc) + (long long)(q_begin + u) * kKeyQ + lane;
+    gload_lds4(src, dst);
+  };
+  auto issue_tile = [&](int u) {
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) issue_part(u, j);
+    issue_small(u);
+  };
+
+  constexpr int NA = (MODE == 0 ? 2 : 1) * (D / 16);   // MFMAs of phase A per 32-query block
+  constexpr int NC = 4 * NB;
+  constexpr int kAhead = 2;                    // fragment reads run this many MFMAs ahead
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  auto compute_tile = [&](int u, int pre, bool masked) {
+    const unsigned char* st = smem + (u % kStages) * kStageBytes;
+    const int rel = masked ? first_h - (q_begin + u) * kKeyQ : -0x7fffffff;   // query positions below rel do not see this key
+    auto cfrag = [&](int c) {
+      const int t16 = c / NB, db = c % NB;
+      return *reinterpret_cast<const bf16x8*>(st + (NOPS - 1) * kOpBytes + plane_b + (t16 * 2 * D + db * 32) * 16);
+    };
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      // chunk c of phase A: k-step ks, operand (0: Q for S, 1: dO for dP)
+      auto afrag = [&](int c) {
+        const int which = MODE == 0 ? c % 2 : 0, ks = MODE == 0 ? c / 2 : c;
+        return *reinterpret_cast<const bf16x8*>(st + which * kOpBytes + qb * (32 * CH * 16) + krow_b + ((ks << 5) ^ khx));
+      };
+      f32x16 s, dp;
+      bf16x8 fa[kAhead];
+#pragma unroll
+      for (int c = 0; c < kAhead; ++c) fa[c] = afrag(c);
+#pragma unroll
+      for (int c = 0; c < NA; ++c) {
+        const int which = MODE == 0 ? c % 2 : 0, ks = MODE == 0 ? c / 2 : c;
+        __builtin_amdgcn_sched_barrier(0);
+        if (which == 0) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c % kAhead], kf[ks], ks == 0 ? zero16 : s, 0, 0, 0);
+        else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c % kAhead], vf[MODE == 0 ? ks : 0], ks == 0 ? zero16 : dp, 0, 0, 0);
+        if (c + kAhead < NA) fa[c % kAhead] = afrag(c + kAhead);
+        // natural operand parts of the tile to prefetch: NOPS - 1 operands x LPH parts over 2 * NA MFMAs
+        constexpr int kParts = (NOPS - 1) * LPH, kEvery = 2 * NA / kParts;
+        if ((qb * NA + c) % kEvery == 0 && pre >= 0) issue_part(pre, (qb * NA + c) / kEvery);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (qb == 0 && pre >= 0) issue_small(pre);
+      // accumulator rows are queries 8 (r/4) + 4 h + r%4 of this block, the column is this lane's key
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int qo = qb * 32 + 8 * q4 + 4 * h;
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + qo * 4);
+        f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+        if (MODE == 0) d4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + 256 + qo * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = q4 * 4 + e;
+          float pv = fast_exp2(fmaf(s[r], c2, -l4[e]));
+          if (qb * 32 + 8 * q4 + e < rel) pv = 0.f;
+          s[r] = MODE == 0 ? pv * (dp[r] - d4[e]) : pv;
+        }
+        if (MODE == 0) __builtin_amdgcn_sched_barrier(0);    // one quad of lse / delta values in registers at a time
+      }
+      // P (or dS) of these 32 queries as two B operands of 16 queries each, then their share of the update
+      bf16x8 bfrag[2];
+      bfrag[0] = pack8(s, 0);
+      bfrag[1] = pack8(s, 8);
+      bf16x8 fc[kAhead];
+#pragma unroll
+      for (int c = 0; c < kAhead; ++c) fc[c] = cfrag(qb * (NC / 2) + c);
+#pragma unroll
+      for (int c = 0; c < NC / 2; ++c) {
+        const int cc = qb * (NC / 2) + c, db = cc % NB;
+        __builtin_amdgcn_sched_barrier(0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[c % kAhead], bfrag[c / NB], acc[db], 0, 0, 0);
+        if (c + kAhead < NC / 2) fc[c % kAhead] = cfrag(cc + kAhead);
+        if (cc % (NC / LPH) == 0 && pre >= 0) issue_part(pre, (NOPS - 1) * LPH + cc / (NC / LPH));   // k-packed operand parts
+      }
+      __builtin_amdgcn_sched_barrier(0);       // keep the two query blocks apart: their accumulators would double up
+    }
+  };
+
+  // Ring of kStages buffers, one barrier per tile: at the top of step u the tiles up to u + kStages - 2 have
+  // been issued; after its barrier everyone is done with tile u-1, whose buffer takes tile u + kStages - 1.
+  const int n = n_qtiles - q_begin;
+  if (n > 0) {
+    wait_vmcnt<0>();
+#pragma unroll
+    for (int a = 0; a < kAheadTiles; ++a)
+      if (a < n) issue_tile(a);
+    for (int u = 0; u < n; ++u) {
+      const int ahead = min(n - 1 - u, kAheadTiles - 1);      // tiles issued after tile u
+      if (has_small) {
+        if (ahead >= 2) wait_vmcnt<2 * (LPT + 1)>();
+        else if (ahead == 1) wait_vmcnt<LPT + 1>();
+        else wait_vmcnt<0>();
+      } else {
+        if (ahead >= 2) wait_vmcnt<2 * LPT>();
+        else if (ahead == 1) wait_vmcnt<LPT>();
+        else wait_vmcnt<0>();
+      }
+      __syncthreads();
+      const int pos0 = (q_begin + u) * kKeyQ;
+      compute_tile(u, u + kAheadTiles < n ? u + kAheadTiles : -1, pos0 < q_full_pos);
+    }
+  }
+
+  // ---- write dK' (scaled) or dV' for this lane's key slot; accumulator rows are d
+  float* orow = (MODE == 0 ? p.dKp : p.dVp) + ((long long)bh * p.npad + slot) * D;
+  const float osc = MODE == 0 ? L.scale : 1.0f;
+#pragma unroll
+  for (int db = 0; db < NB; ++db)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int d = db * 32 + 8 * q4 + 4 * h;
+      f32x4 a = {acc[db][q4 * 4] * osc, acc[db][q4 * 4 + 1] * osc, acc[db][q4 * 4 + 2] * osc, acc[db][q4 * 4 + 3] * osc};
+      *reinterpret_cast<f32x4*>(orow + d) = a;
+    }
+}
+
 // ------------------------------------------------------------------ dK, dV = sum over the heads of a KV group
 
 // grid: (ceil(N / rows_per_block), B*Hkv); one token row per D/4 lanes.
@@ -824,7 +1062,7 @@ __global__ __launch_bounds__(kThreads) void clear_rows_kernel(T* __restrict__ X,
 }
 
 struct BwdWs {
-  void *Kn, *Vn, *Kt, *Qt, *dOt;
+  void *Kn, *Vn, *Kt, *Qt, *dOt, *Qn, *dOn;
   int* kidx;
   float *lse2c, *deltac, *dKp, *dVp;
   int* sched;
@@ -841,6 +1079,8 @@ BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   w.Kt = a.take<unsigned char>(dtype == OMNI_BF16 ? krows * L.D * es : 16);
   w.Qt = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
   w.dOt = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
+  w.Qn = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
+  w.dOn = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
   w.kidx = a.take<int>(krows);
   w.lse2c = a.take<float>(qrows);
   w.deltac = a.take<float>(qrows);
@@ -852,7 +1092,7 @@ BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   return w;
 }
 
-int bwd_npad(int b_cap) { return (int)align_up(b_cap, kBwdKeys); }
+int bwd_npad(int b_cap) { return (int)align_up(b_cap, kKeyTile); }   // a multiple of kBwdKeys as well
 int bwd_nqpad(const Layer& L) { return (int)align_up(L.N, kTileM); }
 
 template <typename T, int D>
@@ -863,11 +1103,12 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   Arena a(ws);
   const int npad = bwd_npad(b_cap), nqpad = bwd_nqpad(L);
   BwdWs w = carve_bwd(a, L, dt, npad, nqpad);
-  int rc = run_pack_kv(L, dt, K, V, 1, kv_idx, b_cap, budget, b_cap, npad, kBwdKeys, w.Kn, w.Vn,
+  int rc = run_pack_kv(L, dt, K, V, 1, kv_idx, b_cap, budget, b_cap, npad, kKeyTile, w.Kn, w.Vn,
                        dt == OMNI_BF16 ? w.Kt : nullptr,
                        nullptr, w.kidx, st);
   if (rc != OMNI_OK) return rc;
-  rc = run_pack_q(L, dt, Q, O, dO, lse, q_idx, q_cnt, nqpad, w.Qt, w.dOt, w.lse2c, w.deltac, st);
+  rc = run_pack_q(L, dt, Q, O, dO, lse, q_idx, q_cnt, nqpad, w.Qt, w.dOt, dt == OMNI_BF16 ? w.Qn : nullptr,
+                  dt == OMNI_BF16 ? w.dOn : nullptr, w.lse2c, w.deltac, st);
   if (rc != OMNI_OK) return rc;
   hipLaunchKernelGGL((clear_rows_kernel<T>), dim3(cdiv(L.N, 64), L.B * L.Hq), dim3(kThreads), 0, st,
                      static_cast<T*>(dQ), L);
@@ -888,6 +1129,8 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.kidx = w.kidx;
   p.Qt = w.Qt;
   p.dOt = w.dOt;
+  p.Qn = w.Qn;
+  p.dOn = w.dOn;
   p.lse2c = w.lse2c;
   p.deltac = w.deltac;
   p.dKp = w.dKp;
@@ -905,7 +1148,13 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   if (rc != OMNI_OK) return rc;
   {
     ProfScope prof__(kProfBwdDkDv, st);
-    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<T, D>), dim3(npad / kBwdKeys, L.B * L.Hq), dim3(kThreads), 0, st, p);
+    if constexpr (sizeof(T) == 2) {
+      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 1>), dim3(npad / kKeyTile, L.B * L.Hq), dim3(kKeyThreads), 0, st, p);
+      OMNI_LAUNCH_CHECK();
+      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 0>), dim3(npad / kKeyTile, L.B * L.Hq), dim3(kKeyThreads), 0, st, p);
+    } else {
+      hipLaunchKernelGGL((attn_bwd_dkdv_kernel<T, D>), dim3(npad / kBwdKeys, L.B * L.Hq), dim3(kThreads), 0, st, p);
+    }
     OMNI_LAUNCH_CHECK();
   }
   {

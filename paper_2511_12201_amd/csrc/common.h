@@ -162,6 +162,33 @@ __device__ __forceinline__ void gload_lds16(const void* gptr, unsigned lds_addr)
       : "v"(gptr), "s"(lds_addr)
       : "memory");
 }
+// The same with the global address split into a wave-uniform base (SGPR pair) and a 32-bit per-lane byte
+// offset: no 64-bit vector address arithmetic, and one VGPR per distinct lane pattern instead of two per load.
+__device__ __forceinline__ void gload_lds16(const void* sbase, unsigned lane_off, unsigned lds_addr) {
+  unsigned saved;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %3\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved)
+      : "v"(lane_off), "s"(sbase), "s"(lds_addr)
+      : "memory");
+}
+// 4 bytes per lane, global -> LDS at lds_addr + lane * 4
+__device__ __forceinline__ void gload_lds4(const void* gptr, unsigned lds_addr) {
+  unsigned saved;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dword %1, off\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved)
+      : "v"(gptr), "s"(lds_addr)
+      : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");

@@ -35,8 +35,8 @@ int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per
                 int idx_stride, const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt,
                 void* Vt, int* kidx, hipStream_t st);
 int run_pack_q(const Layer& L, int dtype, const void* Q, const void* O, const void* dO, const float* lse,
-               const int* q_idx, const int* q_cnt, int nqpad, void* Qt, void* dOt, float* lse2c, float* deltac,
-               hipStream_t st);
+               const int* q_idx, const int* q_cnt, int nqpad, void* Qt, void* dOt, void* Qn, void* dOn, float* lse2c,
+               float* deltac, hipStream_t st);
 
 // qvis [B*Hq, N] / kfirst [B*Hq, npad] (either may be nullptr): visibility bounds of the causal mask on the
 // packed, ascending key and kept-query lists of every query head

@@ -10,8 +10,9 @@
 // use the natural layout (the fp32 MFMA takes one element per lane).
 //
 // pack_q: for the backward pass, the kept rows of Q and dO in the k-packed
-// layout (contraction over queries), plus per kept row lse * log2(e) and
-// delta = rowsum(dO * O).
+// layout (contraction over queries) and, for bf16, also as contiguous natural
+// rows in kept order (so that a tile of them is one linear stream), plus per
+// kept row lse * log2(e) and delta = rowsum(dO * O).
 #include "common.h"
 #include "kernels.h"
 
@@ -115,6 +116,7 @@ __global__ __launch_bounds__(kThreads) void pack_q_kernel(const T* __restrict__ 
                                                          Layer L, const int* __restrict__ q_idx,
                                                          const int* __restrict__ q_cnt, int nqpad,
                                                          T* __restrict__ Qt, T* __restrict__ dOt,
+                                                         T* __restrict__ Qn, T* __restrict__ dOn,
                                                          float* __restrict__ lse2c, float* __restrict__ deltac) {
   constexpr bool kBf16 = sizeof(T) == 2;
   constexpr int E = Elem<T>::kPer16B;
@@ -137,14 +139,21 @@ __global__ __launch_bounds__(kThreads) void pack_q_kernel(const T* __restrict__ 
     const int r = rb + r0;
     const int row = sIdx[r];
     float dot = 0.f;
+    u32x4 g = {0u, 0u, 0u, 0u}, qc = {0u, 0u, 0u, 0u};
     if (row >= 0) {
       const u32x4 a = *reinterpret_cast<const u32x4*>(O + head_off + (long long)row * L.qs[2] + c * E);
-      const u32x4 g = *reinterpret_cast<const u32x4*>(dO + head_off + (long long)row * L.qs[2] + c * E);
+      g = *reinterpret_cast<const u32x4*>(dO + head_off + (long long)row * L.qs[2] + c * E);
+      if (Qn) qc = *reinterpret_cast<const u32x4*>(Q + head_off + (long long)row * L.qs[2] + c * E);
       float av[E], gv[E];
       unpack16(a, av, (const T*)nullptr);
       unpack16(g, gv, (const T*)nullptr);
 #pragma unroll
       for (int e = 0; e < E; ++e) dot = fmaf(av[e], gv[e], dot);
+    }
+    if (Qn) {                                   // natural packed copies (pad rows zero)
+      const long long o = ((long long)bh * nqpad + tile * 64 + r) * D + c * E;
+      *reinterpret_cast<u32x4*>(Qn + o) = qc;
+      *reinterpret_cast<u32x4*>(dOn + o) = g;
     }
 #pragma unroll
     for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
@@ -198,10 +207,12 @@ int launch_pack_kv(const Layer& L, const void* K, const void* V, int per_q_head,
 
 template <typename T, int D>
 int launch_pack_q(const Layer& L, const void* Q, const void* O, const void* dO, const float* lse, const int* q_idx,
-                  const int* q_cnt, int nqpad, void* Qt, void* dOt, float* lse2c, float* deltac, hipStream_t st) {
+                  const int* q_cnt, int nqpad, void* Qt, void* dOt, void* Qn, void* dOn, float* lse2c, float* deltac,
+                  hipStream_t st) {
   hipLaunchKernelGGL((pack_q_kernel<T, D>), dim3(nqpad / 64, L.B * L.Hq), dim3(kThreads), 0, st,
                      static_cast<const T*>(Q), static_cast<const T*>(O), static_cast<const T*>(dO), lse, L, q_idx,
-                     q_cnt, nqpad, static_cast<T*>(Qt), static_cast<T*>(dOt), lse2c, deltac);
+                     q_cnt, nqpad, static_cast<T*>(Qt), static_cast<T*>(dOt), static_cast<T*>(Qn), static_cast<T*>(dOn),
+                     lse2c, deltac);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
 }
@@ -269,14 +280,16 @@ int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per
 }
 
 int run_pack_q(const Layer& L, int dtype, const void* Q, const void* O, const void* dO, const float* lse,
-               const int* q_idx, const int* q_cnt, int nqpad, void* Qt, void* dOt, float* lse2c, float* deltac,
-               hipStream_t st) {
+               const int* q_idx, const int* q_cnt, int nqpad, void* Qt, void* dOt, void* Qn, void* dOn, float* lse2c,
+               float* deltac, hipStream_t st) {
   if (dtype == OMNI_BF16) {
-    if (L.D == 128) return launch_pack_q<u16, 128>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, lse2c, deltac, st);
-    return launch_pack_q<u16, 64>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, lse2c, deltac, st);
+    if (L.D == 128)
+      return launch_pack_q<u16, 128>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, Qn, dOn, lse2c, deltac, st);
+    return launch_pack_q<u16, 64>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, Qn, dOn, lse2c, deltac, st);
   }
-  if (L.D == 128) return launch_pack_q<float, 128>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, lse2c, deltac, st);
-  return launch_pack_q<float, 64>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, lse2c, deltac, st);
+  if (L.D == 128)
+    return launch_pack_q<float, 128>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, nullptr, nullptr, lse2c, deltac, st);
+  return launch_pack_q<float, 64>(L, Q, O, dO, lse, q_idx, q_cnt, nqpad, Qt, dOt, nullptr, nullptr, lse2c, deltac, st);
 }
 
 }  // namespace omni
