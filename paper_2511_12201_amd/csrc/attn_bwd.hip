@@ -602,13 +602,13 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
   const float c2 = L.scale * kLog2e;
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-  int ngoff[LPH], pgoff[LPH];                        // element offsets of this lane's 16-byte chunk: natural (swizzled), packed
+  unsigned ngoff[LPH], pgoff[LPH];                   // byte offsets of this lane's 16-byte chunk: natural (swizzled), packed
 #pragma unroll
   for (int j = 0; j < LPH; ++j) {
     const int pchunk = (j * kDqWaves + wave) * 64 + lane;
     const int row = pchunk / CH, pc = pchunk % CH;
-    ngoff[j] = row * D + ((pc ^ (row % CH)) << 3);
-    pgoff[j] = pchunk << 3;
+    ngoff[j] = (row * D + ((pc ^ (row % CH)) << 3)) * 2;
+    pgoff[j] = pchunk << 4;
   }
   const int krow_b = ln * (CH * 16);
   const int khx = (h << 4) ^ ((ln % CH) << 4);
@@ -618,10 +618,12 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
   __syncthreads();
   if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
   __syncthreads();
-  const int item = sItem;
+  const int item = __builtin_amdgcn_readfirstlane(sItem);   // wave-uniform, and known to be: tile bases stay in SGPRs
   if (item < 0) break;
   int bh, tq;
   sched_decode(p.sched, BH, item, bh, tq);
+  bh = __builtin_amdgcn_readfirstlane(bh);
+  tq = __builtin_amdgcn_readfirstlane(tq);
   const int b = bh / L.Hq, i = bh % L.Hq;
   const int nq = p.q_cnt[bh];
   const int* qlist = p.q_idx + (long long)bh * L.N;
@@ -670,9 +672,9 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
     const int op = part / LPH, j = part % LPH;
     const unsigned dst = lds_base + (unsigned)(t % kDqStages) * kStageBytes + op * kOpBytes + (j * kDqWaves + wave) * 1024;
     const long long tile_off = (long long)t * kTileN * D;
-    if (op == 0) gload_lds16(kn + tile_off + ngoff[j], dst);
-    else if (op == 1) gload_lds16(vn + tile_off + ngoff[j], dst);
-    else gload_lds16(kt + tile_off + pgoff[j], dst);
+    if (op == 0) gload_lds16(kn + tile_off, ngoff[j], dst);
+    else if (op == 1) gload_lds16(vn + tile_off, ngoff[j], dst);
+    else gload_lds16(kt + tile_off, pgoff[j], dst);
   };
   auto issue_tile = [&](int t) {
 #pragma unroll

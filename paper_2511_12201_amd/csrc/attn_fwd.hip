@@ -427,13 +427,13 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
   // per-lane pieces of the copy: which global chunk lands in this lane's LDS slot
-  int kgoff[LPH], vgoff[LPH];
+  unsigned kgoff[LPH], vgoff[LPH];                             // byte offsets inside a tile
 #pragma unroll
   for (int j = 0; j < LPH; ++j) {
     const int pchunk = (j * kFastWaves + wave) * 64 + lane;   // physical 16-byte slot in the K tile
     const int row = pchunk / CH, pc = pchunk % CH;
-    kgoff[j] = row * D + ((pc ^ (row % CH)) << 3);             // elements
-    vgoff[j] = pchunk << 3;
+    kgoff[j] = (row * D + ((pc ^ (row % CH)) << 3)) * 2;
+    vgoff[j] = pchunk << 4;
   }
   // per-lane pieces of the fragment reads
   const int krow_b = ln * (CH * 16);                           // byte offset of row ln in a 32-row block
@@ -444,10 +444,12 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   __syncthreads();
   if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
   __syncthreads();
-  const int item = sItem;
+  const int item = __builtin_amdgcn_readfirstlane(sItem);   // wave-uniform, and known to be: tile bases stay in SGPRs
   if (item < 0) break;
   int bh, tq;
   sched_decode(p.sched, BH, item, bh, tq);
+  bh = __builtin_amdgcn_readfirstlane(bh);
+  tq = __builtin_amdgcn_readfirstlane(tq);
   const int b = bh / L.Hq, i = bh % L.Hq, g = i / L.G;
   const int nq = p.q_cnt ? p.q_cnt[bh] : L.N;
   const int nkeys = p.budget ? min(p.budget[b], p.b_cap) : L.N;
@@ -500,10 +502,10 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   auto issue_part = [&](int t, int part) {
     const unsigned dst = lds_base + (unsigned)(t % kStages) * kStageBytes;
     if (part < LPH) {
-      gload_lds16(kp + (long long)t * kTileN * D + kgoff[part], dst + (part * kFastWaves + wave) * 1024);
+      gload_lds16(kp + (long long)t * kTileN * D, kgoff[part], dst + (part * kFastWaves + wave) * 1024);
     } else {
       const int j = part - LPH;
-      gload_lds16(vp + (long long)t * kTileN * D + vgoff[j], dst + kKBytes + (j * kFastWaves + wave) * 1024);
+      gload_lds16(vp + (long long)t * kTileN * D, vgoff[j], dst + kKBytes + (j * kFastWaves + wave) * 1024);
     }
   };
   auto issue_tile = [&](int t) {
