@@ -187,6 +187,55 @@ def pooled_key_scores(Q, K, probe_block: int, causal: bool, scale: float):
     return out
 
 
+def pooled_block_scores(Q, K, block: int, causal: bool, scale: float):
+    """Accumulated scores of key BLOCKS from the probe with queries and keys both pooled.
+
+    Sec. "Block-wise probing and sparse flash attention kernel" as the paper runs
+    it: queries and keys are mean-pooled along the sequence in blocks of `block`
+    tokens and the pooled map stands in for the full one.  A key block m of c_m
+    tokens enters query block j's softmax with weight c_m (c_m equal keys at the
+    block mean), and under the causal mask j sees the key blocks m <= j.  Row j
+    is added with weight w_j = its number of queries, so the block scores sum to
+    N; they are returned divided by the mean block mass N / n_blocks, i.e. summing
+    to n_blocks, which lets the budget rule (share p of the total) run on them
+    unchanged with "length = total".  [B, Hq, n_blocks] fp64.
+    """
+    Q = _f64(Q)
+    K = _f64(K)
+    B, Hq, N, _ = Q.shape
+    G = _group(Hq, K.shape[1])
+    starts = np.arange(0, N, block)
+    ends = np.minimum(starts + block, N)
+    cnt = (ends - starts).astype(np.float64)
+    nb = starts.size
+    out = np.empty((B, Hq, nb))
+    blk = np.arange(nb)
+    for b in range(B):
+        for i in range(Hq):
+            qbar = np.stack([Q[b, i, s:e].mean(axis=0) for s, e in zip(starts, ends)])
+            kbar = np.stack([K[b, i // G, s:e].mean(axis=0) for s, e in zip(starts, ends)])
+            S = (qbar @ kbar.T) * scale                      # [nb, nb]
+            if causal:
+                S = np.where(blk[None, :] <= blk[:, None], S, NEG_INF)
+            S = S - S.max(axis=1, keepdims=True)
+            P = cnt[None, :] * np.exp(S)
+            P /= P.sum(axis=1, keepdims=True)
+            out[b, i] = (cnt[:, None] * P).sum(axis=0) * (nb / N)
+    return out
+
+
+def expand_blocks(blk_idx, block: int, n_tokens: int):
+    """Token lists of selected key blocks: blk_idx[b][i] ascending block ids -> ascending token ids."""
+    out = []
+    for per_b in blk_idx:
+        heads = []
+        for ids in per_b:
+            toks = [np.arange(int(m) * block, min((int(m) + 1) * block, n_tokens), dtype=np.int32) for m in ids]
+            heads.append(np.concatenate(toks) if toks else np.zeros(0, dtype=np.int32))
+        out.append(heads)
+    return out
+
+
 def kurtosis(a_f32):
     """Excess kurtosis m4 / m2^2 - 3 of each head's score vector, fp64.
 

@@ -183,6 +183,58 @@ def test_pooled_probe_uses_mean_query_and_group_key_head():
         np.testing.assert_allclose(a[0, i], 6 * torch.softmax(z, 0).numpy(), rtol=1e-12)
 
 
+# ------------------------------------------------------------------ probe with pooled queries AND keys (block granular)
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("block", [1, 4, 7, 64])
+def test_block_scores_sum_to_number_of_blocks(block, causal):
+    Q, K = _rand((2, 4, 29, 8), 40), _rand((2, 2, 29, 8), 41)
+    a = oc.pooled_block_scores(Q, K, block, causal, 0.3)
+    nb = math.ceil(29 / block)
+    assert a.shape == (2, 4, nb)
+    np.testing.assert_allclose(a.sum(-1), float(nb), rtol=1e-12)
+    assert np.all(a >= 0)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_block_probe_with_block_one_is_the_exact_map(causal):
+    Q, K = _rand((1, 4, 19, 8), 42), _rand((1, 2, 19, 8), 43)
+    np.testing.assert_allclose(oc.pooled_block_scores(Q, K, 1, causal, 0.4),
+                               oc.exact_key_scores(Q, K, causal, 0.4), rtol=1e-12, atol=1e-14)
+
+
+def test_block_probe_uniform_keys_closed_form():
+    # identical keys: query block j spreads its w_j queries over the visible key blocks in proportion to their sizes
+    N, blk = 11, 4
+    Q = _rand((1, 1, N, 4), 44)
+    K = np.tile(_rand((1, 1, 1, 4), 45), (1, 1, N, 1))
+    a = oc.pooled_block_scores(Q, K, blk, True, 1.0)[0, 0]
+    c = [4, 4, 3]
+    seen = [4, 8, 11]                                     # tokens in the key blocks m <= j
+    mass = np.array([sum(c[j] * c[m] / seen[j] for j in range(3) if m <= j) for m in range(3)])
+    np.testing.assert_allclose(a, mass * 3 / N, rtol=1e-13)
+    a_nc = oc.pooled_block_scores(Q, K, blk, False, 1.0)[0, 0]
+    np.testing.assert_allclose(a_nc, np.array(c) * 3 / N, rtol=1e-13)
+
+
+def test_block_probe_is_softmax_of_pooled_logits():
+    # equal blocks, non causal: mass of key block m = sum_j w_j softmax_m(qbar_j . kbar_m)
+    Q, K = _rand((1, 2, 12, 4), 46), _rand((1, 1, 12, 4), 47)
+    a = oc.pooled_block_scores(Q, K, 4, False, 0.5)
+    for i in range(2):
+        qb = Q[0, i].reshape(3, 4, 4).mean(1)
+        kb = K[0, 0].reshape(3, 4, 4).mean(1)
+        P = torch.softmax(torch.tensor(qb @ kb.T * 0.5), dim=1).numpy()
+        np.testing.assert_allclose(a[0, i], (4 * P).sum(0) * 3 / 12, rtol=1e-12)
+
+
+def test_expand_blocks_gives_ascending_token_ranges():
+    out = oc.expand_blocks([[np.array([0, 2]), np.array([2]), np.array([], dtype=np.int32)]], 4, 11)
+    np.testing.assert_array_equal(out[0][0], [0, 1, 2, 3, 8, 9, 10])
+    np.testing.assert_array_equal(out[0][1], [8, 9, 10])
+    assert out[0][2].size == 0
+
+
 # ------------------------------------------------------------------ kurtosis / flattest head
 
 def test_kurtosis_matches_library_and_known_values():
