@@ -66,7 +66,8 @@ typedef enum {
   OMNI_CALL_SLIM_DECODE = 6,
   OMNI_CALL_DENSE_ATTN_FWD = 7,
   OMNI_CALL_DENSE_DECODE = 8,
-  OMNI_CALL_GROUP_SUBSET = 9
+  OMNI_CALL_GROUP_SUBSET = 9,
+  OMNI_CALL_BLOCK_SCORES = 10
 } omni_call_id;
 
 /* One attention layer during prefill / training.
@@ -268,6 +269,31 @@ int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q,
                              const int32_t* grp_idx, const uint32_t* grp_mask, const int32_t* grp_cnt,
                              int32_t u_cap, void* O, uint8_t* active,
                              void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Block-granular variant of the KV selection -- Sec. "Block-wise probing and sparse
+ * flash attention kernel" as the paper runs it: queries AND keys are mean-pooled in
+ * blocks of `block` tokens, the pooled map gives one accumulated score per key block
+ * (a key block of c tokens enters a row's softmax with weight c; under the causal
+ * mask query block j sees key blocks 0..j; row j counts for its number of queries).
+ *
+ * omni_block_scores writes block_scores [batch, n_q_heads, n_blocks] f32,
+ * n_blocks = ceil(n_tokens / block) <= 2048, normalised to sum to n_blocks per head,
+ * so that omni_budget_from_scores and omni_select_kv run on them unchanged with a
+ * descriptor whose n_tokens is n_blocks (budget and lists are then in blocks).
+ * Workspace: OMNI_CALL_BLOCK_SCORES with param = block.
+ *
+ * omni_expand_blocks turns ascending block lists blk_idx [batch, n_q_heads, blk_cap]
+ * (blk_budget [batch] entries used) into ascending token lists kv_idx [batch,
+ * n_q_heads, b_cap] and writes budget [batch] = min(blk_budget, blk_cap) * block; the
+ * tokens a partial last block lacks become pad entries that no query ever sees.
+ * b_cap must be >= blk_cap * block to hold every list.
+ */
+int omni_block_scores(const omni_layer_desc* desc, const void* Q, const void* K, int32_t block,
+                      float* block_scores, void* ws, size_t ws_bytes, void* stream);
+int omni_expand_blocks(const omni_layer_desc* desc, const int32_t* blk_idx, const int32_t* blk_budget,
+                       int32_t blk_cap, int32_t block, int32_t* kv_idx, int32_t* budget, int32_t b_cap,
+                       void* stream);
 
 /*
  * Baselines used by the reported metric (not part of the method): plain causal

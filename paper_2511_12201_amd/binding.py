@@ -18,14 +18,15 @@ LIB_PATH = os.path.join(_HERE, "libomnisparse.so")
 
 OMNI_F32, OMNI_BF16 = 0, 1
 (CALL_SCORE_QUERIES, CALL_SELECT_QUERIES, CALL_KV_BUDGET, CALL_SELECT_KV, CALL_SPARSE_ATTN_FWD,
- CALL_SPARSE_ATTN_BWD, CALL_SLIM_DECODE, CALL_DENSE_ATTN_FWD, CALL_DENSE_DECODE, CALL_GROUP_SUBSET) = range(10)
+ CALL_SPARSE_ATTN_BWD, CALL_SLIM_DECODE, CALL_DENSE_ATTN_FWD, CALL_DENSE_DECODE, CALL_GROUP_SUBSET,
+ CALL_BLOCK_SCORES) = range(11)
 
 EXPORTED = [
     "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
     "omni_sparse_attn_fwd", "omni_sparse_attn_bwd", "omni_slim_decode", "omni_visual_subset",
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
     "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
-    "omni_group_subset", "omni_slim_decode_grouped",
+    "omni_group_subset", "omni_slim_decode_grouped", "omni_block_scores", "omni_expand_blocks",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -85,6 +86,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_group_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
+    lib.omni_block_scores.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.omni_expand_blocks.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
     lib.omni_slim_decode_grouped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_profile_enable.argtypes = [C.c_int]
     lib.omni_debug_copy.argtypes = [vp, vp, sz, vp]
@@ -385,6 +388,44 @@ def omni_slim_decode(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, v
                                 _ptr(vis_idx), _ptr(vis_cnt), b_cap, _ptr(O), _ptr(active), _ptr(buf), buf.numel(),
                                 _stream()))
     return O, active
+
+
+def block_level_desc(desc: LayerDesc, block: int) -> LayerDesc:
+    """Descriptor of the block-level score arrays: one "token" per block, all of them "visual"."""
+    nb = (desc.n_tokens + block - 1) // block
+    d = LayerDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim, d.n_tokens = desc.batch, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, nb
+    d.vis_begin, d.vis_end, d.sink_index, d.causal, d.dtype = 0, nb, 0, desc.causal, desc.dtype
+    d.softmax_scale = desc.softmax_scale
+    D = desc.head_dim
+    d.q_stride = (C.c_int64 * 3)(desc.n_q_heads * nb * D, nb * D, D)
+    d.kv_stride = (C.c_int64 * 3)(desc.n_kv_heads * nb * D, nb * D, D)
+    return d
+
+
+def omni_block_scores(desc: LayerDesc, Q, K, block: int, ws: Workspace | None = None):
+    """Block-level accumulated key scores [B, Hq, n_blocks] f32, summing to n_blocks per head."""
+    lib = load_library()
+    ws = ws or default_workspace()
+    nb = (desc.n_tokens + block - 1) // block
+    out = torch.empty(desc.batch, desc.n_q_heads, nb, dtype=torch.float32, device=Q.device)
+    buf = ws.get(CALL_BLOCK_SCORES, desc, block)
+    _check(lib.omni_block_scores(C.byref(desc), _ptr(Q), _ptr(K), block, _ptr(out), _ptr(buf), buf.numel(), _stream()))
+    return out
+
+
+def omni_expand_blocks(desc: LayerDesc, blk_idx, blk_budget, block: int, kv_idx=None, budget=None):
+    """(kv_idx [B,Hq,blk_cap*block] i32, budget [B] i32): token lists of the selected key blocks."""
+    lib = load_library()
+    blk_cap = blk_idx.shape[-1]
+    b_cap = blk_cap * block if kv_idx is None else kv_idx.shape[-1]
+    if kv_idx is None:
+        kv_idx = torch.empty(desc.batch, desc.n_q_heads, b_cap, dtype=torch.int32, device=blk_idx.device)
+    if budget is None:
+        budget = torch.empty(desc.batch, dtype=torch.int32, device=blk_idx.device)
+    _check(lib.omni_expand_blocks(C.byref(desc), _ptr(blk_idx), _ptr(blk_budget), blk_cap, block, _ptr(kv_idx),
+                                  _ptr(budget), b_cap, _stream()))
+    return kv_idx, budget
 
 
 def omni_group_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, u_cap: int | None = None,

@@ -243,6 +243,9 @@ size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param) {
       return attn_bwd_ws(L, d->dtype, param);
     case OMNI_CALL_DENSE_ATTN_FWD: return attn_fwd_ws(L, d->dtype, L.N, false);
     case OMNI_CALL_GROUP_SUBSET: return group_subset_ws(L);
+    case OMNI_CALL_BLOCK_SCORES:
+      if (param < 1) { set_error("block must be >= 1"); return 0; }
+      return block_scores_ws(L, param);
     default: set_error("unknown call id %d", call_id); return 0;
   }
 }
@@ -338,6 +341,31 @@ int omni_group_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const 
   const Layer L = make_layer(desc);
   CHECK(check_ws(ws, ws_bytes, group_subset_ws(L)));
   return run_group_subset(L, kv_idx, budget, b_cap, grp_idx, grp_mask, grp_cnt, u_cap, ws, static_cast<hipStream_t>(stream));
+}
+
+int omni_block_scores(const omni_layer_desc* desc, const void* Q, const void* K, int32_t block, float* block_scores,
+                      void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(block_scores);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K);
+  if (block < 1) OMNI_FAIL(OMNI_ERR_INVALID, "block must be >= 1");
+  const Layer L = make_layer(desc);
+  if (cdiv(L.N, block) > block_scores_max_blocks())
+    OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than %d key blocks", block_scores_max_blocks());
+  CHECK(check_ws(ws, ws_bytes, block_scores_ws(L, block)));
+  return run_block_scores(L, desc->dtype, Q, K, block, block_scores, ws, static_cast<hipStream_t>(stream));
+}
+
+int omni_expand_blocks(const omni_layer_desc* desc, const int32_t* blk_idx, const int32_t* blk_budget, int32_t blk_cap,
+                       int32_t block, int32_t* kv_idx, int32_t* budget, int32_t b_cap, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(blk_idx); REQUIRE_PTR(blk_budget); REQUIRE_PTR(kv_idx); REQUIRE_PTR(budget);
+  if (blk_cap < 1 || block < 1 || b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "blk_cap, block and b_cap must be >= 1");
+  if ((long long)blk_cap * block > b_cap) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= blk_cap * block");
+  return run_expand_blocks(make_layer(desc), blk_idx, blk_budget, blk_cap, block, kv_idx, budget, b_cap,
+                           static_cast<hipStream_t>(stream));
 }
 
 int omni_sparse_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,

@@ -62,6 +62,14 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
                const float* probe, const int* vis_idx, const int* vis_cnt, const unsigned* grp_mask, int b_cap,
                void* O, unsigned char* active, void* ws, hipStream_t st);
 
+// block.hip (block-granular variant of the KV selection)
+int block_scores_max_blocks();
+size_t block_scores_ws(const Layer& L, int block);
+int run_block_scores(const Layer& L, int dtype, const void* Q, const void* K, int block, float* out, void* ws,
+                     hipStream_t st);
+int run_expand_blocks(const Layer& L, const int* blk_idx, const int* blk_budget, int blk_cap, int block, int* kv_idx,
+                      int* budget, int b_cap, hipStream_t st);
+
 // diag.hip
 int run_calibration_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 int run_mfma_rate(int random_operands, int iters, double* tflops, double* shader_mhz);

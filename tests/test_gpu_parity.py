@@ -386,6 +386,56 @@ def test_free_running_pipeline_matches_oracle_up_to_ties_at_the_cut(cfg):
     assert compared >= H // 2
 
 
+# ------------------------------------------------------------------ block-granular KV selection
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("block", [64, 100])
+def test_block_granular_selection_and_attention(cfg, block):
+    """Queries and keys both pooled: block scores, budget in blocks, block lists, their token lists, and the
+    sparse forward on them -- each stage against the oracle on the oracle's own inputs for that stage."""
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    nb = math.ceil(N / block)
+    want_a = oc.pooled_block_scores(c.Q, c.K, block, cfg.causal, cfg.scale)
+    got_a = ob.omni_block_scores(c.desc, c.dQ, c.dK, block)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(to_host(got_a) - want_a)) <= 1e-4 * want_a.max()
+    np.testing.assert_allclose(to_host(got_a).sum(-1), float(nb), rtol=1e-4)
+    # budget and block lists: decided on the oracle's fp32 block scores on both sides
+    a32 = want_a.astype(np.float32)
+    bdesc = ob.block_level_desc(c.desc, block)
+    da = torch.from_numpy(a32).cuda()
+    r = ob.omni_budget_from_scores(bdesc, da, 0.9, 0)
+    want_b = oc.kv_budget(a32, 0.9, 0)
+    np.testing.assert_array_equal(to_host(r.budget), want_b["budget"])
+    np.testing.assert_array_equal(to_host(r.flattest), want_b["flattest"])
+    nbud = int(want_b["budget"][0])
+    blk_idx = ob.omni_select_kv(bdesc, da, r.budget, nb)
+    want_blk = oc.select_kv(a32, want_b["budget"])
+    got_blk = to_host(blk_idx)
+    for h in range(H):
+        np.testing.assert_array_equal(got_blk[0, h, :nbud], want_blk[0][h])
+    # token lists
+    kv_idx, budget = ob.omni_expand_blocks(c.desc, blk_idx, r.budget, block)
+    torch.cuda.synchronize()
+    assert int(to_host(budget)[0]) == nbud * block
+    want_tok = oc.expand_blocks(want_blk, block, N)
+    got_tok = to_host(kv_idx)
+    for h in range(H):
+        row = got_tok[0, h, : nbud * block]
+        np.testing.assert_array_equal(row[row < N], want_tok[0][h])
+        assert np.all(np.diff(row.astype(np.int64)) > 0) or np.all(row[row >= N] == row[row >= N][0])
+    # attention on the block lists (kept queries of the token-level case)
+    q_idx, q_cnt = lists_to_padded(c.o_qidx, H, N)
+    O, lse = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, budget, kv_idx.shape[-1])
+    torch.cuda.synchronize()
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, want_tok, cfg.causal, cfg.scale)
+    assert np.max(np.abs(to_host(O) - Oo)) <= TOL_OUT[cfg.dtype]
+    fin = np.isfinite(Lo)
+    assert np.array_equal(np.isfinite(to_host(lse)), fin)
+    assert np.max(np.abs(to_host(lse)[fin] - Lo[fin])) <= (1e-4 if cfg.dtype == "f32" else 2e-2)
+
+
 # ------------------------------------------------------------------ attention backward
 
 def _run_fwd_bwd(c, q_lists, kv_lists, dO_np, desc=None):
