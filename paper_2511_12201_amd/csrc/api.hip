@@ -153,26 +153,30 @@ extern "C" {
 const char* omni_last_error(void) { return g_err; }
 
 int omni_debug_work_list(const omni_layer_desc* desc, const int32_t* q_cnt, const int32_t* budget, int32_t b_cap,
-                         int32_t tile_rows, int32_t* seg_begin, int32_t* item_head, int32_t* item_tile, int32_t capacity,
+                         int32_t tile_rows, int32_t* item_head, int32_t* item_tile, int32_t* item_cost, int32_t capacity,
                          int32_t* n_items) {
   clear_error();
   CHECK(validate_layer(desc));
-  REQUIRE_PTR(seg_begin); REQUIRE_PTR(item_head); REQUIRE_PTR(item_tile); REQUIRE_PTR(n_items);
+  REQUIRE_PTR(item_head); REQUIRE_PTR(item_tile); REQUIRE_PTR(item_cost); REQUIRE_PTR(n_items);
   if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
   if (tile_rows != 128 && tile_rows != 256) OMNI_FAIL(OMNI_ERR_INVALID, "tile_rows must be 128 or 256");
   const int BH = desc->batch * desc->n_q_heads;
-  std::vector<int> sched(sched_ints(BH));
-  sched_build(q_cnt, budget, desc->batch, desc->n_q_heads, desc->n_tokens, b_cap, desc->causal, tile_rows,
-              sched.data());
+  std::vector<int> sched(sched_ints(BH, desc->n_tokens, tile_rows));
+  sched_build_host(q_cnt, budget, desc->batch, desc->n_q_heads, desc->n_tokens, b_cap, desc->causal, tile_rows,
+                   sched.data());
   const int items = sched[kSchedTotal];
   *n_items = items;
-  for (int x = 0; x <= kNumXcd; ++x) seg_begin[x] = sched[kSchedSeg + x];
   if (items > capacity) OMNI_FAIL(OMNI_ERR_WORKSPACE, "work list has %d items, capacity is %d", items, capacity);
+  const size_t order_off = sched_order_off(BH, desc->n_tokens, tile_rows);
   for (int it = 0; it < items; ++it) {
     int bh, tq;
-    sched_decode(sched.data(), BH, it, bh, tq);
+    sched_decode(sched.data(), order_off, it, bh, tq);
     item_head[it] = bh;
     item_tile[it] = tq;
+    const int nt = sched[kSchedPrefix + bh + 1] - sched[kSchedPrefix + bh];
+    int nk = budget ? budget[bh / desc->n_q_heads] : desc->n_tokens;
+    nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
+    item_cost[it] = sched_estimate(tq, nt, nk, desc->causal);
   }
   return OMNI_OK;
 }

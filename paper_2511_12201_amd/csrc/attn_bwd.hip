@@ -54,6 +54,7 @@ struct BwdParams {
   float* dVp;
   void* dQ;
   int* sched;           // work list of the dQ kernel (sched.h)
+  size_t order_off;     // where its hand-out order starts
   const int* qvis;      // [B*Hq, N] visible packed keys per kept-query position (bf16 fast path)
   const int* kfirst;    // [B*Hq, npad] first kept-query position that sees a packed key
 };
@@ -359,19 +360,17 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p) {
 
   __shared__ int sItem;
   const Layer& L = p.L;
-  const int BH = L.B * L.Hq;
-  const int xcd = xcc_id();
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int ln = lane & 31, h = lane >> 5;
 
   for (;;) {                                 // persistent: one (head, query tile) per iteration
   __syncthreads();
-  if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
+  if (threadIdx.x == 0) sItem = sched_next(p.sched);
   __syncthreads();
   const int item = sItem;
   if (item < 0) break;
   int bh, tq;
-  sched_decode(p.sched, BH, item, bh, tq);
+  sched_decode(p.sched, p.order_off, item, bh, tq);
   const int b = bh / L.Hq, i = bh % L.Hq;
   const int nq = p.q_cnt[bh];
   const int nkeys = min(p.budget[b], p.b_cap);
@@ -594,8 +593,6 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
   __shared__ int sItem;
 
   const Layer& L = p.L;
-  const int BH = L.B * L.Hq;
-  const int xcd = xcc_id();
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int ln = lane & 31, h = lane >> 5;
@@ -616,12 +613,12 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
 
   for (;;) {
   __syncthreads();
-  if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
+  if (threadIdx.x == 0) sItem = sched_next(p.sched);
   __syncthreads();
   const int item = __builtin_amdgcn_readfirstlane(sItem);   // wave-uniform, and known to be: tile bases stay in SGPRs
   if (item < 0) break;
   int bh, tq;
-  sched_decode(p.sched, BH, item, bh, tq);
+  sched_decode(p.sched, p.order_off, item, bh, tq);
   bh = __builtin_amdgcn_readfirstlane(bh);
   tq = __builtin_amdgcn_readfirstlane(tq);
   const int b = bh / L.Hq, i = bh % L.Hq;
@@ -1088,7 +1085,7 @@ BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   w.deltac = a.take<float>(qrows);
   w.dKp = a.take<float>(krows * L.D);
   w.dVp = a.take<float>(krows * L.D);
-  w.sched = a.take<int>(sched_ints(L.B * L.Hq));
+  w.sched = a.take<int>(sched_ints(L.B * L.Hq, L.N, kTileM));   // sized for the smaller tile: the longer list
   w.qvis = a.take<int>(dtype == OMNI_BF16 ? BH * L.N : 4);
   w.kfirst = a.take<int>(dtype == OMNI_BF16 ? krows : 4);
   return w;
@@ -1146,7 +1143,8 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
     rc = run_visible_counts(L, q_idx, q_cnt, w.kidx, budget, b_cap, npad, w.qvis, w.kfirst, st);
     if (rc != OMNI_OK) return rc;
   }
-  rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kDqTileM : kTileM, w.sched, st);
+  p.order_off = sched_order_off(L.B * L.Hq, L.N, kFast ? kDqTileM : kTileM);
+  rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kDqTileM : kTileM, kFast ? w.qvis : nullptr, w.sched, st);
   if (rc != OMNI_OK) return rc;
   {
     ProfScope prof__(kProfBwdDkDv, st);

@@ -69,6 +69,7 @@ struct FwdParams {
   int identity_keys;
   const int* qvis;       // [B*Hq, N] visible packed keys per kept-query position (sparse bf16 path), else nullptr    // kidx[p] == p: causal bounds by arithmetic
   int* sched;           // work list (sched.h)
+  size_t order_off;     // where its hand-out order starts
 };
 
 // number of entries <= v in ascending a[0,n)
@@ -87,20 +88,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
 
   __shared__ int sItem;
   const Layer& L = p.L;
-  const int BH = L.B * L.Hq;
-  const int xcd = xcc_id();
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int ln = lane & 31, h = lane >> 5;
   const float c2 = L.scale * kLog2e;
 
   for (;;) {                                 // persistent: one work item (head, query tile) per iteration
   __syncthreads();                           // LDS of the previous item is no longer read
-  if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
+  if (threadIdx.x == 0) sItem = sched_next(p.sched);
   __syncthreads();
   const int item = sItem;
   if (item < 0) break;
   int bh, tq;
-  sched_decode(p.sched, BH, item, bh, tq);
+  sched_decode(p.sched, p.order_off, item, bh, tq);
   const int b = bh / L.Hq, i = bh % L.Hq, g = i / L.G;
   const int nq = p.q_cnt ? p.q_cnt[bh] : L.N;
   const int nkeys = p.budget ? min(p.budget[b], p.b_cap) : L.N;
@@ -418,8 +417,6 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   __shared__ int sItem;
 
   const Layer& L = p.L;
-  const int BH = L.B * L.Hq;
-  const int xcd = xcc_id();
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int ln = lane & 31, h = lane >> 5;
@@ -442,12 +439,12 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
 
   for (;;) {
   __syncthreads();
-  if (threadIdx.x == 0) sItem = sched_next(p.sched, xcd);
+  if (threadIdx.x == 0) sItem = sched_next(p.sched);
   __syncthreads();
   const int item = __builtin_amdgcn_readfirstlane(sItem);   // wave-uniform, and known to be: tile bases stay in SGPRs
   if (item < 0) break;
   int bh, tq;
-  sched_decode(p.sched, BH, item, bh, tq);
+  sched_decode(p.sched, p.order_off, item, bh, tq);
   bh = __builtin_amdgcn_readfirstlane(bh);
   tq = __builtin_amdgcn_readfirstlane(tq);
   const int b = bh / L.Hq, i = bh % L.Hq, g = i / L.G;
@@ -741,7 +738,7 @@ FwdWs carve_fwd(Arena& a, const Layer& L, int dtype, int heads, int npad, bool s
   w.Kp = a.take<unsigned char>(rows * L.D * es);
   w.Vp = a.take<unsigned char>(rows * L.D * es);
   w.kidx = a.take<int>(rows);
-  w.sched = a.take<int>(sched_ints(L.B * L.Hq));
+  w.sched = a.take<int>(sched_ints(L.B * L.Hq, L.N, kTileM));   // sized for the smaller tile: the longer list
   w.qvis = (sparse && dtype == OMNI_BF16) ? a.take<int>((size_t)L.B * L.Hq * L.N) : nullptr;
   return w;
 }
@@ -792,7 +789,8 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   }
   constexpr bool kFast = sizeof(T) == 2;
   {
-    int rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kFastTileM : kTileM, w.sched, st);
+    p.order_off = sched_order_off(L.B * L.Hq, L.N, kFast ? kFastTileM : kTileM);
+    int rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kFastTileM : kTileM, w.qvis, w.sched, st);
     if (rc != OMNI_OK) return rc;
   }
   {

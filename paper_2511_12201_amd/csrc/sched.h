@@ -1,117 +1,69 @@
 // Device-side work list for the query-tile kernels (attention forward, backward dQ).
 //
-// Work item = one tile (tile_m rows, 128 or 256) of a head's kept queries.  Items are ordered head
-// by head, longest tile first (under the causal mask the last tile of a head
-// sees the most keys), and cut into 8 contiguous segments of about equal cost,
-// one per XCD.  The kernels are persistent: every workgroup reads the id of the
-// XCD it runs on, pulls items from that XCD's segment through an atomic
-// counter, and moves on to the other segments when its own is empty.  The
-// workgroups resident on an XCD therefore work on neighbouring tiles of the same
-// head and stream the same packed K/V tiles through that XCD's L2 at about the
-// same time, instead of every workgroup pulling its own copy from HBM.
+// Work item = one tile (tile_m rows, 128 or 256) of a head's kept queries.  Under the causal mask the
+// items differ in length by two orders of magnitude (a head's last tile streams every selected key, its
+// first one tile), and a launch has only a few thousand of them for 256 persistent workgroups: handed out
+// head by head, the long items of the last heads start late and a few workgroups finish them alone
+// (measured: 17 % of the kernel time).  So the items are sorted by cost, longest first, and every
+// workgroup pulls the next one from a single atomic counter -- the classic longest-processing-time
+// rule, whose tail is bounded by the shortest items.  The cost of an item is the number of key tiles
+// it streams: exact when the per-query visible-prefix counts are given, else estimated from the
+// position of the tile.  (Keeping neighbouring tiles of a head on one XCD, so that they share K/V tiles
+// in its L2, was tried first: with all K/V made cache-resident the kernel time does not change, so
+// locality is not what limits it.)
 //
 // Layout of the int array in device memory:
-//   [0..8]   seg_begin  (item index ranges per XCD)
-//   [9..16]  counters   (zeroed by the scheduler kernel before every launch)
-//   [17]     total number of items
-//   [18..]   head_prefix[BH + 1] (cumulative tile counts)
+//   [0] counter (zeroed before every launch)   [1] number of items   [2..3] unused
+//   [4 .. 4 + BH]            head_prefix[BH + 1]  (cumulative tile counts, head-major item ids)
+//   [.. + 2 * cap]           cost keys of the items by id (64-bit: cost << 32 | ~id)
+//   [.. + cap]               order[k] = (head << 16 | tile) of the k-th item to hand out
+// with cap = BH * ceil(N / tile_m) the largest possible number of items.
 #pragma once
 
 #include "common.h"
 
 namespace omni {
 
-constexpr int kSchedSeg = 0, kSchedCounter = 9, kSchedTotal = 17, kSchedPrefix = 18;
-constexpr int kNumXcd = 8;
+constexpr int kSchedCounter = 0, kSchedTotal = 1, kSchedPrefix = 4;
 
-inline size_t sched_ints(int BH) { return (size_t)kSchedPrefix + BH + 1; }
+inline size_t sched_cap(int BH, int N, int tile_m) { return (size_t)BH * ((N + tile_m - 1) / tile_m); }
+inline size_t sched_keys_off(int BH) { return (size_t)((kSchedPrefix + BH + 1 + 1) & ~1); }            // 8-byte aligned
+inline size_t sched_order_off(int BH, int N, int tile_m) { return sched_keys_off(BH) + 2 * sched_cap(BH, N, tile_m); }
+inline size_t sched_ints(int BH, int N, int tile_m) { return sched_order_off(BH, N, tile_m) + sched_cap(BH, N, tile_m); }
 
-int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap, int tile_m, int* sched,
+// qvis (nullable): [B*Hq, N] visible packed keys per kept-query position, for exact costs
+int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap, int tile_m, const int* qvis, int* sched,
                  hipStream_t st);
 int persistent_grid();      // workgroups that fill the device at two per CU
 
-// XCC_ID hardware register (id 20), bits [3:0]
-__device__ __forceinline__ int xcc_id() { return (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u); }
-
-// Called by one thread.  Next item for a workgroup on `xcd`, or -1 when every segment is drained.
-__device__ __forceinline__ int sched_next(int* __restrict__ sched, int xcd) {
-  for (int t = 0; t < kNumXcd; ++t) {
-    const int x = (xcd + t) & (kNumXcd - 1);
-    const int len = sched[kSchedSeg + x + 1] - sched[kSchedSeg + x];
-    if (len <= 0) continue;
-    int* ctr = sched + kSchedCounter + x;
-    if (__atomic_load_n(ctr, __ATOMIC_RELAXED) >= len) continue;
-    const int k = atomicAdd(ctr, 1);
-    if (k < len) return sched[kSchedSeg + x] + k;
-  }
-  return -1;
+// Called by one thread.  Position in the hand-out order of the next item, or -1 when the list is drained.
+__device__ __forceinline__ int sched_next(int* __restrict__ sched) {
+  if (__atomic_load_n(sched + kSchedCounter, __ATOMIC_RELAXED) >= sched[kSchedTotal]) return -1;
+  const int k = atomicAdd(sched + kSchedCounter, 1);
+  return k < sched[kSchedTotal] ? k : -1;
 }
 
-// item -> (head index bh, query tile tq); tiles of a head are handed out last first
-__host__ __device__ inline void sched_decode(const int* __restrict__ sched, int BH, int item, int& bh, int& tq) {
-  const int* prefix = sched + kSchedPrefix;
-  int lo = 0, hi = BH;                     // largest bh with prefix[bh] <= item
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (prefix[mid] <= item) lo = mid; else hi = mid;
-  }
-  bh = lo;
-  tq = prefix[lo + 1] - 1 - item;          // = (tiles of the head) - 1 - (item - prefix[lo])
+// hand-out position -> (head index bh, query tile tq)
+__host__ __device__ inline void sched_decode(const int* __restrict__ sched, size_t order_off, int k, int& bh, int& tq) {
+  const unsigned v = (unsigned)sched[order_off + k];
+  bh = (int)(v >> 16);
+  tq = (int)(v & 0xffffu);
 }
 
-// cost model: keys visited by the m longest tiles of a head (+ a fixed per-tile overhead)
-__host__ __device__ inline double sched_head_cost(int m, int nt, int nk, int causal) {
-  const double overhead = 64.0 * m;
-  if (!causal) return overhead + (double)nk * m;
-  return overhead + (double)nk / nt * ((double)m * nt - 0.5 * (double)m * (m - 1));
+// key tiles streamed by tile tq of a head with nt tiles and nk selected keys, estimated from its position
+__host__ __device__ inline int sched_estimate(int tq, int nt, int nk, int causal) {
+  if (!causal) return (nk + kTileN - 1) / kTileN;
+  const long long keys = ((long long)nk * (tq + 1) + nt - 1) / nt;
+  return (int)((keys + kTileN - 1) / kTileN);
 }
 
-// Fills the whole array (run by one device thread, or on the host by the diagnostic entry point).
-__host__ __device__ inline void sched_build(const int* q_cnt, const int* budget, int B, int Hq, int N, int b_cap,
-                                            int causal, int tile_m, int* sched) {
-  const int BH = B * Hq;
-  int* prefix = sched + kSchedPrefix;
-  int items = 0;
-  double total = 0.0;
-  for (int bh = 0; bh < BH; ++bh) {
-    const int nq = q_cnt ? q_cnt[bh] : N;
-    const int nt = nq > 0 ? (nq + tile_m - 1) / tile_m : 0;
-    int nk = budget ? budget[bh / Hq] : N;
-    nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
-    prefix[bh] = items;
-    items += nt;
-    if (nt) total += sched_head_cost(nt, nt, nk, causal);
-  }
-  prefix[BH] = items;
-  sched[kSchedTotal] = items;
-  for (int x = 0; x < kNumXcd; ++x) sched[kSchedCounter + x] = 0;
-  sched[kSchedSeg] = 0;
-  sched[kSchedSeg + kNumXcd] = items;
-  int bh = 0;
-  double cum = 0.0;                        // cost of the heads before bh
-  for (int x = 1; x < kNumXcd; ++x) {
-    const double target = total * x / kNumXcd;
-    int cut = items;
-    while (bh < BH) {
-      const int nq = q_cnt ? q_cnt[bh] : N;
-      const int nt = nq > 0 ? (nq + tile_m - 1) / tile_m : 0;
-      int nk = budget ? budget[bh / Hq] : N;
-      nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
-      const double hc = nt ? sched_head_cost(nt, nt, nk, causal) : 0.0;
-      if (nt && cum + hc >= target) {
-        int lo = 0, hi = nt;               // smallest m with cum + cost(m) >= target
-        while (lo < hi) {
-          const int mid = (lo + hi) >> 1;
-          if (cum + sched_head_cost(mid, nt, nk, causal) >= target) hi = mid; else lo = mid + 1;
-        }
-        cut = prefix[bh] + lo;
-        break;
-      }
-      cum += hc;
-      ++bh;
-    }
-    sched[kSchedSeg + x] = cut;
-  }
+// head-major item id -> 64-bit sort key: larger cost first, lower id first among equals
+__host__ __device__ inline unsigned long long sched_key(int cost, int id) {
+  return ((unsigned long long)(unsigned)cost << 32) | (unsigned)(0xffffffffu - (unsigned)id);
 }
+
+// Host mirror of the device kernels (diagnostic entry point and CPU tests): fills prefix, total and order.
+void sched_build_host(const int* q_cnt, const int* budget, int B, int Hq, int N, int b_cap, int causal, int tile_m,
+                      int* sched);
 
 }  // namespace omni

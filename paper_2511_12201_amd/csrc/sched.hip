@@ -1,23 +1,130 @@
-// Builds the per-XCD work list described in sched.h (one tiny kernel, no host sync).
+// Builds the cost-sorted work list described in sched.h (three tiny kernels, no host sync).
 #include "sched.h"
+
+#include <algorithm>
+#include <vector>
 
 namespace omni {
 
 namespace {
 
-__global__ void schedule_kernel(const int* __restrict__ q_cnt, const int* __restrict__ budget, int B, int Hq, int N,
-                                int b_cap, int causal, int tile_m, int* __restrict__ sched) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) sched_build(q_cnt, budget, B, Hq, N, b_cap, causal, tile_m, sched);
+// one thread: cumulative tile counts of the heads, total, counter
+__global__ void sched_prefix_kernel(const int* __restrict__ q_cnt, int BH, int N, int tile_m, int* __restrict__ sched) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int items = 0;
+  for (int bh = 0; bh < BH; ++bh) {
+    const int nq = q_cnt ? q_cnt[bh] : N;
+    sched[kSchedPrefix + bh] = items;
+    items += nq > 0 ? (nq + tile_m - 1) / tile_m : 0;
+  }
+  sched[kSchedPrefix + BH] = items;
+  sched[kSchedTotal] = items;
+  sched[kSchedCounter] = 0;
+}
+
+struct ItemRef {
+  int bh, tq, nt;
+};
+
+__device__ __forceinline__ ItemRef item_of(const int* __restrict__ prefix, int BH, int id) {
+  int lo = 0, hi = BH;                     // largest bh with prefix[bh] <= id
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (prefix[mid] <= id) lo = mid; else hi = mid;
+  }
+  ItemRef r;
+  r.bh = lo;
+  r.tq = id - prefix[lo];
+  r.nt = prefix[lo + 1] - prefix[lo];
+  return r;
+}
+
+// thread per item id: its cost key
+__global__ __launch_bounds__(256) void sched_cost_kernel(const int* __restrict__ q_cnt, const int* __restrict__ budget,
+                                                         const int* __restrict__ qvis, int BH, int Hq, int N, int b_cap,
+                                                         int causal, int tile_m, size_t keys_off, int* __restrict__ sched) {
+  const int id = blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= sched[kSchedTotal]) return;
+  const ItemRef it = item_of(sched + kSchedPrefix, BH, id);
+  int nk = budget ? budget[it.bh / Hq] : N;
+  nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
+  int cost;
+  if (qvis) {
+    const int nq = q_cnt ? q_cnt[it.bh] : N;
+    const int last = min((it.tq + 1) * tile_m, nq) - 1;
+    cost = (qvis[(long long)it.bh * N + last] + kTileN - 1) / kTileN;
+  } else {
+    cost = sched_estimate(it.tq, it.nt, nk, causal);
+  }
+  reinterpret_cast<unsigned long long*>(sched + keys_off)[id] = sched_key(cost, id);
+}
+
+// thread per item id: its rank among the keys (all distinct) is its place in the hand-out order
+__global__ __launch_bounds__(256) void sched_rank_kernel(int BH, size_t keys_off, size_t order_off, int* __restrict__ sched) {
+  __shared__ unsigned long long tile[256];
+  const int n = sched[kSchedTotal];
+  const int id = blockIdx.x * blockDim.x + threadIdx.x;
+  const unsigned long long* keys = reinterpret_cast<const unsigned long long*>(sched + keys_off);
+  const unsigned long long mine = id < n ? keys[id] : 0ull;
+  int rank = 0;
+  for (int j0 = 0; j0 < n; j0 += 256) {                     // uniform trip count: every thread helps to stage
+    __syncthreads();
+    tile[threadIdx.x] = j0 + threadIdx.x < n ? keys[j0 + threadIdx.x] : 0ull;
+    __syncthreads();
+    const int m = min(256, n - j0);
+    for (int j = 0; j < m; ++j) rank += tile[j] > mine ? 1 : 0;
+  }
+  if (id < n) {
+    const ItemRef it = item_of(sched + kSchedPrefix, BH, id);
+    sched[order_off + rank] = (int)(((unsigned)it.bh << 16) | (unsigned)it.tq);
+  }
 }
 
 }  // namespace
 
-int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap, int tile_m, int* sched,
+int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap, int tile_m, const int* qvis, int* sched,
                  hipStream_t st) {
-  hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(64), 0, st, q_cnt, budget, L.B, L.Hq, L.N, b_cap, L.causal, tile_m,
-                     sched);
+  const int BH = L.B * L.Hq;
+  if (BH >= 65536 || cdiv(L.N, tile_m) >= 65536) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "work list: too many heads or tiles");
+  const size_t cap = sched_cap(BH, L.N, tile_m);
+  const size_t keys_off = sched_keys_off(BH), order_off = sched_order_off(BH, L.N, tile_m);
+  hipLaunchKernelGGL(sched_prefix_kernel, dim3(1), dim3(64), 0, st, q_cnt, BH, L.N, tile_m, sched);
+  OMNI_LAUNCH_CHECK();
+  const int blocks = (int)cdiv(cap, (size_t)256);
+  hipLaunchKernelGGL(sched_cost_kernel, dim3(blocks), dim3(256), 0, st, q_cnt, budget, qvis, BH, L.Hq, L.N, b_cap, L.causal,
+                     tile_m, keys_off, sched);
+  OMNI_LAUNCH_CHECK();
+  hipLaunchKernelGGL(sched_rank_kernel, dim3(blocks), dim3(256), 0, st, BH, keys_off, order_off, sched);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
+}
+
+void sched_build_host(const int* q_cnt, const int* budget, int B, int Hq, int N, int b_cap, int causal, int tile_m,
+                      int* sched) {
+  const int BH = B * Hq;
+  int items = 0;
+  std::vector<unsigned long long> keys;
+  std::vector<int> packed;
+  for (int bh = 0; bh < BH; ++bh) {
+    const int nq = q_cnt ? q_cnt[bh] : N;
+    const int nt = nq > 0 ? (nq + tile_m - 1) / tile_m : 0;
+    int nk = budget ? budget[bh / Hq] : N;
+    nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
+    sched[kSchedPrefix + bh] = items;
+    for (int tq = 0; tq < nt; ++tq) {
+      keys.push_back(sched_key(sched_estimate(tq, nt, nk, causal), items + tq));
+      packed.push_back((int)(((unsigned)bh << 16) | (unsigned)tq));
+    }
+    items += nt;
+  }
+  sched[kSchedPrefix + BH] = items;
+  sched[kSchedTotal] = items;
+  sched[kSchedCounter] = 0;
+  std::vector<int> idx(items);
+  for (int i = 0; i < items; ++i) idx[i] = i;
+  std::sort(idx.begin(), idx.end(), [&](int a, int b) { return keys[a] > keys[b]; });
+  const size_t order_off = sched_order_off(BH, N, tile_m);
+  for (int k = 0; k < items; ++k) sched[order_off + k] = packed[idx[k]];
 }
 
 int persistent_grid() {
