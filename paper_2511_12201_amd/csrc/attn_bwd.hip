@@ -19,6 +19,8 @@
 //    dK, dV in head order (position found by binary search in the ascending
 //    index list) and writes zeros for unselected tokens.
 // fp32 inputs run the same kernels on the fp32 32x32x2 MFMA with natural layouts.
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 #include "sched.h"
@@ -1006,10 +1008,29 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
 
 // ------------------------------------------------------------------ dK, dV = sum over the heads of a KV group
 
+// inv[bh, token] = slot of the token in the head's selected list, -1 if it is not selected: the reduction then
+// finds a head's partial row with one load instead of a binary search of dependent loads.
+__global__ __launch_bounds__(256) void fill_int_kernel(int* __restrict__ p, long long n, int v) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+// grid: (cdiv(b_cap, 256), B*Hq)
+__global__ __launch_bounds__(256) void inverse_list_kernel(const int* __restrict__ kv_idx, const int* __restrict__ budget,
+                                                           int Hq, int b_cap, int N, int* __restrict__ inv) {
+  const int bh = blockIdx.y, b = bh / Hq;
+  const int nkeys = min(budget[b], b_cap);
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= nkeys) return;
+  const int tok = kv_idx[(long long)bh * b_cap + t];
+  if (tok >= 0 && tok < N) inv[(long long)bh * N + tok] = t;
+}
+
+
 // grid: (ceil(N / rows_per_block), B*Hkv); one token row per D/4 lanes.
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void attn_bwd_reduce_kernel(BwdParams p, const int* __restrict__ kv_idx,
-                                                                  T* __restrict__ dK, T* __restrict__ dV) {
+                                                                  const int* __restrict__ inv, T* __restrict__ dK,
+                                                                  T* __restrict__ dV) {
   constexpr int LPR = D / 4;
   constexpr int RPB = kThreads / LPR;
   const Layer& L = p.L;
@@ -1021,9 +1042,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_reduce_kernel(BwdParams p, 
   f32x4 ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
   for (int j = 0; j < L.G; ++j) {
     const int bh = b * L.Hq + g * L.G + j;
-    const int* list = kv_idx + (long long)bh * p.b_cap;
-    const int pos = lower_pos(list, nkeys, n);
-    if (pos < nkeys && list[pos] == n) {
+    int pos;
+    if (inv) {
+      pos = inv[(long long)bh * L.N + n];                       // slot of token n in the head's list, or -1
+    } else {
+      const int* list = kv_idx + (long long)bh * p.b_cap;
+      pos = lower_pos(list, nkeys, n);
+      if (!(pos < nkeys && list[pos] == n)) pos = -1;
+    }
+    if (pos >= 0) {
       const long long o = ((long long)bh * p.npad + pos) * D + c * 4;
       const f32x4 k4 = *reinterpret_cast<const f32x4*>(p.dKp + o);
       const f32x4 v4 = *reinterpret_cast<const f32x4*>(p.dVp + o);
@@ -1065,7 +1092,7 @@ struct BwdWs {
   int* kidx;
   float *lse2c, *deltac, *dKp, *dVp;
   int* sched;
-  int *qvis, *kfirst;
+  int *qvis, *kfirst, *inv;
 };
 
 BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
@@ -1088,6 +1115,7 @@ BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   w.sched = a.take<int>(sched_ints(L.B * L.Hq, L.N, kTileM));   // sized for the smaller tile: the longer list
   w.qvis = a.take<int>(dtype == OMNI_BF16 ? BH * L.N : 4);
   w.kfirst = a.take<int>(dtype == OMNI_BF16 ? krows : 4);
+  w.inv = a.take<int>(BH * L.N);
   return w;
 }
 
@@ -1168,8 +1196,15 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   {
     ProfScope prof__(kProfBwdReduce, st);
     constexpr int RPB = kThreads / (D / 4);
+    const long long n_inv = (long long)L.B * L.Hq * L.N;
+    hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)std::min<long long>(cdiv(n_inv, 256LL), 8192)), dim3(256), 0, st,
+                       w.inv, n_inv, -1);
+    OMNI_LAUNCH_CHECK();
+    hipLaunchKernelGGL(inverse_list_kernel, dim3(cdiv(b_cap, 256), L.B * L.Hq), dim3(256), 0, st, kv_idx, budget, L.Hq,
+                       b_cap, L.N, w.inv);
+    OMNI_LAUNCH_CHECK();
     hipLaunchKernelGGL((attn_bwd_reduce_kernel<T, D>), dim3(cdiv(L.N, RPB), L.B * L.Hkv), dim3(kThreads), 0, st, p,
-                       kv_idx, static_cast<T*>(dK), static_cast<T*>(dV));
+                       kv_idx, w.inv, static_cast<T*>(dK), static_cast<T*>(dV));
     OMNI_LAUNCH_CHECK();
   }
   return OMNI_OK;
