@@ -723,6 +723,15 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   }  // work-item loop
 }
 
+// Rows of a head's packed K/V buffer: whole tiles, and never a multiple of 4096 rows -- with a power-of-two
+// stride between the heads, workgroups that stream different heads at the same tile index (all of them start
+// at tile 0 together) hit the same cache sets and memory channels.
+int fwd_npad(int rows) {
+  int npad = (int)align_up(rows, kTileN);
+  if (npad % 4096 == 0) npad += kTileN;
+  return npad;
+}
+
 struct FwdWs {
   void* Kp;
   void* Vp;
@@ -749,7 +758,7 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
                hipStream_t st) {
   Arena a(ws);
   const int heads = sparse ? L.Hq : L.Hkv;
-  const int npad = (int)align_up(sparse ? b_cap : L.N, kTileN);
+  const int npad = fwd_npad(sparse ? b_cap : L.N);
   FwdWs w = carve_fwd(a, L, sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32, heads, npad, sparse);
   {
     const int dt = sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32;
@@ -809,7 +818,7 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
 
 size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse) {
   Arena a(nullptr);
-  carve_fwd(a, L, dtype, sparse ? L.Hq : L.Hkv, (int)align_up(sparse ? b_cap : L.N, kTileN), sparse);
+  carve_fwd(a, L, dtype, sparse ? L.Hq : L.Hkv, fwd_npad(sparse ? b_cap : L.N), sparse);
   return a.used();
 }
 
