@@ -570,7 +570,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p) {
 // ------------------------------------------------------------------ dQ, bf16 fast path
 //
 // Same organisation as the bf16 forward kernel: 512 threads = 8 wavefronts x 32 kept queries (256-row work
-// items from the XCD-aware persistent list), K / V / K^T tiles of 64 keys streamed memory -> LDS with
+// items from the longest-first persistent list), K / V / K^T tiles of 64 keys streamed memory -> LDS with
 // LDS-DMA loads into a ring of kDqStages buffers (natural tiles unpadded with the XOR chunk swizzle), one
 // barrier per tile, the loads of tile t+2 spread over the MFMAs of tile t, causal mask from the per-query
 // visible-prefix count.  Per tile and wavefront: S^T = K Q^T and dP^T = V dO^T (32 MFMAs), dS^T on the
