@@ -30,7 +30,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kRowsPerSlice = 512;   // target rows of one workgroup
+constexpr int kMinRowsPerSlice = 64;  // rows of one pass of a workgroup (bf16, d = 128)
 constexpr int kMaxSlices = 256;
 
 struct DecodeParams {
@@ -413,8 +413,10 @@ int launch_decode(const DecodeParams& p, hipStream_t st) {
 }
 
 int slices_for(long long rows, int units, int target_blocks) {
-  // enough workgroups to fill the chip a few times over, but no slice much below kRowsPerSlice rows
-  long long s = cdiv(rows, (long long)kRowsPerSlice);
+  // as many slices as it takes to reach the wanted number of workgroups, but no slice below one pass of a
+  // workgroup (64 rows): a short row list (the few thousand non-visual rows of the slimmed decode) would
+  // otherwise run as a handful of long, latency-bound workgroups
+  long long s = cdiv(rows, (long long)kMinRowsPerSlice);
   const long long want = cdiv(target_blocks, units);
   if (s > want) s = want;
   if (s < 1) s = 1;
