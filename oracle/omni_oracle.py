@@ -280,25 +280,32 @@ def kv_budget(a_f32, recall_p: float, budget_mode: int = 0):
     to every head.  budget_mode 1 takes the largest per-head budget instead,
     which meets the recall target on every head by construction (the paper
     asserts this of mode 0; it holds when the flattest head is also the one
-    that needs the most keys).  recall[i] is the mass of head i's own b largest
-    scores divided by N.  Returns dict(kurtosis [B,Hq] f64, flattest [B] i32,
-    budget [B] i32, recall [B,Hq] f64).
+    that needs the most keys).  budget_mode 2 gives every head the budget of
+    its own scores: the alternative the paper's introduction and KV-selection
+    section weigh against the shared budget and set aside for its cost; budget
+    is then [B,Hq].  recall[i] is the mass of head i's own b (b_i in mode 2)
+    largest scores divided by N.  Returns dict(kurtosis [B,Hq] f64, flattest
+    [B] i32, budget [B] i32 (mode 2: [B,Hq]), recall [B,Hq] f64).
     """
     a = np.asarray(a_f32, dtype=np.float32)
     B, Hq, N = a.shape
     kurt = kurtosis(a)
     flat = flattest_head(kurt)
-    budget = np.empty(B, dtype=np.int32)
+    budget = np.empty((B, Hq) if budget_mode == 2 else B, dtype=np.int32)
     recall = np.empty((B, Hq))
     for b in range(B):
         if budget_mode == 0:
             budget[b] = budget_of(a[b, flat[b]], recall_p, N)
         elif budget_mode == 1:
             budget[b] = max(budget_of(a[b, i], recall_p, N) for i in range(Hq))
+        elif budget_mode == 2:
+            for i in range(Hq):
+                budget[b, i] = budget_of(a[b, i], recall_p, N)
         else:
-            raise ValueError("budget_mode must be 0 or 1")
+            raise ValueError("budget_mode must be 0, 1 or 2")
         for i in range(Hq):
-            top = np.sort(_f64(a[b, i]))[::-1][: budget[b]]
+            bi = budget[b, i] if budget_mode == 2 else budget[b]
+            top = np.sort(_f64(a[b, i]))[::-1][:bi]
             recall[b, i] = top.sum() / N
     return dict(kurtosis=kurt, flattest=flat, budget=budget, recall=recall)
 
@@ -308,18 +315,22 @@ def select_kv(a_f32, budget):
 
     Exactly b keys per head: when several keys share the b-th largest value the
     ones of lower token index are taken.  The value mask equals the key mask.
-    Returns list over batch of int32 arrays [Hq, b], ascending along b.
+    budget is [B] (one b per batch item, the paper's rule) or [B,Hq] (a budget
+    per head).  Returns a list over batch of int32 arrays [Hq, b], ascending
+    along b; with per-head budgets, a list over batch of lists over heads of
+    int32 arrays [b_i].
     """
     a = np.asarray(a_f32, dtype=np.float32)
     B, Hq, N = a.shape
+    budget = np.asarray(budget)
     out = []
     for b in range(B):
-        bb = int(budget[b])
-        idx = np.empty((Hq, bb), dtype=np.int32)
+        rows = []
         for i in range(Hq):
+            bb = int(budget[b, i] if budget.ndim == 2 else budget[b])
             order = np.lexsort((np.arange(N), -a[b, i].astype(np.float64)))
-            idx[i] = np.sort(order[:bb])
-        out.append(idx)
+            rows.append(np.sort(order[:bb]).astype(np.int32))
+        out.append(rows if budget.ndim == 2 else np.stack(rows).reshape(Hq, -1))
     return out
 
 

@@ -336,6 +336,54 @@ def test_shared_budget_meets_recall_on_every_head_of_the_synthetic_layer():
     assert 0.05 * cfg.n_tokens < r["budget"][0] < 0.8 * cfg.n_tokens
 
 
+def test_per_head_budgets_are_each_minimal_and_bracket_the_shared_ones():
+    # budget_mode 2: every head gets the smallest prefix of its own sorted scores
+    # that reaches p*N (brute force), so each head meets the target and no head
+    # could drop a key; modes 0 and 1 are one entry / the maximum of that row
+    cfg = synth.C2_16K.scaled(frames=4, n_text=16, n_q_heads=8, n_kv_heads=2, head_dim=32)
+    L = synth.make_layer(cfg)
+    a = oc.pooled_key_scores(L["Q"], L["K"], 64, True, cfg.scale).astype(np.float32)
+    N = cfg.n_tokens
+    for p in (0.5, 0.82, 0.95):
+        r2 = oc.kv_budget(a, p, 2)
+        assert r2["budget"].shape == (1, cfg.n_q_heads) and r2["budget"].dtype == np.int32
+        target = float(np.float32(p)) * N
+        for i in range(cfg.n_q_heads):
+            bi = int(r2["budget"][0, i])
+            assert bi == _brute_budget(a[0, i], p, N)
+            srt = np.sort(a[0, i].astype(np.float64))[::-1]
+            assert srt[:bi].sum() >= target
+            assert bi == 1 or srt[: bi - 1].sum() < target
+            assert abs(srt[:bi].sum() / N - r2["recall"][0, i]) < 1e-12
+        assert np.all(r2["recall"][0] >= float(np.float32(p)) - 1e-12)
+        r0 = oc.kv_budget(a, p, 0)
+        r1 = oc.kv_budget(a, p, 1)
+        assert r0["budget"][0] == r2["budget"][0, int(r0["flattest"][0])]
+        assert r1["budget"][0] == r2["budget"][0].max()
+        np.testing.assert_array_equal(r2["kurtosis"], r0["kurtosis"])
+    with pytest.raises(ValueError):
+        oc.kv_budget(a, 0.5, 3)
+
+
+def test_select_kv_with_per_head_budgets_is_ragged_and_matches_the_shared_rule_per_head():
+    rng = np.random.default_rng(27)
+    a = rng.random((2, 3, 9)).astype(np.float32)
+    budget = np.array([[1, 9, 4], [3, 3, 0]], dtype=np.int32)
+    out = oc.select_kv(a, budget)
+    assert len(out) == 2 and all(len(rows) == 3 for rows in out)
+    for b in range(2):
+        for i in range(3):
+            bi = int(budget[b, i])
+            got = out[b][i]
+            assert got.dtype == np.int32 and got.shape == (bi,)
+            # head by head it is the shared-budget selection at that head's b
+            if bi:
+                np.testing.assert_array_equal(got, oc.select_kv(a[b:b + 1], [bi])[0][i])
+                best = max(a[b, i, list(c)].astype(np.float64).sum()
+                           for c in itertools.combinations(range(9), bi))
+                assert a[b, i, got].astype(np.float64).sum() == pytest.approx(best, rel=0, abs=1e-12)
+
+
 # ------------------------------------------------------------------ top-b key selection
 
 def test_select_kv_maximises_retained_mass_bruteforce():
