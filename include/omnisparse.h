@@ -138,13 +138,19 @@ int omni_select_queries(const omni_layer_desc* desc, const float* scores,
  * budget = min { b : sum of the b largest key_scores[flattest] >= recall_p * n_tokens }
  * (budget_mode 0, the paper's rule) or the maximum over heads of each head's own
  * such b (budget_mode 1).  recall[i] = mass of head i's b largest scores / n_tokens.
+ * budget_mode 2 gives every head the budget of its own scores (b_i = the same
+ * minimum taken on key_scores[i]): the per-head alternative that the paper's
+ * introduction and this section set aside as too slow.  budget and budget_host
+ * then hold [batch, n_q_heads] entries, recall[i] is the mass of head i's b_i
+ * largest scores, and the *_per_head entry points below consume the result.
  *   key_scores [batch, n_q_heads, n_tokens] f32, out
  *   kurtosis   [batch, n_q_heads] f64, out
  *   flattest   [batch] i32, out
- *   budget     [batch] i32, out (device)
+ *   budget     [batch] i32, out (device); [batch, n_q_heads] in budget_mode 2
  *   recall     [batch, n_q_heads] f32, out
- *   budget_host: optional pinned HOST pointer [batch]; if not null the budget is
- *                also copied there (valid after the stream is synchronised).
+ *   budget_host: optional pinned HOST pointer, same shape as budget; if not null
+ *                the budget is also copied there (valid after the stream is
+ *                synchronised).
  * 0 < recall_p <= 1, probe_block >= 1.
  */
 int omni_kv_budget(const omni_layer_desc* desc, const void* Q, const void* K,
@@ -174,6 +180,36 @@ int omni_budget_from_scores(const omni_layer_desc* desc, const float* key_scores
 int omni_select_kv(const omni_layer_desc* desc, const float* key_scores, const int32_t* budget,
                    int32_t b_cap, int32_t* kv_idx,
                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_select_kv_per_head, omni_sparse_attn_fwd_per_head,
+ * omni_sparse_attn_bwd_per_head, omni_visual_subset_per_head -- the calls of the
+ * same names without the suffix, with one budget per head instead of one per
+ * batch item (same section: the key-mask equation holds per head for any b; the
+ * paper shares one b between the heads to save the per-head search, the
+ * budget_mode 2 of omni_kv_budget does that search).
+ *   budget [batch, n_q_heads] i32 (device): head i keeps, attends and stores
+ *   min(budget[batch, i], b_cap) keys; kv_idx keeps its [batch, n_q_heads, b_cap]
+ *   layout, so b_cap bounds the largest head.
+ * Everything else (arguments, outputs, workspace sizes by the same call ids,
+ * errors) is as in the unsuffixed call.
+ */
+int omni_select_kv_per_head(const omni_layer_desc* desc, const float* key_scores, const int32_t* budget,
+                            int32_t b_cap, int32_t* kv_idx,
+                            void* ws, size_t ws_bytes, void* stream);
+int omni_sparse_attn_fwd_per_head(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                                  const int32_t* q_idx, const int32_t* q_cnt,
+                                  const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                                  void* O, float* lse,
+                                  void* ws, size_t ws_bytes, void* stream);
+int omni_sparse_attn_bwd_per_head(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                                  const void* O, const void* dO, const float* lse,
+                                  const int32_t* q_idx, const int32_t* q_cnt,
+                                  const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                                  void* dQ, void* dK, void* dV,
+                                  void* ws, size_t ws_bytes, void* stream);
+int omni_visual_subset_per_head(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget,
+                                int32_t b_cap, int32_t* vis_idx, int32_t* vis_cnt, void* stream);
 
 /*
  * omni_sparse_attn_fwd -- Sec. "Preliminary" (attention equation restricted by

@@ -27,6 +27,8 @@ EXPORTED = [
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
     "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
     "omni_group_subset", "omni_slim_decode_grouped", "omni_block_scores", "omni_expand_blocks",
+    "omni_select_kv_per_head", "omni_sparse_attn_fwd_per_head", "omni_sparse_attn_bwd_per_head",
+    "omni_visual_subset_per_head",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -80,9 +82,13 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_budget_from_scores.argtypes = [vp, vp, f32, C.c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_select_kv.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
     lib.omni_visual_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp]
+    lib.omni_select_kv_per_head.argtypes = lib.omni_select_kv.argtypes
+    lib.omni_visual_subset_per_head.argtypes = lib.omni_visual_subset.argtypes
     lib.omni_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.omni_sparse_attn_fwd_per_head.argtypes = lib.omni_sparse_attn_fwd.argtypes
+    lib.omni_sparse_attn_bwd_per_head.argtypes = lib.omni_sparse_attn_bwd.argtypes
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_group_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
@@ -283,7 +289,8 @@ def omni_kv_budget(desc: LayerDesc, Q, K, recall_p: float, probe_block: int = 25
     if out is None:
         out = BudgetResult(
             torch.empty(B, H, N, dtype=torch.float32, device=dev), torch.empty(B, H, dtype=torch.float64, device=dev),
-            torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+            torch.empty(B, dtype=torch.int32, device=dev),
+            torch.empty((B, H) if budget_mode == 2 else (B,), dtype=torch.int32, device=dev),
             torch.empty(B, H, dtype=torch.float32, device=dev))
     buf = ws.get(CALL_KV_BUDGET, desc, probe_block)
     _check(lib.omni_kv_budget(C.byref(desc), _ptr(Q), _ptr(K), recall_p, probe_block, budget_mode,
@@ -299,7 +306,8 @@ def omni_budget_from_scores(desc: LayerDesc, key_scores, recall_p: float, budget
     dev = key_scores.device
     B, H = desc.batch, desc.n_q_heads
     out = BudgetResult(key_scores, torch.empty(B, H, dtype=torch.float64, device=dev),
-                       torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+                       torch.empty(B, dtype=torch.int32, device=dev),
+                       torch.empty((B, H) if budget_mode == 2 else (B,), dtype=torch.int32, device=dev),
                        torch.empty(B, H, dtype=torch.float32, device=dev))
     buf = ws.get(CALL_KV_BUDGET, desc, 256)
     _check(lib.omni_budget_from_scores(C.byref(desc), _ptr(key_scores), recall_p, budget_mode, _ptr(out.kurtosis),
@@ -308,41 +316,66 @@ def omni_budget_from_scores(desc: LayerDesc, key_scores, recall_p: float, budget
     return out
 
 
-def omni_select_kv(desc: LayerDesc, key_scores, budget, b_cap: int, kv_idx=None, ws: Workspace | None = None):
+def _budget_shape_ok(desc, budget, per_head: bool):
+    want = desc.batch * (desc.n_q_heads if per_head else 1)
+    if budget.numel() != want:
+        raise ValueError(f"budget has {budget.numel()} entries, this call reads {want}")
+
+
+def omni_select_kv(desc: LayerDesc, key_scores, budget, b_cap: int, kv_idx=None, ws: Workspace | None = None,
+                   _per_head: bool = False):
     lib = load_library()
+    _budget_shape_ok(desc, budget, _per_head)
     ws = ws or default_workspace()
     if kv_idx is None:
         kv_idx = torch.empty(desc.batch, desc.n_q_heads, b_cap, dtype=torch.int32, device=key_scores.device)
     buf = ws.get(CALL_SELECT_KV, desc)
-    _check(lib.omni_select_kv(C.byref(desc), _ptr(key_scores), _ptr(budget), b_cap, _ptr(kv_idx), _ptr(buf),
-                              buf.numel(), _stream()))
+    fn = lib.omni_select_kv_per_head if _per_head else lib.omni_select_kv
+    _check(fn(C.byref(desc), _ptr(key_scores), _ptr(budget), b_cap, _ptr(kv_idx), _ptr(buf), buf.numel(), _stream()))
     return kv_idx
 
 
-def omni_visual_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, vis_idx=None, vis_cnt=None):
+def omni_select_kv_per_head(desc: LayerDesc, key_scores, budget, b_cap: int, kv_idx=None, ws: Workspace | None = None):
+    return omni_select_kv(desc, key_scores, budget, b_cap, kv_idx, ws, _per_head=True)
+
+
+def omni_visual_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, vis_idx=None, vis_cnt=None,
+                       _per_head: bool = False):
     lib = load_library()
+    _budget_shape_ok(desc, budget, _per_head)
     dev = kv_idx.device
     if vis_idx is None:
         vis_idx = torch.empty(desc.batch, desc.n_q_heads, b_cap, dtype=torch.int32, device=dev)
     if vis_cnt is None:
         vis_cnt = torch.empty(desc.batch, desc.n_q_heads, dtype=torch.int32, device=dev)
-    _check(lib.omni_visual_subset(C.byref(desc), _ptr(kv_idx), _ptr(budget), b_cap, _ptr(vis_idx), _ptr(vis_cnt),
-                                  _stream()))
+    fn = lib.omni_visual_subset_per_head if _per_head else lib.omni_visual_subset
+    _check(fn(C.byref(desc), _ptr(kv_idx), _ptr(budget), b_cap, _ptr(vis_idx), _ptr(vis_cnt), _stream()))
     return vis_idx, vis_cnt
 
 
+def omni_visual_subset_per_head(desc: LayerDesc, kv_idx, budget, b_cap: int, vis_idx=None, vis_cnt=None):
+    return omni_visual_subset(desc, kv_idx, budget, b_cap, vis_idx, vis_cnt, _per_head=True)
+
+
 def omni_sparse_attn_fwd(desc: LayerDesc, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap: int, O=None, lse=None,
-                         ws: Workspace | None = None):
+                         ws: Workspace | None = None, _per_head: bool = False):
     lib = load_library()
+    _budget_shape_ok(desc, budget, _per_head)
     ws = ws or default_workspace()
     if O is None:
         O = torch.empty_like(Q)
     if lse is None:
         lse = torch.empty(desc.batch, desc.n_q_heads, desc.n_tokens, dtype=torch.float32, device=Q.device)
     buf = ws.get(CALL_SPARSE_ATTN_FWD, desc, b_cap)
-    _check(lib.omni_sparse_attn_fwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(q_idx), _ptr(q_cnt), _ptr(kv_idx),
-                                    _ptr(budget), b_cap, _ptr(O), _ptr(lse), _ptr(buf), buf.numel(), _stream()))
+    fn = lib.omni_sparse_attn_fwd_per_head if _per_head else lib.omni_sparse_attn_fwd
+    _check(fn(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(q_idx), _ptr(q_cnt), _ptr(kv_idx), _ptr(budget), b_cap,
+              _ptr(O), _ptr(lse), _ptr(buf), buf.numel(), _stream()))
     return O, lse
+
+
+def omni_sparse_attn_fwd_per_head(desc: LayerDesc, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap: int, O=None, lse=None,
+                                  ws: Workspace | None = None):
+    return omni_sparse_attn_fwd(desc, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, _per_head=True)
 
 
 def omni_dense_attn_fwd(desc: LayerDesc, Q, K, V, O=None, lse=None, ws: Workspace | None = None):
@@ -359,8 +392,9 @@ def omni_dense_attn_fwd(desc: LayerDesc, Q, K, V, O=None, lse=None, ws: Workspac
 
 
 def omni_sparse_attn_bwd(desc: LayerDesc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap: int,
-                         dQ=None, dK=None, dV=None, ws: Workspace | None = None):
+                         dQ=None, dK=None, dV=None, ws: Workspace | None = None, _per_head: bool = False):
     lib = load_library()
+    _budget_shape_ok(desc, budget, _per_head)
     ws = ws or default_workspace()
     if dQ is None:
         dQ = torch.empty_like(Q)
@@ -369,10 +403,16 @@ def omni_sparse_attn_bwd(desc: LayerDesc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_
     if dV is None:
         dV = torch.empty_like(V)
     buf = ws.get(CALL_SPARSE_ATTN_BWD, desc, b_cap)
-    _check(lib.omni_sparse_attn_bwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse),
-                                    _ptr(q_idx), _ptr(q_cnt), _ptr(kv_idx), _ptr(budget), b_cap, _ptr(dQ), _ptr(dK),
-                                    _ptr(dV), _ptr(buf), buf.numel(), _stream()))
+    fn = lib.omni_sparse_attn_bwd_per_head if _per_head else lib.omni_sparse_attn_bwd
+    _check(fn(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(q_idx), _ptr(q_cnt),
+              _ptr(kv_idx), _ptr(budget), b_cap, _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(buf), buf.numel(), _stream()))
     return dQ, dK, dV
+
+
+def omni_sparse_attn_bwd_per_head(desc: LayerDesc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap: int,
+                                  dQ=None, dK=None, dV=None, ws: Workspace | None = None):
+    return omni_sparse_attn_bwd(desc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws,
+                                _per_head=True)
 
 
 def omni_slim_decode(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, vis_idx, vis_cnt, b_cap: int,

@@ -88,6 +88,7 @@ Layer make_layer(const omni_layer_desc* d) {
   L.v1 = d->vis_end;
   L.sink = d->sink_index;
   L.causal = d->causal;
+  L.bph = 0;
   L.scale = d->softmax_scale;
   for (int k = 0; k < 3; ++k) {
     L.qs[k] = d->q_stride[k];
@@ -288,7 +289,7 @@ int omni_kv_budget(const omni_layer_desc* desc, const void* Q, const void* K, fl
   REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K);
   if (!(recall_p > 0.f && recall_p <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "recall_p must be in (0, 1]");
   if (probe_block < 1) OMNI_FAIL(OMNI_ERR_INVALID, "probe_block must be >= 1");
-  if (budget_mode != 0 && budget_mode != 1) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0 or 1");
+  if (budget_mode < 0 || budget_mode > 2) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0, 1 or 2");
   const Layer L = make_layer(desc);
   CHECK(check_ws(ws, ws_bytes, kv_budget_ws(L, desc->dtype, probe_block)));
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -296,7 +297,8 @@ int omni_kv_budget(const omni_layer_desc* desc, const void* Q, const void* K, fl
   void* ws2 = static_cast<char*>(ws) + align_up(probe_ws(L, desc->dtype, probe_block), 256);
   CHECK(run_budget_stats(L, key_scores, recall_p, budget_mode, kurtosis, flattest, budget, recall, ws2, st));
   if (budget_host)
-    OMNI_HIP_CHECK(hipMemcpyAsync(budget_host, budget, sizeof(int32_t) * L.B, hipMemcpyDeviceToHost, st));
+    OMNI_HIP_CHECK(hipMemcpyAsync(budget_host, budget, sizeof(int32_t) * L.B * (budget_mode == 2 ? L.Hq : 1),
+                                   hipMemcpyDeviceToHost, st));
   return OMNI_OK;
 }
 
@@ -307,31 +309,54 @@ int omni_budget_from_scores(const omni_layer_desc* desc, const float* key_scores
   CHECK(validate_layer(desc));
   REQUIRE_PTR(key_scores); REQUIRE_PTR(kurtosis); REQUIRE_PTR(flattest); REQUIRE_PTR(budget); REQUIRE_PTR(recall);
   if (!(recall_p > 0.f && recall_p <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "recall_p must be in (0, 1]");
-  if (budget_mode != 0 && budget_mode != 1) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0 or 1");
+  if (budget_mode < 0 || budget_mode > 2) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0, 1 or 2");
   const Layer L = make_layer(desc);
   CHECK(check_ws(ws, ws_bytes, budget_stats_ws(L)));
   return run_budget_stats(L, key_scores, recall_p, budget_mode, kurtosis, flattest, budget, recall, ws,
                           static_cast<hipStream_t>(stream));
 }
 
-int omni_select_kv(const omni_layer_desc* desc, const float* key_scores, const int32_t* budget, int32_t b_cap,
-                   int32_t* kv_idx, void* ws, size_t ws_bytes, void* stream) {
+static int select_kv_impl(const omni_layer_desc* desc, int per_head, const float* key_scores, const int32_t* budget,
+                          int32_t b_cap, int32_t* kv_idx, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
   CHECK(validate_layer(desc));
   REQUIRE_PTR(key_scores); REQUIRE_PTR(budget); REQUIRE_PTR(kv_idx);
   if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
-  const Layer L = make_layer(desc);
+  Layer L = make_layer(desc);
+  L.bph = per_head;
   CHECK(check_ws(ws, ws_bytes, select_ws(L)));
   return run_select_kv(L, key_scores, budget, b_cap, kv_idx, ws, static_cast<hipStream_t>(stream));
 }
 
-int omni_visual_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
-                       int32_t* vis_idx, int32_t* vis_cnt, void* stream) {
+int omni_select_kv(const omni_layer_desc* desc, const float* key_scores, const int32_t* budget, int32_t b_cap,
+                   int32_t* kv_idx, void* ws, size_t ws_bytes, void* stream) {
+  return select_kv_impl(desc, 0, key_scores, budget, b_cap, kv_idx, ws, ws_bytes, stream);
+}
+
+int omni_select_kv_per_head(const omni_layer_desc* desc, const float* key_scores, const int32_t* budget,
+                            int32_t b_cap, int32_t* kv_idx, void* ws, size_t ws_bytes, void* stream) {
+  return select_kv_impl(desc, 1, key_scores, budget, b_cap, kv_idx, ws, ws_bytes, stream);
+}
+
+static int visual_subset_impl(const omni_layer_desc* desc, int per_head, const int32_t* kv_idx, const int32_t* budget,
+                              int32_t b_cap, int32_t* vis_idx, int32_t* vis_cnt, void* stream) {
   clear_error();
   CHECK(validate_layer(desc));
   REQUIRE_PTR(kv_idx); REQUIRE_PTR(budget); REQUIRE_PTR(vis_idx); REQUIRE_PTR(vis_cnt);
   if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
-  return run_visual_subset(make_layer(desc), kv_idx, budget, b_cap, vis_idx, vis_cnt, static_cast<hipStream_t>(stream));
+  Layer L = make_layer(desc);
+  L.bph = per_head;
+  return run_visual_subset(L, kv_idx, budget, b_cap, vis_idx, vis_cnt, static_cast<hipStream_t>(stream));
+}
+
+int omni_visual_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                       int32_t* vis_idx, int32_t* vis_cnt, void* stream) {
+  return visual_subset_impl(desc, 0, kv_idx, budget, b_cap, vis_idx, vis_cnt, stream);
+}
+
+int omni_visual_subset_per_head(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget,
+                                int32_t b_cap, int32_t* vis_idx, int32_t* vis_cnt, void* stream) {
+  return visual_subset_impl(desc, 1, kv_idx, budget, b_cap, vis_idx, vis_cnt, stream);
 }
 
 int omni_group_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
@@ -372,19 +397,34 @@ int omni_expand_blocks(const omni_layer_desc* desc, const int32_t* blk_idx, cons
                            static_cast<hipStream_t>(stream));
 }
 
-int omni_sparse_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
-                         const int32_t* q_idx, const int32_t* q_cnt, const int32_t* kv_idx, const int32_t* budget,
-                         int32_t b_cap, void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
+static int sparse_attn_fwd_impl(const omni_layer_desc* desc, int per_head, const void* Q, const void* K, const void* V,
+                                const int32_t* q_idx, const int32_t* q_cnt, const int32_t* kv_idx,
+                                const int32_t* budget, int32_t b_cap, void* O, float* lse, void* ws, size_t ws_bytes,
+                                void* stream) {
   clear_error();
   CHECK(validate_layer(desc));
   REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(V); REQUIRE_PTR(q_idx); REQUIRE_PTR(q_cnt); REQUIRE_PTR(kv_idx);
   REQUIRE_PTR(budget); REQUIRE_PTR(O); REQUIRE_PTR(lse);
   REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K); REQUIRE_ALIGNED(V); REQUIRE_ALIGNED(O);
   if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
-  const Layer L = make_layer(desc);
+  Layer L = make_layer(desc);
+  L.bph = per_head;
   CHECK(check_ws(ws, ws_bytes, attn_fwd_ws(L, desc->dtype, b_cap, true)));
   return run_attn_fwd(L, desc->dtype, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, true,
                       static_cast<hipStream_t>(stream));
+}
+
+int omni_sparse_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                         const int32_t* q_idx, const int32_t* q_cnt, const int32_t* kv_idx, const int32_t* budget,
+                         int32_t b_cap, void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  return sparse_attn_fwd_impl(desc, 0, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, ws_bytes, stream);
+}
+
+int omni_sparse_attn_fwd_per_head(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                                  const int32_t* q_idx, const int32_t* q_cnt, const int32_t* kv_idx,
+                                  const int32_t* budget, int32_t b_cap, void* O, float* lse, void* ws, size_t ws_bytes,
+                                  void* stream) {
+  return sparse_attn_fwd_impl(desc, 1, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, ws_bytes, stream);
 }
 
 int omni_dense_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, void* O, float* lse,
@@ -399,10 +439,10 @@ int omni_dense_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* 
                       static_cast<hipStream_t>(stream));
 }
 
-int omni_sparse_attn_bwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, const void* O,
-                         const void* dO, const float* lse, const int32_t* q_idx, const int32_t* q_cnt,
-                         const int32_t* kv_idx, const int32_t* budget, int32_t b_cap, void* dQ, void* dK, void* dV,
-                         void* ws, size_t ws_bytes, void* stream) {
+static int sparse_attn_bwd_impl(const omni_layer_desc* desc, int per_head, const void* Q, const void* K, const void* V,
+                                const void* O, const void* dO, const float* lse, const int32_t* q_idx,
+                                const int32_t* q_cnt, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                                void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
   CHECK(validate_layer(desc));
   REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(V); REQUIRE_PTR(O); REQUIRE_PTR(dO); REQUIRE_PTR(lse);
@@ -411,10 +451,27 @@ int omni_sparse_attn_bwd(const omni_layer_desc* desc, const void* Q, const void*
   REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K); REQUIRE_ALIGNED(V); REQUIRE_ALIGNED(O); REQUIRE_ALIGNED(dO);
   REQUIRE_ALIGNED(dQ); REQUIRE_ALIGNED(dK); REQUIRE_ALIGNED(dV);
   if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
-  const Layer L = make_layer(desc);
+  Layer L = make_layer(desc);
+  L.bph = per_head;
   CHECK(check_ws(ws, ws_bytes, attn_bwd_ws(L, desc->dtype, b_cap)));
   return run_attn_bwd(L, desc->dtype, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws,
                       static_cast<hipStream_t>(stream));
+}
+
+int omni_sparse_attn_bwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, const void* O,
+                         const void* dO, const float* lse, const int32_t* q_idx, const int32_t* q_cnt,
+                         const int32_t* kv_idx, const int32_t* budget, int32_t b_cap, void* dQ, void* dK, void* dV,
+                         void* ws, size_t ws_bytes, void* stream) {
+  return sparse_attn_bwd_impl(desc, 0, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws,
+                              ws_bytes, stream);
+}
+
+int omni_sparse_attn_bwd_per_head(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                                  const void* O, const void* dO, const float* lse, const int32_t* q_idx,
+                                  const int32_t* q_cnt, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                                  void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream) {
+  return sparse_attn_bwd_impl(desc, 1, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws,
+                              ws_bytes, stream);
 }
 
 int omni_slim_decode(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(BwdParams p)
   const Layer& L = p.L;
   const int ktile = blockIdx.x, bh = blockIdx.y;
   const int b = bh / L.Hq, i = bh % L.Hq;
-  const int nkeys = min(p.budget[b], p.b_cap);
+  const int nkeys = min(p.budget[budget_slot(L.bph, b, bh)], p.b_cap);
   if (ktile * kBwdKeys >= nkeys) return;
   const int nq = p.q_cnt[bh];
   const int lane = lane_id(), wave = threadIdx.x >> 6;
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dq_kernel(BwdParams p) {
   sched_decode(p.sched, p.order_off, item, bh, tq);
   const int b = bh / L.Hq, i = bh % L.Hq;
   const int nq = p.q_cnt[bh];
-  const int nkeys = min(p.budget[b], p.b_cap);
+  const int nkeys = min(p.budget[budget_slot(L.bph, b, bh)], p.b_cap);
   const int* kidx = p.kidx + (long long)bh * p.npad;
   const int* qlist = p.q_idx + (long long)bh * L.N;
 
@@ -817,7 +817,7 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
   const int ktile = within / heads_here, bh = grp * p.head_group + within % heads_here;
   if (ktile >= nkt) return;
   const int b = bh / L.Hq;
-  const int nkeys = min(p.budget[b], p.b_cap);
+  const int nkeys = min(p.budget[budget_slot(L.bph, b, bh)], p.b_cap);
   if (ktile * kKeyTile >= nkeys) return;
   const int nq = p.q_cnt[bh];
   const int lane = lane_id();
@@ -1024,9 +1024,9 @@ __global__ __launch_bounds__(256) void fill_int_kernel(int* __restrict__ p, long
 }
 // grid: (cdiv(b_cap, 256), B*Hq)
 __global__ __launch_bounds__(256) void inverse_list_kernel(const int* __restrict__ kv_idx, const int* __restrict__ budget,
-                                                           int Hq, int b_cap, int N, int* __restrict__ inv) {
+                                                           int bph, int Hq, int b_cap, int N, int* __restrict__ inv) {
   const int bh = blockIdx.y, b = bh / Hq;
-  const int nkeys = min(budget[b], b_cap);
+  const int nkeys = min(budget[budget_slot(bph, b, bh)], b_cap);
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= nkeys) return;
   const int tok = kv_idx[(long long)bh * b_cap + t];
@@ -1046,7 +1046,6 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_reduce_kernel(BwdParams p, 
   const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
   const int n = blockIdx.x * RPB + r0;
   if (n >= L.N) return;
-  const int nkeys = min(p.budget[b], p.b_cap);
   f32x4 ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
   for (int j = 0; j < L.G; ++j) {
     const int bh = b * L.Hq + g * L.G + j;
@@ -1055,6 +1054,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_reduce_kernel(BwdParams p, 
       pos = inv[(long long)bh * L.N + n];                       // slot of token n in the head's list, or -1
     } else {
       const int* list = kv_idx + (long long)bh * p.b_cap;
+      const int nkeys = min(p.budget[budget_slot(L.bph, b, bh)], p.b_cap);
       pos = lower_pos(list, nkeys, n);
       if (!(pos < nkeys && list[pos] == n)) pos = -1;
     }
@@ -1224,7 +1224,7 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
     hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)std::min<long long>(cdiv(n_inv, 256LL), 8192)), dim3(256), 0, st,
                        w.inv, n_inv, -1);
     OMNI_LAUNCH_CHECK();
-    hipLaunchKernelGGL(inverse_list_kernel, dim3(cdiv(b_cap, 256), L.B * L.Hq), dim3(256), 0, st, kv_idx, budget, L.Hq,
+    hipLaunchKernelGGL(inverse_list_kernel, dim3(cdiv(b_cap, 256), L.B * L.Hq), dim3(256), 0, st, kv_idx, budget, L.bph, L.Hq,
                        b_cap, L.N, w.inv);
     OMNI_LAUNCH_CHECK();
     hipLaunchKernelGGL((attn_bwd_reduce_kernel<T, D>), dim3(cdiv(L.N, RPB), L.B * L.Hkv), dim3(kThreads), 0, st, p,

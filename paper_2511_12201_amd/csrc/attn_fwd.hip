@@ -62,7 +62,7 @@ struct FwdParams {
   const void* Kp;       // packed keys  [BHx, npad, D]
   const void* Vp;       // packed values, tile layout (bf16) or row-major (fp32)
   const int* kidx;      // [BHx, npad] original token index of every slot
-  const int* budget;    // [B] number of packed keys (device); nullptr: N
+  const int* budget;    // [B] (or [B,Hq] when L.bph) number of packed keys (device); nullptr: N
   int b_cap;
   int npad;
   int per_q_head;       // packed buffers per query head (sparse) or per KV head (dense)
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
   sched_decode(p.sched, p.order_off, item, bh, tq);
   const int b = bh / L.Hq, i = bh % L.Hq, g = i / L.G;
   const int nq = p.q_cnt ? p.q_cnt[bh] : L.N;
-  const int nkeys = p.budget ? min(p.budget[b], p.b_cap) : L.N;
+  const int nkeys = p.budget ? min(p.budget[budget_slot(L.bph, b, bh)], p.b_cap) : L.N;
   const int bhx = p.per_q_head ? bh : b * L.Hkv + g;
   const int* kidx = p.kidx + (long long)bhx * p.npad;
   const int* qlist = p.q_idx ? p.q_idx + (long long)bh * L.N : nullptr;
@@ -449,7 +449,7 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   tq = __builtin_amdgcn_readfirstlane(tq);
   const int b = bh / L.Hq, i = bh % L.Hq, g = i / L.G;
   const int nq = p.q_cnt ? p.q_cnt[bh] : L.N;
-  const int nkeys = p.budget ? min(p.budget[b], p.b_cap) : L.N;
+  const int nkeys = p.budget ? min(p.budget[budget_slot(L.bph, b, bh)], p.b_cap) : L.N;
   const int bhx = p.per_q_head ? bh : b * L.Hkv + g;
   const int* kidx = p.kidx + (long long)bhx * p.npad;
   const int* qlist = p.q_idx ? p.q_idx + (long long)bh * L.N : nullptr;

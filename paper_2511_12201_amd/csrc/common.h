@@ -55,11 +55,14 @@ struct Layer {
   int B, Hq, Hkv, G, D, N;
   int v0, v1, sink;
   int causal;
+  int bph;                       // 1: the budget array holds one key count per head [B,Hq], 0: one per batch item [B]
   float scale;
   long long qs[3];
   long long ks[3];
 };
 Layer make_layer(const omni_layer_desc* d);
+// Entry of a budget array that holds the key count of head bh (b = bh / Hq).
+__host__ __device__ inline int budget_slot(int bph, int b, int bh) { return bph ? bh : b; }
 
 // Optional HIP-event timing of individual kernels (omni_profile_* in the C ABI).
 enum ProfId {

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kThreads) void pack_kv_kernel(const T* __restrict__
   const int H = per_q_head ? L.Hq : L.Hkv;
   const int b = bhx / H, hx = bhx % H;
   const int g = per_q_head ? hx / L.G : hx;
-  const int nkeys = budget ? min(budget[b], b_cap) : L.N;
+  const int nkeys = budget ? min(budget[per_q_head ? budget_slot(L.bph, b, bhx) : b], b_cap) : L.N;
   if (tile * kTileN >= (int)align_up((size_t)max(nkeys, 0), (size_t)pad_to)) return;   // consumers read whole pad_to-slot groups
   if (threadIdx.x < kTileN) {
     const int p = tile * kTileN + threadIdx.x;
@@ -226,10 +226,10 @@ int launch_pack_q(const Layer& L, const void* Q, const void* O, const void* dO, 
 // grid: (cdiv(max(N, npad), 256), B*Hq)
 __global__ __launch_bounds__(256) void visibility_kernel(const int* __restrict__ q_idx, const int* __restrict__ q_cnt,
                                                          const int* __restrict__ kidx, const int* __restrict__ budget,
-                                                         int b_cap, int npad, int N, int Hq, int causal,
+                                                         int bph, int b_cap, int npad, int N, int Hq, int causal,
                                                          int* __restrict__ qvis, int* __restrict__ kfirst) {
   const int bh = blockIdx.y, b = bh / Hq;
-  const int nq = q_cnt[bh], nkeys = min(budget[b], b_cap);
+  const int nq = q_cnt[bh], nkeys = min(budget[budget_slot(bph, b, bh)], b_cap);
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   const int* qlist = q_idx + (long long)bh * N;
   const int* klist = kidx + (long long)bh * npad;
@@ -257,7 +257,7 @@ int run_visible_counts(const Layer& L, const int* q_idx, const int* q_cnt, const
                        int b_cap, int npad, int* qvis, int* kfirst, hipStream_t st) {
   const int n = kfirst ? max(L.N, npad) : L.N;
   hipLaunchKernelGGL(visibility_kernel, dim3(cdiv(n, 256), L.B * L.Hq), dim3(256), 0, st, q_idx, q_cnt, kidx, budget,
-                     b_cap, npad, L.N, L.Hq, L.causal, qvis, kfirst);
+                     L.bph, b_cap, npad, L.N, L.Hq, L.causal, qvis, kfirst);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
 }

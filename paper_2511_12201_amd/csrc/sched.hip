@@ -41,12 +41,12 @@ __device__ __forceinline__ ItemRef item_of(const int* __restrict__ prefix, int B
 
 // thread per item id: its cost key
 __global__ __launch_bounds__(256) void sched_cost_kernel(const int* __restrict__ q_cnt, const int* __restrict__ budget,
-                                                         const int* __restrict__ qvis, int BH, int Hq, int N, int b_cap,
+                                                         const int* __restrict__ qvis, int bph, int BH, int Hq, int N, int b_cap,
                                                          int causal, int tile_m, size_t keys_off, int* __restrict__ sched) {
   const int id = blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= sched[kSchedTotal]) return;
   const ItemRef it = item_of(sched + kSchedPrefix, BH, id);
-  int nk = budget ? budget[it.bh / Hq] : N;
+  int nk = budget ? budget[budget_slot(bph, it.bh / Hq, it.bh)] : N;
   nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
   int cost;
   if (qvis) {
@@ -91,7 +91,7 @@ int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap,
   hipLaunchKernelGGL(sched_prefix_kernel, dim3(1), dim3(64), 0, st, q_cnt, BH, L.N, tile_m, sched);
   OMNI_LAUNCH_CHECK();
   const int blocks = (int)cdiv(cap, (size_t)256);
-  hipLaunchKernelGGL(sched_cost_kernel, dim3(blocks), dim3(256), 0, st, q_cnt, budget, qvis, BH, L.Hq, L.N, b_cap, L.causal,
+  hipLaunchKernelGGL(sched_cost_kernel, dim3(blocks), dim3(256), 0, st, q_cnt, budget, qvis, L.bph, BH, L.Hq, L.N, b_cap, L.causal,
                      tile_m, keys_off, sched);
   OMNI_LAUNCH_CHECK();
   hipLaunchKernelGGL(sched_rank_kernel, dim3(blocks), dim3(256), 0, st, BH, keys_off, order_off, sched);

@@ -226,8 +226,8 @@ __device__ int radix_budget_block(const float* __restrict__ x, int n, unsigned l
 // keep-everything threshold (the first head's queries are all preserved).
 __global__ __launch_bounds__(kSelThreads) void radix_select_kernel(const float* __restrict__ x, int n_stride, int H,
                                                                   int lo, int hi, int k_scalar,
-                                                                  const int* __restrict__ k_dev, int k_cap,
-                                                                  int skip_head0, unsigned* __restrict__ thr,
+                                                                  const int* __restrict__ k_dev, int k_per_head,
+                                                                  int k_cap, int skip_head0, unsigned* __restrict__ thr,
                                                                   int* __restrict__ need, float* __restrict__ recall,
                                                                   float recall_div) {
   __shared__ RadixShared sh;
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kSelThreads) void radix_select_kernel(const float* 
     }
     return;
   }
-  long long k = k_dev ? (long long)min(k_dev[b], k_cap) : (long long)k_scalar;
+  long long k = k_dev ? (long long)min(k_dev[budget_slot(k_per_head, b, bh)], k_cap) : (long long)k_scalar;
   __shared__ unsigned long long mass;
   radix_select_block(x + (long long)bh * n_stride, lo, hi, k, sh, &thr[bh], &need[bh], recall ? &mass : nullptr,
                      recall != nullptr);
@@ -484,12 +484,12 @@ __global__ __launch_bounds__(kChunkThreads) void chunk_write_kernel(const float*
 }
 
 // grid: B*H.  The sub-range of an ascending index list that lies in [v0, v1).
-__global__ void visual_subset_kernel(const int* __restrict__ kv_idx, const int* __restrict__ budget, int H, int b_cap,
+__global__ void visual_subset_kernel(const int* __restrict__ kv_idx, const int* __restrict__ budget, int bph, int H, int b_cap,
                                      int v0, int v1, int* __restrict__ vis_idx, int* __restrict__ vis_cnt) {
   __shared__ int range[2];
   const int bh = blockIdx.x, b = bh / H;
   const int* src = kv_idx + (long long)bh * b_cap;
-  const int n = min(budget[b], b_cap);
+  const int n = min(budget[budget_slot(bph, b, bh)], b_cap);
   if (threadIdx.x < 2) {
     const int target = threadIdx.x == 0 ? v0 : v1;      // first position with index >= target
     int lo = 0, hi = n;
@@ -567,7 +567,7 @@ int run_select_queries(const Layer& L, const float* scores, int mode, float para
     if (want < 0) want = 0;
     if (want > n_vis) want = n_vis;
     hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, scores, L.N, L.Hq, L.v0, L.v1,
-                       (int)want, (const int*)nullptr, 0, 1, w.thr, w.need, (float*)nullptr, 1.f);
+                       (int)want, (const int*)nullptr, 0, 0, 1, w.thr, w.need, (float*)nullptr, 1.f);
     OMNI_LAUNCH_CHECK();
   }
   return compact(scores, BH, L.N, L.Hq, rule, w.thr, w.need, w.cnt_keep, w.cnt_eq, q_idx, L.N, q_cnt, st);
@@ -579,7 +579,7 @@ int run_select_kv(const Layer& L, const float* key_scores, const int* budget, in
   SelWs w = carve_select(a, L);
   const int BH = L.B * L.Hq;
   hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, 0, L.N, 0, budget,
-                     b_cap, 0, w.thr, w.need, (float*)nullptr, 1.f);
+                     L.bph, b_cap, 0, w.thr, w.need, (float*)nullptr, 1.f);
   OMNI_LAUNCH_CHECK();
   KeepRule rule;
   rule.lo = 0;
@@ -611,7 +611,11 @@ int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, in
   hipLaunchKernelGGL(argmin_kernel, dim3(L.B), dim3(64), 0, st, kurt, L.Hq, flattest);
   OMNI_LAUNCH_CHECK();
   const double target = (double)recall_p * (double)L.N;
-  if (budget_mode == 0) {
+  if (budget_mode == 2) {                      // every head its own budget, written straight to budget[B,Hq]
+    hipLaunchKernelGGL(radix_budget_kernel, dim3(L.Hq, L.B), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, flattest,
+                       1, target, budget);
+    OMNI_LAUNCH_CHECK();
+  } else if (budget_mode == 0) {
     hipLaunchKernelGGL(radix_budget_kernel, dim3(1, L.B), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, flattest, 0,
                        target, budget);
     OMNI_LAUNCH_CHECK();
@@ -623,7 +627,7 @@ int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, in
     OMNI_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, 0, L.N, 0, budget,
-                     L.N, 0, thr, need, recall, (float)L.N);
+                     budget_mode == 2 ? 1 : 0, L.N, 0, thr, need, recall, (float)L.N);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
 }
@@ -638,10 +642,10 @@ __global__ void fill_u32_kernel(unsigned* p, long long n, unsigned v) {
 }
 
 // grid: (cdiv(b_cap, 256), B*Hq)
-__global__ void group_mark_kernel(const int* __restrict__ kv_idx, const int* __restrict__ budget, int Hq, int Hkv, int b_cap,
+__global__ void group_mark_kernel(const int* __restrict__ kv_idx, const int* __restrict__ budget, int bph, int Hq, int Hkv, int b_cap,
                                   int v0, int v1, unsigned* __restrict__ umask) {
   const int bh = blockIdx.y, b = bh / Hq, i = bh % Hq, G = Hq / Hkv, g = i / G;
-  const int n = min(budget[b], b_cap);
+  const int n = min(budget[budget_slot(bph, b, bh)], b_cap);
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= n) return;
   const int tok = kv_idx[(long long)bh * b_cap + t];
@@ -699,7 +703,7 @@ int run_group_subset(const Layer& L, const int* kv_idx, const int* budget, int b
   hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<long long>(cdiv(n, 256LL), 4096)), dim3(256), 0, st, umask, n,
                      0u);
   OMNI_LAUNCH_CHECK();
-  hipLaunchKernelGGL(group_mark_kernel, dim3(cdiv(b_cap, 256), L.B * L.Hq), dim3(256), 0, st, kv_idx, budget, L.Hq, L.Hkv,
+  hipLaunchKernelGGL(group_mark_kernel, dim3(cdiv(b_cap, 256), L.B * L.Hq), dim3(256), 0, st, kv_idx, budget, L.bph, L.Hq, L.Hkv,
                      b_cap, L.v0, L.v1, umask);
   OMNI_LAUNCH_CHECK();
   hipLaunchKernelGGL(group_compact_kernel, dim3(L.B * L.Hkv), dim3(1024), 0, st, umask, nv, L.v0, u_cap, grp_idx, grp_mask,
@@ -710,7 +714,7 @@ int run_group_subset(const Layer& L, const int* kv_idx, const int* budget, int b
 
 int run_visual_subset(const Layer& L, const int* kv_idx, const int* budget, int b_cap, int* vis_idx, int* vis_cnt,
                       hipStream_t st) {
-  hipLaunchKernelGGL(visual_subset_kernel, dim3(L.B * L.Hq), dim3(256), 0, st, kv_idx, budget, L.Hq, b_cap, L.v0, L.v1,
+  hipLaunchKernelGGL(visual_subset_kernel, dim3(L.B * L.Hq), dim3(256), 0, st, kv_idx, budget, L.bph, L.Hq, b_cap, L.v0, L.v1,
                      vis_idx, vis_cnt);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
