@@ -216,10 +216,17 @@ def main():
                                                                 bud, O, lse, args.steps)
         except Exception as e:
             out["block_granular_variant"] = {"error": repr(e)}
+        try:
+            out["per_head_budget_variant"] = bench_per_head_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx,
+                                                                    q_cnt, bud, O, lse, args.steps)
+        except Exception as e:
+            out["per_head_budget_variant"] = {"error": repr(e)}
         out["cpu_baseline"] = cpu_baseline(cfg, layer, q_lists, kv_lists, valid, ms_per_step)
         del Q, K, V, O, dev, layer
         torch.cuda.empty_cache()
-        for name, fn in (("train_step_32k", bench_train), ("decode_131k", bench_decode)):
+        for name, fn in (("train_step_32k", bench_train),
+                         ("train_step_32k_per_head_budgets", lambda *a: bench_train(*a, per_head=True)),
+                         ("decode_131k", bench_decode)):
             try:
                 t0 = time.time()
                 out[name] = fn(torch, ob, synth)
@@ -284,7 +291,56 @@ def bench_block_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, q_c
             "attn_algorithmic_tflops": round(4.0 * cfg.head_dim * valid / (attn_ms / max(1, n) * 1e-3) / 1e12, 1)}
 
 
-def bench_train(torch, ob, synth, steps: int = 5):
+def bench_per_head_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, q_cnt, bud, O, lse, steps):
+    """The alternative the paper sets aside: every head searches its own budget (same probe, same recall target)."""
+    N, Hq = cfg.n_tokens, cfg.n_q_heads
+    res = ob.BudgetResult(bud.key_scores, torch.empty_like(bud.kurtosis), torch.empty_like(bud.flattest),
+                          torch.empty(cfg.batch, Hq, dtype=torch.int32, device="cuda"), torch.empty_like(bud.recall))
+    kv_idx = torch.empty(cfg.batch, Hq, N, dtype=torch.int32, device="cuda")
+
+    def selection():
+        ob.omni_score_queries(desc, Q, K, probe, scores)
+        ob.omni_select_queries(desc, scores, 0, TAU, q_idx, q_cnt)
+        ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 2, out=res)
+        ob.omni_select_kv_per_head(desc, res.key_scores, res.budget, N, kv_idx)
+
+    def step():
+        selection()
+        ob.omni_sparse_attn_fwd_per_head(desc, Q, K, V, q_idx, q_cnt, kv_idx, res.budget, N, O, lse)
+
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    ob.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    attn_ms, n = ob.profile_read("attn_fwd")
+    ob.profile_enable(False)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(steps):
+        selection()
+    ev1.record()
+    torch.cuda.synchronize()
+    b = res.budget.cpu().numpy()[0]
+    cnt = q_cnt.cpu().numpy()[0]
+    qi, ki = q_idx.cpu().numpy()[0], kv_idx.cpu().numpy()[0]
+    valid, _ = pair_counts([qi[h, : cnt[h]] for h in range(Hq)], [ki[h, : b[h]] for h in range(Hq)], cfg.causal, tile_m=256)
+    attn = attn_ms / max(1, n)
+    return {"what": f"budget_mode 2: each head keeps the fewest keys that reach recall {RECALL_P} on its own scores",
+            "ms_per_step": round(ms, 4), "selection_ms": round(ev0.elapsed_time(ev1) / steps, 4),
+            "attn_fwd_ms": round(attn, 4),
+            "budget_fraction_min_mean_max": [round(float(b.min()) / N, 4), round(float(b.mean()) / N, 4),
+                                             round(float(b.max()) / N, 4)],
+            "recall_min": round(float(res.recall.min().item()), 4),
+            "flops_fraction_of_dense": round(valid / (Hq * N * (N + 1) // 2), 4),
+            "attn_algorithmic_tflops": round(4.0 * cfg.head_dim * valid / (attn * 1e-3) / 1e12, 1)}
+
+
+def bench_train(torch, ob, synth, steps: int = 5, per_head: bool = False):
     """Training step of one layer at N=32768: selection recomputed, sparse forward, sparse backward."""
     cfg = synth.C4_TRAIN_32K
     layer = synth.make_layer(cfg)
@@ -306,10 +362,11 @@ def bench_train(torch, ob, synth, steps: int = 5):
         nonlocal bud
         ob.omni_score_queries(desc, Q, K, probe, scores)
         ob.omni_select_queries(desc, scores, 0, TAU, q_idx, q_cnt)
-        bud = ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 0, out=bud)
-        ob.omni_select_kv(desc, bud.key_scores, bud.budget, N, kv_idx)
-        ob.omni_sparse_attn_fwd(desc, Q, K, V, q_idx, q_cnt, kv_idx, bud.budget, N, O, lse)
-        ob.omni_sparse_attn_bwd(desc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, bud.budget, N, dQ, dK, dV)
+        bud = ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 2 if per_head else 0, out=bud)
+        ob.omni_select_kv(desc, bud.key_scores, bud.budget, N, kv_idx, _per_head=per_head)
+        ob.omni_sparse_attn_fwd(desc, Q, K, V, q_idx, q_cnt, kv_idx, bud.budget, N, O, lse, _per_head=per_head)
+        ob.omni_sparse_attn_bwd(desc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, bud.budget, N, dQ, dK, dV,
+                                _per_head=per_head)
 
     step()
     step()
@@ -327,11 +384,14 @@ def bench_train(torch, ob, synth, steps: int = 5):
             kern[name] = round(t / n, 4)
     ob.profile_enable(False)
     cnt = q_cnt.cpu().numpy()[0]
-    b = int(bud.budget.cpu()[0])
+    bh = bud.budget.cpu().numpy().reshape(-1)
+    bh = bh if per_head else np.full(Hq, bh[0])
+    b = float(bh.mean())
     qi, ki = q_idx.cpu().numpy()[0], kv_idx.cpu().numpy()[0]
-    valid, _ = pair_counts([qi[h, : cnt[h]] for h in range(Hq)], [ki[h, :b] for h in range(Hq)], cfg.causal)
+    valid, _ = pair_counts([qi[h, : cnt[h]] for h in range(Hq)], [ki[h, : bh[h]] for h in range(Hq)], cfg.causal)
     bwd_ms = kern.get("bwd_dkdv", 0) + kern.get("bwd_dq", 0)
-    res = {"workload": f"{cfg.name}: N={N}, bf16, selection + sparse fwd + sparse bwd", "ms_per_step": round(ms, 4),
+    res = {"workload": f"{cfg.name}: N={N}, bf16, selection + sparse fwd + sparse bwd"
+                       + (", one budget per head" if per_head else ""), "ms_per_step": round(ms, 4),
            "kernel_ms": kern, "kept_query_fraction": round(float(cnt.sum()) / (Hq * N), 4),
            "budget_fraction": round(b / N, 4),
            "bwd_algorithmic_tflops": round(10.0 * D * valid / (bwd_ms * 1e-3) / 1e12, 2) if bwd_ms else None,

@@ -10,11 +10,13 @@
 // pooled row: the row statistics are per-lane scalars and the column sums are
 // accumulated per lane and reduced across lanes once at the end.
 //
-// bf16 inputs: Qbar is an fp32 mean; it is split into three bf16 terms
-// (hi + mid + lo carry all 24 mantissa bits) and multiplied with the exact bf16
-// keys in three MFMAs, so the logits have fp32 accuracy and the key scores that
-// decide the selection do not inherit bf16 rounding of the pooled query.
-// fp32 inputs use the fp32 MFMA.
+// bf16 inputs: Qbar is an fp32 mean; the pooling kernel splits it into two bf16
+// terms (hi + mid carry 16 mantissa bits) that are multiplied with the exact bf16
+// keys in two MFMAs, so the logits are good to ~1e-5 relative and the key scores
+// that decide the selection do not inherit bf16 rounding of the pooled query.
+// One workgroup serves all query heads of a KV group with one K fragment; the
+// Qbar blocks of its heads arrive by global->LDS DMA, double buffered, one
+// barrier per block.  fp32 inputs use the fp32 MFMA and stage Qbar by hand.
 #include "common.h"
 #include "kernels.h"
 
@@ -25,20 +27,23 @@ namespace {
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
+// bf16 terms that carry the fp32 pooled query into the bf16 matrix cores (hi + mid [+ lo])
+constexpr int kQbarTerms = 2;
+
 // ---------------------------------------------------------------- pooling
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void pool_queries_kernel(const T* __restrict__ Q, Layer L, int pb, int nblk,
-                                                               float* __restrict__ qbar) {
+                                                               float* __restrict__ qbar, u16* __restrict__ qsplit) {
   constexpr int E = Elem<T>::kPer16B;
   constexpr int LPR = D / E;
   constexpr int RPP = kThreads / LPR;
   __shared__ float red[RPP][D];
-  const int j = blockIdx.x, bh = blockIdx.y;
+  const int j = blockIdx.x, bh = blockIdx.y;          // j >= nblk (bf16 only): a zero row that pads the last 32-row block
   const int b = bh / L.Hq, i = bh % L.Hq;
   const T* base = Q + b * L.qs[0] + i * L.qs[1];
   const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
-  const int row_begin = j * pb, row_end = min(L.N, row_begin + pb);
+  const int row_begin = min(j * pb, L.N), row_end = min(L.N, row_begin + pb);
   float acc[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) acc[e] = 0.f;
@@ -56,7 +61,25 @@ __global__ __launch_bounds__(kThreads) void pool_queries_kernel(const T* __restr
     float s = 0.f;
 #pragma unroll 4
     for (int r = 0; r < RPP; ++r) s += red[r][threadIdx.x];
-    qbar[((long long)bh * nblk + j) * D + threadIdx.x] = s / (float)(row_end - row_begin);
+    const float mean = row_end > row_begin ? s / (float)(row_end - row_begin) : 0.f;
+    if constexpr (sizeof(T) == 2) {
+      // split terms, laid out as the probe's LDS stage: [head][row block][term][32 rows][16-byte chunks, XOR-swizzled by row]
+      constexpr int CH = D / 8;
+      const int nrb = cdiv(nblk, 32);
+      const int jb = j >> 5, r = j & 31, d = threadIdx.x;
+      const u16 hi = f32_to_bf16_bits(mean);
+      const float r1 = mean - bf16_bits_to_f32(hi);
+      u16 term[3];
+      term[0] = hi;
+      term[1] = f32_to_bf16_bits(r1);
+      term[2] = f32_to_bf16_bits(r1 - bf16_bits_to_f32(term[1]));
+      const int col = (((d >> 3) ^ (r % CH)) << 3) + (d & 7);
+#pragma unroll
+      for (int t = 0; t < kQbarTerms; ++t)
+        qsplit[((((long long)bh * nrb + jb) * kQbarTerms + t) * 32 + r) * D + col] = term[t];
+    } else {
+      qbar[((long long)bh * nblk + j) * D + threadIdx.x] = mean;
+    }
   }
 }
 
@@ -78,20 +101,21 @@ __host__ __device__ constexpr int probe_keys_per_wg() {
   return 4 * ProbeTraits<T>::kKeyBlocks * 32;
 }
 
+// fp32 inputs: one workgroup per (key chunk, query head), fp32 MFMA, Qbar blocks staged through LDS by hand.
 // PASS 1: partial (max, sum) per pooled row for this workgroup's key range.
 // PASS 2: column sums.
-template <typename T, int D, int PASS>
-__global__ __launch_bounds__(kThreads) void probe_kernel(const T* __restrict__ K, Layer L, int pb, int nblk, int nchunk,
-                                                        const float* __restrict__ qbar,
-                                                        float* __restrict__ part_m, float* __restrict__ part_l,
-                                                        const float* __restrict__ lse2w, float* __restrict__ a_out) {
-  constexpr bool kBf16 = sizeof(T) == 2;
+template <int D, int PASS>
+__global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float* __restrict__ K, Layer L, int pb, int nblk,
+                                                            int nchunk, const float* __restrict__ qbar,
+                                                            float* __restrict__ part_m, float* __restrict__ part_l,
+                                                            const float* __restrict__ lse2w,
+                                                            float* __restrict__ a_out) {
+  using T = float;
   constexpr int KB = ProbeTraits<T>::kKeyBlocks;
   constexpr int KPW = KB * 32;            // keys per wavefront
   constexpr int KPG = 4 * KPW;            // keys per workgroup
-  constexpr int QLD = kBf16 ? D + 8 : D + 4;
-  // Qbar block as MFMA B operand: bf16 -> three split terms, fp32 -> as is
-  __shared__ __attribute__((aligned(16))) unsigned char sQ_raw[(kBf16 ? 3 * 32 * QLD * 2 : 32 * QLD * 4)];
+  constexpr int QLD = D + 4;
+  __shared__ __attribute__((aligned(16))) float sQ[32 * QLD];   // Qbar block, MFMA B operand
   __shared__ float sLse[32];
   __shared__ float sRedM[4][32], sRedL[4][32];
 
@@ -104,19 +128,13 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const T* __restrict__ K
   const T* kbase = K + b * L.ks[0] + g * L.ks[1];
 
   // K fragment (A operand), rows clamped into range; out-of-range keys are masked below
-  bf16x8 kf16[kBf16 ? KB : 1][kBf16 ? D / 16 : 1];
-  f32x4 kf32[kBf16 ? 1 : KB][kBf16 ? 1 : D / 8];
+  f32x4 kf32[KB][D / 8];
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb) {
     const int key = min(k0 + kb * 32 + ln, L.N - 1);
     const T* row = kbase + (long long)key * L.ks[2];
-    if constexpr (kBf16) {
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) kf16[kb][ks] = *reinterpret_cast<const bf16x8*>(row + ks * 16 + h * 8);
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < D / 8; ++ks) kf32[kb][ks] = *reinterpret_cast<const f32x4*>(row + ks * 8 + h * 4);
-    }
+    for (int ks = 0; ks < D / 8; ++ks) kf32[kb][ks] = *reinterpret_cast<const f32x4*>(row + ks * 8 + h * 4);
   }
 
   float colacc[KB][16];
@@ -137,28 +155,11 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const T* __restrict__ K
       const int j = jb * 32 + row;
       f32x4 v = {0.f, 0.f, 0.f, 0.f};
       if (j < nblk) v = *reinterpret_cast<const f32x4*>(qsrc + (long long)j * D + col);
-      if constexpr (kBf16) {
-        u16* s0 = reinterpret_cast<u16*>(sQ_raw);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float x = v[e];
-          const u16 hi = f32_to_bf16_bits(x);
-          const float r1 = x - bf16_bits_to_f32(hi);
-          const u16 mid = f32_to_bf16_bits(r1);
-          const float r2 = r1 - bf16_bits_to_f32(mid);
-          const u16 lo = f32_to_bf16_bits(r2);
-          s0[(0 * 32 + row) * QLD + col + e] = hi;
-          s0[(1 * 32 + row) * QLD + col + e] = mid;
-          s0[(2 * 32 + row) * QLD + col + e] = lo;
-        }
-      } else {
-        float* s0 = reinterpret_cast<float*>(sQ_raw);
-        *reinterpret_cast<f32x4*>(s0 + row * QLD + col) = v;
-      }
+      *reinterpret_cast<f32x4*>(sQ + row * QLD + col) = v;
     }
     if (PASS == 2 && threadIdx.x < 32) {
       const int j = jb * 32 + threadIdx.x;
-      sLse[threadIdx.x] = j < nblk ? lse2w[(long long)bh * nblk + j] : 0.f;
+      sLse[threadIdx.x] = j < nblk ? lse2w[(long long)bh * nrb * 32 + j] : 0.f;
     }
     __syncthreads();
 
@@ -170,25 +171,12 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const T* __restrict__ K
     for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[kb][r] = 0.f;
-      if constexpr (kBf16) {
-        const u16* s0 = reinterpret_cast<const u16*>(sQ_raw);
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
+      for (int ks = 0; ks < D / 8; ++ks) {
+        const f32x4 qf = *reinterpret_cast<const f32x4*>(sQ + ln * QLD + ks * 8 + h * 4);
 #pragma unroll
-          for (int s = 2; s >= 0; --s) {            // small terms first
-            const bf16x8 qf = *reinterpret_cast<const bf16x8*>(s0 + (s * 32 + ln) * QLD + ks * 16 + h * 8);
-            acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf16[kb][ks], qf, acc[kb], 0, 0, 0);
-          }
-        }
-      } else {
-        const float* s0 = reinterpret_cast<const float*>(sQ_raw);
-#pragma unroll
-        for (int ks = 0; ks < D / 8; ++ks) {
-          const f32x4 qf = *reinterpret_cast<const f32x4*>(s0 + ln * QLD + ks * 8 + h * 4);
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            acc[kb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf32[kb][ks][e], qf[e], acc[kb], 0, 0, 0);
-        }
+        for (int e = 0; e < 4; ++e)
+          acc[kb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf32[kb][ks][e], qf[e], acc[kb], 0, 0, 0);
       }
     }
     if (PASS == 1) {
@@ -268,6 +256,237 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const T* __restrict__ K
   }
 }
 
+// ---------------------------------------------------------------- bf16 probe: one workgroup per (key chunk, KV group)
+
+// Sum of v[i] over the 32 lanes of a half-wave, for 32 values at once: a reduce-scatter butterfly (31 exchanges)
+// that leaves the total of value index (lane & 31) in v[0].
+template <int W>
+__device__ __forceinline__ void reduce_scatter_step(float (&v)[32], int ln) {
+  const bool up = (ln & W) != 0;
+#pragma unroll
+  for (int i = 0; i < W; ++i) {
+    const float send = up ? v[i] : v[i + W];
+    const float keep = up ? v[i + W] : v[i];
+    v[i] = keep + __shfl_xor(send, W, 64);
+  }
+}
+__device__ __forceinline__ float half_wave_reduce_scatter(float (&v)[32], int ln) {
+  reduce_scatter_step<16>(v, ln);
+  reduce_scatter_step<8>(v, ln);
+  reduce_scatter_step<4>(v, ln);
+  reduce_scatter_step<2>(v, ln);
+  reduce_scatter_step<1>(v, ln);
+  return v[0];
+}
+
+// grid: nchunk * B*Hkv workgroups, chunk-major (the chunks of low key index see the most pooled rows: longest first).
+// PASS 1: (max, sum) of every pooled row over this workgroup's 256 keys -> part_m / part_l.
+// PASS 2: a[head, key] = sum over pooled rows of exp2(s2 - lse2w[row]).
+template <int D, int PASS>
+__global__ __launch_bounds__(kThreads, 2) void probe_bf16_kernel(const u16* __restrict__ K, Layer L, int pb, int nblk,
+                                                             int nchunk, const u16* __restrict__ qsplit,
+                                                             float* __restrict__ part_m, float* __restrict__ part_l,
+                                                             const float* __restrict__ lse2w,
+                                                             float* __restrict__ a_out) {
+  constexpr int KB = 2;                        // 32-key blocks per wavefront
+  constexpr int KPW = KB * 32, KPG = 4 * KPW;
+  constexpr int CH = D / 8;                    // 16-byte chunks per row
+  constexpr int kStage = kQbarTerms * 32 * D * 2;
+  constexpr int IPW = kStage / 1024 / 4;       // DMA instructions (1 KiB each) per wavefront per stage
+  constexpr int IPB = IPW + (PASS == 2 ? 1 : 0);   // ... per block, with the lse row
+  constexpr int NS = 3;                        // ring of stages: blocks it+1 and it+2 are in flight while block it is used
+  static_assert(kStage % 4096 == 0, "stage must split evenly over the four wavefronts");
+  __shared__ __attribute__((aligned(1024))) unsigned char sQ[NS][kStage];
+  __shared__ float sRedM[2][4][32], sRedL[2][4][32];
+  __shared__ __attribute__((aligned(256))) float sLse[NS][64];
+
+  const int ngrp = L.B * L.Hkv;
+  const int chunk = blockIdx.x / ngrp, bg = blockIdx.x % ngrp;
+  const int b = bg / L.Hkv, g = bg % L.Hkv;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int ln = lane & 31, h = lane >> 5;
+  const int k0 = chunk * KPG + wave * KPW;     // first key of this wavefront
+  const int wg_end = chunk * KPG + KPG;
+  const float c2 = L.scale * kLog2e;
+  const int nrb = cdiv(nblk, 32);
+  const int jb0 = L.causal ? ((chunk * KPG) / pb) / 32 : 0;
+  const int n_it = L.G * (nrb - jb0);
+  const int bh0 = b * L.Hq + g * L.G;
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)&sQ[0][0];
+  const unsigned lane_off = (unsigned)(wave * 1024 + lane * 16);
+  const unsigned lse_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)&sLse[0][0];
+
+  auto issue = [&](int jh, int jb, int stage) {
+    const unsigned char* src =
+        reinterpret_cast<const unsigned char*>(qsplit) + ((long long)(bh0 + jh) * nrb + jb) * kStage;
+#pragma unroll
+    for (int q = 0; q < IPW; ++q)
+      gload_lds16(src + q * 4096, lane_off, lds_base + stage * kStage + q * 4096 + wave * 1024);
+    // the rows' lse ride along (64 floats: this block's 32 and 32 that nobody reads), so that no ordinary load --
+    // whose wait would also drain the DMA queue -- sits in the loop; every wavefront fetches them (same bytes, same
+    // place) so that all wavefronts have the same number of loads in flight
+    if (PASS == 2)
+      gload_lds4(lse2w + ((long long)(bh0 + jh) * nrb + jb) * 32 + lane, lse_base + stage * 256);
+  };
+
+  // block `it` of this workgroup is (head jh, row block jb); the issue cursor runs NS-1 blocks ahead
+  int jh_i = 0, jb_i = jb0, it_i = 0;
+  auto issue_next = [&]() {
+    if (it_i < n_it) {
+      issue(jh_i, jb_i, it_i % NS);
+      ++it_i;
+      if (++jb_i == nrb) {
+        jb_i = jb0;
+        ++jh_i;
+      }
+    }
+  };
+#pragma unroll
+  for (int pre = 0; pre < NS - 1; ++pre) issue_next();
+
+  // K fragment (A operand), rows clamped into range; out-of-range keys are masked below
+  const u16* kbase = K + b * L.ks[0] + g * L.ks[1];
+  bf16x8 kf[KB][D / 16];
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb) {
+    const int key = min(k0 + kb * 32 + ln, L.N - 1);
+    const u16* row = kbase + (long long)key * L.ks[2];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) kf[kb][ks] = *reinterpret_cast<const bf16x8*>(row + ks * 16 + h * 8);
+  }
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(kf[kb][ks]));      // landed before the loop starts
+
+  float colacc[32];
+#pragma unroll
+  for (int r = 0; r < 32; ++r) colacc[r] = 0.f;
+
+  // combine the four wavefronts' (max, sum) of one row block and write the workgroup's partial
+  auto combine = [&](int jh, int jb, int buf) {
+    const int j = jb * 32 + lane;
+    if (lane < 32 && j < nblk) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) M = fmaxf(M, sRedM[buf][w][lane]);
+      const float Mr = M == -INFINITY ? 0.f : M;
+      float Ls = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float mw = sRedM[buf][w][lane];
+        Ls += mw == -INFINITY ? 0.f : sRedL[buf][w][lane] * fast_exp2(mw - Mr);
+      }
+      const long long o = ((long long)(bh0 + jh) * nblk + j) * nchunk + chunk;
+      part_m[o] = M;
+      part_l[o] = Ls;
+    }
+  };
+
+  int jh = 0, jb = jb0, jh_prev = 0, jb_prev = jb0;
+  for (int it = 0; it < n_it; ++it) {
+    // this wavefront's share of block `it` has landed (the blocks after it may still be in flight)
+    if (it + NS - 2 < n_it) {
+      wait_vmcnt<(NS - 2) * IPB>();
+    } else {
+      wait_vmcnt<0>();
+    }
+    __syncthreads();                               // everyone's has; everyone is done reading block it-1
+    int jh_n = jh, jb_n = jb + 1;
+    if (jb_n == nrb) {
+      jb_n = jb0;
+      ++jh_n;
+    }
+    issue_next();                                  // block it+NS-1 into the stage that block it-1 used
+    if (PASS == 1 && it > 0 && wave == (it & 3)) combine(jh_prev, jb_prev, (it - 1) & 1);
+
+    const unsigned char* st = sQ[it % NS];
+    f32x16 acc[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[kb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+#pragma unroll
+      for (int s = kQbarTerms - 1; s >= 0; --s) {  // small terms first
+        const bf16x8 qf =
+            *reinterpret_cast<const bf16x8*>(st + ((s * 32 + ln) * CH + ((ks * 2 + h) ^ (ln % CH))) * 16);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf, acc[kb], 0, 0, 0);
+      }
+    }
+
+    // every key of the workgroup is real and visible to every row of the block?
+    const bool full = jb * 32 + 32 <= nblk && wg_end <= L.N && (!L.causal || (long long)(jb * 32 + 1) * pb >= wg_end);
+    const int j = jb * 32 + ln;                    // this lane's pooled row
+    const int vis_end = j < nblk ? (L.causal ? min((j + 1) * pb, L.N) : L.N) : 0;
+    const int rel = vis_end - k0 - 4 * h;          // element (kb, r) is visible iff kb*32 + 8*(r>>2) + (r&3) < rel
+
+    if (PASS == 1) {
+      float m = -INFINITY;
+      if (full) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[kb][r]);
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            if (kb * 32 + 8 * (r >> 2) + (r & 3) >= rel) acc[kb][r] = -INFINITY;
+            m = fmaxf(m, acc[kb][r]);
+          }
+      }
+      m = pair_max(m);                             // the other half-wave holds the other keys of the same row
+      const float ms = m == -INFINITY ? 0.f : m * c2;
+      float l = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) l += fast_exp2(fmaf(acc[kb][r], c2, -ms));
+      l = pair_sum(l);
+      if (h == 0) {
+        sRedM[it & 1][wave][ln] = m == -INFINITY ? m : m * c2;
+        sRedL[it & 1][wave][ln] = l;
+      }
+    } else {
+      const float lse = sLse[it % NS][ln];
+      if (full) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) colacc[kb * 16 + r] += fast_exp2(fmaf(acc[kb][r], c2, -lse));
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float pv = fast_exp2(fmaf(acc[kb][r], c2, -lse));
+            colacc[kb * 16 + r] += kb * 32 + 8 * (r >> 2) + (r & 3) < rel ? pv : 0.f;
+          }
+      }
+      if (jb == nrb - 1) {                         // last row block of this head: reduce over its rows and store
+        const float total = half_wave_reduce_scatter(colacc, ln);
+        const int key = k0 + (ln >> 4) * 32 + 8 * ((ln & 15) >> 2) + 4 * h + (ln & 3);
+        if (key < L.N) a_out[(long long)(bh0 + jh) * L.N + key] = total;
+#pragma unroll
+        for (int r = 0; r < 32; ++r) colacc[r] = 0.f;
+      }
+    }
+    jh_prev = jh;
+    jb_prev = jb;
+    jh = jh_n;
+    jb = jb_n;
+  }
+  if (PASS == 1) {
+    __syncthreads();
+    if (wave == 0) combine(jh_prev, jb_prev, (n_it - 1) & 1);
+  }
+}
+
 // One wavefront per pooled row: combine the per-chunk (max, sum) into
 // lse2w[j] = log2(sum_k 2^{s2_jk}) - log2(w_j).
 __global__ __launch_bounds__(kThreads) void probe_lse_kernel(Layer L, int pb, int nblk, int nchunk, int keys_per_chunk,
@@ -293,11 +512,12 @@ __global__ __launch_bounds__(kThreads) void probe_lse_kernel(Layer L, int pb, in
     s += m == -INFINITY ? 0.f : pl[c] * exp2f(m - Mr);
   }
   s = wave_sum(s);
-  if (lane == 0) lse2w[(long long)bh * nblk + j] = Mr + log2f(s) - log2f((float)(row_end - j * pb));
+  if (lane == 0) lse2w[(long long)bh * cdiv(nblk, 32) * 32 + j] = Mr + log2f(s) - log2f((float)(row_end - j * pb));
 }
 
 struct ProbeWs {
-  float* qbar;
+  float* qbar;                 // fp32 path: pooled queries [BH, nblk, D]
+  u16* qsplit;                 // bf16 path: split terms in the probe's stage layout
   float* part_m;
   float* part_l;
   float* lse2w;
@@ -309,10 +529,15 @@ ProbeWs carve_probe(Arena& a, const Layer& L, int pb) {
   const size_t BH = (size_t)L.B * L.Hq;
   const int nblk = cdiv(L.N, pb);
   const int nchunk = cdiv(L.N, probe_keys_per_wg<T>());
-  w.qbar = a.take<float>(BH * nblk * L.D);
+  w.qbar = nullptr;
+  w.qsplit = nullptr;
+  if (sizeof(T) == 2)
+    w.qsplit = a.take<u16>(BH * cdiv(nblk, 32) * kQbarTerms * 32 * L.D);
+  else
+    w.qbar = a.take<float>(BH * nblk * L.D);
   w.part_m = a.take<float>(BH * nblk * nchunk);
   w.part_l = a.take<float>(BH * nblk * nchunk);
-  w.lse2w = a.take<float>(BH * nblk);
+  w.lse2w = a.take<float>(BH * cdiv(nblk, 32) * 32 + 32);   // [BH, 32-row blocks, 32] and one block of slack for 64-wide reads
   return w;
 }
 
@@ -326,13 +551,34 @@ int launch_probe(const Layer& L, const void* Q, const void* K, int pb, float* ke
   const int BH = L.B * L.Hq;
   {
     ProfScope prof__(kProfPool, st);
-    hipLaunchKernelGGL((pool_queries_kernel<T, D>), dim3(nblk, BH), dim3(kThreads), 0, st, static_cast<const T*>(Q), L,
-                       pb, nblk, w.qbar);
+    const int pooled_rows = sizeof(T) == 2 ? cdiv(nblk, 32) * 32 : nblk;
+    hipLaunchKernelGGL((pool_queries_kernel<T, D>), dim3(pooled_rows, BH), dim3(kThreads), 0, st,
+                       static_cast<const T*>(Q), L, pb, nblk, w.qbar, w.qsplit);
     OMNI_LAUNCH_CHECK();
   }
+  if constexpr (sizeof(T) == 2) {
+    const u16* Kp = static_cast<const u16*>(K);
+    const int nwg = nchunk * L.B * L.Hkv;
+    {
+      ProfScope prof__(kProfProbeLse, st);
+      hipLaunchKernelGGL((probe_bf16_kernel<D, 1>), dim3(nwg), dim3(kThreads), 0, st, Kp, L, pb, nblk, nchunk, w.qsplit,
+                         w.part_m, w.part_l, (const float*)nullptr, (float*)nullptr);
+      OMNI_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(probe_lse_kernel, dim3(cdiv(nblk, 4), BH), dim3(kThreads), 0, st, L, pb, nblk, nchunk, KPG,
+                       w.part_m, w.part_l, w.lse2w);
+    OMNI_LAUNCH_CHECK();
+    {
+      ProfScope prof__(kProfProbeSum, st);
+      hipLaunchKernelGGL((probe_bf16_kernel<D, 2>), dim3(nwg), dim3(kThreads), 0, st, Kp, L, pb, nblk, nchunk, w.qsplit,
+                         (float*)nullptr, (float*)nullptr, w.lse2w, key_scores);
+      OMNI_LAUNCH_CHECK();
+    }
+    return OMNI_OK;
+  } else {
   {
     ProfScope prof__(kProfProbeLse, st);
-    hipLaunchKernelGGL((probe_kernel<T, D, 1>), dim3(nchunk, BH), dim3(kThreads), 0, st, static_cast<const T*>(K), L, pb,
+    hipLaunchKernelGGL((probe_f32_kernel<D, 1>), dim3(nchunk, BH), dim3(kThreads), 0, st, static_cast<const T*>(K), L, pb,
                        nblk, nchunk, w.qbar, w.part_m, w.part_l, (const float*)nullptr, (float*)nullptr);
     OMNI_LAUNCH_CHECK();
   }
@@ -341,11 +587,12 @@ int launch_probe(const Layer& L, const void* Q, const void* K, int pb, float* ke
   OMNI_LAUNCH_CHECK();
   {
     ProfScope prof__(kProfProbeSum, st);
-    hipLaunchKernelGGL((probe_kernel<T, D, 2>), dim3(nchunk, BH), dim3(kThreads), 0, st, static_cast<const T*>(K), L, pb,
+    hipLaunchKernelGGL((probe_f32_kernel<D, 2>), dim3(nchunk, BH), dim3(kThreads), 0, st, static_cast<const T*>(K), L, pb,
                        nblk, nchunk, w.qbar, (float*)nullptr, (float*)nullptr, w.lse2w, key_scores);
     OMNI_LAUNCH_CHECK();
   }
   return OMNI_OK;
+  }
 }
 
 }  // namespace
