@@ -58,13 +58,24 @@ __device__ __forceinline__ void radix_histogram(const float* __restrict__ x, int
   __syncthreads();
   const unsigned prefix = sh.prefix, mask = sh.mask;
   const int rep = threadIdx.x & (kRep - 1);
-  for (int n = lo + threadIdx.x; n < hi; n += blockDim.x) {
-    const float v = x[n];
-    const unsigned key = float_key(v);
-    if ((key & mask) == prefix) {
-      const unsigned d = (key >> shift) & 255u;
-      atomicAdd(&sh.rcnt[d * kRep + rep], 1u);
-      if (with_sum) atomicAdd(&sh.rsum[d * kRep + rep], to_fixed(v));
+  // kBatch loads are in flight together: one workgroup walks a whole vector, and with one load per
+  // trip the pass would cost a memory latency per element
+  constexpr int kBatch = 16;
+  for (int n0 = lo + threadIdx.x; n0 < hi; n0 += kBatch * blockDim.x) {
+    float v[kBatch];
+#pragma unroll
+    for (int e = 0; e < kBatch; ++e) {
+      const int n = n0 + e * blockDim.x;
+      v[e] = n < hi ? x[n] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < kBatch; ++e) {
+      const unsigned key = float_key(v[e]);
+      if (n0 + e * (int)blockDim.x < hi && (key & mask) == prefix) {
+        const unsigned d = (key >> shift) & 255u;
+        atomicAdd(&sh.rcnt[d * kRep + rep], 1u);
+        if (with_sum) atomicAdd(&sh.rsum[d * kRep + rep], to_fixed(v[e]));
+      }
     }
   }
   __syncthreads();
@@ -276,6 +287,7 @@ __global__ __launch_bounds__(kSelThreads) void kurtosis_kernel(const float* __re
   const float* x = a + (long long)blockIdx.x * N;
   const int w = threadIdx.x >> 6;
   double s = 0.0;
+#pragma unroll 8
   for (int n = threadIdx.x; n < N; n += kSelThreads) s += (double)x[n];
   s = wave_sum(s);
   if (lane_id() == 0) red[0][w] = s;
@@ -288,6 +300,7 @@ __global__ __launch_bounds__(kSelThreads) void kurtosis_kernel(const float* __re
   __syncthreads();
   const double mu = mean_sh;
   double s2 = 0.0, s4 = 0.0;
+#pragma unroll 8
   for (int n = threadIdx.x; n < N; n += kSelThreads) {
     const double c = (double)x[n] - mu;
     const double c2 = c * c;
