@@ -102,11 +102,11 @@ def main():
     O = torch.empty_like(Q)
     lse = torch.empty(B, Hq, N, dtype=f32, device="cuda")
 
+    sel = ob.SelectionResult(probe, scores, q_idx, q_cnt, bud, kv_idx)
+
     def selection():
-        ob.omni_score_queries(desc, Q, K, probe, scores)
-        ob.omni_select_queries(desc, scores, 0, TAU, q_idx, q_cnt)
-        ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 0, out=bud)
-        ob.omni_select_kv(desc, bud.key_scores, bud.budget, b_cap, kv_idx)
+        # omni_score_queries + omni_select_queries + omni_kv_budget + omni_select_kv in their fused form
+        ob.omni_prefill_select(desc, Q, K, 0, TAU, RECALL_P, PROBE_BLOCK, 0, b_cap, out=sel)
 
     def step():
         selection()
@@ -167,7 +167,7 @@ def main():
         "config": {"workload": f"{cfg.name}: 1 layer, batch 1, {Hq} q heads / {cfg.n_kv_heads} kv heads, head_dim {D}, "
                                f"N={N} ({cfg.frames} frames x {cfg.tok_per_frame} visual + {cfg.n_text} text), causal, "
                                f"tau={TAU}, recall p={RECALL_P}, probe block {PROBE_BLOCK}",
-                   "step": "score_queries + select_queries + kv_budget + select_kv + sparse_attn_fwd"},
+                   "step": "prefill_select (= score_queries + select_queries + kv_budget + select_kv) + sparse_attn_fwd"},
         "roofline": {"bound": "mfma", "kernel": "attn_fwd_bf16_kernel<128> (sparse)", "achieved": round(ach, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(cfg.name), "kernel_ms": round(attn_ms, 4),
@@ -298,11 +298,10 @@ def bench_per_head_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, 
                           torch.empty(cfg.batch, Hq, dtype=torch.int32, device="cuda"), torch.empty_like(bud.recall))
     kv_idx = torch.empty(cfg.batch, Hq, N, dtype=torch.int32, device="cuda")
 
+    sel = ob.SelectionResult(probe, scores, q_idx, q_cnt, res, kv_idx)
+
     def selection():
-        ob.omni_score_queries(desc, Q, K, probe, scores)
-        ob.omni_select_queries(desc, scores, 0, TAU, q_idx, q_cnt)
-        ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 2, out=res)
-        ob.omni_select_kv_per_head(desc, res.key_scores, res.budget, N, kv_idx)
+        ob.omni_prefill_select(desc, Q, K, 0, TAU, RECALL_P, PROBE_BLOCK, 2, N, out=sel)
 
     def step():
         selection()
@@ -349,21 +348,14 @@ def bench_train(torch, ob, synth, steps: int = 5, per_head: bool = False):
     N, Hq, D = cfg.n_tokens, cfg.n_q_heads, cfg.head_dim
     desc = ob.make_layer_desc(Q, K, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
     f32, i32 = torch.float32, torch.int32
-    probe = torch.empty(1, cfg.n_kv_heads, 2, D, dtype=f32, device="cuda")
-    scores = torch.empty(1, Hq, N, dtype=f32, device="cuda")
-    q_idx = torch.empty(1, Hq, N, dtype=i32, device="cuda")
-    q_cnt = torch.empty(1, Hq, dtype=i32, device="cuda")
-    kv_idx = torch.empty(1, Hq, N, dtype=i32, device="cuda")
     O, dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
     lse = torch.empty(1, Hq, N, dtype=f32, device="cuda")
-    bud = None
+    sel = None
 
     def step():
-        nonlocal bud
-        ob.omni_score_queries(desc, Q, K, probe, scores)
-        ob.omni_select_queries(desc, scores, 0, TAU, q_idx, q_cnt)
-        bud = ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 2 if per_head else 0, out=bud)
-        ob.omni_select_kv(desc, bud.key_scores, bud.budget, N, kv_idx, _per_head=per_head)
+        nonlocal sel
+        sel = ob.omni_prefill_select(desc, Q, K, 0, TAU, RECALL_P, PROBE_BLOCK, 2 if per_head else 0, N, out=sel)
+        bud, q_idx, q_cnt, kv_idx = sel.budget, sel.q_idx, sel.q_cnt, sel.kv_idx
         ob.omni_sparse_attn_fwd(desc, Q, K, V, q_idx, q_cnt, kv_idx, bud.budget, N, O, lse, _per_head=per_head)
         ob.omni_sparse_attn_bwd(desc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, bud.budget, N, dQ, dK, dV,
                                 _per_head=per_head)
@@ -383,6 +375,7 @@ def bench_train(torch, ob, synth, steps: int = 5, per_head: bool = False):
         if n:
             kern[name] = round(t / n, 4)
     ob.profile_enable(False)
+    bud, q_idx, q_cnt, kv_idx = sel.budget, sel.q_idx, sel.q_cnt, sel.kv_idx
     cnt = q_cnt.cpu().numpy()[0]
     bh = bud.budget.cpu().numpy().reshape(-1)
     bh = bh if per_head else np.full(Hq, bh[0])

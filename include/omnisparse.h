@@ -67,7 +67,8 @@ typedef enum {
   OMNI_CALL_DENSE_ATTN_FWD = 7,
   OMNI_CALL_DENSE_DECODE = 8,
   OMNI_CALL_GROUP_SUBSET = 9,
-  OMNI_CALL_BLOCK_SCORES = 10
+  OMNI_CALL_BLOCK_SCORES = 10,
+  OMNI_CALL_PREFILL_SELECT = 11
 } omni_call_id;
 
 /* One attention layer during prefill / training.
@@ -169,6 +170,31 @@ int omni_budget_from_scores(const omni_layer_desc* desc, const float* key_scores
                             float recall_p, int budget_mode,
                             double* kurtosis, int32_t* flattest, int32_t* budget, float* recall,
                             void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_prefill_select -- the four selection calls of a prefill step in one:
+ * omni_score_queries, omni_select_queries, omni_kv_budget and omni_select_kv
+ * (omni_select_kv_per_head when budget_mode is 2), i.e. Sec. "Query Selection"
+ * (probe-softmax and query-mask equations) followed by Sec. "KV Selection"
+ * (accumulated key score, kurtosis, budget and key-mask equations).  Every
+ * output is bit-identical to what the separate calls write on the same inputs;
+ * the fused call reads Q once for both the query scores and the pooled queries,
+ * and compacts the key lists from the per-head cut that the recall computation
+ * already finds, instead of searching it again.
+ * Arguments and outputs as in the separate calls (q_mode, q_param: mode and
+ * param of omni_select_queries), with one difference: recall[i] is the mass of
+ * the min(budget, b_cap) keys that are actually selected, which is the recall
+ * of omni_kv_budget whenever b_cap >= budget.
+ * Workspace: OMNI_CALL_PREFILL_SELECT with param = probe_block.
+ */
+int omni_prefill_select(const omni_layer_desc* desc, const void* Q, const void* K,
+                        int q_mode, float q_param,
+                        float recall_p, int probe_block, int budget_mode,
+                        float* probe_keys, float* scores, int32_t* q_idx, int32_t* q_cnt,
+                        float* key_scores, double* kurtosis, int32_t* flattest,
+                        int32_t* budget, float* recall,
+                        int32_t* kv_idx, int32_t b_cap,
+                        void* ws, size_t ws_bytes, void* stream);
 
 /*
  * omni_select_kv -- same section, key-mask equation (value mask = key mask).
@@ -345,7 +371,8 @@ int omni_dense_decode(const omni_decode_desc* desc, const void* q,
 /* Workspace bytes needed by call `call_id` (omni_call_id) for the given
  * descriptor (omni_layer_desc* for prefill calls, omni_decode_desc* for the two
  * decode calls).  `param` is the index capacity b_cap for the calls that take
- * one, the probe block for OMNI_CALL_KV_BUDGET, and ignored otherwise.
+ * one, the probe block for OMNI_CALL_KV_BUDGET and OMNI_CALL_PREFILL_SELECT,
+ * and ignored otherwise.
  * Returns 0 on invalid input (a valid call never needs 0 bytes). */
 size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param);
 

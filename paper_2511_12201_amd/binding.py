@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libomnisparse.so")
 OMNI_F32, OMNI_BF16 = 0, 1
 (CALL_SCORE_QUERIES, CALL_SELECT_QUERIES, CALL_KV_BUDGET, CALL_SELECT_KV, CALL_SPARSE_ATTN_FWD,
  CALL_SPARSE_ATTN_BWD, CALL_SLIM_DECODE, CALL_DENSE_ATTN_FWD, CALL_DENSE_DECODE, CALL_GROUP_SUBSET,
- CALL_BLOCK_SCORES) = range(11)
+ CALL_BLOCK_SCORES, CALL_PREFILL_SELECT) = range(12)
 
 EXPORTED = [
     "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
@@ -28,7 +28,7 @@ EXPORTED = [
     "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
     "omni_group_subset", "omni_slim_decode_grouped", "omni_block_scores", "omni_expand_blocks",
     "omni_select_kv_per_head", "omni_sparse_attn_fwd_per_head", "omni_sparse_attn_bwd_per_head",
-    "omni_visual_subset_per_head",
+    "omni_visual_subset_per_head", "omni_prefill_select",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -80,6 +80,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_select_queries.argtypes = [vp, vp, C.c_int, f32, vp, vp, vp, sz, vp]
     lib.omni_kv_budget.argtypes = [vp, vp, vp, f32, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_budget_from_scores.argtypes = [vp, vp, f32, C.c_int, vp, vp, vp, vp, vp, sz, vp]
+    lib.omni_prefill_select.argtypes = [vp, vp, vp, C.c_int, f32, f32, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                        vp, i32, vp, sz, vp]
     lib.omni_select_kv.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
     lib.omni_visual_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.omni_select_kv_per_head.argtypes = lib.omni_select_kv.argtypes
@@ -296,6 +298,47 @@ def omni_kv_budget(desc: LayerDesc, Q, K, recall_p: float, probe_block: int = 25
     _check(lib.omni_kv_budget(C.byref(desc), _ptr(Q), _ptr(K), recall_p, probe_block, budget_mode,
                               _ptr(out.key_scores), _ptr(out.kurtosis), _ptr(out.flattest), _ptr(out.budget),
                               _ptr(out.recall), _ptr(budget_host), _ptr(buf), buf.numel(), _stream()))
+    return out
+
+
+@dataclass
+class SelectionResult:
+    probe_keys: torch.Tensor
+    scores: torch.Tensor
+    q_idx: torch.Tensor
+    q_cnt: torch.Tensor
+    budget: BudgetResult
+    kv_idx: torch.Tensor
+
+
+def omni_prefill_select(desc: LayerDesc, Q, K, q_mode: int, q_param: float, recall_p: float, probe_block: int = 256,
+                        budget_mode: int = 0, b_cap: int | None = None, out: SelectionResult | None = None,
+                        ws: Workspace | None = None) -> SelectionResult:
+    lib = load_library()
+    ws = ws or default_workspace()
+    dev = Q.device
+    B, H, Hkv, N, D = desc.batch, desc.n_q_heads, desc.n_kv_heads, desc.n_tokens, desc.head_dim
+    b_cap = N if b_cap is None else b_cap
+    f32, i32 = torch.float32, torch.int32
+    if out is None:
+        bud = BudgetResult(
+            torch.empty(B, H, N, dtype=f32, device=dev), torch.empty(B, H, dtype=torch.float64, device=dev),
+            torch.empty(B, dtype=i32, device=dev),
+            torch.empty((B, H) if budget_mode == 2 else (B,), dtype=i32, device=dev),
+            torch.empty(B, H, dtype=f32, device=dev))
+        out = SelectionResult(
+            torch.empty(B, Hkv, 2, D, dtype=f32, device=dev), torch.empty(B, H, N, dtype=f32, device=dev),
+            torch.empty(B, H, N, dtype=i32, device=dev), torch.empty(B, H, dtype=i32, device=dev), bud,
+            torch.empty(B, H, b_cap, dtype=i32, device=dev))
+    _budget_shape_ok(desc, out.budget.budget, budget_mode == 2)
+    if out.kv_idx.shape[-1] != b_cap:
+        raise ValueError("kv_idx must be [batch, n_q_heads, b_cap]")
+    buf = ws.get(CALL_PREFILL_SELECT, desc, probe_block)
+    r = out.budget
+    _check(lib.omni_prefill_select(C.byref(desc), _ptr(Q), _ptr(K), q_mode, q_param, recall_p, probe_block, budget_mode,
+                                   _ptr(out.probe_keys), _ptr(out.scores), _ptr(out.q_idx), _ptr(out.q_cnt),
+                                   _ptr(r.key_scores), _ptr(r.kurtosis), _ptr(r.flattest), _ptr(r.budget),
+                                   _ptr(r.recall), _ptr(out.kv_idx), b_cap, _ptr(buf), buf.numel(), _stream()))
     return out
 
 

@@ -126,6 +126,11 @@ void prof_end(int id, hipStream_t st) {
 
 static bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
+static size_t prefill_select_ws(const Layer& L, int dtype, int pb) {
+  return align_up(score_queries_ws(L), 256) + align_up(probe_ws(L, dtype, pb), 256) +
+         align_up(budget_stats_ws(L), 256) + select_ws(L);
+}
+
 static size_t kv_budget_ws(const Layer& L, int dtype, int pb) {
   return align_up(probe_ws(L, dtype, pb), 256) + budget_stats_ws(L);
 }
@@ -248,6 +253,9 @@ size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param) {
       return attn_bwd_ws(L, d->dtype, param);
     case OMNI_CALL_DENSE_ATTN_FWD: return attn_fwd_ws(L, d->dtype, L.N, false);
     case OMNI_CALL_GROUP_SUBSET: return group_subset_ws(L);
+    case OMNI_CALL_PREFILL_SELECT:
+      if (param < 1) { set_error("probe block must be >= 1"); return 0; }
+      return prefill_select_ws(L, d->dtype, param);
     case OMNI_CALL_BLOCK_SCORES:
       if (param < 1) { set_error("block must be >= 1"); return 0; }
       return block_scores_ws(L, param);
@@ -300,6 +308,41 @@ int omni_kv_budget(const omni_layer_desc* desc, const void* Q, const void* K, fl
     OMNI_HIP_CHECK(hipMemcpyAsync(budget_host, budget, sizeof(int32_t) * L.B * (budget_mode == 2 ? L.Hq : 1),
                                    hipMemcpyDeviceToHost, st));
   return OMNI_OK;
+}
+
+int omni_prefill_select(const omni_layer_desc* desc, const void* Q, const void* K, int q_mode, float q_param,
+                        float recall_p, int probe_block, int budget_mode, float* probe_keys, float* scores,
+                        int32_t* q_idx, int32_t* q_cnt, float* key_scores, double* kurtosis, int32_t* flattest,
+                        int32_t* budget, float* recall, int32_t* kv_idx, int32_t b_cap, void* ws, size_t ws_bytes,
+                        void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(probe_keys); REQUIRE_PTR(scores); REQUIRE_PTR(q_idx); REQUIRE_PTR(q_cnt);
+  REQUIRE_PTR(key_scores); REQUIRE_PTR(kurtosis); REQUIRE_PTR(flattest); REQUIRE_PTR(budget); REQUIRE_PTR(recall);
+  REQUIRE_PTR(kv_idx);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K);
+  if (q_mode != 0 && q_mode != 1) OMNI_FAIL(OMNI_ERR_INVALID, "mode must be 0 (threshold) or 1 (top fraction)");
+  if (!std::isfinite(q_param)) OMNI_FAIL(OMNI_ERR_INVALID, "param must be finite");
+  if (q_mode == 1 && !(q_param > 0.f && q_param <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "top fraction must be in (0, 1]");
+  if (!(recall_p > 0.f && recall_p <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "recall_p must be in (0, 1]");
+  if (probe_block < 1) OMNI_FAIL(OMNI_ERR_INVALID, "probe_block must be >= 1");
+  if (budget_mode < 0 || budget_mode > 2) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0, 1 or 2");
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  Layer L = make_layer(desc);
+  L.bph = budget_mode == 2;
+  CHECK(check_ws(ws, ws_bytes, prefill_select_ws(L, desc->dtype, probe_block)));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws_score = static_cast<char*>(ws);
+  char* ws_probe = ws_score + align_up(score_queries_ws(L), 256);
+  char* ws_stats = ws_probe + align_up(probe_ws(L, desc->dtype, probe_block), 256);
+  char* ws_sel = ws_stats + align_up(budget_stats_ws(L), 256);
+  CHECK(run_probe_keys(L, desc->dtype, K, probe_keys, ws_score, st));
+  // one pass over Q: lazy/active scores and pooled queries; then the two probe passes over K
+  CHECK(run_probe(L, desc->dtype, Q, K, probe_block, key_scores, ws_probe, st, probe_keys, scores));
+  CHECK(run_select_queries(L, scores, q_mode, q_param, q_idx, q_cnt, ws_sel, st));
+  // the recall pass already finds each head's cut for its budget: the key lists are compacted from it
+  CHECK(run_budget_stats(L, key_scores, recall_p, budget_mode, kurtosis, flattest, budget, recall, ws_stats, st, b_cap));
+  return run_select_kv_from_stats(L, key_scores, ws_stats, b_cap, kv_idx, ws_sel, st);
 }
 
 int omni_budget_from_scores(const omni_layer_desc* desc, const float* key_scores, float recall_p, int budget_mode,

@@ -9,6 +9,7 @@ namespace omni {
 size_t score_queries_ws(const Layer& L);
 int run_score_queries(const Layer& L, int dtype, const void* Q, const void* K, float* probe, float* scores, void* ws,
                       hipStream_t st);
+int run_probe_keys(const Layer& L, int dtype, const void* K, float* probe, void* ws, hipStream_t st);
 
 // select.hip
 size_t select_ws(const Layer& L);
@@ -18,7 +19,9 @@ int run_select_kv(const Layer& L, const float* key_scores, const int* budget, in
                   hipStream_t st);
 size_t budget_stats_ws(const Layer& L);
 int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, int budget_mode, double* kurt,
-                     int* flattest, int* budget, float* recall, void* ws, hipStream_t st);
+                     int* flattest, int* budget, float* recall, void* ws, hipStream_t st, int k_cap = 0x7fffffff);
+int run_select_kv_from_stats(const Layer& L, const float* key_scores, void* stats_ws, int b_cap, int* kv_idx,
+                             void* ws, hipStream_t st);
 int run_visual_subset(const Layer& L, const int* kv_idx, const int* budget, int b_cap, int* vis_idx, int* vis_cnt,
                       hipStream_t st);
 size_t group_subset_ws(const Layer& L);
@@ -27,8 +30,9 @@ int run_group_subset(const Layer& L, const int* kv_idx, const int* budget, int b
 
 // probe.hip
 size_t probe_ws(const Layer& L, int dtype, int pb);
+// probe_keys / scores not null: the pooling pass over Q also writes the lazy/active query scores
 int run_probe(const Layer& L, int dtype, const void* Q, const void* K, int pb, float* key_scores, void* ws,
-              hipStream_t st);
+              hipStream_t st, const float* probe_keys = nullptr, float* scores = nullptr);
 
 // pack.hip (outputs that are nullptr are skipped; Kt / Vt / Qt / dOt exist for bf16 only)
 int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per_q_head, const int* src_idx,

@@ -32,9 +32,13 @@ constexpr int kQbarTerms = 2;
 
 // ---------------------------------------------------------------- pooling
 
-template <typename T, int D>
+// SCORE: the same pass over Q also writes the lazy/active score of every row (paper Sec. "Query Selection",
+// probe-softmax equation), with the arithmetic of the stand-alone scoring kernel, so that Q is read once.
+template <typename T, int D, bool SCORE>
 __global__ __launch_bounds__(kThreads) void pool_queries_kernel(const T* __restrict__ Q, Layer L, int pb, int nblk,
-                                                               float* __restrict__ qbar, u16* __restrict__ qsplit) {
+                                                               float* __restrict__ qbar, u16* __restrict__ qsplit,
+                                                               const float* __restrict__ probe_keys,
+                                                               float* __restrict__ scores) {
   constexpr int E = Elem<T>::kPer16B;
   constexpr int LPR = D / E;
   constexpr int RPP = kThreads / LPR;
@@ -47,12 +51,38 @@ __global__ __launch_bounds__(kThreads) void pool_queries_kernel(const T* __restr
   float acc[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) acc[e] = 0.f;
-  for (int r = row_begin + r0; r < row_end; r += RPP) {
-    u32x4 raw = *reinterpret_cast<const u32x4*>(base + (long long)r * L.qs[2] + c * E);
-    float v[E];
-    unpack16(raw, v, (const T*)nullptr);
+  if constexpr (SCORE) {
+    const float* pk = probe_keys + ((long long)(b * L.Hkv + i / L.G) * 2) * D;
+    float diff[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] += v[e];
+    for (int e = 0; e < E; ++e) diff[e] = pk[D + c * E + e] - pk[c * E + e];
+    float* out = scores + (long long)bh * L.N;
+    for (int rb = row_begin; rb < row_end; rb += RPP) {    // uniform trip count: shuffles need every lane
+      const int r = rb + r0;
+      const bool live = r < row_end;
+      float dot = 0.f;
+      if (live) {
+        u32x4 raw = *reinterpret_cast<const u32x4*>(base + (long long)r * L.qs[2] + c * E);
+        float v[E];
+        unpack16(raw, v, (const T*)nullptr);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          acc[e] += v[e];
+          dot = fmaf(v[e], diff[e], dot);
+        }
+      }
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+      if (live && c == 0) out[r] = 1.0f / (1.0f + expf(-dot * L.scale));
+    }
+  } else {
+    for (int r = row_begin + r0; r < row_end; r += RPP) {
+      u32x4 raw = *reinterpret_cast<const u32x4*>(base + (long long)r * L.qs[2] + c * E);
+      float v[E];
+      unpack16(raw, v, (const T*)nullptr);
+#pragma unroll
+      for (int e = 0; e < E; ++e) acc[e] += v[e];
+    }
   }
 #pragma unroll
   for (int e = 0; e < E; ++e) red[r0][c * E + e] = acc[e];
@@ -542,7 +572,8 @@ ProbeWs carve_probe(Arena& a, const Layer& L, int pb) {
 }
 
 template <typename T, int D>
-int launch_probe(const Layer& L, const void* Q, const void* K, int pb, float* key_scores, void* ws, hipStream_t st) {
+int launch_probe(const Layer& L, const void* Q, const void* K, int pb, float* key_scores, void* ws, hipStream_t st,
+                 const float* probe_keys, float* scores) {
   Arena a(ws);
   ProbeWs w = carve_probe<T>(a, L, pb);
   const int nblk = cdiv(L.N, pb);
@@ -552,8 +583,14 @@ int launch_probe(const Layer& L, const void* Q, const void* K, int pb, float* ke
   {
     ProfScope prof__(kProfPool, st);
     const int pooled_rows = sizeof(T) == 2 ? cdiv(nblk, 32) * 32 : nblk;
-    hipLaunchKernelGGL((pool_queries_kernel<T, D>), dim3(pooled_rows, BH), dim3(kThreads), 0, st,
-                       static_cast<const T*>(Q), L, pb, nblk, w.qbar, w.qsplit);
+    if (scores) {
+      hipLaunchKernelGGL((pool_queries_kernel<T, D, true>), dim3(pooled_rows, BH), dim3(kThreads), 0, st,
+                         static_cast<const T*>(Q), L, pb, nblk, w.qbar, w.qsplit, probe_keys, scores);
+    } else {
+      hipLaunchKernelGGL((pool_queries_kernel<T, D, false>), dim3(pooled_rows, BH), dim3(kThreads), 0, st,
+                         static_cast<const T*>(Q), L, pb, nblk, w.qbar, w.qsplit, (const float*)nullptr,
+                         (float*)nullptr);
+    }
     OMNI_LAUNCH_CHECK();
   }
   if constexpr (sizeof(T) == 2) {
@@ -604,13 +641,13 @@ size_t probe_ws(const Layer& L, int dtype, int pb) {
 }
 
 int run_probe(const Layer& L, int dtype, const void* Q, const void* K, int pb, float* key_scores, void* ws,
-              hipStream_t st) {
+              hipStream_t st, const float* probe_keys, float* scores) {
   if (dtype == OMNI_BF16) {
-    if (L.D == 128) return launch_probe<u16, 128>(L, Q, K, pb, key_scores, ws, st);
-    return launch_probe<u16, 64>(L, Q, K, pb, key_scores, ws, st);
+    if (L.D == 128) return launch_probe<u16, 128>(L, Q, K, pb, key_scores, ws, st, probe_keys, scores);
+    return launch_probe<u16, 64>(L, Q, K, pb, key_scores, ws, st, probe_keys, scores);
   }
-  if (L.D == 128) return launch_probe<float, 128>(L, Q, K, pb, key_scores, ws, st);
-  return launch_probe<float, 64>(L, Q, K, pb, key_scores, ws, st);
+  if (L.D == 128) return launch_probe<float, 128>(L, Q, K, pb, key_scores, ws, st, probe_keys, scores);
+  return launch_probe<float, 64>(L, Q, K, pb, key_scores, ws, st, probe_keys, scores);
 }
 
 }  // namespace omni

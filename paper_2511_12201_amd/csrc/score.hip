@@ -102,9 +102,7 @@ __global__ __launch_bounds__(kThreads) void score_queries_kernel(const T* __rest
 }
 
 template <typename T, int D>
-int launch_score(const Layer& L, const void* Q, const void* K, float* probe, float* scores, float* partial,
-                 int nchunk, hipStream_t st) {
-  const T* q = static_cast<const T*>(Q);
+int launch_probe_keys(const Layer& L, const void* K, float* probe, float* partial, int nchunk, hipStream_t st) {
   const T* k = static_cast<const T*>(K);
   hipLaunchKernelGGL((mean_key_partial_kernel<T, D>), dim3(nchunk, L.B * L.Hkv), dim3(kThreads), 0, st, k, L, nchunk,
                      partial);
@@ -112,6 +110,15 @@ int launch_score(const Layer& L, const void* Q, const void* K, float* probe, flo
   hipLaunchKernelGGL((probe_keys_finalize_kernel<T, D>), dim3(L.B * L.Hkv), dim3(128), 0, st, k, L, nchunk, partial,
                      probe);
   OMNI_LAUNCH_CHECK();
+  return OMNI_OK;
+}
+
+template <typename T, int D>
+int launch_score(const Layer& L, const void* Q, const void* K, float* probe, float* scores, float* partial,
+                 int nchunk, hipStream_t st) {
+  const T* q = static_cast<const T*>(Q);
+  const int rc = launch_probe_keys<T, D>(L, K, probe, partial, nchunk, st);
+  if (rc != OMNI_OK) return rc;
   const int rows_per_block = 256;
   {
     ProfScope prof__(kProfScore, st);
@@ -130,6 +137,18 @@ size_t score_queries_ws(const Layer& L) {
   Arena a(nullptr);
   a.take<float>((size_t)L.B * L.Hkv * score_mean_chunks(L) * L.D);
   return a.used();
+}
+
+int run_probe_keys(const Layer& L, int dtype, const void* K, float* probe, void* ws, hipStream_t st) {
+  Arena a(ws);
+  const int nchunk = score_mean_chunks(L);
+  float* partial = a.take<float>((size_t)L.B * L.Hkv * nchunk * L.D);
+  if (dtype == OMNI_BF16) {
+    if (L.D == 128) return launch_probe_keys<u16, 128>(L, K, probe, partial, nchunk, st);
+    return launch_probe_keys<u16, 64>(L, K, probe, partial, nchunk, st);
+  }
+  if (L.D == 128) return launch_probe_keys<float, 128>(L, K, probe, partial, nchunk, st);
+  return launch_probe_keys<float, 64>(L, K, probe, partial, nchunk, st);
 }
 
 int run_score_queries(const Layer& L, int dtype, const void* Q, const void* K, float* probe, float* scores, void* ws,

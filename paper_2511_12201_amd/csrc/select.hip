@@ -613,7 +613,7 @@ size_t budget_stats_ws(const Layer& L) {
 }
 
 int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, int budget_mode, double* kurt,
-                     int* flattest, int* budget, float* recall, void* ws, hipStream_t st) {
+                     int* flattest, int* budget, float* recall, void* ws, hipStream_t st, int k_cap) {
   Arena a(ws);
   const int BH = L.B * L.Hq;
   unsigned* thr = a.take<unsigned>(BH);
@@ -640,9 +640,28 @@ int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, in
     OMNI_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, 0, L.N, 0, budget,
-                     budget_mode == 2 ? 1 : 0, L.N, 0, thr, need, recall, (float)L.N);
+                     budget_mode == 2 ? 1 : 0, std::min(k_cap, L.N), 0, thr, need, recall, (float)L.N);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
+}
+
+// Key selection from the thresholds that run_budget_stats left in its workspace (the recall pass finds, per
+// head, the k-th largest score for k = min(budget, k_cap): the cut of the key-mask equation for that budget).
+int run_select_kv_from_stats(const Layer& L, const float* key_scores, void* stats_ws, int b_cap, int* kv_idx,
+                             void* ws, hipStream_t st) {
+  Arena sa(stats_ws);
+  const int BH = L.B * L.Hq;
+  const unsigned* thr = sa.take<unsigned>(BH);
+  const int* need = sa.take<int>(BH);
+  Arena a(ws);
+  SelWs w = carve_select(a, L);
+  KeepRule rule;
+  rule.lo = 0;
+  rule.hi = L.N;
+  rule.keep_all_head0 = 0;
+  rule.use_table = 1;
+  rule.thr_scalar = 0;
+  return compact(key_scores, BH, L.N, L.Hq, rule, thr, need, w.cnt_keep, w.cnt_eq, kv_idx, b_cap, nullptr, st);
 }
 
 // ---- union of the stored visual rows over the heads of a KV group, with a membership bit per head

@@ -386,6 +386,47 @@ def test_free_running_pipeline_matches_oracle_up_to_ties_at_the_cut(cfg):
     assert compared >= H // 2
 
 
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("budget_mode", [0, 1, 2])
+def test_fused_selection_call_writes_what_the_four_separate_calls_write(cfg, budget_mode):
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    probe, scores = ob.omni_score_queries(c.desc, c.dQ, c.dK)
+    q_idx, q_cnt = ob.omni_select_queries(c.desc, scores, c.q_mode, c.q_param)
+    r = ob.omni_kv_budget(c.desc, c.dQ, c.dK, c.recall_p, c.probe_block, budget_mode)
+    kv_idx = ob.omni_select_kv(c.desc, r.key_scores, r.budget, N, _per_head=budget_mode == 2)
+    f = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, budget_mode)
+    torch.cuda.synchronize()
+    assert torch.equal(f.probe_keys, probe) and torch.equal(f.scores, scores)
+    assert torch.equal(f.q_cnt, q_cnt)
+    for a, b in zip(padded_to_lists(f.q_idx, f.q_cnt), padded_to_lists(q_idx, q_cnt)):
+        for x, y in zip(a, b):
+            np.testing.assert_array_equal(x, y)
+    fb = f.budget
+    assert torch.equal(fb.key_scores, r.key_scores) and torch.equal(fb.kurtosis, r.kurtosis)
+    assert torch.equal(fb.flattest, r.flattest) and torch.equal(fb.budget, r.budget) and torch.equal(fb.recall, r.recall)
+    bud = to_host(r.budget).reshape(cfg.batch, -1)
+    got, want = to_host(f.kv_idx), to_host(kv_idx)
+    for b in range(cfg.batch):
+        for h in range(H):
+            n = int(bud[b, h if budget_mode == 2 else 0])
+            np.testing.assert_array_equal(got[b, h, :n], want[b, h, :n])
+
+
+def test_fused_selection_call_with_a_capacity_below_the_budget():
+    cfg = CFG_BF16
+    c = case_for(cfg)
+    cap = 200
+    f = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0, b_cap=cap)
+    torch.cuda.synchronize()
+    assert int(to_host(f.budget.budget)[0]) > cap                 # the budget itself is reported unclamped
+    a = to_host(f.budget.key_scores)
+    want = oc.select_kv(a, [cap])
+    np.testing.assert_array_equal(to_host(f.kv_idx)[0], want[0])
+    mass = np.sort(a[0].astype(np.float64), axis=-1)[:, ::-1][:, :cap].sum(-1) / cfg.n_tokens
+    np.testing.assert_allclose(to_host(f.budget.recall)[0], mass, atol=1e-6)
+
+
 # ------------------------------------------------------------------ block-granular KV selection
 
 @pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
