@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the sparse forward kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # file, scaled by the calibration copy (profiles/attn_fwd_c3_64k_hbm_traffic.txt); None where not profiled.
-MEASURED_TRAFFIC = {"c3_64k": 1.643e10}
+MEASURED_TRAFFIC = {"c3_64k": 1.660e10}
 
 TAU = 0.08
 RECALL_P = 0.95
@@ -183,10 +183,11 @@ def main():
         "paper_context": "paper reports 2.7x prefill speedup and 2.4x decode memory reduction for the whole "
                          "LLaVA-Video-7b model on one H100 (not this metric)",
     }
-    score_bytes = Q.numel() * 2 + Hq * N * 4
-    if "score" in kern:
-        out["score_queries_hbm"] = {"GB/s": round(score_bytes / kern["score"] / 1e6, 1),
-                                    "frac": round(score_bytes / kern["score"] / 1e6 / PEAK_HBM_GBS, 4)}
+    # the one pass over Q (query scores + pooled queries): Q in, scores and the split pooled queries out
+    pool_bytes = Q.numel() * 2 + Hq * N * 4 + Hq * ((N + PROBE_BLOCK - 1) // PROBE_BLOCK) * D * 4
+    if "pool_q" in kern:
+        out["score_and_pool_pass_hbm"] = {"GB/s": round(pool_bytes / kern["pool_q"] / 1e6, 1),
+                                          "frac": round(pool_bytes / kern["pool_q"] / 1e6 / PEAK_HBM_GBS, 4)}
 
     if not args.no_extras:
         # dense attention baseline from the same library, same inputs
