@@ -227,7 +227,8 @@ def main():
         torch.cuda.empty_cache()
         for name, fn in (("train_step_32k", bench_train),
                          ("train_step_32k_per_head_budgets", lambda *a: bench_train(*a, per_head=True)),
-                         ("decode_131k", bench_decode)):
+                         ("decode_131k", bench_decode),
+                         ("decode_131k_per_head_budgets", lambda *a: bench_decode(*a, per_head=True, batches=(1, 8)))):
             try:
                 t0 = time.time()
                 out[name] = fn(torch, ob, synth)
@@ -395,7 +396,7 @@ def bench_train(torch, ob, synth, steps: int = 5, per_head: bool = False):
     return res
 
 
-def bench_decode(torch, ob, synth, n_steps: int = 256):
+def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, batches=(1, 2, 4, 8)):
     """Decode with KV cache slimming on a 131072-token cache, batch 1..8, 256 steps each."""
     cfg = synth.C5_DECODE_131K
     layer = synth.make_layer(cfg)
@@ -403,15 +404,18 @@ def bench_decode(torch, ob, synth, n_steps: int = 256):
     N, Hq, Hkv, D = cfg.n_tokens, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     desc = ob.make_layer_desc(Q, K, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
     probe, _ = ob.omni_score_queries(desc, Q, K)
-    bud = ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 0)
-    b = int(bud.budget.cpu()[0])
-    kv_idx = ob.omni_select_kv(desc, bud.key_scores, bud.budget, b)
-    vis_idx1, vis_cnt1 = ob.omni_visual_subset(desc, kv_idx, bud.budget, b)
-    grp_idx1, grp_mask1, grp_cnt1 = ob.omni_group_subset(desc, kv_idx, bud.budget, b)
+    bud = ob.omni_kv_budget(desc, Q, K, RECALL_P, PROBE_BLOCK, 2 if per_head else 0)
+    b = int(bud.budget.max().cpu())
+    b_mean = float(bud.budget.float().mean().cpu())
+    kv_idx = ob.omni_select_kv(desc, bud.key_scores, bud.budget, b, _per_head=per_head)
+    vis_idx1, vis_cnt1 = ob.omni_visual_subset(desc, kv_idx, bud.budget, b, _per_head=per_head)
+    grp_idx1, grp_mask1, grp_cnt1 = ob.omni_group_subset(desc, kv_idx, bud.budget, b, _per_head=per_head)
     torch.cuda.synchronize()
     del Q, bud
     cap = N + n_steps
-    res = {"workload": f"{cfg.name}: cache {N} tokens + {n_steps} decoded, bf16, tau={TAU}", "budget_fraction": round(b / N, 4),
+    res = {"workload": f"{cfg.name}: cache {N} tokens + {n_steps} decoded, bf16, tau={TAU}"
+                       + (", one budget per head" if per_head else ""),
+           "budget_fraction": round(b_mean / N, 4),
            "timing": "us_per_token = GPU time of the decode call's kernels (HIP events, first 64 steps); the Python loop "
                      "around it (cache append, ctypes launches) is host-bound and listed separately",
            "per_batch": {}}
@@ -420,7 +424,7 @@ def bench_decode(torch, ob, synth, n_steps: int = 256):
     member = np.zeros((Hq, N), dtype=bool)            # member[h, n]: head h stores visual row n
     for h in range(Hq):
         member[h, vis_idx_host[h, : vis_cnt_host[h]]] = True
-    for B in (1, 2, 4, 8):
+    for B in batches:
         steps = synth.make_decode_steps(cfg, layer, n_steps, batch=B)
         q_all = _upload(torch, synth, steps["q"])                      # [S,B,Hq,D]
         k_new = _upload(torch, synth, steps["k_new"])
@@ -439,8 +443,18 @@ def bench_decode(torch, ob, synth, n_steps: int = 256):
         act = torch.empty(B, Hq, dtype=torch.uint8, device="cuda")
         ddesc = ob.make_decode_desc(q_all[0], Kc, cfg.vis_begin, cfg.vis_end, TAU)
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        # the compacted store: the rows of the group lists side by side (built once after prefill)
+        u_max = int(grp_cnt.max().cpu())
+        g_idx_c, g_mask_c = grp_idx[:, :, :u_max].contiguous(), grp_mask[:, :, :u_max].contiguous()
+        Kcomp, Vcomp = ob.omni_compact_cache(ddesc, Kc, Vc, g_idx_c, grp_cnt)
+        torch.cuda.synchronize()
+        ev0.record()
+        ob.omni_compact_cache(ddesc, Kc, Vc, g_idx_c, grp_cnt, Kcomp, Vcomp)
+        ev1.record()
+        torch.cuda.synchronize()
+        compact_us = ev0.elapsed_time(ev1) * 1e3
         timing, ktime = {}, {}
-        for mode in ("slim", "slim_grouped", "dense"):
+        for mode in ("slim", "slim_grouped", "slim_compact", "dense"):
             ctx.fill_(N + 1)
             for _ in range(3):                                    # untimed warm-up of both entry points
                 ob.omni_slim_decode_grouped(ddesc, q_all[0], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act)
@@ -458,6 +472,9 @@ def bench_decode(torch, ob, synth, n_steps: int = 256):
                     ob.omni_slim_decode(ddesc, q_all[s], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
                 elif mode == "slim_grouped":
                     ob.omni_slim_decode_grouped(ddesc, q_all[s], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act)
+                elif mode == "slim_compact":
+                    ob.omni_slim_decode_compact(ddesc, q_all[s], Kc, Vc, ctx, probe_b, Kcomp, Vcomp, g_idx_c, g_mask_c,
+                                                grp_cnt, O, act)
                 else:
                     ob.omni_dense_decode(ddesc, q_all[s], Kc, Vc, ctx, O)
             ev1.record()
@@ -489,6 +506,12 @@ def bench_decode(torch, ob, synth, n_steps: int = 256):
             "slim_us_per_token": round(ktime["slim"], 2), "dense_us_per_token": round(ktime["dense"], 2),
             "speedup": round(ktime["dense"] / ktime["slim"], 3),
             "slim_grouped_us_per_token": round(ktime["slim_grouped"], 2),
+            "slim_compact_us_per_token": round(ktime["slim_compact"], 2),
+            "compaction_us_once": round(compact_us, 1),
+            # what a serving stack has to keep per layer: the whole cache, or the compacted visual rows (with their
+            # token index and membership word) plus the non-visual rows
+            "kv_store_bytes": {"full_cache": int(rows_dense * row_bytes),
+                               "compacted": int(int(grp_cnt.sum().cpu()) * (row_bytes + 8) + B * Hkv * n_text * row_bytes)},
             "python_loop_us_per_token": {k: round(v, 1) for k, v in timing.items()},
             "active_head_fraction_last_step": round(float(a.mean()), 4),
             "rows_requested_vs_dense": {"slim": round(rows_head / rows_dense, 4), "slim_grouped": round(rows_union / rows_dense, 4)},

@@ -209,7 +209,8 @@ int omni_select_kv(const omni_layer_desc* desc, const float* key_scores, const i
 
 /*
  * omni_select_kv_per_head, omni_sparse_attn_fwd_per_head,
- * omni_sparse_attn_bwd_per_head, omni_visual_subset_per_head -- the calls of the
+ * omni_sparse_attn_bwd_per_head, omni_visual_subset_per_head,
+ * omni_group_subset_per_head -- the calls of the
  * same names without the suffix, with one budget per head instead of one per
  * batch item (same section: the key-mask equation holds per head for any b; the
  * paper shares one b between the heads to save the per-head search, the
@@ -236,6 +237,9 @@ int omni_sparse_attn_bwd_per_head(const omni_layer_desc* desc, const void* Q, co
                                   void* ws, size_t ws_bytes, void* stream);
 int omni_visual_subset_per_head(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget,
                                 int32_t b_cap, int32_t* vis_idx, int32_t* vis_cnt, void* stream);
+int omni_group_subset_per_head(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget,
+                               int32_t b_cap, int32_t* grp_idx, uint32_t* grp_mask, int32_t* grp_cnt,
+                               int32_t u_cap, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * omni_sparse_attn_fwd -- Sec. "Preliminary" (attention equation restricted by
@@ -362,6 +366,35 @@ int omni_expand_blocks(const omni_layer_desc* desc, const int32_t* blk_idx, cons
  * / non-causal attention of the attention equation in Sec. "Preliminary" built
  * on the same tile engine, and plain decode attention over rows [0, ctx_len).
  */
+/*
+ * omni_compact_cache / omni_slim_decode_compact -- Sec. "KV Cache Slimming": what
+ * the decode stage keeps of the visual KV cache is the selected rows only.  Under
+ * grouped-query attention a cache row belongs to a KV head, so the rows that can
+ * be dropped are those no query head of the group selected: omni_compact_cache
+ * copies the rows of the group lists (omni_group_subset) side by side,
+ *   Kcomp, Vcomp [batch, n_kv_heads, u_cap, head_dim] dtype, out:
+ *   row u of group (b, g) = cache row grp_idx[b, g, u], for u < min(grp_cnt, u_cap)
+ *   (rows beyond that are left untouched),
+ * and omni_slim_decode_compact is omni_slim_decode_grouped reading the listed rows
+ * from Kcomp / Vcomp (sequentially, no gather) instead of the cache.  It reads
+ * Kcache / Vcache at non-visual rows only ([0, vis_begin) and [vis_end, ctx_len)),
+ * so a caller may release the visual part of the cache after compaction; the
+ * store it then holds is Kcomp, Vcomp, grp_idx, grp_mask and the non-visual rows.
+ * Output and `active` equal omni_slim_decode_grouped's (same rows, same order).
+ * Workspace of the decode call: OMNI_CALL_SLIM_DECODE.
+ */
+int omni_compact_cache(const omni_decode_desc* desc, const void* Kcache, const void* Vcache,
+                       const int32_t* grp_idx, const int32_t* grp_cnt, int32_t u_cap,
+                       void* Kcomp, void* Vcomp, void* stream);
+int omni_slim_decode_compact(const omni_decode_desc* desc, const void* q,
+                             const void* Kcache, const void* Vcache, const int32_t* ctx_len,
+                             const float* probe_keys,
+                             const void* Kcomp, const void* Vcomp,
+                             const int32_t* grp_idx, const uint32_t* grp_mask, const int32_t* grp_cnt,
+                             int32_t u_cap,
+                             void* O, uint8_t* active,
+                             void* ws, size_t ws_bytes, void* stream);
+
 int omni_dense_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
                         void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
 int omni_dense_decode(const omni_decode_desc* desc, const void* q,

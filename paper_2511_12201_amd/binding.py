@@ -28,7 +28,8 @@ EXPORTED = [
     "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
     "omni_group_subset", "omni_slim_decode_grouped", "omni_block_scores", "omni_expand_blocks",
     "omni_select_kv_per_head", "omni_sparse_attn_fwd_per_head", "omni_sparse_attn_bwd_per_head",
-    "omni_visual_subset_per_head", "omni_prefill_select",
+    "omni_visual_subset_per_head", "omni_prefill_select", "omni_compact_cache", "omni_slim_decode_compact",
+    "omni_group_subset_per_head",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -94,9 +95,12 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_group_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
+    lib.omni_group_subset_per_head.argtypes = lib.omni_group_subset.argtypes
     lib.omni_block_scores.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
     lib.omni_expand_blocks.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
     lib.omni_slim_decode_grouped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.omni_compact_cache.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.omni_slim_decode_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_profile_enable.argtypes = [C.c_int]
     lib.omni_debug_copy.argtypes = [vp, vp, sz, vp]
     lib.omni_debug_mfma_rate.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -512,9 +516,10 @@ def omni_expand_blocks(desc: LayerDesc, blk_idx, blk_budget, block: int, kv_idx=
 
 
 def omni_group_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, u_cap: int | None = None,
-                      ws: Workspace | None = None):
+                      ws: Workspace | None = None, _per_head: bool = False):
     """(grp_idx [B,Hkv,u_cap] i32, grp_mask [B,Hkv,u_cap] i32 holding the u32 bits, grp_cnt [B,Hkv] i32)."""
     lib = load_library()
+    _budget_shape_ok(desc, budget, _per_head)
     ws = ws or default_workspace()
     if u_cap is None:
         u_cap = desc.vis_end - desc.vis_begin
@@ -523,9 +528,15 @@ def omni_group_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, u_cap: int | 
     grp_mask = torch.empty(desc.batch, desc.n_kv_heads, u_cap, dtype=torch.int32, device=dev)
     grp_cnt = torch.empty(desc.batch, desc.n_kv_heads, dtype=torch.int32, device=dev)
     buf = ws.get(CALL_GROUP_SUBSET, desc)
-    _check(lib.omni_group_subset(C.byref(desc), _ptr(kv_idx), _ptr(budget), b_cap, _ptr(grp_idx), _ptr(grp_mask),
-                                 _ptr(grp_cnt), u_cap, _ptr(buf), buf.numel(), _stream()))
+    fn = lib.omni_group_subset_per_head if _per_head else lib.omni_group_subset
+    _check(fn(C.byref(desc), _ptr(kv_idx), _ptr(budget), b_cap, _ptr(grp_idx), _ptr(grp_mask), _ptr(grp_cnt), u_cap,
+              _ptr(buf), buf.numel(), _stream()))
     return grp_idx, grp_mask, grp_cnt
+
+
+def omni_group_subset_per_head(desc: LayerDesc, kv_idx, budget, b_cap: int, u_cap: int | None = None,
+                               ws: Workspace | None = None):
+    return omni_group_subset(desc, kv_idx, budget, b_cap, u_cap, ws, _per_head=True)
 
 
 def omni_slim_decode_grouped(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_mask, grp_cnt,
@@ -540,6 +551,37 @@ def omni_slim_decode_grouped(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe
     _check(lib.omni_slim_decode_grouped(C.byref(desc), _ptr(q), _ptr(Kcache), _ptr(Vcache), _ptr(ctx_len),
                                         _ptr(probe_keys), _ptr(grp_idx), _ptr(grp_mask), _ptr(grp_cnt),
                                         grp_idx.shape[-1], _ptr(O), _ptr(active), _ptr(buf), buf.numel(), _stream()))
+    return O, active
+
+
+def omni_compact_cache(desc: DecodeDesc, Kcache, Vcache, grp_idx, grp_cnt, Kcomp=None, Vcomp=None):
+    lib = load_library()
+    u_cap = grp_idx.shape[-1]
+    shape = (desc.batch, desc.n_kv_heads, u_cap, desc.head_dim)
+    if Kcomp is None:
+        Kcomp = torch.zeros(shape, dtype=Kcache.dtype, device=Kcache.device)
+    if Vcomp is None:
+        Vcomp = torch.zeros(shape, dtype=Vcache.dtype, device=Vcache.device)
+    _check(lib.omni_compact_cache(C.byref(desc), _ptr(Kcache), _ptr(Vcache), _ptr(grp_idx), _ptr(grp_cnt), u_cap,
+                                  _ptr(Kcomp), _ptr(Vcomp), _stream()))
+    return Kcomp, Vcomp
+
+
+def omni_slim_decode_compact(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, Kcomp, Vcomp, grp_idx, grp_mask,
+                             grp_cnt, O=None, active=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if O is None:
+        O = torch.empty_like(q)
+    if active is None:
+        active = torch.empty(desc.batch, desc.n_q_heads, dtype=torch.uint8, device=q.device)
+    if tuple(Kcomp.shape) != (desc.batch, desc.n_kv_heads, grp_idx.shape[-1], desc.head_dim) or not Kcomp.is_contiguous():
+        raise ValueError("Kcomp / Vcomp must be contiguous [batch, n_kv_heads, u_cap, head_dim]")
+    buf = ws.get(CALL_SLIM_DECODE, desc)
+    _check(lib.omni_slim_decode_compact(C.byref(desc), _ptr(q), _ptr(Kcache), _ptr(Vcache), _ptr(ctx_len),
+                                        _ptr(probe_keys), _ptr(Kcomp), _ptr(Vcomp), _ptr(grp_idx), _ptr(grp_mask),
+                                        _ptr(grp_cnt), grp_idx.shape[-1], _ptr(O), _ptr(active), _ptr(buf), buf.numel(),
+                                        _stream()))
     return O, active
 
 

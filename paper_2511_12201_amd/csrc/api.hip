@@ -402,17 +402,30 @@ int omni_visual_subset_per_head(const omni_layer_desc* desc, const int32_t* kv_i
   return visual_subset_impl(desc, 1, kv_idx, budget, b_cap, vis_idx, vis_cnt, stream);
 }
 
-int omni_group_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
-                      int32_t* grp_idx, uint32_t* grp_mask, int32_t* grp_cnt, int32_t u_cap, void* ws, size_t ws_bytes,
-                      void* stream) {
+static int group_subset_impl(const omni_layer_desc* desc, int per_head, const int32_t* kv_idx, const int32_t* budget,
+                             int32_t b_cap, int32_t* grp_idx, uint32_t* grp_mask, int32_t* grp_cnt, int32_t u_cap,
+                             void* ws, size_t ws_bytes, void* stream) {
   clear_error();
   CHECK(validate_layer(desc));
   REQUIRE_PTR(kv_idx); REQUIRE_PTR(budget); REQUIRE_PTR(grp_idx); REQUIRE_PTR(grp_mask); REQUIRE_PTR(grp_cnt);
   if (b_cap < 1 || u_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap and u_cap must be >= 1");
   if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
-  const Layer L = make_layer(desc);
+  Layer L = make_layer(desc);
+  L.bph = per_head;
   CHECK(check_ws(ws, ws_bytes, group_subset_ws(L)));
   return run_group_subset(L, kv_idx, budget, b_cap, grp_idx, grp_mask, grp_cnt, u_cap, ws, static_cast<hipStream_t>(stream));
+}
+
+int omni_group_subset(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget, int32_t b_cap,
+                      int32_t* grp_idx, uint32_t* grp_mask, int32_t* grp_cnt, int32_t u_cap, void* ws, size_t ws_bytes,
+                      void* stream) {
+  return group_subset_impl(desc, 0, kv_idx, budget, b_cap, grp_idx, grp_mask, grp_cnt, u_cap, ws, ws_bytes, stream);
+}
+
+int omni_group_subset_per_head(const omni_layer_desc* desc, const int32_t* kv_idx, const int32_t* budget,
+                               int32_t b_cap, int32_t* grp_idx, uint32_t* grp_mask, int32_t* grp_cnt, int32_t u_cap,
+                               void* ws, size_t ws_bytes, void* stream) {
+  return group_subset_impl(desc, 1, kv_idx, budget, b_cap, grp_idx, grp_mask, grp_cnt, u_cap, ws, ws_bytes, stream);
 }
 
 int omni_block_scores(const omni_layer_desc* desc, const void* Q, const void* K, int32_t block, float* block_scores,
@@ -547,6 +560,36 @@ int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q, const 
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
   return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
                     static_cast<hipStream_t>(stream));
+}
+
+int omni_compact_cache(const omni_decode_desc* desc, const void* Kcache, const void* Vcache, const int32_t* grp_idx,
+                       const int32_t* grp_cnt, int32_t u_cap, void* Kcomp, void* Vcomp, void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(grp_idx); REQUIRE_PTR(grp_cnt); REQUIRE_PTR(Kcomp);
+  REQUIRE_PTR(Vcomp);
+  REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache); REQUIRE_ALIGNED(Kcomp); REQUIRE_ALIGNED(Vcomp);
+  if (u_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "u_cap must be >= 1");
+  return run_compact_cache(desc, Kcache, Vcache, grp_idx, grp_cnt, u_cap, Kcomp, Vcomp,
+                           static_cast<hipStream_t>(stream));
+}
+
+int omni_slim_decode_compact(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,
+                             const int32_t* ctx_len, const float* probe_keys, const void* Kcomp, const void* Vcomp,
+                             const int32_t* grp_idx, const uint32_t* grp_mask, const int32_t* grp_cnt, int32_t u_cap,
+                             void* O, uint8_t* active, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(q); REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(ctx_len); REQUIRE_PTR(probe_keys);
+  REQUIRE_PTR(Kcomp); REQUIRE_PTR(Vcomp);
+  REQUIRE_PTR(grp_idx); REQUIRE_PTR(grp_mask); REQUIRE_PTR(grp_cnt); REQUIRE_PTR(O); REQUIRE_PTR(active);
+  REQUIRE_ALIGNED(q); REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache); REQUIRE_ALIGNED(Kcomp); REQUIRE_ALIGNED(Vcomp);
+  if (u_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "u_cap must be >= 1");
+  if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
+  if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
+  CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
+  return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
+                    static_cast<hipStream_t>(stream), Kcomp, Vcomp);
 }
 
 int omni_dense_decode(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,

@@ -42,6 +42,8 @@ struct DecodeParams {
   const int* vis_idx;      // per-head lists [B*Hq, b_cap], or group lists [B*Hkv, b_cap] (grouped call)
   const int* vis_cnt;
   const unsigned* grp_mask; // membership bits of the group lists, nullptr for the per-head call
+  const void* Kcomp;       // compacted copies of the group lists' rows [B*Hkv, b_cap, D] (row u = cache row
+  const void* Vcomp;       // vis_idx[u]), or nullptr: the listed rows are read from the cache itself
   int b_cap;
   void* O;
   unsigned char* active;
@@ -88,17 +90,19 @@ __device__ __forceinline__ float row_group_sum(float v) {
 // or -1.  Every thread of the workgroup must call it (it contains barriers).
 // mask_of gives the heads (bit h = head0 + h) that attend the row; heads outside head_bits are skipped
 // altogether (a wave-uniform decision) and get an empty partial state.
+// krows / vrows point at row 0 of the (batch, KV head) the rows belong to; rows are row_stride elements apart.
 template <typename T, int D, int GT, typename RowOf, typename MaskOf>
 __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g, int head0, int begin, int end,
-                                            RowOf row_of, MaskOf mask_of, unsigned head_bits, int slot) {
+                                            RowOf row_of, MaskOf mask_of, unsigned head_bits, int slot,
+                                            const T* krows, const T* vrows, long long row_stride) {
   constexpr int E = Elem<T>::kPer16B;
   constexpr int LPR = D / E;              // lanes per row
   constexpr int RPP = kThreads / LPR;     // lane groups = rows per pass
   __shared__ float sM[GT][RPP], sL[GT][RPP];
   __shared__ float sO[RPP][D];
   const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
-  const T* kbase = static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1] + c * E;
-  const T* vbase = static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1] + c * E;
+  const T* kbase = krows + c * E;
+  const T* vbase = vrows + c * E;
   const float c2 = p.scale * kLog2e;
 
   u32x4 qraw[GT];
@@ -130,7 +134,7 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
       kraw[u] = u32x4{0u, 0u, 0u, 0u};
       vraw[u] = u32x4{0u, 0u, 0u, 0u};
       if (row[u] >= 0) {
-        const long long off = (long long)row[u] * p.ks[2];
+        const long long off = (long long)row[u] * row_stride;
         kraw[u] = *reinterpret_cast<const u32x4*>(kbase + off);
         vraw[u] = *reinterpret_cast<const u32x4*>(vbase + off);
       }
@@ -231,7 +235,8 @@ __global__ __launch_bounds__(kThreads) void decode_shared_kernel(DecodeParams p)
   const int begin = min(total, slice * per), end = min(total, begin + per);
   stream_rows<T, D, GT>(p, b, g, g * p.G + chunk * GT, begin, end,
                         [&](int it) { return it < n_lo ? it : hi0 + (it - n_lo); }, [](int) { return ~0u; },
-                        (1u << GT) - 1u, slice);
+                        (1u << GT) - 1u, slice, static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1],
+                        static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1], p.ks[2]);
 }
 
 // A head's own (stored visual) rows.  grid = (n_head, B * Hq).  Also classifies the decoding query.
@@ -266,7 +271,9 @@ __global__ __launch_bounds__(kThreads) void decode_head_kernel(DecodeParams p) {
                          const int r = vlist[it];
                          return r < ctx ? r : -1;          // stored rows beyond the context are ignored
                        },
-                       [](int) { return 1u; }, 1u, p.n_shared + slice);
+                       [](int) { return 1u; }, 1u, p.n_shared + slice,
+                       static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1],
+                       static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1], p.ks[2]);
 }
 
 // The union list of a KV group, GT heads per workgroup.  grid = (n_head, B * Hkv * (G / GT)).  Classifies the
@@ -309,12 +316,21 @@ __global__ __launch_bounds__(kThreads) void decode_group_kernel(DecodeParams p) 
   const int* vlist = p.vis_idx + (long long)bg * p.b_cap;
   const unsigned* mlist = p.grp_mask + (long long)bg * p.b_cap;
   const int shift = chunk * GT;
+  if (p.Kcomp) {                 // the listed rows sit side by side in the compacted store: position = row
+    const long long base = (long long)bg * p.b_cap * D;
+    stream_rows<T, D, GT>(p, b, g, head0, begin, end, [&](int it) { return vlist[it] < ctx ? it : -1; },
+                          [&](int it) { return mlist[it] >> shift; }, bits, p.n_shared + slice,
+                          static_cast<const T*>(p.Kcomp) + base, static_cast<const T*>(p.Vcomp) + base, (long long)D);
+    return;
+  }
   stream_rows<T, D, GT>(p, b, g, head0, begin, end,
                         [&](int it) {
                           const int r = vlist[it];
                           return r < ctx ? r : -1;
                         },
-                        [&](int it) { return mlist[it] >> shift; }, bits, p.n_shared + slice);
+                        [&](int it) { return mlist[it] >> shift; }, bits, p.n_shared + slice,
+                        static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1],
+                        static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1], p.ks[2]);
 }
 
 // Merges the slices of one head.  grid = B * Hq, kCombineThreads threads: lane groups of D/2 threads (two
@@ -442,6 +458,53 @@ Slices decode_slices(const omni_decode_desc* d, bool slim) {
 
 }  // namespace
 
+// ---- compaction of the group lists' rows (paper Sec. "KV Cache Slimming": the selected KV pairs are what is stored)
+
+namespace {
+// grid: (cdiv(u_cap, rows per block), B*Hkv); a row is copied by D*sizeof(T)/16 lanes
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void compact_rows_kernel(const T* __restrict__ K, const T* __restrict__ V,
+                                                               const int* __restrict__ idx,
+                                                               const int* __restrict__ cnt, int u_cap, int Hkv, int cap,
+                                                               long long s0, long long s1, long long s2,
+                                                               T* __restrict__ Kc, T* __restrict__ Vc) {
+  constexpr int E = Elem<T>::kPer16B;
+  constexpr int LPR = D / E;
+  constexpr int RPB = kThreads / LPR;
+  const int bg = blockIdx.y, b = bg / Hkv, g = bg % Hkv;
+  const int c = threadIdx.x % LPR, u = blockIdx.x * RPB + threadIdx.x / LPR;
+  if (u >= min(cnt[bg], u_cap)) return;
+  const int row = idx[(long long)bg * u_cap + u];
+  if (row < 0 || row >= cap) return;
+  const long long src = b * s0 + g * s1 + (long long)row * s2 + c * E;
+  const long long dst = ((long long)bg * u_cap + u) * D + c * E;
+  *reinterpret_cast<u32x4*>(Kc + dst) = *reinterpret_cast<const u32x4*>(K + src);
+  *reinterpret_cast<u32x4*>(Vc + dst) = *reinterpret_cast<const u32x4*>(V + src);
+}
+
+template <typename T, int D>
+int launch_compact(const omni_decode_desc* d, const void* K, const void* V, const int* idx, const int* cnt, int u_cap,
+                   void* Kc, void* Vc, hipStream_t st) {
+  constexpr int RPB = kThreads / (D / Elem<T>::kPer16B);
+  hipLaunchKernelGGL((compact_rows_kernel<T, D>), dim3(cdiv(u_cap, RPB), d->batch * d->n_kv_heads), dim3(kThreads), 0,
+                     st, static_cast<const T*>(K), static_cast<const T*>(V), idx, cnt, u_cap, d->n_kv_heads,
+                     d->cache_capacity, d->kv_stride[0], d->kv_stride[1], d->kv_stride[2], static_cast<T*>(Kc),
+                     static_cast<T*>(Vc));
+  OMNI_LAUNCH_CHECK();
+  return OMNI_OK;
+}
+}  // namespace
+
+int run_compact_cache(const omni_decode_desc* d, const void* K, const void* V, const int* grp_idx, const int* grp_cnt,
+                      int u_cap, void* Kc, void* Vc, hipStream_t st) {
+  if (d->dtype == OMNI_BF16) {
+    if (d->head_dim == 128) return launch_compact<u16, 128>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, st);
+    return launch_compact<u16, 64>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, st);
+  }
+  if (d->head_dim == 128) return launch_compact<float, 128>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, st);
+  return launch_compact<float, 64>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, st);
+}
+
 size_t decode_ws(const omni_decode_desc* d) {
   Arena a(nullptr);
   // one size for both calls: the larger of the slimmed and the plain slice counts
@@ -454,7 +517,7 @@ size_t decode_ws(const omni_decode_desc* d) {
 
 int run_decode(const omni_decode_desc* d, const void* q, const void* K, const void* V, const int* ctx_len,
                const float* probe, const int* vis_idx, const int* vis_cnt, const unsigned* grp_mask, int b_cap,
-               void* O, unsigned char* active, void* ws, hipStream_t st) {
+               void* O, unsigned char* active, void* ws, hipStream_t st, const void* Kcomp, const void* Vcomp) {
   Arena a(ws);
   DecodeParams p;
   p.q = q;
@@ -465,6 +528,8 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
   p.vis_idx = vis_idx;
   p.vis_cnt = vis_cnt;
   p.grp_mask = grp_mask;
+  p.Kcomp = Kcomp;
+  p.Vcomp = Vcomp;
   p.b_cap = b_cap;
   p.O = O;
   p.active = active;

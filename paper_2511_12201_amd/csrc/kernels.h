@@ -64,7 +64,10 @@ size_t decode_ws(const omni_decode_desc* d);
 // grp_mask == nullptr: vis_idx / vis_cnt are per query head; otherwise per KV group with membership bits
 int run_decode(const omni_decode_desc* d, const void* q, const void* K, const void* V, const int* ctx_len,
                const float* probe, const int* vis_idx, const int* vis_cnt, const unsigned* grp_mask, int b_cap,
-               void* O, unsigned char* active, void* ws, hipStream_t st);
+               void* O, unsigned char* active, void* ws, hipStream_t st, const void* Kcomp = nullptr,
+               const void* Vcomp = nullptr);
+int run_compact_cache(const omni_decode_desc* d, const void* K, const void* V, const int* grp_idx, const int* grp_cnt,
+                      int u_cap, void* Kc, void* Vc, hipStream_t st);
 
 // block.hip (block-granular variant of the KV selection)
 int block_scores_max_blocks();

@@ -328,6 +328,48 @@ def test_grouped_slim_decode(cfg, batch):
     assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
 
 
+@pytest.mark.parametrize("cfg,batch", [(CFG_BF16, 1), (CFG_BF16, 3), (CFG_BF16_64, 2), (CFG_F32, 2), (CFG_F32_128, 1)],
+                         ids=lambda x: getattr(x, "name", str(x)))
+def test_compacted_cache_decode(cfg, batch):
+    """The rows of the group lists copied side by side: the copy is exact, and the decode step that reads it gives
+    the oracle's result while the visual part of the cache itself holds garbage (it is never read)."""
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    tau = 0.08
+    H, Hkv = cfg.n_q_heads, cfg.n_kv_heads
+    b = len(c.o_kvidx[0][0])
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])] * batch, H, b)
+    budget = torch.full((batch,), b, dtype=torch.int32, device="cuda")
+    ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                               cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset(ldesc, kv_idx, budget, b)
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    dctx = torch.from_numpy(ctx).cuda()
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    desc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau)
+    Kcomp, Vcomp = ob.omni_compact_cache(desc, dKc, dVc, grp_idx, grp_cnt)
+    torch.cuda.synchronize()
+    gi, gc = to_host(grp_idx), to_host(grp_cnt)
+    Kh, Vh = to_host(dKc), to_host(dVc)
+    for bb in range(batch):
+        for g in range(Hkv):
+            n = int(gc[bb, g])
+            np.testing.assert_array_equal(to_host(Kcomp)[bb, g, :n], Kh[bb, g, gi[bb, g, :n]])
+            np.testing.assert_array_equal(to_host(Vcomp)[bb, g, :n], Vh[bb, g, gi[bb, g, :n]])
+    # the caller may now drop the visual rows of the cache: fill them with values that would wreck any sum
+    dKc[:, :, cfg.vis_begin:cfg.vis_end] = float("nan")
+    dVc[:, :, cfg.vis_begin:cfg.vis_end] = float("nan")
+    O, act = ob.omni_slim_decode_compact(desc, dq, dKc, dVc, dctx, dprobe, Kcomp, Vcomp, grp_idx, grp_mask, grp_cnt)
+    torch.cuda.synchronize()
+    Oo, acto, sc = oc.slim_decode(q, Kc, Vc, ctx, probe.astype(np.float32), vis, tau, cfg.vis_begin, cfg.vis_end, cfg.scale)
+    act = to_host(act)
+    clear = np.abs(sc - tau) > 1e-5
+    np.testing.assert_array_equal(act[clear], acto[clear])
+    same = act == acto
+    got = to_host(O)
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
+
+
 def test_visual_subset_matches_oracle():
     cfg = CFG_BF16
     c = case_for(cfg)

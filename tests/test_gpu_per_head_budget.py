@@ -157,6 +157,29 @@ def test_visual_subset_per_head_matches_oracle():
         np.testing.assert_array_equal(got[0][h], want[0][h])
 
 
+def test_group_subset_per_head_is_the_union_of_the_ragged_lists_with_membership_bits():
+    cfg = CFG_BF16
+    c = case_for(cfg)
+    H, Hkv = cfg.n_q_heads, cfg.n_kv_heads
+    G = H // Hkv
+    bud = oc.kv_budget(c.o_a32, c.recall_p, 2)["budget"]
+    kv_lists = oc.select_kv(c.o_a32, bud)
+    cap = int(bud.max())
+    kv_idx, budget = lists_to_padded(kv_lists, H, cap)
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset_per_head(c.desc, kv_idx, budget, cap)
+    torch.cuda.synchronize()
+    vis = oc.visual_subset(kv_lists, cfg.vis_begin, cfg.vis_end)
+    gi, gm, gc = to_host(grp_idx), to_host(grp_mask).view(np.uint32), to_host(grp_cnt)
+    for g in range(Hkv):
+        sets = [set(int(x) for x in vis[0][g * G + j]) for j in range(G)]
+        union = sorted(set().union(*sets))
+        n = int(gc[0, g])
+        assert n == len(union)
+        np.testing.assert_array_equal(gi[0, g, :n], np.array(union, dtype=np.int32))
+        want = np.array([sum((1 << j) for j in range(G) if t in sets[j]) for t in union], dtype=np.uint32)
+        np.testing.assert_array_equal(gm[0, g, :n], want)
+
+
 @pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
 def test_free_running_per_head_pipeline_matches_oracle_up_to_ties_at_the_cut(cfg):
     c = case_for(cfg)
