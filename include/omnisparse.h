@@ -456,6 +456,14 @@ int omni_debug_copy(const void* src, void* dst, size_t bytes, void* stream);
  */
 int omni_debug_mfma_rate(int random_operands, int iters, double* tflops /* host */, double* shader_mhz /* host */);
 
+/*
+ * Diagnostic: the backward pass shares a key tile that is seen by very many query tiles (a head
+ * that keeps every query, at long context) between several workgroups, from `tiles` 64-query
+ * tiles per share on (default 128).  A small value makes short test inputs take that path.
+ * tiles <= 0 restores the default.  Process-wide; not for use while a backward call is running.
+ */
+int omni_debug_key_split_len(int tiles);
+
 /* Message of the last error on this thread ("" if none). */
 const char* omni_last_error(void);
 

@@ -29,7 +29,7 @@ EXPORTED = [
     "omni_group_subset", "omni_slim_decode_grouped", "omni_block_scores", "omni_expand_blocks",
     "omni_select_kv_per_head", "omni_sparse_attn_fwd_per_head", "omni_sparse_attn_bwd_per_head",
     "omni_visual_subset_per_head", "omni_prefill_select", "omni_compact_cache", "omni_slim_decode_compact",
-    "omni_group_subset_per_head",
+    "omni_group_subset_per_head", "omni_debug_key_split_len",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -103,6 +103,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_slim_decode_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_profile_enable.argtypes = [C.c_int]
     lib.omni_debug_copy.argtypes = [vp, vp, sz, vp]
+    lib.omni_debug_key_split_len.argtypes = [C.c_int]
     lib.omni_debug_mfma_rate.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.omni_debug_work_list.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, i32, vp]   # same shape: three output arrays
     lib.omni_profile_read.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
@@ -193,6 +194,11 @@ def debug_copy(src, dst):
     nbytes = src.numel() * src.element_size()
     assert nbytes == dst.numel() * dst.element_size()
     _check(load_library().omni_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream()))
+
+
+def debug_key_split_len(tiles: int):
+    """Query tiles per share of a split key tile in the backward pass (<= 0: default)."""
+    _check(load_library().omni_debug_key_split_len(int(tiles)))
 
 
 def debug_mfma_rate(random_operands: bool, iters: int = 40000):

@@ -194,6 +194,12 @@ int omni_debug_copy(const void* src, void* dst, size_t bytes, void* stream) {
   return run_calibration_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
 }
 
+int omni_debug_key_split_len(int tiles) {
+  clear_error();
+  set_key_split_len(tiles);
+  return OMNI_OK;
+}
+
 int omni_debug_mfma_rate(int random_operands, int iters, double* tflops, double* shader_mhz) {
   clear_error();
   REQUIRE_PTR(tflops); REQUIRE_PTR(shader_mhz);

@@ -60,6 +60,10 @@ struct BwdParams {
   const int* qvis;      // [B*Hq, N] visible packed keys per kept-query position (bf16 fast path)
   const int* kfirst;    // [B*Hq, npad] first kept-query position that sees a packed key
   int head_group;       // heads per dispatch group of the key kernels
+  int nsplit;           // most workgroups that share the query tiles of one key tile (bf16 key kernels)
+  int split_len;        // query tiles per split, at least
+  long long plane;      // floats between the partial-gradient planes of two splits
+  int* klist;           // work list of the key kernels: [0], [1] counters (dV, dK kernel), [2] items, [4..] items
 };
 
 // first position in ascending a[0,n) with a[pos] >= v
@@ -788,6 +792,72 @@ constexpr int kKeyWaves = 8;
 constexpr int kKeyThreads = kKeyWaves * 64;
 constexpr int kKeyTile = kKeyWaves * 32;     // packed keys per workgroup
 constexpr int kKeyQ = 64;                    // queries per streamed tile
+// A key tile seen by many query tiles (the first tiles of a head that keeps every query: 512 query tiles at 32k,
+// against a few dozen for most workgroups) is shared by several workgroups, each with a contiguous range of the
+// query tiles and a partial-gradient plane of its own; the group reduction adds the planes in split order.
+constexpr int kKeySplitLen = 128;            // query tiles per split, at least (64..128 measure alike, 32 and 256 worse)
+constexpr int kKeyMaxSplits = 4;             // at most 8: a work item carries the split in 3 bits
+__host__ __device__ inline int key_tile_splits(int n_qtiles, int max_splits, int split_len) {
+  const int s = n_qtiles / split_len;
+  return s < 1 ? 1 : (s > max_splits ? max_splits : s);
+}
+
+// Work items of the key kernels: (head, key tile, split), in dispatch order -- heads in groups of p.head_group,
+// inside a group key tile by key tile (the first key tiles, seen by the most queries, first), the splits of a
+// tile side by side.  Slot i of that order decodes to an item; most slots are empty (key tiles beyond a head's
+// budget, splits a tile does not need), so one workgroup compacts the live ones into a list that the
+// persistent key kernels pull from: an empty workgroup would still wait for a whole CU's LDS.
+constexpr int kKeyListHeader = 4;
+__device__ __forceinline__ int key_slot_item(const BwdParams& p, long long i) {
+  const Layer& L = p.L;
+  const int BH = L.B * L.Hq, nkt = p.npad / kKeyTile;
+  const long long per_group = (long long)p.head_group * nkt * p.nsplit;
+  const int grp = (int)(i / per_group);
+  const int within = (int)(i % per_group);
+  const int heads_here = min(p.head_group, BH - grp * p.head_group);
+  if (heads_here <= 0) return -1;
+  const int kts = within / heads_here, bh = grp * p.head_group + within % heads_here;
+  const int ktile = kts / p.nsplit, sp = kts % p.nsplit;
+  if (ktile >= nkt) return -1;
+  const int nkeys = min(p.budget[budget_slot(L.bph, bh / L.Hq, bh)], p.b_cap);
+  if (ktile * kKeyTile >= nkeys) return -1;
+  if (sp > 0) {
+    const int first = p.kfirst[(long long)bh * p.npad + ktile * kKeyTile];
+    if (sp >= key_tile_splits(cdiv(p.q_cnt[bh], kKeyQ) - first / kKeyQ, p.nsplit, p.split_len)) return -1;
+  }
+  return (bh << 16) | (ktile << 3) | sp;
+}
+
+// one workgroup of 1024 threads; stable compaction of the live slots
+__global__ __launch_bounds__(1024) void key_list_kernel(BwdParams p, long long n_slots) {
+  __shared__ int wave_cnt[16];
+  __shared__ int base;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  for (long long i0 = 0; i0 < n_slots; i0 += 1024) {
+    const long long i = i0 + threadIdx.x;
+    const int item = i < n_slots ? key_slot_item(p, i) : -1;
+    const unsigned long long live = __ballot(item >= 0);
+    if (lane == 0) wave_cnt[wave] = __popcll(live);
+    __syncthreads();
+    int before = base;
+    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+    if (item >= 0) p.klist[kKeyListHeader + before + __popcll(live & ((1ull << lane) - 1ull))] = item;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = base;
+      for (int w = 0; w < 16; ++w) t += wave_cnt[w];
+      base = t;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    p.klist[0] = 0;
+    p.klist[1] = 0;
+    p.klist[2] = base;
+  }
+}
 
 template <int D, int MODE>
 __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdParams p) {
@@ -806,25 +876,28 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
   static_assert(LPH >= 1, "tile too small for the copy scheme");
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kStages * kStageBytes];
   __shared__ int sBound[2];
+  __shared__ int sItem;
 
   const Layer& L = p.L;
-  // 1-D grid, heads in groups of p.head_group: inside a group the workgroups are dispatched key tile by key tile
-  // (the first key tiles -- seen by the most queries, the longest workgroups -- of all its heads first)
-  const int nkt = p.npad / kKeyTile;
-  const int per_group = p.head_group * nkt;
-  const int grp = blockIdx.x / per_group, within = blockIdx.x % per_group;
-  const int heads_here = min(p.head_group, L.B * L.Hq - grp * p.head_group);
-  const int ktile = within / heads_here, bh = grp * p.head_group + within % heads_here;
-  if (ktile >= nkt) return;
-  const int b = bh / L.Hq;
-  const int nkeys = min(p.budget[budget_slot(L.bph, b, bh)], p.b_cap);
-  if (ktile * kKeyTile >= nkeys) return;
-  const int nq = p.q_cnt[bh];
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int ln = lane & 31, h = lane >> 5;
   const float c2 = L.scale * kLog2e;
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+  for (;;) {                                   // persistent: one item of the work list per iteration
+  __syncthreads();                             // LDS of the previous item is no longer read
+  if (threadIdx.x == 0) {
+    const int k = atomicAdd(&p.klist[MODE], 1);
+    sItem = k < p.klist[2] ? p.klist[kKeyListHeader + k] : -1;
+  }
+  __syncthreads();
+  const int item = __builtin_amdgcn_readfirstlane(sItem);
+  if (item < 0) break;
+  const int bh = item >> 16, ktile = (item >> 3) & 0x1fff, sp = item & 7;
+  const int b = bh / L.Hq;
+  const int nkeys = min(p.budget[budget_slot(L.bph, b, bh)], p.b_cap);
+  const int nq = p.q_cnt[bh];
   const int slot0 = ktile * kKeyTile;
   const int slot = slot0 + wave * 32 + ln;                  // this lane's key slot (< npad by construction)
   const int* kfirst = p.kfirst + (long long)bh * p.npad;
@@ -835,9 +908,13 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
   int my_first = kfirst[slot];
   __syncthreads();
   const bool has_pad = slot0 + kKeyTile > nkeys;
-  const int q_begin = sBound[0] / kKeyQ;                    // first query tile with an admissible pair
   const int q_full_pos = has_pad ? 0x7fffffff : sBound[1];  // tiles starting at or after this position need no mask
   const int n_qtiles = cdiv(nq, kKeyQ);
+  const int q_first = sBound[0] / kKeyQ;                    // first query tile with an admissible pair
+  const int n_all = n_qtiles - q_first;
+  const int n_sp = key_tile_splits(n_all, p.nsplit, p.split_len);
+  const int per_split = cdiv(n_all, n_sp);
+  const int q_begin = q_first + sp * per_split;             // this workgroup's query tiles: [q_begin, q_begin + n)
 
   // resident K (and V) fragments: B operands, lane = key column
   const T* krow = static_cast<const T*>(p.Kn) + ((long long)bh * p.npad + slot) * D;
@@ -978,7 +1055,7 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
 
   // Ring of kStages buffers, one barrier per tile: at the top of step u the tiles up to u + kStages - 2 have
   // been issued; after its barrier everyone is done with tile u-1, whose buffer takes tile u + kStages - 1.
-  const int n = n_qtiles - q_begin;
+  const int n = min(per_split, n_qtiles - q_begin);
   if (n > 0) {
     wait_vmcnt<0>();
 #pragma unroll
@@ -1002,7 +1079,7 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
   }
 
   // ---- write dK' (scaled) or dV' for this lane's key slot; accumulator rows are d
-  float* orow = (MODE == 0 ? p.dKp : p.dVp) + ((long long)bh * p.npad + slot) * D;
+  float* orow = (MODE == 0 ? p.dKp : p.dVp) + sp * p.plane + ((long long)bh * p.npad + slot) * D;
   const float osc = MODE == 0 ? L.scale : 1.0f;
 #pragma unroll
   for (int db = 0; db < NB; ++db)
@@ -1012,6 +1089,7 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
       f32x4 a = {acc[db][q4 * 4] * osc, acc[db][q4 * 4 + 1] * osc, acc[db][q4 * 4 + 2] * osc, acc[db][q4 * 4 + 3] * osc};
       *reinterpret_cast<f32x4*>(orow + d) = a;
     }
+  }   // items
 }
 
 // ------------------------------------------------------------------ dK, dV = sum over the heads of a KV group
@@ -1059,11 +1137,16 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_reduce_kernel(BwdParams p, 
       if (!(pos < nkeys && list[pos] == n)) pos = -1;
     }
     if (pos >= 0) {
+      int n_sp = 1;
+      if (p.nsplit > 1) {                  // as the key kernels counted: the query tiles from the tile's first visible pair on
+        const int first = p.kfirst[(long long)bh * p.npad + pos / kKeyTile * kKeyTile];
+        n_sp = key_tile_splits(cdiv(p.q_cnt[bh], kKeyQ) - first / kKeyQ, p.nsplit, p.split_len);
+      }
       const long long o = ((long long)bh * p.npad + pos) * D + c * 4;
-      const f32x4 k4 = *reinterpret_cast<const f32x4*>(p.dKp + o);
-      const f32x4 v4 = *reinterpret_cast<const f32x4*>(p.dVp + o);
-      ak += k4;
-      av += v4;
+      for (int sp = 0; sp < n_sp; ++sp) {
+        ak += *reinterpret_cast<const f32x4*>(p.dKp + sp * p.plane + o);
+        av += *reinterpret_cast<const f32x4*>(p.dVp + sp * p.plane + o);
+      }
     }
   }
   const long long o = b * L.ks[0] + g * L.ks[1] + (long long)n * L.ks[2] + c * 4;
@@ -1100,8 +1183,15 @@ struct BwdWs {
   int* kidx;
   float *lse2c, *deltac, *dKp, *dVp;
   int* sched;
-  int *qvis, *kfirst, *inv;
+  int *qvis, *kfirst, *inv, *klist;
 };
+
+constexpr int kKeyHeadGroup = 7;
+int g_key_split_len = kKeySplitLen;          // omni_debug_key_split_len: tests split short key tiles too
+// slots of the key kernels' dispatch order (an upper bound of the live items)
+size_t key_list_slots(const Layer& L, int npad) {
+  return (size_t)cdiv(L.B * L.Hq, kKeyHeadGroup) * kKeyHeadGroup * (npad / kKeyTile) * kKeyMaxSplits;
+}
 
 BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   BwdWs w;
@@ -1118,12 +1208,14 @@ BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   w.kidx = a.take<int>(krows);
   w.lse2c = a.take<float>(qrows);
   w.deltac = a.take<float>(qrows);
-  w.dKp = a.take<float>(krows * L.D);
-  w.dVp = a.take<float>(krows * L.D);
+  const size_t planes = dtype == OMNI_BF16 ? kKeyMaxSplits : 1;
+  w.dKp = a.take<float>(planes * krows * L.D);
+  w.dVp = a.take<float>(planes * krows * L.D);
   w.sched = a.take<int>(sched_ints(L.B * L.Hq, L.N, kTileM));   // sized for the smaller tile: the longer list
   w.qvis = a.take<int>(dtype == OMNI_BF16 ? BH * L.N : 4);
   w.kfirst = a.take<int>(dtype == OMNI_BF16 ? krows : 4);
   w.inv = a.take<int>(BH * L.N);
+  w.klist = a.take<int>(kKeyListHeader + key_list_slots(L, npad));
   return w;
 }
 
@@ -1181,6 +1273,9 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.deltac = w.deltac;
   p.dKp = w.dKp;
   p.dVp = w.dVp;
+  p.nsplit = sizeof(T) == 2 ? kKeyMaxSplits : 1;
+  p.split_len = g_key_split_len;
+  p.plane = (long long)L.B * L.Hq * npad * D;
   p.dQ = dQ;
   p.sched = w.sched;
   p.qvis = w.qvis;
@@ -1200,10 +1295,14 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
       // first key tiles of the last heads for the end (measured 3.9 ms at 32k), all heads at once spreads 28
       // query streams over the caches (4.4 ms); groups of 7 take 3.4 ms.  Group sizes that share a factor with
       // the 8 XCDs (workgroup i runs on XCD i mod 8) pin heads to XCDs and unbalance them: 8 takes 5.6 ms.
-      p.head_group = 7;
-      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 1>), dim3((npad / kKeyTile) * L.B * L.Hq), dim3(kKeyThreads), 0, st, p);
+      p.head_group = kKeyHeadGroup;
+      p.klist = w.klist;
+      hipLaunchKernelGGL(key_list_kernel, dim3(1), dim3(1024), 0, st, p, (long long)key_list_slots(L, npad));
       OMNI_LAUNCH_CHECK();
-      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 0>), dim3((npad / kKeyTile) * L.B * L.Hq), dim3(kKeyThreads), 0, st, p);
+      const unsigned key_wgs = (unsigned)persistent_grid() / 2;       // one workgroup per CU (its LDS ring fills it)
+      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 1>), dim3(key_wgs), dim3(kKeyThreads), 0, st, p);
+      OMNI_LAUNCH_CHECK();
+      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 0>), dim3(key_wgs), dim3(kKeyThreads), 0, st, p);
     } else {
       hipLaunchKernelGGL((attn_bwd_dkdv_kernel<T, D>), dim3(npad / kBwdKeys, L.B * L.Hq), dim3(kThreads), 0, st, p);
     }
@@ -1235,6 +1334,8 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
 }
 
 }  // namespace
+
+void set_key_split_len(int tiles) { g_key_split_len = tiles > 0 ? tiles : kKeySplitLen; }
 
 size_t attn_bwd_ws(const Layer& L, int dtype, int b_cap) {
   Arena a(nullptr);

@@ -59,6 +59,8 @@ int run_attn_bwd(const Layer& L, int dtype, const void* Q, const void* K, const 
                  const void* dO, const float* lse, const int* q_idx, const int* q_cnt, const int* kv_idx,
                  const int* budget, int b_cap, void* dQ, void* dK, void* dV, void* ws, hipStream_t st);
 
+void set_key_split_len(int tiles);   // attn_bwd.hip; <= 0 restores the default
+
 // decode.hip
 size_t decode_ws(const omni_decode_desc* d);
 // grp_mask == nullptr: vis_idx / vis_cnt are per query head; otherwise per KV group with membership bits

@@ -598,3 +598,23 @@ def test_sparse_attn_bwd_edge_sets(cfg):
         want = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO, q_lists, kv_lists, cfg.causal, cfg.scale)
         _check_grads(cfg, got, want, q_lists, kv_lists)
         assert np.all(to_host(got[0])[0, 1] == 0)
+
+
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_BF16_64], ids=lambda c: c.name)
+@pytest.mark.parametrize("split_len", [1, 3])
+def test_sparse_attn_bwd_with_key_tiles_shared_between_workgroups(cfg, split_len):
+    """Long-context path of the key kernels (several workgroups per key tile, partial planes added in order),
+    forced on a short input by lowering the split length."""
+    c = case_for(cfg)
+    dO = synth.make_grad_output(cfg)
+    kv_lists = [list(c.o_kvidx[b]) for b in range(cfg.batch)]
+    want = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+    ob.debug_key_split_len(split_len)
+    try:
+        got = _run_fwd_bwd(c, c.o_qidx, kv_lists, dO)
+        again = _run_fwd_bwd(c, c.o_qidx, kv_lists, dO)
+    finally:
+        ob.debug_key_split_len(0)
+    _check_grads(cfg, got, want, c.o_qidx, kv_lists)
+    for x, y in zip(got, again):
+        assert torch.equal(x, y)
