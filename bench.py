@@ -190,6 +190,23 @@ def main():
                                           "frac": round(pool_bytes / kern["pool_q"] / 1e6 / PEAK_HBM_GBS, 4)}
 
     if not args.no_extras:
+        # the same step replayed from a captured HIP graph (no call of it allocates, synchronises or memsets):
+        # what the launch gaps between its ~25 kernels cost
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            for _ in range(3):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            out["hip_graph_replay_ms_per_step"] = round((time.perf_counter() - t0) * 1e3 / args.steps, 4)
+            del graph
+        except Exception as e:
+            out["hip_graph_replay_ms_per_step"] = {"error": repr(e)}
         # dense attention baseline from the same library, same inputs
         Od = torch.empty_like(Q)
         ob.omni_dense_attn_fwd(desc, Q, K, V, Od, lse)

@@ -1296,6 +1296,8 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
       // query streams over the caches (4.4 ms); groups of 7 take 3.4 ms.  Group sizes that share a factor with
       // the 8 XCDs (workgroup i runs on XCD i mod 8) pin heads to XCDs and unbalance them: 8 takes 5.6 ms.
       p.head_group = kKeyHeadGroup;
+      if (L.B * L.Hq >= 32768 || npad / kKeyTile >= 8192)
+        OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "key work list: too many heads or key tiles");
       p.klist = w.klist;
       hipLaunchKernelGGL(key_list_kernel, dim3(1), dim3(1024), 0, st, p, (long long)key_list_slots(L, npad));
       OMNI_LAUNCH_CHECK();

@@ -618,3 +618,40 @@ def test_sparse_attn_bwd_with_key_tiles_shared_between_workgroups(cfg, split_len
     _check_grads(cfg, got, want, c.o_qidx, kv_lists)
     for x, y in zip(got, again):
         assert torch.equal(x, y)
+
+
+def test_prefill_step_replays_from_a_hip_graph():
+    """No call of the step allocates, synchronises or clears memory from the host, so a caller may capture it.
+    Replays are interleaved with eager work and each one must reproduce the eager result bit for bit."""
+    cfg = CFG_BF16
+    c = case_for(cfg)
+    N = cfg.n_tokens
+    eager_sel = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0)
+    eager_O, eager_lse = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, eager_sel.q_idx, eager_sel.q_cnt,
+                                                 eager_sel.kv_idx, eager_sel.budget.budget, N)
+    torch.cuda.synchronize()
+    sel = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0)
+    O, lse = torch.empty_like(eager_O), torch.empty_like(eager_lse)
+
+    def step():
+        ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0, out=sel)
+        ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, sel.q_idx, sel.q_cnt, sel.kv_idx, sel.budget.budget, N, O, lse)
+
+    step()                                    # workspaces exist before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for replay in range(3):
+        O.zero_()
+        lse.zero_()
+        sel.kv_idx.zero_()
+        scratch = torch.randn(1 << 20, device="cuda").sum()      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, eager_O) and torch.equal(lse, eager_lse), f"replay {replay}"
+        assert torch.equal(sel.q_cnt, eager_sel.q_cnt) and torch.equal(sel.budget.budget, eager_sel.budget.budget)
+        b = int(eager_sel.budget.budget[0])
+        assert torch.equal(sel.kv_idx[..., :b], eager_sel.kv_idx[..., :b])
+        assert torch.isfinite(scratch)
