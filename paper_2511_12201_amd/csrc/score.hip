@@ -13,7 +13,7 @@ namespace omni {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMeanRowsPerChunk = 1024;
+constexpr int kMeanRowsPerChunk = 256;     // ~1000 workgroups at 64k: enough to fill the memory system
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void mean_key_partial_kernel(const T* __restrict__ K, Layer L, int nchunk,
@@ -50,15 +50,25 @@ __global__ __launch_bounds__(kThreads) void mean_key_partial_kernel(const T* __r
   }
 }
 
+constexpr int kFinalSplit = 8;
+
 template <typename T, int D>
 __global__ void probe_keys_finalize_kernel(const T* __restrict__ K, Layer L, int nchunk,
                                            const float* __restrict__ partial, float* __restrict__ probe) {
   const int bg = blockIdx.x;
   const int b = bg / L.Hkv, g = bg % L.Hkv;
-  const int t = threadIdx.x;
-  if (t >= D) return;
+  // blockDim.x = kFinalSplit * D: kFinalSplit interleaved partial sums per element, added in a fixed order
+  __shared__ float part[kFinalSplit][128];
+  const int t = threadIdx.x % D, k = threadIdx.x / D;
   float s = 0.f;
-  for (int c = 0; c < nchunk; ++c) s += partial[((long long)bg * nchunk + c) * D + t];
+#pragma unroll 4
+  for (int c = k; c < nchunk; c += kFinalSplit) s += partial[((long long)bg * nchunk + c) * D + t];
+  part[k][t] = s;
+  __syncthreads();
+  if (k != 0) return;
+  s = 0.f;
+#pragma unroll
+  for (int j = 0; j < kFinalSplit; ++j) s += part[j][t];
   const T* sink = K + b * L.ks[0] + g * L.ks[1] + (long long)L.sink * L.ks[2];
   probe[((long long)bg * 2 + 0) * D + t] = Elem<T>::load(sink + t);
   probe[((long long)bg * 2 + 1) * D + t] = s / (float)(L.v1 - L.v0);
@@ -107,7 +117,7 @@ int launch_probe_keys(const Layer& L, const void* K, float* probe, float* partia
   hipLaunchKernelGGL((mean_key_partial_kernel<T, D>), dim3(nchunk, L.B * L.Hkv), dim3(kThreads), 0, st, k, L, nchunk,
                      partial);
   OMNI_LAUNCH_CHECK();
-  hipLaunchKernelGGL((probe_keys_finalize_kernel<T, D>), dim3(L.B * L.Hkv), dim3(128), 0, st, k, L, nchunk, partial,
+  hipLaunchKernelGGL((probe_keys_finalize_kernel<T, D>), dim3(L.B * L.Hkv), dim3(kFinalSplit * D), 0, st, k, L, nchunk, partial,
                      probe);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
