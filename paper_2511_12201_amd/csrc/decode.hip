@@ -23,6 +23,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace omni {
 
 namespace {
@@ -98,17 +100,39 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
   constexpr int E = Elem<T>::kPer16B;
   constexpr int LPR = D / E;              // lanes per row
   constexpr int RPP = kThreads / LPR;     // lane groups = rows per pass
+  // bf16 with several heads per workgroup: the scores of 32 rows x GT heads are one chain of MFMAs per
+  // wavefront (K rows as the A operand straight from memory, the heads' queries as the B operand) and reach
+  // the lane groups, which own the rows for the softmax and the V side, through a wavefront-private LDS tile.
+  // Otherwise every lane group forms its rows' dot products itself.
+  constexpr bool kMfma = sizeof(T) == 2 && GT >= 2 && GT <= 8;
+  constexpr int GPW = 64 / LPR;                     // lane groups (rows per pass) of a wavefront
+  constexpr int U = kMfma ? 32 / GPW : kUnroll;     // rows per lane group and trip
+  static_assert(U % kUnroll == 0, "a trip is consumed in chunks of kUnroll rows");
   __shared__ float sM[GT][RPP], sL[GT][RPP];
   __shared__ float sO[RPP][D];
+  __shared__ __attribute__((aligned(16))) float sS[kMfma ? kThreads / 64 : 1][kMfma ? 32 : 1][8];
   const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const T* kbase = krows + c * E;
   const T* vbase = vrows + c * E;
   const float c2 = p.scale * kLog2e;
 
-  u32x4 qraw[GT];
+  u32x4 qraw[kMfma ? 1 : GT];
+  bf16x8 qf[kMfma ? D / 16 : 1];
+  if constexpr (kMfma) {
+    const int n = lane & 31, h = lane >> 5;         // B operand: column n = head, 8 elements of the k chunk h
 #pragma unroll
-  for (int h = 0; h < GT; ++h)
-    qraw[h] = *reinterpret_cast<const u32x4*>(static_cast<const T*>(p.q) + (long long)(b * p.Hq + head0 + h) * D + c * E);
+    for (int ks = 0; ks < D / 16; ++ks) {
+      u32x4 raw = {0u, 0u, 0u, 0u};
+      if (n < GT)
+        raw = *reinterpret_cast<const u32x4*>(static_cast<const T*>(p.q) + (long long)(b * p.Hq + head0 + n) * D + ks * 16 + h * 8);
+      qf[ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+  } else {
+#pragma unroll
+    for (int h = 0; h < GT; ++h)
+      qraw[h] = *reinterpret_cast<const u32x4*>(static_cast<const T*>(p.q) + (long long)(b * p.Hq + head0 + h) * D + c * E);
+  }
   float m[GT], l[GT], acc[GT][E];
 #pragma unroll
   for (int h = 0; h < GT; ++h) {
@@ -118,34 +142,8 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
     for (int e = 0; e < E; ++e) acc[h][e] = 0.f;
   }
 
-  for (int it0 = begin; it0 < end; it0 += RPP * kUnroll) {      // uniform trip count over the workgroup
-    int row[kUnroll];
-    unsigned member[kUnroll];
-    u32x4 kraw[kUnroll], vraw[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int it = it0 + u * RPP + grp;
-      row[u] = it < end ? row_of(it) : -1;
-      member[u] = (it < end && row[u] >= 0) ? (mask_of(it) & head_bits) : 0u;
-      if (member[u] == 0u) row[u] = -1;                     // nobody wants it: not loaded
-    }
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      kraw[u] = u32x4{0u, 0u, 0u, 0u};
-      vraw[u] = u32x4{0u, 0u, 0u, 0u};
-      if (row[u] >= 0) {
-        const long long off = (long long)row[u] * row_stride;
-        kraw[u] = *reinterpret_cast<const u32x4*>(kbase + off);
-        vraw[u] = *reinterpret_cast<const u32x4*>(vbase + off);
-      }
-    }
-    float s[GT][kUnroll];
-#pragma unroll
-    for (int h = 0; h < GT; ++h) {
-      if (!((head_bits >> h) & 1u)) continue;
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) s[h][u] = row_group_sum<LPR>(chunk_dot(qraw[h], kraw[u], (const T*)nullptr));
-    }
+  // online-softmax update of this lane group's state with kUnroll rows: scores s (unscaled), V chunks, members
+  auto consume = [&](float (&s)[GT][kUnroll], const u32x4 (&vraw)[kUnroll], const unsigned (&member)[kUnroll]) {
     float vv[kUnroll][E];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) unpack16(vraw[u], vv[u], (const T*)nullptr);
@@ -176,6 +174,107 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
       }
       m[h] = mx;
     }
+  };
+
+  // rows (and member bits) of a trip: list lookups, so they are fetched one trip ahead of the rows themselves --
+  // a row's address depends on its list entry, and two dependent memory latencies per trip would otherwise add up
+  auto fetch_meta = [&](int it0, int (&row)[U], unsigned (&member)[U], int& krow) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      // MFMA: a wavefront owns 32 consecutive list positions, pass u covers GPW of them
+      const int it = kMfma ? it0 + wave * 32 + u * GPW + (grp % GPW) : it0 + u * RPP + grp;
+      row[u] = it < end ? row_of(it) : -1;
+      member[u] = (it < end && row[u] >= 0) ? (mask_of(it) & head_bits) : 0u;
+      if (member[u] == 0u) row[u] = -1;                     // nobody wants it: not loaded
+    }
+    krow = -1;
+    if constexpr (kMfma) {                                  // the K row this lane holds as MFMA A operand
+      const int itk = it0 + wave * 32 + (lane & 31);
+      krow = itk < end ? row_of(itk) : -1;
+      if (krow >= 0 && (mask_of(itk) & head_bits) == 0u) krow = -1;
+    }
+  };
+  int row[U], krow;
+  unsigned member[U];
+  if (begin < end) fetch_meta(begin, row, member, krow);
+
+  for (int it0 = begin; it0 < end; it0 += RPP * U) {      // uniform trip count over the workgroup
+    u32x4 vraw[U];
+    int row_n[U], krow_n = -1;
+    unsigned member_n[U];
+    if constexpr (kMfma) {
+      // K rows of the wavefront's block as the A operand: lane (r, h) holds elements 16 ks + 8 h .. + 7 of row r
+      const int r = lane & 31, h = lane >> 5;
+      bf16x8 kf[D / 16];
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        if (krow >= 0) raw = *reinterpret_cast<const u32x4*>(krows + (long long)krow * row_stride + ks * 16 + h * 8);
+        kf[ks] = __builtin_bit_cast(bf16x8, raw);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        vraw[u] = u32x4{0u, 0u, 0u, 0u};
+        if (row[u] >= 0) vraw[u] = *reinterpret_cast<const u32x4*>(vbase + (long long)row[u] * row_stride);
+      }
+      if (it0 + RPP * U < end) fetch_meta(it0 + RPP * U, row_n, member_n, krow_n);
+      f32x16 sacc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
+      // accumulator register i of lane (n, h): row 8 (i / 4) + 4 h + i % 4 of the block, head n
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the previous trip's reads of the tile are done
+      if (r < 8) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sS[wave][8 * (i >> 2) + 4 * h + (i & 3)][r] = sacc[i];
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // same wavefront: LDS operations complete in order
+#pragma unroll
+      for (int half = 0; half < U / kUnroll; ++half) {
+        float s[GT][kUnroll];
+        u32x4 vpart[kUnroll];
+        unsigned mpart[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          const int uu = half * kUnroll + u;
+          const float* srow = sS[wave][uu * GPW + (grp % GPW)];
+          const f32x4 lo = *reinterpret_cast<const f32x4*>(srow), hi = *reinterpret_cast<const f32x4*>(srow + 4);
+#pragma unroll
+          for (int hh = 0; hh < GT; ++hh) s[hh][u] = hh < 4 ? lo[hh] : hi[hh - 4];
+          vpart[u] = vraw[uu];
+          mpart[u] = member[uu];
+        }
+        consume(s, vpart, mpart);
+      }
+    } else {
+      u32x4 kraw[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        kraw[u] = u32x4{0u, 0u, 0u, 0u};
+        vraw[u] = u32x4{0u, 0u, 0u, 0u};
+        if (row[u] >= 0) {
+          const long long off = (long long)row[u] * row_stride;
+          kraw[u] = *reinterpret_cast<const u32x4*>(kbase + off);
+          vraw[u] = *reinterpret_cast<const u32x4*>(vbase + off);
+        }
+      }
+      if (it0 + RPP * U < end) fetch_meta(it0 + RPP * U, row_n, member_n, krow_n);
+      float s[GT][kUnroll];
+#pragma unroll
+      for (int h = 0; h < GT; ++h) {
+        if (!((head_bits >> h) & 1u)) continue;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) s[h][u] = row_group_sum<LPR>(chunk_dot(qraw[h], kraw[u], (const T*)nullptr));
+      }
+      consume(s, vraw, member);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      row[u] = row_n[u];
+      member[u] = member_n[u];
+    }
+    krow = krow_n;
   }
 
   if (begin >= end) {                       // empty slice: mark it, the combine pass skips its output row
@@ -450,7 +549,9 @@ Slices decode_slices(const omni_decode_desc* d, bool slim) {
   const int G = d->n_q_heads / d->n_kv_heads;
   const int units = d->batch * d->n_kv_heads * (G / group_tile(G));
   const long long shared_rows = slim ? (long long)d->cache_capacity - (d->vis_end - d->vis_begin) : d->cache_capacity;
-  s.n_shared = slices_for(shared_rows, units, 2048);
+  // two workgroups per CU: with more, the merge of a workgroup's lane groups and the slice combine weigh more
+  // than the parallelism gains (plain decode at batch 1: 89 us with 1024 workgroups, 75 us with 512)
+  s.n_shared = slices_for(shared_rows, units, 512);
   // only the active heads (typically a quarter) have rows to read, so aim higher
   s.n_head = slim ? slices_for(d->vis_end - d->vis_begin, d->batch * d->n_q_heads, 8192) : 0;
   return s;
@@ -544,6 +645,10 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
   const Slices s = decode_slices(d, probe != nullptr);
   p.n_shared = s.n_shared;
   p.n_head = s.n_head;
+  if (grp_mask) {            // group lists: one workgroup serves all heads of a group, so fewer, longer slices do
+    const int units = p.B * p.Hkv * (p.G / group_tile(p.G));
+    p.n_head = std::min(s.n_head, slices_for(d->vis_end - d->vis_begin, units, 512));
+  }
   p.scale = d->softmax_scale;
   p.tau = d->tau;
   for (int k = 0; k < 3; ++k) p.ks[k] = d->kv_stride[k];
