@@ -15,11 +15,12 @@
 //    what turns fewer rows per head into fewer bytes from HBM, since the plain decode already
 //    shares every row between the heads of a group.
 //
-// A cache row is read by D*sizeof(T)/16 lanes with one 16-byte load each for K and for V; a lane
-// group has kUnroll rows in flight per iteration.  bf16 dot products use the packed dot
-// instruction on the raw 16-byte chunks (products of bf16 pairs are exact in fp32).  Every lane
-// group keeps an online-softmax state per head; groups, then slices, are merged with the usual
-// (max, sum, weighted output) rule in a fixed order, so results are bitwise reproducible.
+// A cache row is read by D*sizeof(T)/16 lanes (a lane group) with one 16-byte load for V, and for K
+// too where the lane group forms the row's dot products itself (fp32 inputs; one head per workgroup).
+// bf16 with several heads per workgroup: the scores of 32 rows x all heads are one chain of MFMAs per
+// wavefront, with the K rows loaded in fragment layout.  Every lane group keeps an online-softmax
+// state per head; groups, then slices, are merged with the usual (max, sum, weighted output) rule in
+// a fixed order, so results are bitwise reproducible.
 #include "common.h"
 #include "kernels.h"
 
