@@ -544,9 +544,10 @@ def cpu_baseline(cfg, layer, q_lists, kv_lists, total_pairs, gpu_ms):
     """The oracle as it stands, timed on a bounded sample of the same step and scaled to the full step."""
     from oracle import omni_oracle as oc      # the only place the benchmark touches the oracle
     Q, K, V = layer["Q"], layer["K"], layer["V"]
-    heads = [0, 1, 2, 3]
+    G = cfg.n_q_heads // cfg.n_kv_heads
+    heads = list(range(2 * G))                      # two whole KV groups
     t0 = time.perf_counter()
-    Qs, Ks = Q[:, heads], K[:, :1]
+    Qs, Ks = Q[:, heads], K[:, :2]
     pk = oc.probe_keys(Ks, cfg.vis_begin, cfg.vis_end, cfg.sink_index)
     sc = oc.score_queries(Qs, pk, cfg.scale).astype(np.float32)
     oc.select_queries(sc, 0, TAU, cfg.vis_begin, cfg.vis_end)
@@ -554,16 +555,18 @@ def cpu_baseline(cfg, layer, q_lists, kv_lists, total_pairs, gpu_ms):
     r = oc.kv_budget(a, RECALL_P, 0)
     oc.select_kv(a, r["budget"])
     t_sel = time.perf_counter() - t0
-    # attention on a sample of head 1's kept queries with the realised selection
-    h = 1
-    sample_q = q_lists[h][:: max(1, q_lists[h].size // 8192)][:8192]
+    # attention on samples of the kept queries of heads 1..4 with the realised selection
+    att_heads = [1, 2, 3, 4]
+    empty = np.zeros(0, dtype=np.int32)
+    samples = {h: q_lists[h][:: max(1, q_lists[h].size // 8192)][:8192] for h in att_heads}
     t0 = time.perf_counter()
-    q_arg = [[np.zeros(0, dtype=np.int32)] * h + [sample_q]]
-    kv_arg = [[np.zeros(0, dtype=np.int32)] * h + [kv_lists[h]]]
-    oc.sparse_attn_fwd(Q[:, : h + 1], K[:, :1], V[:, :1], q_arg, kv_arg, cfg.causal, cfg.scale)
+    q_arg = [[samples.get(h, empty) for h in range(G)]]
+    kv_arg = [[kv_lists[h] if h in samples else empty for h in range(G)]]
+    oc.sparse_attn_fwd(Q[:, :G], K[:, :1], V[:, :1], q_arg, kv_arg, cfg.causal, cfg.scale)
     t_att = time.perf_counter() - t0
-    sample_pairs = int(np.searchsorted(kv_lists[h], sample_q, side="right").sum()) if cfg.causal \
-        else sample_q.size * kv_lists[h].size
+    sample_pairs = sum(int(np.searchsorted(kv_lists[h], samples[h], side="right").sum()) if cfg.causal
+                       else samples[h].size * kv_lists[h].size for h in att_heads)
+    sample_q_total = sum(s.size for s in samples.values())
     est_ms = (t_sel * cfg.n_q_heads / len(heads) + t_att * total_pairs / max(1, sample_pairs)) * 1e3
     try:
         from threadpoolctl import threadpool_info
@@ -571,8 +574,8 @@ def cpu_baseline(cfg, layer, q_lists, kv_lists, total_pairs, gpu_ms):
     except Exception:
         cores = os.cpu_count()
     return {"value": round(est_ms, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
-            "sample": f"selection pipeline on query heads {heads} ({t_sel:.1f}s, scaled x{cfg.n_q_heads // len(heads)}) + "
-                      f"sparse attention of {sample_q.size} kept queries of head {h} against its selected keys "
+            "sample": f"selection pipeline on query heads 0..{len(heads) - 1} ({t_sel:.1f}s, scaled x{cfg.n_q_heads / len(heads):g}) + "
+                      f"sparse attention of {sample_q_total} kept queries of heads {att_heads} against their selected keys "
                       f"({t_att:.1f}s, {sample_pairs} of {total_pairs} pairs, scaled by pairs)",
             "gpu_speedup": round(est_ms / gpu_ms, 1)}
 
