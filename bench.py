@@ -555,8 +555,8 @@ def cpu_baseline(cfg, layer, q_lists, kv_lists, total_pairs, gpu_ms):
     r = oc.kv_budget(a, RECALL_P, 0)
     oc.select_kv(a, r["budget"])
     t_sel = time.perf_counter() - t0
-    # attention on samples of the kept queries of heads 1..4 with the realised selection
-    att_heads = [1, 2, 3, 4]
+    # attention on samples of the kept queries of heads 1..6 with the realised selection
+    att_heads = [1, 2, 3, 4, 5, 6]
     empty = np.zeros(0, dtype=np.int32)
     samples = {h: q_lists[h][:: max(1, q_lists[h].size // 8192)][:8192] for h in att_heads}
     t0 = time.perf_counter()
