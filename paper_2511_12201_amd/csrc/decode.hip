@@ -317,13 +317,12 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
   }
 }
 
-// Shared rows of one KV group, GT heads per workgroup.  grid = (n_shared, B * Hkv * (G / GT)).
+// Shared rows of one KV group, GT heads per workgroup: slice `slice` of unit `unit` in [0, B * Hkv * (G / GT)).
 template <typename T, int D, int GT>
-__global__ __launch_bounds__(kThreads) void decode_shared_kernel(DecodeParams p) {
+__device__ __forceinline__ void decode_shared_rows(const DecodeParams& p, int slice, int unit) {
   constexpr int RPP = kThreads / (D / Elem<T>::kPer16B);
-  const int slice = blockIdx.x;
   const int chunks = p.G / GT;
-  const int unit = blockIdx.y, chunk = unit % chunks, bg = unit / chunks;
+  const int chunk = unit % chunks, bg = unit / chunks;
   const int b = bg / p.Hkv, g = bg % p.Hkv;
   const int ctx = min(p.ctx_len[b], p.cap);
   const int n_lo = p.probe ? min(p.v0, ctx) : ctx;       // rows below the visual segment (all rows if plain)
@@ -339,12 +338,11 @@ __global__ __launch_bounds__(kThreads) void decode_shared_kernel(DecodeParams p)
                         static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1], p.ks[2]);
 }
 
-// A head's own (stored visual) rows.  grid = (n_head, B * Hq).  Also classifies the decoding query.
+// A head's own (stored visual) rows: slice `slice` of head bh.  Also classifies the decoding query.
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void decode_head_kernel(DecodeParams p) {
+__device__ __forceinline__ void decode_head_rows(const DecodeParams& p, int slice, int bh) {
   constexpr int RPP = kThreads / (D / Elem<T>::kPer16B);
   __shared__ int sActive;
-  const int slice = blockIdx.x, bh = blockIdx.y;
   const int b = bh / p.Hq, i = bh % p.Hq, g = i / p.G;
   if (threadIdx.x < 64) {
     const T* qptr = static_cast<const T*>(p.q) + (long long)bh * D;
@@ -376,15 +374,14 @@ __global__ __launch_bounds__(kThreads) void decode_head_kernel(DecodeParams p) {
                        static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1], p.ks[2]);
 }
 
-// The union list of a KV group, GT heads per workgroup.  grid = (n_head, B * Hkv * (G / GT)).  Classifies the
+// The union list of a KV group, GT heads per workgroup: slice `slice` of unit `unit`.  Classifies the
 // decoding queries of its heads first: only active heads take part.
 template <typename T, int D, int GT>
-__global__ __launch_bounds__(kThreads) void decode_group_kernel(DecodeParams p) {
+__device__ __forceinline__ void decode_group_rows(const DecodeParams& p, int slice, int unit) {
   constexpr int RPP = kThreads / (D / Elem<T>::kPer16B);
   __shared__ unsigned sBits;
-  const int slice = blockIdx.x;
   const int chunks = p.G / GT;
-  const int unit = blockIdx.y, chunk = unit % chunks, bg = unit / chunks;
+  const int chunk = unit % chunks, bg = unit / chunks;
   const int b = bg / p.Hkv, g = bg % p.Hkv;
   const int head0 = g * p.G + chunk * GT;
   if (threadIdx.x == 0) sBits = 0u;
@@ -497,13 +494,43 @@ int group_tile(int G) {
   return 1;
 }
 
+// One launch for the row streams of a step that share a register footprint.  GROUP: the group lists, then the
+// shared rows -- the list workgroups come first in the grid (they are the long ones) and the few shared
+// (non-visual) rows of a slimmed step fill in behind them instead of costing a launch of their own (11 us at
+// batch 1).  Otherwise the shared rows only (plain decode; per-head lists, whose one-head workgroups need half
+// the registers and lose their occupancy inside a common kernel: 70 -> 84 us when fused).
+template <typename T, int D, int GT, bool GROUP>
+__global__ __launch_bounds__(kThreads) void decode_rows_kernel(DecodeParams p) {
+  const int units_s = p.B * p.Hkv * (p.G / GT);
+  const int n_list = GROUP ? p.n_head * units_s : 0;
+  const int i = blockIdx.x;
+  if constexpr (GROUP) {
+    if (i < n_list) {
+      decode_group_rows<T, D, GT>(p, i % p.n_head, i / p.n_head);
+      return;
+    }
+  }
+  const int j = i - n_list;
+  decode_shared_rows<T, D, GT>(p, j % p.n_shared, j / p.n_shared);
+}
+
+// grid = (n_head, B * Hq)
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void decode_head_kernel(DecodeParams p) {
+  decode_head_rows<T, D>(p, blockIdx.x, blockIdx.y);
+}
+
 template <typename T, int D, int GT>
-void launch_shared(const DecodeParams& p, hipStream_t st) {
-  hipLaunchKernelGGL((decode_shared_kernel<T, D, GT>), dim3(p.n_shared, p.B * p.Hkv * (p.G / GT)), dim3(kThreads), 0,
-                     st, p);
-  if (p.grp_mask && p.n_head > 0)
-    hipLaunchKernelGGL((decode_group_kernel<T, D, GT>), dim3(p.n_head, p.B * p.Hkv * (p.G / GT)), dim3(kThreads), 0,
-                       st, p);
+void launch_rows(const DecodeParams& p, hipStream_t st) {
+  const int units_s = p.B * p.Hkv * (p.G / GT);
+  const int n_shared = p.n_shared * units_s;
+  if (p.n_head > 0 && p.grp_mask) {
+    hipLaunchKernelGGL((decode_rows_kernel<T, D, GT, true>), dim3(n_shared + p.n_head * units_s), dim3(kThreads), 0, st, p);
+    return;
+  }
+  if (p.n_head > 0)      // per-head lists: the long kernel first
+    hipLaunchKernelGGL((decode_head_kernel<T, D>), dim3(p.n_head, p.B * p.Hq), dim3(kThreads), 0, st, p);
+  hipLaunchKernelGGL((decode_rows_kernel<T, D, GT, false>), dim3(n_shared), dim3(kThreads), 0, st, p);
 }
 
 template <typename T, int D>
@@ -511,17 +538,13 @@ int launch_decode(const DecodeParams& p, hipStream_t st) {
   {
     ProfScope prof__(kProfDecode, st);
     switch (group_tile(p.G)) {
-      case 8: launch_shared<T, D, 8>(p, st); break;
-      case 7: launch_shared<T, D, 7>(p, st); break;
-      case 4: launch_shared<T, D, 4>(p, st); break;
-      case 2: launch_shared<T, D, 2>(p, st); break;
-      default: launch_shared<T, D, 1>(p, st); break;
+      case 8: launch_rows<T, D, 8>(p, st); break;
+      case 7: launch_rows<T, D, 7>(p, st); break;
+      case 4: launch_rows<T, D, 4>(p, st); break;
+      case 2: launch_rows<T, D, 2>(p, st); break;
+      default: launch_rows<T, D, 1>(p, st); break;
     }
     OMNI_LAUNCH_CHECK();
-    if (!p.grp_mask && p.n_head > 0) {
-      hipLaunchKernelGGL((decode_head_kernel<T, D>), dim3(p.n_head, p.B * p.Hq), dim3(kThreads), 0, st, p);
-      OMNI_LAUNCH_CHECK();
-    }
     hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(p.B * p.Hq), dim3(kCombineThreads), 0, st, p);
     OMNI_LAUNCH_CHECK();
   }
