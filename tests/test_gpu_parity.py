@@ -655,3 +655,52 @@ def test_prefill_step_replays_from_a_hip_graph():
         b = int(eager_sel.budget.budget[0])
         assert torch.equal(sel.kv_idx[..., :b], eager_sel.kv_idx[..., :b])
         assert torch.isfinite(scratch)
+
+
+# ------------------------------------------------------------------ batch > 1
+
+CFG_B2 = synth.C2_16K.scaled(name="bf16_batch2", batch=2, frames=4, tok_per_frame=252, n_text=70, n_q_heads=8, n_kv_heads=2,
+                             seed=23)
+
+
+@pytest.mark.parametrize("budget_mode", [0, 2])
+def test_two_sequences_in_a_batch_have_their_own_sets_budgets_and_gradients(budget_mode):
+    cfg = CFG_B2
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    per_head = budget_mode == 2
+    want_bud = oc.kv_budget(c.o_a32, c.recall_p, budget_mode)
+    assert not np.array_equal(want_bud["budget"][0], want_bud["budget"][1])      # the two sequences really differ
+    kv_lists = oc.select_kv(c.o_a32, want_bud["budget"])
+    kv_lists = [list(x) for x in kv_lists]
+    # selection, teacher-forced on the oracle's score arrays: exact
+    a = torch.from_numpy(c.o_a32).cuda()
+    r = ob.omni_budget_from_scores(c.desc, a, c.recall_p, budget_mode)
+    np.testing.assert_array_equal(to_host(r.budget), want_bud["budget"])
+    kv_idx = ob.omni_select_kv(c.desc, a, r.budget, N, _per_head=per_head)
+    got = to_host(kv_idx)
+    for b in range(2):
+        for h in range(H):
+            np.testing.assert_array_equal(got[b, h, : len(kv_lists[b][h])], kv_lists[b][h])
+    sc = torch.from_numpy(c.o_scores32).cuda()
+    q_idx, q_cnt = ob.omni_select_queries(c.desc, sc, c.q_mode, c.q_param)
+    for b, (x, y) in enumerate(zip(padded_to_lists(q_idx, q_cnt), c.o_qidx)):
+        for h in range(H):
+            np.testing.assert_array_equal(x[h], y[h], err_msg=f"batch {b} head {h}")
+    # attention and gradients on those sets (dO halved: the sink key collects the gradient of every query of its
+    # group, and the bf16 bar is an absolute one)
+    dO_np = synth.round_to_bf16(0.5 * synth.make_grad_output(cfg))
+    dO = to_device(dO_np, cfg.dtype)
+    O, lse = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, r.budget, N, _per_head=per_head)
+    grads = ob.omni_sparse_attn_bwd(c.desc, c.dQ, c.dK, c.dV, O, dO, lse, q_idx, q_cnt, kv_idx, r.budget, N,
+                                    _per_head=per_head)
+    torch.cuda.synchronize()
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+    _check_fwd(c, to_host(O), to_host(lse), Oo, Lo)
+    want = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO_np, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+    _check_grads(cfg, grads, want, c.o_qidx, kv_lists)
+    # free-running fused selection: same budgets up to the probe's numeric error, on both sequences
+    f = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, budget_mode)
+    torch.cuda.synchronize()
+    bg = to_host(f.budget.budget).astype(np.int64)
+    assert np.all(np.abs(bg - want_bud["budget"]) <= np.maximum(2, (2e-3 * want_bud["budget"]).astype(np.int64)))
