@@ -704,3 +704,36 @@ def test_two_sequences_in_a_batch_have_their_own_sets_budgets_and_gradients(budg
     torch.cuda.synchronize()
     bg = to_host(f.budget.budget).astype(np.int64)
     assert np.all(np.abs(bg - want_bud["budget"]) <= np.maximum(2, (2e-3 * want_bud["budget"]).astype(np.int64)))
+
+
+# ------------------------------------------------------------------ strides
+
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
+def test_token_major_memory_layout_gives_the_same_bits(cfg):
+    """Q, K, V as a projection leaves them in memory ([batch, token, head, dim], viewed as [batch, head, token, dim]):
+    every call reads and writes through the descriptor's strides and reproduces the head-major results bit for bit."""
+    c = case_for(cfg)
+    N = cfg.n_tokens
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Q2, K2, V2 = tm(c.dQ), tm(c.dK), tm(c.dV)
+    assert Q2.stride(1) == cfg.head_dim and Q2.stride(2) == cfg.n_q_heads * cfg.head_dim
+    desc2 = ob.make_layer_desc(Q2, K2, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    dO = to_device(synth.make_grad_output(cfg), cfg.dtype)
+    dO2 = tm(dO)
+
+    def run(desc, Q, K, V, g):
+        sel = ob.omni_prefill_select(desc, Q, K, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0)
+        O, lse = ob.omni_sparse_attn_fwd(desc, Q, K, V, sel.q_idx, sel.q_cnt, sel.kv_idx, sel.budget.budget, N)
+        grads = ob.omni_sparse_attn_bwd(desc, Q, K, V, O, g, lse, sel.q_idx, sel.q_cnt, sel.kv_idx, sel.budget.budget, N)
+        Od, _ = ob.omni_dense_attn_fwd(desc, Q, K, V)
+        torch.cuda.synchronize()
+        return sel, O, lse, grads, Od
+
+    s1, O1, l1, g1, d1 = run(c.desc, c.dQ, c.dK, c.dV, dO)
+    s2, O2, l2, g2, d2 = run(desc2, Q2, K2, V2, dO2)
+    assert O2.stride() == Q2.stride() and g2[1].stride() == K2.stride()          # outputs laid out like their inputs
+    assert torch.equal(s1.scores, s2.scores) and torch.equal(s1.budget.key_scores, s2.budget.key_scores)
+    assert torch.equal(s1.q_cnt, s2.q_cnt) and torch.equal(s1.budget.budget, s2.budget.budget)
+    assert torch.equal(O1, O2) and torch.equal(l1, l2) and torch.equal(d1, d2)
+    for x, y in zip(g1, g2):
+        assert torch.equal(x, y)
