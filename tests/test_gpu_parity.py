@@ -737,3 +737,62 @@ def test_token_major_memory_layout_gives_the_same_bits(cfg):
     assert torch.equal(O1, O2) and torch.equal(l1, l2) and torch.equal(d1, d2)
     for x, y in zip(g1, g2):
         assert torch.equal(x, y)
+
+
+# ------------------------------------------------------------------ visual tokens in the middle of the sequence
+
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
+def test_visual_range_between_two_text_segments_and_a_sink_that_is_not_token_0(cfg):
+    """[system text][visual tokens][question]: the visual range, the sink and the rows a decode step always reads
+    are descriptor arguments; the oracle is called with the same ones."""
+    c, q, Kc, Vc, ctx, _, _ = _decode_case(cfg, 2)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    v0, v1, sink = 69, N - 131, 2
+    desc = ob.make_layer_desc(c.dQ, c.dK, v0, v1, sink, cfg.causal)
+    o_probe = oc.probe_keys(c.K, v0, v1, sink)
+    o_scores = oc.score_queries(c.Q, o_probe, cfg.scale)
+    probe, scores = ob.omni_score_queries(desc, c.dQ, c.dK)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_host(probe), o_probe, rtol=0, atol=2e-5)
+    np.testing.assert_allclose(to_host(scores), o_scores, rtol=0, atol=2e-5)
+    s32 = o_scores.astype(np.float32)
+    for mode, param in ((0, 0.08), (1, 0.3)):
+        want = oc.select_queries(s32, mode, param, v0, v1)
+        q_idx, q_cnt = ob.omni_select_queries(desc, torch.from_numpy(s32).cuda(), mode, param)
+        got = padded_to_lists(q_idx, q_cnt)
+        for h in range(H):
+            np.testing.assert_array_equal(got[0][h], want[0][h], err_msg=f"mode {mode} head {h}")
+            assert np.all(np.isin(np.arange(0, v0), got[0][h])) and np.all(np.isin(np.arange(v1, N), got[0][h]))
+    # decode: stored visual rows are the selected keys inside [v0, v1); rows below v0 and from v1 on are always read
+    batch = 2
+    b = len(c.o_kvidx[0][0])
+    vis = oc.visual_subset([list(c.o_kvidx[0])] * batch, v0, v1)
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])] * batch, H, b)
+    budget = torch.full((batch,), b, dtype=torch.int32, device="cuda")
+    ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                               v0, v1, sink, cfg.causal)
+    vis_idx, vis_cnt = ob.omni_visual_subset(ldesc, kv_idx, budget, b)
+    for bb in range(batch):
+        for h in range(H):
+            np.testing.assert_array_equal(padded_to_lists(vis_idx, vis_cnt)[bb][h], vis[bb][h])
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset(ldesc, kv_idx, budget, b)
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    dctx = torch.from_numpy(ctx).cuda()
+    probe_b = np.repeat(o_probe, batch, axis=0).astype(np.float32)
+    dprobe = torch.from_numpy(probe_b).cuda()
+    tau = 0.08
+    ddesc = ob.make_decode_desc(dq, dKc, v0, v1, tau)
+    Oo, acto, sc = oc.slim_decode(q, Kc, Vc, ctx, probe_b, vis, tau, v0, v1, cfg.scale)
+    clear = np.abs(sc - tau) > 1e-5
+    Kcomp, Vcomp = ob.omni_compact_cache(ddesc, dKc, dVc, grp_idx, grp_cnt)
+    outs = {
+        "per-head": ob.omni_slim_decode(ddesc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b),
+        "grouped": ob.omni_slim_decode_grouped(ddesc, dq, dKc, dVc, dctx, dprobe, grp_idx, grp_mask, grp_cnt),
+        "compact": ob.omni_slim_decode_compact(ddesc, dq, dKc, dVc, dctx, dprobe, Kcomp, Vcomp, grp_idx, grp_mask, grp_cnt),
+    }
+    torch.cuda.synchronize()
+    for name, (O, act) in outs.items():
+        act = to_host(act)
+        np.testing.assert_array_equal(act[clear], acto[clear], err_msg=name)
+        same = act == acto
+        assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype], name
