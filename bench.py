@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3_64k", choices=["c3_64k", "c2_16k"])
     ap.add_argument("--no-extras", action="store_true", help="skip dense baseline / oracle timing")
+    ap.add_argument("--only", choices=["train", "decode"],
+                    help="run just the training-step or the decode extra and print its JSON (for profiling; the "
+                         "headline line is the default run)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known HBM traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -76,6 +79,10 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(1)
     ob.load_library()
+    if args.only:
+        fn = bench_train if args.only == "train" else (lambda *a: bench_decode(*a, batches=(1, 8)))
+        print(json.dumps({args.only: fn(torch, ob, synth)}), flush=True)
+        return
     cfg = synth.C3_64K if args.workload == "c3_64k" else synth.C2_16K
     N, Hq, D = cfg.n_tokens, cfg.n_q_heads, cfg.head_dim
 
