@@ -796,3 +796,44 @@ def test_visual_range_between_two_text_segments_and_a_sink_that_is_not_token_0(c
         np.testing.assert_array_equal(act[clear], acto[clear], err_msg=name)
         same = act == acto
         assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype], name
+
+
+# ------------------------------------------------------------------ decode: every head-group tiling
+
+@pytest.mark.parametrize("G,hkv,d", [(7, 2, 128), (8, 1, 128), (6, 2, 64), (3, 2, 128), (5, 1, 64), (16, 1, 128)])
+def test_decode_with_other_group_sizes(G, hkv, d):
+    """Heads per KV group decide how many heads a workgroup serves at once (8, 7, 4, 2 or 1) and whether the scores
+    come from the matrix cores: all three decode calls and the plain one on each tiling."""
+    cfg = synth.C2_16K.scaled(name=f"dec_g{G}", frames=3, tok_per_frame=211, n_text=45, n_q_heads=G * hkv, n_kv_heads=hkv,
+                              head_dim=d, seed=60 + G)
+    batch = 2
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    tau = 0.08
+    H = cfg.n_q_heads
+    b = len(c.o_kvidx[0][0])
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])] * batch, H, b)
+    budget = torch.full((batch,), b, dtype=torch.int32, device="cuda")
+    ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                               cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    vis_idx, vis_cnt = ob.omni_visual_subset(ldesc, kv_idx, budget, b)
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset(ldesc, kv_idx, budget, b)
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    dctx = torch.from_numpy(ctx).cuda()
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    desc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau)
+    Kcomp, Vcomp = ob.omni_compact_cache(desc, dKc, dVc, grp_idx, grp_cnt)
+    outs = {
+        "per-head": ob.omni_slim_decode(desc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b),
+        "grouped": ob.omni_slim_decode_grouped(desc, dq, dKc, dVc, dctx, dprobe, grp_idx, grp_mask, grp_cnt),
+        "compact": ob.omni_slim_decode_compact(desc, dq, dKc, dVc, dctx, dprobe, Kcomp, Vcomp, grp_idx, grp_mask, grp_cnt),
+    }
+    Od = ob.omni_dense_decode(desc, dq, dKc, dVc, dctx)
+    torch.cuda.synchronize()
+    Oo, acto, sc = oc.slim_decode(q, Kc, Vc, ctx, probe.astype(np.float32), vis, tau, cfg.vis_begin, cfg.vis_end, cfg.scale)
+    clear = np.abs(sc - tau) > 1e-5
+    for name, (O, act) in outs.items():
+        act = to_host(act)
+        np.testing.assert_array_equal(act[clear], acto[clear], err_msg=name)
+        same = act == acto
+        assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype], name
+    assert np.max(np.abs(to_host(Od) - oc.dense_decode(q, Kc, Vc, ctx, cfg.scale))) <= TOL_OUT[cfg.dtype]

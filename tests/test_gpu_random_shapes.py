@@ -1,0 +1,66 @@
+"""GPU parity on a spread of seeded shapes: odd token counts, head counts and group sizes, both head dims and
+dtypes, several probe blocks -- the whole prefill path against the oracle on each."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import omni_oracle as oc
+from paper_2511_12201_amd import binding as ob
+from paper_2511_12201_amd import synth
+from tests.helpers import lists_to_padded, padded_to_lists, to_device, to_host
+from tests.test_gpu_parity import TOL_OUT, Case, _check_fwd, _check_grads
+
+pytestmark = pytest.mark.gpu
+
+
+def _shapes():
+    rng = np.random.default_rng(2024)
+    out = []
+    for k in range(10):
+        hkv = int(rng.choice([1, 2, 3, 4]))
+        g = int(rng.choice([1, 2, 4, 7, 8]))
+        out.append(synth.C2_16K.scaled(
+            name=f"rand{k}", frames=int(rng.integers(2, 9)), tok_per_frame=int(rng.integers(60, 300)),
+            n_text=int(rng.integers(1, 200)), n_q_heads=hkv * g, n_kv_heads=hkv,
+            head_dim=int(rng.choice([64, 128])), dtype=str(rng.choice(["bf16", "f32"])),
+            structured=bool(rng.integers(0, 2)), seed=100 + k))
+    return out
+
+
+@pytest.mark.parametrize("cfg", _shapes(), ids=lambda c: f"{c.name}-N{c.n_tokens}-H{c.n_q_heads}x{c.n_kv_heads}-d{c.head_dim}-{c.dtype}")
+def test_prefill_path_on_a_seeded_random_shape(cfg):
+    pb = [32, 64, 100, 256][cfg.seed % 4]
+    c = Case.get(cfg, probe_block=pb) if cfg.structured else Case.get(cfg, q_mode=1, q_param=0.3, probe_block=pb)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    # scores and key scores against the oracle
+    probe, scores = ob.omni_score_queries(c.desc, c.dQ, c.dK)
+    np.testing.assert_allclose(to_host(scores), c.o_scores, rtol=0, atol=2e-5)
+    for mode in (0, 2):
+        want = oc.kv_budget(c.o_a32, c.recall_p, mode)
+        r = ob.omni_kv_budget(c.desc, c.dQ, c.dK, c.recall_p, pb, mode)
+        torch.cuda.synchronize()
+        a = to_host(r.key_scores).astype(np.float64)
+        assert np.max(np.abs(a - c.o_a)) <= 1e-4 * c.o_a.max()
+        # selection on the oracle's scores: exact
+        a32 = torch.from_numpy(c.o_a32).cuda()
+        rb = ob.omni_budget_from_scores(c.desc, a32, c.recall_p, mode)
+        np.testing.assert_array_equal(to_host(rb.budget), want["budget"])
+        kv_lists = [list(x) for x in oc.select_kv(c.o_a32, want["budget"])]
+        kv_idx = ob.omni_select_kv(c.desc, a32, rb.budget, N, _per_head=mode == 2)
+        got = to_host(kv_idx)
+        for h in range(H):
+            np.testing.assert_array_equal(got[0, h, : len(kv_lists[0][h])], kv_lists[0][h])
+        # attention and gradients on the oracle's sets
+        q_idx, q_cnt = lists_to_padded(c.o_qidx, H, N)
+        dO_np = synth.make_grad_output(cfg)
+        if cfg.dtype == "bf16":
+            dO_np = synth.round_to_bf16(0.5 * dO_np)
+        dO = to_device(dO_np, cfg.dtype)
+        O, lse = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, rb.budget, N, _per_head=mode == 2)
+        grads = ob.omni_sparse_attn_bwd(c.desc, c.dQ, c.dK, c.dV, O, dO, lse, q_idx, q_cnt, kv_idx, rb.budget, N,
+                                        _per_head=mode == 2)
+        torch.cuda.synchronize()
+        Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+        _check_fwd(c, to_host(O), to_host(lse), Oo, Lo)
+        wantg = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO_np, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+        _check_grads(cfg, grads, wantg, c.o_qidx, kv_lists)
