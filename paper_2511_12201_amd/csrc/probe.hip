@@ -57,23 +57,33 @@ __global__ __launch_bounds__(kThreads) void pool_queries_kernel(const T* __restr
 #pragma unroll
     for (int e = 0; e < E; ++e) diff[e] = pk[D + c * E + e] - pk[c * E + e];
     float* out = scores + (long long)bh * L.N;
-    for (int rb = row_begin; rb < row_end; rb += RPP) {    // uniform trip count: shuffles need every lane
-      const int r = rb + r0;
-      const bool live = r < row_end;
-      float dot = 0.f;
-      if (live) {
-        u32x4 raw = *reinterpret_cast<const u32x4*>(base + (long long)r * L.qs[2] + c * E);
-        float v[E];
-        unpack16(raw, v, (const T*)nullptr);
+    constexpr int kRowsInFlight = 4;                       // loads of this many rows per lane group are issued together
+    for (int rb = row_begin; rb < row_end; rb += RPP * kRowsInFlight) {   // uniform trip count: shuffles need every lane
+      u32x4 raw[kRowsInFlight];
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-          acc[e] += v[e];
-          dot = fmaf(v[e], diff[e], dot);
-        }
+      for (int u = 0; u < kRowsInFlight; ++u) {
+        const int r = rb + u * RPP + r0;
+        raw[u] = u32x4{0u, 0u, 0u, 0u};
+        if (r < row_end) raw[u] = *reinterpret_cast<const u32x4*>(base + (long long)r * L.qs[2] + c * E);
       }
 #pragma unroll
-      for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
-      if (live && c == 0) out[r] = 1.0f / (1.0f + expf(-dot * L.scale));
+      for (int u = 0; u < kRowsInFlight; ++u) {            // rows in ascending order: the sums match the plain pooling pass
+        const int r = rb + u * RPP + r0;
+        const bool live = r < row_end;
+        float dot = 0.f;
+        if (live) {
+          float v[E];
+          unpack16(raw[u], v, (const T*)nullptr);
+#pragma unroll
+          for (int e = 0; e < E; ++e) {
+            acc[e] += v[e];
+            dot = fmaf(v[e], diff[e], dot);
+          }
+        }
+#pragma unroll
+        for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+        if (live && c == 0) out[r] = 1.0f / (1.0f + expf(-dot * L.scale));
+      }
     }
   } else {
     for (int r = row_begin + r0; r < row_end; r += RPP) {
