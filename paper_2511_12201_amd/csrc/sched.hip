@@ -59,22 +59,32 @@ __global__ __launch_bounds__(256) void sched_cost_kernel(const int* __restrict__
   reinterpret_cast<unsigned long long*>(sched + keys_off)[id] = sched_key(cost, id);
 }
 
-// thread per item id: its rank among the keys (all distinct) is its place in the hand-out order
+// kRankLanes threads per item id: its rank among the keys (all distinct) is its place in the hand-out order
+constexpr int kRankLanes = 4;
+constexpr int kRankItems = 256 / kRankLanes;                // items per workgroup
 __global__ __launch_bounds__(256) void sched_rank_kernel(int BH, size_t keys_off, size_t order_off, int* __restrict__ sched) {
-  __shared__ unsigned long long tile[256];
+  constexpr int kTile = 2048;                               // keys staged per pass: a 64k layer's list in one
+  __shared__ unsigned long long tile[kTile];
   const int n = sched[kSchedTotal];
-  const int id = blockIdx.x * blockDim.x + threadIdx.x;
+  const int id = blockIdx.x * kRankItems + threadIdx.x / kRankLanes, sub = threadIdx.x % kRankLanes;
   const unsigned long long* keys = reinterpret_cast<const unsigned long long*>(sched + keys_off);
   const unsigned long long mine = id < n ? keys[id] : 0ull;
   int rank = 0;
-  for (int j0 = 0; j0 < n; j0 += 256) {                     // uniform trip count: every thread helps to stage
+  for (int j0 = 0; j0 < n; j0 += kTile) {                   // uniform trip count: every thread helps to stage
     __syncthreads();
-    tile[threadIdx.x] = j0 + threadIdx.x < n ? keys[j0 + threadIdx.x] : 0ull;
+#pragma unroll
+    for (int u = 0; u < kTile / 256; ++u) {                 // independent loads: one memory latency per pass
+      const int j = j0 + u * 256 + (int)threadIdx.x;
+      tile[u * 256 + threadIdx.x] = j < n ? keys[j] : 0ull;
+    }
     __syncthreads();
-    const int m = min(256, n - j0);
-    for (int j = 0; j < m; ++j) rank += tile[j] > mine ? 1 : 0;
+    const int m = min(kTile, n - j0);
+#pragma unroll 16
+    for (int j = sub; j < m; j += kRankLanes) rank += tile[j] > mine ? 1 : 0;     // unrolled: LDS reads in flight together
   }
-  if (id < n) {
+#pragma unroll
+  for (int o = 1; o < kRankLanes; o <<= 1) rank += __shfl_xor(rank, o, 64);
+  if (id < n && sub == 0) {
     const ItemRef it = item_of(sched + kSchedPrefix, BH, id);
     sched[order_off + rank] = (int)(((unsigned)it.bh << 16) | (unsigned)it.tq);
   }
@@ -94,7 +104,8 @@ int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap,
   hipLaunchKernelGGL(sched_cost_kernel, dim3(blocks), dim3(256), 0, st, q_cnt, budget, qvis, L.bph, BH, L.Hq, L.N, b_cap, L.causal,
                      tile_m, keys_off, sched);
   OMNI_LAUNCH_CHECK();
-  hipLaunchKernelGGL(sched_rank_kernel, dim3(blocks), dim3(256), 0, st, BH, keys_off, order_off, sched);
+  hipLaunchKernelGGL(sched_rank_kernel, dim3((unsigned)cdiv(cap, (size_t)kRankItems)), dim3(256), 0, st, BH, keys_off, order_off,
+                     sched);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
 }
