@@ -461,15 +461,19 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(DecodeP
   const float Mr = sMax == -INFINITY ? 0.f : sMax;
   const int grp = threadIdx.x / LG, c = threadIdx.x % LG;
   float Ls = 0.f, O0 = 0.f, O1 = 0.f;
+  // every load of a trip is issued before any is used (a branch on the slice's maximum would put two memory
+  // latencies in sequence per slice); an empty slice, or one with nothing visible in it, may hold an unwritten
+  // output row, so it is dropped by selection, not by a zero weight
+#pragma unroll 4
   for (int s = grp; s < n; s += NG) {
     const float* row = src + s * (D + 2);
-    const float ms = row[D];
-    if (ms == -INFINITY) continue;                 // empty slice or nothing visible in it: its output row may be unwritten
-    const float w = exp2f(ms - Mr);
+    const float ms = row[D], ls = row[D + 1];
     const float2 o = *reinterpret_cast<const float2*>(row + 2 * c);
-    Ls = fmaf(row[D + 1], w, Ls);
-    O0 = fmaf(o.x, w, O0);
-    O1 = fmaf(o.y, w, O1);
+    const bool live = ms != -INFINITY;
+    const float w = fast_exp2(ms - Mr);
+    Ls = live ? fmaf(ls, w, Ls) : Ls;
+    O0 = live ? fmaf(o.x, w, O0) : O0;
+    O1 = live ? fmaf(o.y, w, O1) : O1;
   }
   if (c == 0) sL[grp] = Ls;
   sO[grp][2 * c] = O0;
