@@ -107,6 +107,31 @@ def test_argument_errors(lib):
     assert lib.omni_select_kv(C.byref(d), FAKE, FAKE, 0, FAKE, FAKE, 1 << 30, None) == -1
     assert lib.omni_sparse_attn_fwd(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 1 << 30, None) == -1
     assert lib.omni_sparse_attn_fwd(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 300, FAKE, FAKE, FAKE, 16, None) == -3
+    # the fused selection call, the per-head variants and the compacted decode store validate like their base calls
+    ps = lambda **kw: lib.omni_prefill_select(
+        C.byref(d), FAKE, FAKE, kw.get("q_mode", 0), kw.get("q_param", 0.08), kw.get("p", 0.95), kw.get("pb", 256),
+        kw.get("mode", 0), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, kw.get("kv", FAKE), kw.get("cap", 300),
+        FAKE, kw.get("ws", 1 << 30), None)
+    assert ps(mode=3) == -1 and "budget_mode" in ob.last_error()
+    assert ps(q_mode=2) == -1 and ps(q_mode=1, q_param=0.0) == -1 and ps(p=0.0) == -1 and ps(pb=0) == -1 and ps(cap=0) == -1
+    assert ps(kv=None) == -1 and "null" in ob.last_error()
+    assert ps(ws=64) == -3
+    assert ob.workspace_bytes(ob.CALL_PREFILL_SELECT, d, 256) >= ob.workspace_bytes(ob.CALL_KV_BUDGET, d, 256)
+    with pytest.raises(ob.OmniError):
+        ob.workspace_bytes(ob.CALL_PREFILL_SELECT, d, 0)
+    assert lib.omni_select_kv_per_head(C.byref(d), FAKE, FAKE, 0, FAKE, FAKE, 1 << 30, None) == -1
+    assert lib.omni_sparse_attn_fwd_per_head(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 300, FAKE, FAKE, FAKE,
+                                             1 << 30, None) == -1
+    assert lib.omni_group_subset_per_head(C.byref(d), FAKE, FAKE, 300, FAKE, FAKE, FAKE, 0, FAKE, 1 << 30, None) == -1
+    dd = ob.DecodeDesc()
+    dd.batch, dd.n_q_heads, dd.n_kv_heads, dd.head_dim, dd.cache_capacity = 2, 4, 2, 128, 1000
+    dd.vis_begin, dd.vis_end, dd.dtype, dd.softmax_scale, dd.tau = 0, 900, ob.OMNI_BF16, 0.088, 0.08
+    dd.kv_stride = (C.c_int64 * 3)(2 * 1000 * 128, 1000 * 128, 128)
+    assert lib.omni_compact_cache(C.byref(dd), FAKE, FAKE, FAKE, FAKE, 0, FAKE, FAKE, None) == -1
+    assert lib.omni_compact_cache(C.byref(dd), FAKE, FAKE, FAKE, FAKE, 64, None, FAKE, None) == -1
+    assert lib.omni_slim_decode_compact(C.byref(dd), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, FAKE,
+                                        FAKE, FAKE, 16, None) == -3
+    assert lib.omni_debug_key_split_len(0) == 0
     # a successful validation path clears the message
     assert ob.workspace_bytes(ob.CALL_SELECT_KV, d) > 0
     assert ob.last_error() == ""
