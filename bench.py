@@ -529,6 +529,7 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
         res["per_batch"][str(B)] = {
             "slim_us_per_token": round(ktime["slim"], 2), "dense_us_per_token": round(ktime["dense"], 2),
             "speedup": round(ktime["dense"] / ktime["slim"], 3),
+            "speedup_grouped": round(ktime["dense"] / ktime["slim_grouped"], 3),
             "slim_grouped_us_per_token": round(ktime["slim_grouped"], 2),
             "slim_compact_us_per_token": round(ktime["slim_compact"], 2),
             "compaction_us_once": round(compact_us, 1),
