@@ -299,6 +299,30 @@ def bench_block_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, q_c
     ms = (time.perf_counter() - t0) * 1e3 / steps
     attn_ms, n = ob.profile_read("attn_fwd")
     ob.profile_enable(False)
+
+    # the same lists walked in place: one token-ordered K/V copy per KV head, no gather, no token lists
+    O2, lse2 = torch.empty_like(O), torch.empty_like(lse)
+
+    def step_in_place():
+        ob.omni_score_queries(desc, Q, K, probe, scores)
+        ob.omni_select_queries(desc, scores, 0, TAU, q_idx, q_cnt)
+        a_blk = ob.omni_block_scores(desc, Q, K, block)
+        r = ob.omni_budget_from_scores(bdesc, a_blk, RECALL_P, 0)
+        ob.omni_select_kv(bdesc, a_blk, r.budget, nb, blk_idx)
+        ob.omni_block_attn_fwd(desc, Q, K, V, q_idx, q_cnt, blk_idx, r.budget, block, O2, lse2)
+
+    for _ in range(3):
+        step_in_place()
+    torch.cuda.synchronize()
+    same = bool(torch.equal(O.view(torch.int16), O2.view(torch.int16)))
+    ob.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step_in_place()
+    torch.cuda.synchronize()
+    ms2 = (time.perf_counter() - t0) * 1e3 / steps
+    attn2_ms, n2 = ob.profile_read("attn_fwd")
+    ob.profile_enable(False)
     b_tok = int(budget.cpu()[0])
     # share of the token-level accumulated scores (the main path's probe) that the block lists capture, per head
     a_tok = bud.key_scores[0]
@@ -312,6 +336,9 @@ def bench_block_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, q_c
     return {"what": f"queries and keys pooled in blocks of {block}; recall target {RECALL_P} on the block scores; "
                     "same kept queries, same attention kernel on the token lists of the selected blocks",
             "ms_per_step": round(ms, 4), "attn_fwd_ms": round(attn_ms / max(1, n), 4),
+            "in_place": {"what": "block lists walked inside one token-ordered K/V copy per KV head (no gather)",
+                         "ms_per_step": round(ms2, 4), "attn_fwd_ms": round(attn2_ms / max(1, n2), 4),
+                         "output_bit_identical": same},
             "budget_blocks": int(res.budget.cpu()[0]), "budget_fraction": round(b_tok / N, 4),
             "token_level_recall_min": round(float(recall.min()), 4), "token_level_recall_mean": round(float(recall.mean()), 4),
             "attn_algorithmic_tflops": round(4.0 * cfg.head_dim * valid / (attn_ms / max(1, n) * 1e-3) / 1e12, 1)}

@@ -68,7 +68,8 @@ typedef enum {
   OMNI_CALL_DENSE_DECODE = 8,
   OMNI_CALL_GROUP_SUBSET = 9,
   OMNI_CALL_BLOCK_SCORES = 10,
-  OMNI_CALL_PREFILL_SELECT = 11
+  OMNI_CALL_PREFILL_SELECT = 11,
+  OMNI_CALL_BLOCK_ATTN_FWD = 12
 } omni_call_id;
 
 /* One attention layer during prefill / training.
@@ -362,6 +363,27 @@ int omni_expand_blocks(const omni_layer_desc* desc, const int32_t* blk_idx, cons
                        void* stream);
 
 /*
+ * omni_block_attn_fwd -- the sparse flash attention kernel of Sec. "Block-wise
+ * probing and sparse flash attention kernel" on block lists, with no gathered copy
+ * of K/V: K and V are laid out once per KV head in token order, and every query
+ * head's kernel walks its own list of selected blocks inside that one copy, so the
+ * heads of a group share it.  Same result as omni_expand_blocks followed by
+ * omni_sparse_attn_fwd (same tile engine, same order of accumulation).
+ *
+ * bf16 only; block must be a multiple of 64 (the key tile of the kernel) and
+ * blk_cap * block <= 131072.  blk_idx [batch, n_q_heads, blk_cap] ascending block
+ * ids, blk_budget [batch] entries used (shared by the heads, clamped to blk_cap);
+ * q_idx / q_cnt, O and lse as in omni_sparse_attn_fwd.  Without the causal mask
+ * n_tokens must be a multiple of block (pad tokens of a partial last block are
+ * hidden by the mask only).
+ * Workspace: OMNI_CALL_BLOCK_ATTN_FWD with param = blk_cap * block.
+ */
+int omni_block_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                        const int32_t* q_idx, const int32_t* q_cnt,
+                        const int32_t* blk_idx, const int32_t* blk_budget, int32_t blk_cap,
+                        int32_t block, void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Baselines used by the reported metric (not part of the method): plain causal
  * / non-causal attention of the attention equation in Sec. "Preliminary" built
  * on the same tile engine, and plain decode attention over rows [0, ctx_len).
@@ -405,7 +427,7 @@ int omni_dense_decode(const omni_decode_desc* desc, const void* q,
  * descriptor (omni_layer_desc* for prefill calls, omni_decode_desc* for the two
  * decode calls).  `param` is the index capacity b_cap for the calls that take
  * one, the probe block for OMNI_CALL_KV_BUDGET and OMNI_CALL_PREFILL_SELECT,
- * and ignored otherwise.
+ * blk_cap * block for OMNI_CALL_BLOCK_ATTN_FWD, and ignored otherwise.
  * Returns 0 on invalid input (a valid call never needs 0 bytes). */
 size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param);
 

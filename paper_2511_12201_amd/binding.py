@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libomnisparse.so")
 OMNI_F32, OMNI_BF16 = 0, 1
 (CALL_SCORE_QUERIES, CALL_SELECT_QUERIES, CALL_KV_BUDGET, CALL_SELECT_KV, CALL_SPARSE_ATTN_FWD,
  CALL_SPARSE_ATTN_BWD, CALL_SLIM_DECODE, CALL_DENSE_ATTN_FWD, CALL_DENSE_DECODE, CALL_GROUP_SUBSET,
- CALL_BLOCK_SCORES, CALL_PREFILL_SELECT) = range(12)
+ CALL_BLOCK_SCORES, CALL_PREFILL_SELECT, CALL_BLOCK_ATTN_FWD) = range(13)
 
 EXPORTED = [
     "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
@@ -27,6 +27,7 @@ EXPORTED = [
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
     "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
     "omni_group_subset", "omni_slim_decode_grouped", "omni_block_scores", "omni_expand_blocks",
+    "omni_block_attn_fwd",
     "omni_select_kv_per_head", "omni_sparse_attn_fwd_per_head", "omni_sparse_attn_bwd_per_head",
     "omni_visual_subset_per_head", "omni_prefill_select", "omni_compact_cache", "omni_slim_decode_compact",
     "omni_group_subset_per_head", "omni_debug_key_split_len",
@@ -98,6 +99,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_group_subset_per_head.argtypes = lib.omni_group_subset.argtypes
     lib.omni_block_scores.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
     lib.omni_expand_blocks.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
+    lib.omni_block_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.omni_slim_decode_grouped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_compact_cache.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.omni_slim_decode_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
@@ -519,6 +521,23 @@ def omni_expand_blocks(desc: LayerDesc, blk_idx, blk_budget, block: int, kv_idx=
     _check(lib.omni_expand_blocks(C.byref(desc), _ptr(blk_idx), _ptr(blk_budget), blk_cap, block, _ptr(kv_idx),
                                   _ptr(budget), b_cap, _stream()))
     return kv_idx, budget
+
+
+def omni_block_attn_fwd(desc: LayerDesc, Q, K, V, q_idx, q_cnt, blk_idx, blk_budget, block: int, O=None, lse=None,
+                        ws: Workspace | None = None):
+    """Sparse forward pass on block lists blk_idx [B,Hq,blk_cap] without a gathered K/V copy (bf16, block % 64 == 0)."""
+    lib = load_library()
+    ws = ws or default_workspace()
+    blk_cap = blk_idx.shape[-1]
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty(desc.batch, desc.n_q_heads, desc.n_tokens, dtype=torch.float32, device=Q.device)
+    buf = ws.get(CALL_BLOCK_ATTN_FWD, desc, blk_cap * block)
+    _check(lib.omni_block_attn_fwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(q_idx), _ptr(q_cnt), _ptr(blk_idx),
+                                   _ptr(blk_budget), blk_cap, block, _ptr(O), _ptr(lse), _ptr(buf), buf.numel(),
+                                   _stream()))
+    return O, lse
 
 
 def omni_group_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, u_cap: int | None = None,

@@ -265,6 +265,9 @@ size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param) {
     case OMNI_CALL_BLOCK_SCORES:
       if (param < 1) { set_error("block must be >= 1"); return 0; }
       return block_scores_ws(L, param);
+    case OMNI_CALL_BLOCK_ATTN_FWD:
+      if (param < 64 || param % 64) { set_error("blk_cap * block must be a positive multiple of 64"); return 0; }
+      return attn_fwd_blocks_ws(L, param);
     default: set_error("unknown call id %d", call_id); return 0;
   }
 }
@@ -487,6 +490,27 @@ int omni_sparse_attn_fwd_per_head(const omni_layer_desc* desc, const void* Q, co
                                   const int32_t* budget, int32_t b_cap, void* O, float* lse, void* ws, size_t ws_bytes,
                                   void* stream) {
   return sparse_attn_fwd_impl(desc, 1, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, ws_bytes, stream);
+}
+
+int omni_block_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, const int32_t* q_idx,
+                        const int32_t* q_cnt, const int32_t* blk_idx, const int32_t* blk_budget, int32_t blk_cap,
+                        int32_t block, void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(V); REQUIRE_PTR(q_idx); REQUIRE_PTR(q_cnt); REQUIRE_PTR(blk_idx);
+  REQUIRE_PTR(blk_budget); REQUIRE_PTR(O); REQUIRE_PTR(lse);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K); REQUIRE_ALIGNED(V); REQUIRE_ALIGNED(O);
+  if (desc->dtype != OMNI_BF16) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "omni_block_attn_fwd runs in bf16 only");
+  if (blk_cap < 1 || block < 1) OMNI_FAIL(OMNI_ERR_INVALID, "blk_cap and block must be >= 1");
+  if (block % 64) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "block must be a multiple of 64 (the kernel's key tile)");
+  if ((long long)blk_cap * block > attn_fwd_blocks_max_keys())
+    OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "blk_cap * block above %d", attn_fwd_blocks_max_keys());
+  if (!desc->causal && desc->n_tokens % block)
+    OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "without the causal mask n_tokens must be a multiple of block");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, attn_fwd_blocks_ws(L, blk_cap * block)));
+  return run_attn_fwd_blocks(L, Q, K, V, q_idx, q_cnt, blk_idx, blk_budget, blk_cap, block, O, lse, ws,
+                             static_cast<hipStream_t>(stream));
 }
 
 int omni_dense_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, void* O, float* lse,

@@ -70,6 +70,8 @@ struct FwdParams {
   const int* qvis;       // [B*Hq, N] visible packed keys per kept-query position (sparse bf16 path), else nullptr    // kidx[p] == p: causal bounds by arithmetic
   int* sched;           // work list (sched.h)
   size_t order_off;     // where its hand-out order starts
+  const int* tile_map;  // in-place variant: [B*Hq, tile_stride] tile of the packed K/V that tile t of a head's key list is
+  int tile_stride;
 };
 
 // number of entries <= v in ascending a[0,n)
@@ -402,8 +404,11 @@ constexpr int kFastWaves = 8;
 constexpr int kFastThreads = kFastWaves * 64;
 constexpr int kFastTileM = kFastWaves * 32;
 constexpr int kStages = 4;
+constexpr int kMaxMapTiles = 2048;                   // key tiles of one head in the in-place variant (128k tokens)
 
-template <int D>
+// TILEMAP: the key list of a head is a sequence of whole 64-key tiles of the KV head's (ungathered) K/V -- the
+// block-granular selection -- and tile t of the list is read in place, at tile p.tile_map[head][t].
+template <int D, bool TILEMAP>
 __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParams p) {
   typedef u16 T;
   constexpr int CH = D / 8;                          // 16-byte chunks per K row
@@ -415,6 +420,7 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kStages * kStageBytes];
   __shared__ int sBound[2];
   __shared__ int sItem;
+  __shared__ int sTileMap[TILEMAP ? kMaxMapTiles : 1];
 
   const Layer& L = p.L;
   const int lane = lane_id();
@@ -470,6 +476,11 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   __syncthreads();
   const int n_full_tiles = sBound[0] / kTileN;
   const int ntiles = cdiv(sBound[1], kTileN);
+  if constexpr (TILEMAP) {                                     // this item's share of the head's tile map
+    const int* tm = p.tile_map + (long long)bh * p.tile_stride;
+    for (int t = threadIdx.x; t < ntiles; t += kFastThreads) sTileMap[t] = tm[t];
+    __syncthreads();
+  }
 
   const int qpos = pos_first + wave * 32 + ln;
   const bool qvalid = qpos < nq;
@@ -498,11 +509,13 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   // one load instruction of tile t: part < LPH is a K part, the rest are V parts
   auto issue_part = [&](int t, int part) {
     const unsigned dst = lds_base + (unsigned)(t % kStages) * kStageBytes;
+    // where tile t of the key list lives (wave-uniform: the tile base stays in scalar registers)
+    const int src = TILEMAP ? __builtin_amdgcn_readfirstlane(sTileMap[t]) : t;
     if (part < LPH) {
-      gload_lds16(kp + (long long)t * kTileN * D, kgoff[part], dst + (part * kFastWaves + wave) * 1024);
+      gload_lds16(kp + (long long)src * kTileN * D, kgoff[part], dst + (part * kFastWaves + wave) * 1024);
     } else {
       const int j = part - LPH;
-      gload_lds16(vp + (long long)t * kTileN * D, vgoff[j], dst + kKBytes + (j * kFastWaves + wave) * 1024);
+      gload_lds16(vp + (long long)src * kTileN * D, vgoff[j], dst + kKBytes + (j * kFastWaves + wave) * 1024);
     }
   };
   auto issue_tile = [&](int t) {
@@ -792,6 +805,8 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.identity_keys = sparse ? 0 : 1;
   p.sched = w.sched;
   p.qvis = w.qvis;
+  p.tile_map = nullptr;
+  p.tile_stride = 0;
   if (w.qvis) {
     int rc = run_visible_counts(L, q_idx, q_cnt, w.kidx, budget, b_cap, npad, w.qvis, nullptr, st);
     if (rc != OMNI_OK) return rc;
@@ -805,7 +820,7 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   {
     ProfScope prof__(kProfAttnFwd, st);
     if constexpr (kFast) {
-      hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), dim3(persistent_grid() / 2), dim3(kFastThreads), 0, st, p);
+      hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, false>), dim3(persistent_grid() / 2), dim3(kFastThreads), 0, st, p);
     } else {
       hipLaunchKernelGGL((attn_fwd_kernel<T, D>), dim3(persistent_grid()), dim3(kThreads), 0, st, p);
     }
@@ -814,7 +829,115 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   return OMNI_OK;
 }
 
+// ---- in-place variant for block lists (the paper's block-sparse kernel: no gather)
+
+// tile_map[bh, t] = tile of the KV head's packed K/V that holds tile t of the head's key list
+// grid: (cdiv(blk_cap * tiles_per_block, 256), B*Hq)
+__global__ __launch_bounds__(256) void tile_map_kernel(const int* __restrict__ blk_idx, const int* __restrict__ blk_budget,
+                                                       int Hq, int blk_cap, int tiles_per_block, int last_tile,
+                                                       int* __restrict__ tile_map) {
+  const int bh = blockIdx.y, b = bh / Hq;
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int nb = min(blk_budget[b], blk_cap);
+  if (t >= blk_cap * tiles_per_block) return;
+  int tile = 0;
+  if (t < nb * tiles_per_block)
+    tile = min(blk_idx[(long long)bh * blk_cap + t / tiles_per_block] * tiles_per_block + t % tiles_per_block, last_tile);
+  tile_map[(long long)bh * blk_cap * tiles_per_block + t] = tile;
+}
+
+struct BlockFwdWs {
+  FwdWs f;
+  int* klist;       // [B*Hq, blk_cap * block] token index of every entry of the heads' key lists
+  int* vbudget;     // [B] their length
+  int* tile_map;    // [B*Hq, blk_cap * block / 64]
+};
+
+BlockFwdWs carve_block_fwd(Arena& a, const Layer& L, int cap_keys) {
+  BlockFwdWs w;
+  w.f = carve_fwd(a, L, OMNI_BF16, L.Hkv, fwd_npad(L.N), false);
+  const size_t BH = (size_t)L.B * L.Hq;
+  w.f.qvis = a.take<int>(BH * L.N);
+  w.klist = a.take<int>(BH * cap_keys);
+  w.vbudget = a.take<int>(L.B);
+  w.tile_map = a.take<int>(BH * (cap_keys / kTileN));
+  return w;
+}
+
+template <int D>
+int launch_fwd_blocks(const Layer& L, const void* Q, const void* K, const void* V, const int* q_idx, const int* q_cnt,
+                      const int* blk_idx, const int* blk_budget, int blk_cap, int block, void* O, float* lse, void* ws,
+                      hipStream_t st) {
+  typedef u16 T;
+  Arena a(ws);
+  const int tpb = block / kTileN, cap_keys = blk_cap * block;
+  BlockFwdWs w = carve_block_fwd(a, L, cap_keys);
+  const int npad = fwd_npad(L.N);
+  // K and V of every KV head once, in the kernel's tile layouts, in token order: shared by the heads of a group
+  int rc = run_pack_kv(L, OMNI_BF16, K, V, 0, nullptr, L.N, nullptr, L.N, npad, kTileN, w.f.Kp, nullptr, nullptr, w.f.Vp,
+                       w.f.kidx, st);
+  if (rc != OMNI_OK) return rc;
+  {
+    ProfScope prof__(kProfClear, st);
+    hipLaunchKernelGGL((clear_output_kernel<T>), dim3(cdiv(L.N, 64), L.B * L.Hq), dim3(kThreads), 0, st,
+                       static_cast<T*>(O), lse, L);
+    OMNI_LAUNCH_CHECK();
+  }
+  // token lists of the selected blocks (for the causal bounds) and the tile map
+  rc = run_expand_blocks(L, blk_idx, blk_budget, blk_cap, block, w.klist, w.vbudget, cap_keys, st);
+  if (rc != OMNI_OK) return rc;
+  hipLaunchKernelGGL(tile_map_kernel, dim3(cdiv(blk_cap * tpb, 256), L.B * L.Hq), dim3(256), 0, st, blk_idx, blk_budget,
+                     L.Hq, blk_cap, tpb, npad / kTileN - 1, w.tile_map);
+  OMNI_LAUNCH_CHECK();
+  rc = run_visible_counts(L, q_idx, q_cnt, w.klist, w.vbudget, cap_keys, cap_keys, w.f.qvis, nullptr, st);
+  if (rc != OMNI_OK) return rc;
+  FwdParams p;
+  p.Q = Q;
+  p.O = O;
+  p.lse = lse;
+  p.L = L;
+  p.q_idx = q_idx;
+  p.q_cnt = q_cnt;
+  p.Kp = w.f.Kp;
+  p.Vp = w.f.Vp;
+  p.kidx = w.f.kidx;
+  p.budget = w.vbudget;
+  p.b_cap = cap_keys;
+  p.npad = npad;
+  p.per_q_head = 0;
+  p.identity_keys = 0;
+  p.sched = w.f.sched;
+  p.qvis = w.f.qvis;
+  p.tile_map = w.tile_map;
+  p.tile_stride = blk_cap * tpb;
+  p.order_off = sched_order_off(L.B * L.Hq, L.N, kFastTileM);
+  rc = run_schedule(L, q_cnt, w.vbudget, cap_keys, kFastTileM, w.f.qvis, w.f.sched, st);
+  if (rc != OMNI_OK) return rc;
+  {
+    ProfScope prof__(kProfAttnFwd, st);
+    hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, true>), dim3(persistent_grid() / 2), dim3(kFastThreads), 0, st, p);
+    OMNI_LAUNCH_CHECK();
+  }
+  return OMNI_OK;
+}
+
 }  // namespace
+
+size_t attn_fwd_blocks_ws(const Layer& L, int cap_keys) {
+  Arena a(nullptr);
+  carve_block_fwd(a, L, cap_keys);
+  return a.used();
+}
+
+int attn_fwd_blocks_max_keys() { return kMaxMapTiles * kTileN; }
+
+int run_attn_fwd_blocks(const Layer& L, const void* Q, const void* K, const void* V, const int* q_idx, const int* q_cnt,
+                        const int* blk_idx, const int* blk_budget, int blk_cap, int block, void* O, float* lse,
+                        void* ws, hipStream_t st) {
+  if (L.D == 128)
+    return launch_fwd_blocks<128>(L, Q, K, V, q_idx, q_cnt, blk_idx, blk_budget, blk_cap, block, O, lse, ws, st);
+  return launch_fwd_blocks<64>(L, Q, K, V, q_idx, q_cnt, blk_idx, blk_budget, blk_cap, block, O, lse, ws, st);
+}
 
 size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse) {
   Arena a(nullptr);

@@ -53,6 +53,13 @@ int run_attn_fwd(const Layer& L, int dtype, const void* Q, const void* K, const 
                  const int* q_cnt, const int* kv_idx, const int* budget, int b_cap, void* O, float* lse, void* ws,
                  bool sparse, hipStream_t st);
 
+// bf16 only, block % 64 == 0: the forward pass on block lists without a gathered copy of K/V per query head
+int attn_fwd_blocks_max_keys();
+size_t attn_fwd_blocks_ws(const Layer& L, int cap_keys);   // cap_keys = blk_cap * block
+int run_attn_fwd_blocks(const Layer& L, const void* Q, const void* K, const void* V, const int* q_idx, const int* q_cnt,
+                        const int* blk_idx, const int* blk_budget, int blk_cap, int block, void* O, float* lse,
+                        void* ws, hipStream_t st);
+
 // attn_bwd.hip
 size_t attn_bwd_ws(const Layer& L, int dtype, int b_cap);
 int run_attn_bwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const void* O,

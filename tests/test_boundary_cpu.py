@@ -131,6 +131,18 @@ def test_argument_errors(lib):
     assert lib.omni_compact_cache(C.byref(dd), FAKE, FAKE, FAKE, FAKE, 64, None, FAKE, None) == -1
     assert lib.omni_slim_decode_compact(C.byref(dd), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, FAKE,
                                         FAKE, FAKE, 16, None) == -3
+    # block lists walked in place: bf16, block a multiple of the key tile, bounded list length
+    ba = lambda dd_=d, **kw: lib.omni_block_attn_fwd(
+        C.byref(dd_), FAKE, FAKE, FAKE, FAKE, FAKE, kw.get("blk", FAKE), FAKE, kw.get("cap", 4), kw.get("block", 64), FAKE,
+        FAKE, FAKE, kw.get("ws", 1 << 30), None)
+    assert ba(block=100) == -2 and "multiple of 64" in ob.last_error()
+    assert ba(cap=0) == -1 and ba(blk=None) == -1 and ba(ws=16) == -3
+    assert ba(cap=4096, block=64) == -2
+    assert ba(_desc(dtype=ob.OMNI_F32)) == -2 and "bf16" in ob.last_error()
+    assert ba(_desc(causal=0), block=128) == -2
+    assert ob.workspace_bytes(ob.CALL_BLOCK_ATTN_FWD, d, 5 * 64) > 0
+    with pytest.raises(ob.OmniError):
+        ob.workspace_bytes(ob.CALL_BLOCK_ATTN_FWD, d, 100)
     assert lib.omni_debug_key_split_len(0) == 0
     # a successful validation path clears the message
     assert ob.workspace_bytes(ob.CALL_SELECT_KV, d) > 0

@@ -519,6 +519,35 @@ def test_block_granular_selection_and_attention(cfg, block):
     assert np.max(np.abs(to_host(lse)[fin] - Lo[fin])) <= (1e-4 if cfg.dtype == "f32" else 2e-2)
 
 
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_BF16_64], ids=lambda c: c.name)
+@pytest.mark.parametrize("block,frac", [(64, 0.4), (128, 0.5), (256, 1.0), (192, 0.3)])
+def test_block_attention_in_place_equals_gathered_path_and_oracle(cfg, block, frac):
+    """The forward pass that walks block lists inside one token-ordered copy of K/V per KV head: bit-for-bit the
+    result of expanding the lists to tokens and gathering, and within the bf16 bar of the oracle."""
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    nb = math.ceil(N / block)
+    nsel = max(1, int(round(frac * nb)))
+    rng = np.random.default_rng(1000 + block)
+    lists = [[np.sort(rng.choice(nb, nsel, replace=False)).astype(np.int32) for _ in range(H)]]
+    lists[0][0] = np.sort(np.concatenate([rng.choice(nb - 1, nsel - 1, replace=False), [nb - 1]])).astype(np.int32)
+    blk_idx, _ = lists_to_padded(lists, H, nb)
+    blk_budget = torch.tensor([nsel], dtype=torch.int32, device="cuda")
+    q_idx, q_cnt = lists_to_padded(c.o_qidx, H, N)
+    O1, lse1 = ob.omni_block_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, blk_idx, blk_budget, block)
+    kv_idx, budget = ob.omni_expand_blocks(c.desc, blk_idx, blk_budget, block)
+    O2, lse2 = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, budget, kv_idx.shape[-1])
+    torch.cuda.synchronize()
+    assert torch.equal(O1.view(torch.int16), O2.view(torch.int16))
+    assert torch.equal(lse1.view(torch.int32), lse2.view(torch.int32))
+    want_tok = oc.expand_blocks(lists, block, N)
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, want_tok, cfg.causal, cfg.scale)
+    assert np.max(np.abs(to_host(O1) - Oo)) <= TOL_OUT["bf16"]
+    fin = np.isfinite(Lo)
+    assert np.array_equal(np.isfinite(to_host(lse1)), fin)
+    assert np.max(np.abs(to_host(lse1)[fin] - Lo[fin])) <= 2e-2
+
+
 # ------------------------------------------------------------------ attention backward
 
 def _run_fwd_bwd(c, q_lists, kv_lists, dO_np, desc=None):
