@@ -504,8 +504,23 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
         ev1.record()
         torch.cuda.synchronize()
         compact_us = ev0.elapsed_time(ev1) * 1e3
+        # the same store in pages of 256 rows handed out in a seeded random order, as a block allocator would
+        page_rows = 256
+        need = ((grp_cnt + page_rows - 1) // page_rows).cpu().numpy()
+        n_pages = int(need.sum())
+        perm = np.random.default_rng(5).permutation(n_pages).astype(np.int32)
+        table = np.full((B, Hkv, (u_max + page_rows - 1) // page_rows), -1, dtype=np.int32)
+        used = 0
+        for bb in range(B):
+            for g in range(Hkv):
+                table[bb, g, : need[bb, g]] = perm[used: used + need[bb, g]]
+                used += int(need[bb, g])
+        Kpool = torch.empty(n_pages, page_rows, D, dtype=torch.bfloat16, device="cuda")
+        Vpool = torch.empty_like(Kpool)
+        pool = ob.make_page_pool(Kpool, Vpool, torch.from_numpy(table).cuda())
+        ob.omni_compact_cache_paged(ddesc, Kc, Vc, g_idx_c, grp_cnt, pool)
         timing, ktime = {}, {}
-        for mode in ("slim", "slim_grouped", "slim_compact", "dense"):
+        for mode in ("slim", "slim_grouped", "slim_compact", "slim_paged", "dense"):
             ctx.fill_(N + 1)
             for _ in range(3):                                    # untimed warm-up of both entry points
                 ob.omni_slim_decode_grouped(ddesc, q_all[0], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act)
@@ -526,6 +541,8 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
                 elif mode == "slim_compact":
                     ob.omni_slim_decode_compact(ddesc, q_all[s], Kc, Vc, ctx, probe_b, Kcomp, Vcomp, g_idx_c, g_mask_c,
                                                 grp_cnt, O, act)
+                elif mode == "slim_paged":
+                    ob.omni_slim_decode_paged(ddesc, q_all[s], Kc, Vc, ctx, probe_b, pool, g_idx_c, g_mask_c, grp_cnt, O, act)
                 else:
                     ob.omni_dense_decode(ddesc, q_all[s], Kc, Vc, ctx, O)
             ev1.record()
@@ -559,6 +576,7 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
             "speedup_grouped": round(ktime["dense"] / ktime["slim_grouped"], 3),
             "slim_grouped_us_per_token": round(ktime["slim_grouped"], 2),
             "slim_compact_us_per_token": round(ktime["slim_compact"], 2),
+            "slim_paged_us_per_token": round(ktime["slim_paged"], 2),
             "compaction_us_once": round(compact_us, 1),
             # what a serving stack has to keep per layer: the whole cache, or the compacted visual rows (with their
             # token index and membership word) plus the non-visual rows
@@ -570,7 +588,7 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
             "GBps_of_requested_rows": {"slim": gbps(rows_head, ktime["slim"]), "slim_grouped": gbps(rows_union, ktime["slim_grouped"]),
                                        "dense": gbps(rows_dense, ktime["dense"])},
             "dense_frac_of_hbm_peak": round(rows_dense * row_bytes / (ktime["dense"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)}
-        del Kc, Vc
+        del Kc, Vc, Kpool, Vpool, Kcomp, Vcomp
         torch.cuda.empty_cache()
     return res
 

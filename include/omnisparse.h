@@ -97,6 +97,21 @@ typedef struct {
   int64_t kv_stride[3];        /* batch, head, token strides of the caches, in elements */
 } omni_decode_desc;
 
+/* Paged form of the compacted visual KV store (omni_compact_cache_paged,
+ * omni_slim_decode_paged): one pool of fixed-size pages shared by all sequences and
+ * KV heads of a layer, and a table that says which page holds which stretch of a
+ * (sequence, KV head) pair's group list. */
+typedef struct {
+  void* K;                     /* device, [n_pages, page_rows, head_dim] dtype of the decode descriptor */
+  void* V;                     /* same shape */
+  const int32_t* page_table;   /* device, [batch, n_kv_heads, pages_cap]: page of the pool that holds list
+                                  positions [j * page_rows, (j + 1) * page_rows) of the pair's group list;
+                                  an entry outside [0, n_pages) marks a page that is not there */
+  int32_t n_pages;             /* pages in the pool; n_pages * page_rows < 2^31 */
+  int32_t page_rows;           /* rows per page, a power of two */
+  int32_t pages_cap;           /* table entries per pair; pages_cap * page_rows >= u_cap of the call */
+} omni_page_pool;
+
 /*
  * omni_score_queries -- Sec. "Query Selection as Binary Lazy-Active
  * Classification", probe-softmax equation.
@@ -405,6 +420,25 @@ int omni_block_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* 
  * Output and `active` equal omni_slim_decode_grouped's (same rows, same order).
  * Workspace of the decode call: OMNI_CALL_SLIM_DECODE.
  */
+/*
+ * Paged variants: the same store cut into pages of a pool (omni_page_pool), the
+ * layout a serving engine's block allocator hands out.  The caller owns pool and
+ * table and assigns the pages (ceil(grp_cnt / page_rows) per pair; two pairs never
+ * share a page).  omni_compact_cache_paged writes row u of pair (b, g) to row
+ * u % page_rows of page page_table[b, g, u / page_rows]; omni_slim_decode_paged is
+ * omni_slim_decode_compact reading the rows from there.  Rows whose table entry is
+ * outside [0, n_pages) are neither stored nor attended (no error).  With every
+ * page present the output equals omni_slim_decode_compact's bit for bit.
+ */
+int omni_compact_cache_paged(const omni_decode_desc* desc, const void* Kcache, const void* Vcache,
+                             const int32_t* grp_idx, const int32_t* grp_cnt, int32_t u_cap,
+                             const omni_page_pool* pool, void* stream);
+int omni_slim_decode_paged(const omni_decode_desc* desc, const void* q,
+                           const void* Kcache, const void* Vcache, const int32_t* ctx_len,
+                           const float* probe_keys, const omni_page_pool* pool,
+                           const int32_t* grp_idx, const uint32_t* grp_mask, const int32_t* grp_cnt,
+                           int32_t u_cap, void* O, uint8_t* active,
+                           void* ws, size_t ws_bytes, void* stream);
 int omni_compact_cache(const omni_decode_desc* desc, const void* Kcache, const void* Vcache,
                        const int32_t* grp_idx, const int32_t* grp_cnt, int32_t u_cap,
                        void* Kcomp, void* Vcomp, void* stream);

@@ -30,6 +30,7 @@ EXPORTED = [
     "omni_block_attn_fwd",
     "omni_select_kv_per_head", "omni_sparse_attn_fwd_per_head", "omni_sparse_attn_bwd_per_head",
     "omni_visual_subset_per_head", "omni_prefill_select", "omni_compact_cache", "omni_slim_decode_compact",
+    "omni_compact_cache_paged", "omni_slim_decode_paged",
     "omni_group_subset_per_head", "omni_debug_key_split_len",
 ]
 
@@ -52,6 +53,26 @@ class DecodeDesc(C.Structure):
         ("cache_capacity", C.c_int32), ("vis_begin", C.c_int32), ("vis_end", C.c_int32), ("dtype", C.c_int32),
         ("softmax_scale", C.c_float), ("tau", C.c_float), ("kv_stride", C.c_int64 * 3),
     ]
+
+
+class PagePool(C.Structure):
+    _fields_ = [
+        ("K", C.c_void_p), ("V", C.c_void_p), ("page_table", C.c_void_p),
+        ("n_pages", C.c_int32), ("page_rows", C.c_int32), ("pages_cap", C.c_int32),
+    ]
+
+
+def make_page_pool(Kpool, Vpool, page_table) -> PagePool:
+    """Descriptor of a page pool: Kpool / Vpool [n_pages, page_rows, D], page_table [B, Hkv, pages_cap] int32."""
+    if not (Kpool.is_contiguous() and Vpool.is_contiguous() and page_table.is_contiguous()):
+        raise ValueError("pool tensors and page table must be contiguous")
+    if page_table.dtype != torch.int32 or Kpool.shape != Vpool.shape or Kpool.dim() != 3:
+        raise ValueError("page_table must be int32; Kpool and Vpool [n_pages, page_rows, head_dim]")
+    pool = PagePool()
+    pool.K, pool.V, pool.page_table = Kpool.data_ptr(), Vpool.data_ptr(), page_table.data_ptr()
+    pool.n_pages, pool.page_rows, pool.pages_cap = Kpool.shape[0], Kpool.shape[1], page_table.shape[-1]
+    pool._keep = (Kpool, Vpool, page_table)
+    return pool
 
 
 class OmniError(RuntimeError):
@@ -103,6 +124,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_slim_decode_grouped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_compact_cache.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.omni_slim_decode_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.omni_compact_cache_paged.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.omni_slim_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_profile_enable.argtypes = [C.c_int]
     lib.omni_debug_copy.argtypes = [vp, vp, sz, vp]
     lib.omni_debug_key_split_len.argtypes = [C.c_int]
@@ -607,6 +630,31 @@ def omni_slim_decode_compact(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe
                                         _ptr(probe_keys), _ptr(Kcomp), _ptr(Vcomp), _ptr(grp_idx), _ptr(grp_mask),
                                         _ptr(grp_cnt), grp_idx.shape[-1], _ptr(O), _ptr(active), _ptr(buf), buf.numel(),
                                         _stream()))
+    return O, active
+
+
+def omni_compact_cache_paged(desc: DecodeDesc, Kcache, Vcache, grp_idx, grp_cnt, pool: PagePool):
+    lib = load_library()
+    if pool._keep[0].dtype != Kcache.dtype or pool._keep[0].shape[-1] != desc.head_dim:
+        raise ValueError("pool dtype / head_dim differ from the cache's")
+    _check(lib.omni_compact_cache_paged(C.byref(desc), _ptr(Kcache), _ptr(Vcache), _ptr(grp_idx), _ptr(grp_cnt),
+                                        grp_idx.shape[-1], C.byref(pool), _stream()))
+
+
+def omni_slim_decode_paged(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, pool: PagePool, grp_idx, grp_mask,
+                           grp_cnt, O=None, active=None, ws: Workspace | None = None):
+    lib = load_library()
+    ws = ws or default_workspace()
+    if O is None:
+        O = torch.empty_like(q)
+    if active is None:
+        active = torch.empty(desc.batch, desc.n_q_heads, dtype=torch.uint8, device=q.device)
+    if pool._keep[0].dtype != q.dtype or pool._keep[0].shape[-1] != desc.head_dim:
+        raise ValueError("pool dtype / head_dim differ from the query's")
+    buf = ws.get(CALL_SLIM_DECODE, desc)
+    _check(lib.omni_slim_decode_paged(C.byref(desc), _ptr(q), _ptr(Kcache), _ptr(Vcache), _ptr(ctx_len),
+                                      _ptr(probe_keys), C.byref(pool), _ptr(grp_idx), _ptr(grp_mask), _ptr(grp_cnt),
+                                      grp_idx.shape[-1], _ptr(O), _ptr(active), _ptr(buf), buf.numel(), _stream()))
     return O, active
 
 

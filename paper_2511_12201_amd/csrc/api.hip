@@ -622,6 +622,57 @@ int omni_slim_decode_compact(const omni_decode_desc* desc, const void* q, const 
                     static_cast<hipStream_t>(stream), Kcomp, Vcomp);
 }
 
+static int validate_pool(const omni_page_pool* pool, int32_t u_cap, PagePool* out) {
+  if (!pool) OMNI_FAIL(OMNI_ERR_INVALID, "pool is null");
+  if (!pool->K || !pool->V || !pool->page_table) OMNI_FAIL(OMNI_ERR_INVALID, "pool: K, V or page_table is null");
+  if ((reinterpret_cast<uintptr_t>(pool->K) | reinterpret_cast<uintptr_t>(pool->V)) & 15)
+    OMNI_FAIL(OMNI_ERR_INVALID, "pool: K and V must be 16-byte aligned");
+  if (pool->n_pages < 1 || pool->page_rows < 1 || pool->pages_cap < 1)
+    OMNI_FAIL(OMNI_ERR_INVALID, "pool: n_pages, page_rows and pages_cap must be >= 1");
+  if (pool->page_rows & (pool->page_rows - 1)) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "pool: page_rows must be a power of two");
+  if ((long long)pool->n_pages * pool->page_rows >= (1ll << 31)) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "pool: 2^31 rows or more");
+  if ((long long)pool->pages_cap * pool->page_rows < u_cap)
+    OMNI_FAIL(OMNI_ERR_INVALID, "pool: pages_cap * page_rows must be >= u_cap");
+  out->page_table = pool->page_table;
+  out->page_shift = __builtin_ctz((unsigned)pool->page_rows);
+  out->pages_cap = pool->pages_cap;
+  out->pool_pages = pool->n_pages;
+  return OMNI_OK;
+}
+
+int omni_compact_cache_paged(const omni_decode_desc* desc, const void* Kcache, const void* Vcache,
+                             const int32_t* grp_idx, const int32_t* grp_cnt, int32_t u_cap, const omni_page_pool* pool,
+                             void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(grp_idx); REQUIRE_PTR(grp_cnt);
+  REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache);
+  if (u_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "u_cap must be >= 1");
+  PagePool pp;
+  CHECK(validate_pool(pool, u_cap, &pp));
+  return run_compact_cache(desc, Kcache, Vcache, grp_idx, grp_cnt, u_cap, pool->K, pool->V,
+                           static_cast<hipStream_t>(stream), &pp);
+}
+
+int omni_slim_decode_paged(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,
+                           const int32_t* ctx_len, const float* probe_keys, const omni_page_pool* pool,
+                           const int32_t* grp_idx, const uint32_t* grp_mask, const int32_t* grp_cnt, int32_t u_cap,
+                           void* O, uint8_t* active, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(q); REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(ctx_len); REQUIRE_PTR(probe_keys);
+  REQUIRE_PTR(grp_idx); REQUIRE_PTR(grp_mask); REQUIRE_PTR(grp_cnt); REQUIRE_PTR(O); REQUIRE_PTR(active);
+  REQUIRE_ALIGNED(q); REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache);
+  if (u_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "u_cap must be >= 1");
+  if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
+  if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
+  PagePool pp;
+  CHECK(validate_pool(pool, u_cap, &pp));
+  CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
+  return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
+                    static_cast<hipStream_t>(stream), pool->K, pool->V, &pp);
+}
+
 int omni_dense_decode(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,
                       const int32_t* ctx_len, void* O, void* ws, size_t ws_bytes, void* stream) {
   clear_error();

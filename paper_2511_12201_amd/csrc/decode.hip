@@ -47,6 +47,8 @@ struct DecodeParams {
   const unsigned* grp_mask; // membership bits of the group lists, nullptr for the per-head call
   const void* Kcomp;       // compacted copies of the group lists' rows [B*Hkv, b_cap, D] (row u = cache row
   const void* Vcomp;       // vis_idx[u]), or nullptr: the listed rows are read from the cache itself
+  const int* page_table;   // not nullptr: Kcomp / Vcomp are a pool [pool_pages, 1 << page_shift, D] and list position u
+  int page_shift, pages_cap, pool_pages;   // of group bg sits in page page_table[bg, u >> page_shift] of it
   int b_cap;
   void* O;
   unsigned char* active;
@@ -413,6 +415,30 @@ __device__ __forceinline__ void decode_group_rows(const DecodeParams& p, int sli
   const int* vlist = p.vis_idx + (long long)bg * p.b_cap;
   const unsigned* mlist = p.grp_mask + (long long)bg * p.b_cap;
   const int shift = chunk * GT;
+  if (p.page_table) {            // the listed rows sit in pages of a pool: position -> (page, offset) -> pool row
+    // The slice's stretch of the page table goes to LDS first: a table entry fetched from memory next to every
+    // list entry costs 4 % of the call at batch 8.
+    constexpr int kStaged = 128;
+    __shared__ int sPages[kStaged];
+    const int* table = p.page_table + (long long)bg * p.pages_cap;
+    const int pshift = p.page_shift, pmask = (1 << p.page_shift) - 1;
+    const int slot0 = begin >> pshift, nslots = begin < end ? ((end - 1) >> pshift) - slot0 + 1 : 0;
+    const bool staged = nslots <= kStaged;
+    if (staged) {
+      for (int i = threadIdx.x; i < nslots; i += kThreads) sPages[i] = slot0 + i < p.pages_cap ? table[slot0 + i] : -1;
+      __syncthreads();
+    }
+    stream_rows<T, D, GT>(p, b, g, head0, begin, end,
+                          [&](int it) {
+                            const int slot = it >> pshift;
+                            if (vlist[it] >= ctx || slot >= p.pages_cap) return -1;
+                            const int page = staged ? sPages[slot - slot0] : table[slot];
+                            return (unsigned)page < (unsigned)p.pool_pages ? (page << pshift) + (it & pmask) : -1;
+                          },
+                          [&](int it) { return mlist[it] >> shift; }, bits, p.n_shared + slice,
+                          static_cast<const T*>(p.Kcomp), static_cast<const T*>(p.Vcomp), (long long)D);
+    return;
+  }
   if (p.Kcomp) {                 // the listed rows sit side by side in the compacted store: position = row
     const long long base = (long long)bg * p.b_cap * D;
     stream_rows<T, D, GT>(p, b, g, head0, begin, end, [&](int it) { return vlist[it] < ctx ? it : -1; },
@@ -596,7 +622,9 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(const T* __restr
                                                                const int* __restrict__ idx,
                                                                const int* __restrict__ cnt, int u_cap, int Hkv, int cap,
                                                                long long s0, long long s1, long long s2,
-                                                               T* __restrict__ Kc, T* __restrict__ Vc) {
+                                                               T* __restrict__ Kc, T* __restrict__ Vc,
+                                                               const int* __restrict__ page_table, int page_shift,
+                                                               int pages_cap, int pool_pages) {
   constexpr int E = Elem<T>::kPer16B;
   constexpr int LPR = D / E;
   constexpr int RPB = kThreads / LPR;
@@ -606,32 +634,40 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(const T* __restr
   const int row = idx[(long long)bg * u_cap + u];
   if (row < 0 || row >= cap) return;
   const long long src = b * s0 + g * s1 + (long long)row * s2 + c * E;
-  const long long dst = ((long long)bg * u_cap + u) * D + c * E;
+  long long dst = ((long long)bg * u_cap + u) * D + c * E;
+  if (page_table) {
+    const int slot = u >> page_shift;
+    if (slot >= pages_cap) return;
+    const int page = page_table[(long long)bg * pages_cap + slot];
+    if ((unsigned)page >= (unsigned)pool_pages) return;          // page not allocated: the row is not stored
+    dst = ((long long)((page << page_shift) + (u & ((1 << page_shift) - 1)))) * D + c * E;
+  }
   *reinterpret_cast<u32x4*>(Kc + dst) = *reinterpret_cast<const u32x4*>(K + src);
   *reinterpret_cast<u32x4*>(Vc + dst) = *reinterpret_cast<const u32x4*>(V + src);
 }
 
 template <typename T, int D>
 int launch_compact(const omni_decode_desc* d, const void* K, const void* V, const int* idx, const int* cnt, int u_cap,
-                   void* Kc, void* Vc, hipStream_t st) {
+                   void* Kc, void* Vc, const PagePool* pool, hipStream_t st) {
   constexpr int RPB = kThreads / (D / Elem<T>::kPer16B);
   hipLaunchKernelGGL((compact_rows_kernel<T, D>), dim3(cdiv(u_cap, RPB), d->batch * d->n_kv_heads), dim3(kThreads), 0,
                      st, static_cast<const T*>(K), static_cast<const T*>(V), idx, cnt, u_cap, d->n_kv_heads,
                      d->cache_capacity, d->kv_stride[0], d->kv_stride[1], d->kv_stride[2], static_cast<T*>(Kc),
-                     static_cast<T*>(Vc));
+                     static_cast<T*>(Vc), pool ? pool->page_table : nullptr, pool ? pool->page_shift : 0,
+                     pool ? pool->pages_cap : 0, pool ? pool->pool_pages : 0);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
 }
 }  // namespace
 
 int run_compact_cache(const omni_decode_desc* d, const void* K, const void* V, const int* grp_idx, const int* grp_cnt,
-                      int u_cap, void* Kc, void* Vc, hipStream_t st) {
+                      int u_cap, void* Kc, void* Vc, hipStream_t st, const PagePool* pool) {
   if (d->dtype == OMNI_BF16) {
-    if (d->head_dim == 128) return launch_compact<u16, 128>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, st);
-    return launch_compact<u16, 64>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, st);
+    if (d->head_dim == 128) return launch_compact<u16, 128>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, pool, st);
+    return launch_compact<u16, 64>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, pool, st);
   }
-  if (d->head_dim == 128) return launch_compact<float, 128>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, st);
-  return launch_compact<float, 64>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, st);
+  if (d->head_dim == 128) return launch_compact<float, 128>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, pool, st);
+  return launch_compact<float, 64>(d, K, V, grp_idx, grp_cnt, u_cap, Kc, Vc, pool, st);
 }
 
 size_t decode_ws(const omni_decode_desc* d) {
@@ -646,7 +682,8 @@ size_t decode_ws(const omni_decode_desc* d) {
 
 int run_decode(const omni_decode_desc* d, const void* q, const void* K, const void* V, const int* ctx_len,
                const float* probe, const int* vis_idx, const int* vis_cnt, const unsigned* grp_mask, int b_cap,
-               void* O, unsigned char* active, void* ws, hipStream_t st, const void* Kcomp, const void* Vcomp) {
+               void* O, unsigned char* active, void* ws, hipStream_t st, const void* Kcomp, const void* Vcomp,
+               const PagePool* pool) {
   Arena a(ws);
   DecodeParams p;
   p.q = q;
@@ -659,6 +696,10 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
   p.grp_mask = grp_mask;
   p.Kcomp = Kcomp;
   p.Vcomp = Vcomp;
+  p.page_table = pool ? pool->page_table : nullptr;
+  p.page_shift = pool ? pool->page_shift : 0;
+  p.pages_cap = pool ? pool->pages_cap : 0;
+  p.pool_pages = pool ? pool->pool_pages : 0;
   p.b_cap = b_cap;
   p.O = O;
   p.active = active;

@@ -70,13 +70,19 @@ void set_key_split_len(int tiles);   // attn_bwd.hip; <= 0 restores the default
 
 // decode.hip
 size_t decode_ws(const omni_decode_desc* d);
+// paged form of the compacted store: Kcomp / Vcomp are a pool [pool_pages, 1 << page_shift, D] shared by all
+// (batch, KV head) pairs; position u of a pair's group list lives in page page_table[pair, u >> page_shift]
+struct PagePool {
+  const int* page_table;   // [B*Hkv, pages_cap]; entries outside [0, pool_pages) mark pages that are not there
+  int page_shift, pages_cap, pool_pages;
+};
 // grp_mask == nullptr: vis_idx / vis_cnt are per query head; otherwise per KV group with membership bits
 int run_decode(const omni_decode_desc* d, const void* q, const void* K, const void* V, const int* ctx_len,
                const float* probe, const int* vis_idx, const int* vis_cnt, const unsigned* grp_mask, int b_cap,
                void* O, unsigned char* active, void* ws, hipStream_t st, const void* Kcomp = nullptr,
-               const void* Vcomp = nullptr);
+               const void* Vcomp = nullptr, const PagePool* pool = nullptr);
 int run_compact_cache(const omni_decode_desc* d, const void* K, const void* V, const int* grp_idx, const int* grp_cnt,
-                      int u_cap, void* Kc, void* Vc, hipStream_t st);
+                      int u_cap, void* Kc, void* Vc, hipStream_t st, const PagePool* pool = nullptr);
 
 // block.hip (block-granular variant of the KV selection)
 int block_scores_max_blocks();

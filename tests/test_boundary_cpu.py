@@ -143,6 +143,25 @@ def test_argument_errors(lib):
     assert ob.workspace_bytes(ob.CALL_BLOCK_ATTN_FWD, d, 5 * 64) > 0
     with pytest.raises(ob.OmniError):
         ob.workspace_bytes(ob.CALL_BLOCK_ATTN_FWD, d, 100)
+    # paged store: the pool descriptor is validated before any launch
+    def pool(**kw):
+        pp = ob.PagePool()
+        pp.K, pp.V, pp.page_table = kw.get("K", 0x10000), 0x10000, kw.get("table", 0x10000)
+        pp.n_pages, pp.page_rows, pp.pages_cap = kw.get("n_pages", 8), kw.get("page_rows", 16), kw.get("pages_cap", 4)
+        return pp
+    cp = lambda pp, u_cap=64: lib.omni_compact_cache_paged(C.byref(dd), FAKE, FAKE, FAKE, FAKE, u_cap,
+                                                           C.byref(pp) if pp else None, None)
+    assert cp(None) == -1 and "pool" in ob.last_error()
+    assert cp(pool(K=None)) == -1 and cp(pool(table=None)) == -1 and cp(pool(K=0x10008)) == -1
+    assert cp(pool(page_rows=24)) == -2 and "power of two" in ob.last_error()
+    assert cp(pool(n_pages=0)) == -1 and cp(pool(n_pages=1 << 28, page_rows=16)) == -2
+    assert cp(pool(), u_cap=65) == -1 and "pages_cap" in ob.last_error()
+    assert cp(pool(), u_cap=0) == -1
+    pp = pool()
+    assert lib.omni_slim_decode_paged(C.byref(dd), FAKE, FAKE, FAKE, FAKE, FAKE, C.byref(pp), FAKE, FAKE, FAKE, 64, FAKE,
+                                      FAKE, FAKE, 16, None) == -3
+    assert lib.omni_slim_decode_paged(C.byref(dd), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 64, FAKE,
+                                      FAKE, FAKE, 1 << 30, None) == -1
     assert lib.omni_debug_key_split_len(0) == 0
     # a successful validation path clears the message
     assert ob.workspace_bytes(ob.CALL_SELECT_KV, d) > 0

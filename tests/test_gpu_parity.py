@@ -370,6 +370,90 @@ def test_compacted_cache_decode(cfg, batch):
     assert np.max(np.abs(got[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
 
 
+@pytest.mark.parametrize("cfg,batch,page_rows", [(CFG_BF16, 1, 16), (CFG_BF16, 3, 64), (CFG_BF16_64, 2, 1), (CFG_F32, 2, 32),
+                                                 (CFG_F32_128, 1, 256)], ids=lambda x: getattr(x, "name", str(x)))
+def test_paged_cache_decode(cfg, batch, page_rows):
+    """The compacted store cut into pages of a shared pool, the pages of every (sequence, KV head) pair scattered
+    over it in a seeded random order: every row lands in its page, the decode step equals the contiguous store's
+    bit for bit and the oracle's to the bar; a pair whose last page is missing loses exactly those rows."""
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    tau = 0.08
+    H, Hkv, D = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    b = len(c.o_kvidx[0][0])
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])] * batch, H, b)
+    budget = torch.full((batch,), b, dtype=torch.int32, device="cuda")
+    ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                               cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset(ldesc, kv_idx, budget, b)
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    dctx = torch.from_numpy(ctx).cuda()
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    desc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau)
+    gi, gc = to_host(grp_idx), to_host(grp_cnt)
+    u_cap = grp_idx.shape[-1]
+    pages_cap = -(-u_cap // page_rows)
+    need = [[-(-int(gc[bb, g]) // page_rows) for g in range(Hkv)] for bb in range(batch)]
+    n_pages = sum(map(sum, need)) + 3                                  # a few pages nobody owns
+    rng = np.random.default_rng(77 + page_rows)
+    free = list(rng.permutation(n_pages))
+    table = np.full((batch, Hkv, pages_cap), -1, dtype=np.int32)
+    for bb in range(batch):
+        for g in range(Hkv):
+            for j in range(need[bb][g]):
+                table[bb, g, j] = free.pop()
+    dtable = torch.from_numpy(table).cuda()
+    Kpool = torch.full((n_pages, page_rows, D), float("nan"), dtype=dKc.dtype, device="cuda")
+    Vpool = torch.full_like(Kpool, float("nan"))
+    pool = ob.make_page_pool(Kpool, Vpool, dtable)
+    ob.omni_compact_cache_paged(desc, dKc, dVc, grp_idx, grp_cnt, pool)
+    Kcomp, Vcomp = ob.omni_compact_cache(desc, dKc, dVc, grp_idx, grp_cnt)
+    torch.cuda.synchronize()
+    Kh, Vh, Kp, Vp = to_host(dKc), to_host(dVc), to_host(Kpool), to_host(Vpool)
+    for bb in range(batch):
+        for g in range(Hkv):
+            n = int(gc[bb, g])
+            u = np.arange(n)
+            rows = table[bb, g, u // page_rows].astype(np.int64) * page_rows + u % page_rows
+            np.testing.assert_array_equal(Kp.reshape(-1, D)[rows], Kh[bb, g, gi[bb, g, :n]])
+            np.testing.assert_array_equal(Vp.reshape(-1, D)[rows], Vh[bb, g, gi[bb, g, :n]])
+    owned = np.zeros(n_pages * page_rows, dtype=bool)
+    for bb in range(batch):
+        for g in range(Hkv):
+            u = np.arange(int(gc[bb, g]))
+            owned[table[bb, g, u // page_rows].astype(np.int64) * page_rows + u % page_rows] = True
+    assert np.all(np.isnan(Kp.reshape(-1, D)[~owned]))                  # nothing written outside the owned rows
+    dKc2, dVc2 = dKc.clone(), dVc.clone()
+    dKc2[:, :, cfg.vis_begin:cfg.vis_end] = float("nan")
+    dVc2[:, :, cfg.vis_begin:cfg.vis_end] = float("nan")
+    O1, act1 = ob.omni_slim_decode_paged(desc, dq, dKc2, dVc2, dctx, dprobe, pool, grp_idx, grp_mask, grp_cnt)
+    O2, act2 = ob.omni_slim_decode_compact(desc, dq, dKc2, dVc2, dctx, dprobe, Kcomp, Vcomp, grp_idx, grp_mask, grp_cnt)
+    torch.cuda.synchronize()
+    assert torch.equal(act1, act2)
+    assert torch.equal(O1.view(torch.int16 if cfg.dtype == "bf16" else torch.int32),
+                       O2.view(torch.int16 if cfg.dtype == "bf16" else torch.int32))
+    Oo, acto, sc = oc.slim_decode(q, Kc, Vc, ctx, probe.astype(np.float32), vis, tau, cfg.vis_begin, cfg.vis_end, cfg.scale)
+    same = to_host(act1) == acto
+    got = to_host(O1)
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
+    # drop the last page of pair (0, 0): the decode step then sees the list without that page's rows
+    last = need[0][0] - 1
+    if last >= 1:
+        table2 = table.copy()
+        table2[0, 0, last] = -1
+        pool2 = ob.make_page_pool(Kpool, Vpool, torch.from_numpy(table2).cuda())
+        O3, act3 = ob.omni_slim_decode_paged(desc, dq, dKc2, dVc2, dctx, dprobe, pool2, grp_idx, grp_mask, grp_cnt)
+        torch.cuda.synchronize()
+        G = H // Hkv
+        gone = set(int(x) for x in gi[0, 0, last * page_rows: int(gc[0, 0])])
+        vis3 = [[np.array([t for t in vis[bb][h] if not (bb == 0 and h < G and int(t) in gone)], dtype=np.int32)
+                 for h in range(H)] for bb in range(batch)]
+        Oo3, acto3, _ = oc.slim_decode(q, Kc, Vc, ctx, probe.astype(np.float32), vis3, tau, cfg.vis_begin, cfg.vis_end,
+                                       cfg.scale)
+        same3 = to_host(act3) == acto3
+        assert np.max(np.abs(to_host(O3)[same3] - Oo3[same3])) <= TOL_OUT[cfg.dtype]
+
+
 def test_visual_subset_matches_oracle():
     cfg = CFG_BF16
     c = case_for(cfg)
