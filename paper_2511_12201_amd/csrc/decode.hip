@@ -35,6 +35,7 @@ constexpr int kUnroll = 4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kMinRowsPerSlice = 64;  // rows of one pass of a workgroup (bf16, d = 128)
 constexpr int kMaxSlices = 256;
+constexpr bool kMmaValues = true;    // bf16 group kernels: P.V on the matrix cores too (stream_rows_mma)
 
 struct DecodeParams {
   const void* q;
@@ -90,6 +91,197 @@ __device__ __forceinline__ float row_group_sum(float v) {
   return v;
 }
 
+template <int BYTES>
+__device__ __forceinline__ unsigned char* lds_block() {
+  __shared__ __attribute__((aligned(16))) unsigned char buf[BYTES];
+  return buf;
+}
+
+// bf16, 2..8 heads per workgroup: both products of a row block on the matrix cores.  A wavefront owns 32
+// consecutive list positions per trip and nothing in the loop is shared between wavefronts (no barriers):
+//  * S^T = K . q^T: the K rows are the A operand straight from memory (lane = row), the heads' queries the B
+//    operand (columns beyond GT are zero: the matrix cores are idle anyway).  Lane (n, h) of the accumulator
+//    then holds head n's scores of 16 of the 32 rows, so the online softmax is per-lane arithmetic plus one
+//    exchange with lane n + 32, and the weights are a B operand as they stand.
+//  * O^T += V^T . P^T: V rows go to a wavefront-private LDS tile as they come from memory (whole rows, coalesced)
+//    and are read back transposed, 2 bytes at a time, in the row order the accumulator layout dictates
+//    (k index 8 h + e of step s <-> row 16 s + 8 (e / 4) + 4 h + e % 4 on both operands).
+// Same contract as stream_rows below.
+template <int D, int GT, typename RowOf, typename MaskOf>
+__device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, int head0, int begin, int end,
+                                                RowOf row_of, MaskOf mask_of, unsigned head_bits, int slot,
+                                                const u16* krows, const u16* vrows, long long row_stride) {
+  constexpr int kWaves = kThreads / 64;
+  constexpr int CPR = D / 8;                 // 16-byte chunks of a row
+  constexpr int RPI = 64 / CPR;              // rows one load instruction of a wavefront covers
+  constexpr int NVL = 32 / RPI;              // V load instructions of a trip
+  constexpr int PITCH = D * 2 + 16;          // bytes between rows of the V tile: lanes n and n + 32 read rows 4 apart
+  constexpr int NB = D / 32;
+  constexpr int OP = D + 8;                  // floats between (wavefront, head) rows of the merge buffer
+  static_assert(kWaves * 8 * OP * 4 <= kWaves * 32 * PITCH, "the merge buffer reuses the V tiles");
+  // One LDS block per kernel whatever the list type: the instantiations for the different row_of / mask_of of a
+  // kernel are alternatives of which a workgroup runs one.
+  constexpr int kTileBytes = kWaves * 32 * PITCH;
+  unsigned char* sV = lds_block<kTileBytes + kWaves * (32 + 8 + 8) * 4>();
+  unsigned (*sMem)[32] = reinterpret_cast<unsigned (*)[32]>(sV + kTileBytes);
+  float (*sM)[8] = reinterpret_cast<float (*)[8]>(sV + kTileBytes + kWaves * 32 * 4);
+  float (*sL)[8] = reinterpret_cast<float (*)[8]>(sV + kTileBytes + kWaves * 40 * 4);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int n = lane & 31, h = lane >> 5;
+  const float c2 = p.scale * kLog2e;
+  unsigned char* tile = sV + wave * 32 * PITCH;
+
+  bf16x8 qf[D / 16];                         // B operand of the scores: column n = head, 8 elements of k chunk h
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (n < GT)
+      raw = *reinterpret_cast<const u32x4*>(static_cast<const u16*>(p.q) + (long long)(b * p.Hq + head0 + n) * D + ks * 16 + h * 8);
+    qf[ks] = __builtin_bit_cast(bf16x8, raw);
+  }
+  f32x16 o[NB];
+#pragma unroll
+  for (int db = 0; db < NB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+  float m = -INFINITY, l = 0.f;              // head n: running maximum (scaled), sum over this lane's rows
+
+  // cache row and member word of list position it0 + 32 wave + n (both lane halves hold it); -1 / 0: nothing to read
+  auto fetch_meta = [&](int it0, int& krow, unsigned& mem) {
+    const int it = it0 + wave * 32 + n;
+    krow = it < end ? row_of(it) : -1;
+    mem = krow >= 0 ? (mask_of(it) & head_bits) : 0u;
+    if (mem == 0u) krow = -1;
+  };
+  int krow = -1;
+  unsigned mem = 0u;
+  if (begin < end) fetch_meta(begin, krow, mem);
+
+  for (int it0 = begin; it0 < end; it0 += kWaves * 32) {
+    bf16x8 kf[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      u32x4 raw = {0u, 0u, 0u, 0u};
+      if (krow >= 0) raw = *reinterpret_cast<const u32x4*>(krows + (long long)krow * row_stride + ks * 16 + h * 8);
+      kf[ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+    u32x4 vraw[NVL];
+#pragma unroll
+    for (int j = 0; j < NVL; ++j) {
+      const int vr = __shfl(krow, j * RPI + lane / CPR, 64);
+      vraw[j] = u32x4{0u, 0u, 0u, 0u};
+      if (vr >= 0) vraw[j] = *reinterpret_cast<const u32x4*>(vrows + (long long)vr * row_stride + (lane % CPR) * 8);
+    }
+    if (h == 0) sMem[wave][n] = mem;
+    // list lookups of the next trip: a row's address depends on its entry, two dependent latencies would add up
+    int krow_n = -1;
+    unsigned mem_n = 0u;
+    if (it0 + kWaves * 32 < end) fetch_meta(it0 + kWaves * 32, krow_n, mem_n);
+
+    f32x16 sacc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < NVL; ++j)
+      *reinterpret_cast<u32x4*>(tile + (j * RPI + lane / CPR) * PITCH + (lane % CPR) * 16) = vraw[j];
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");        // same wavefront: LDS operations complete in order
+
+    // accumulator register i: row 8 (i / 4) + 4 h + i % 4 of the block, head n
+    float sc[16], mx = m;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const u32x4 mw = *reinterpret_cast<const u32x4*>(&sMem[wave][8 * q4 + 4 * h]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = q4 * 4 + e;
+        sc[i] = ((mw[e] >> n) & 1u) ? sacc[i] * c2 : -INFINITY;
+        mx = fmaxf(mx, sc[i]);
+      }
+    }
+    mx = pair_max(mx);
+    const float mref = mx == -INFINITY ? 0.f : mx;
+    const float alpha = mx == m ? 1.f : fast_exp2(m - mref);   // m = -inf -> 0
+    float pw[16], ps = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      pw[i] = fast_exp2(sc[i] - mref);
+      ps += pw[i];
+    }
+    l = fmaf(l, alpha, ps);
+    m = mx;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int db = 0; db < NB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    }
+    union { bf16x8 v[2]; unsigned w[8]; } pf;
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) pf.w[i / 2] = pack_bf16x2(pw[i], pw[i + 1]);
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int db = 0; db < NB; ++db) {
+        bf16x8 vf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          vf[e] = *reinterpret_cast<const __bf16*>(tile + (16 * s2 + 8 * (e / 4) + 4 * h + e % 4) * PITCH + (32 * db + n) * 2);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v[s2], o[db], 0, 0, 0);
+      }
+    krow = krow_n;
+    mem = mem_n;
+  }
+
+  if (begin >= end) {                       // empty slice: mark it, the combine pass skips its output row
+    if (threadIdx.x < GT) {
+      float* dst = p.part + ((long long)(b * p.Hq + head0 + threadIdx.x) * (p.n_shared + p.n_head) + slot) * (D + 2);
+      dst[D] = -INFINITY;
+      dst[D + 1] = 0.f;
+    }
+    return;
+  }
+  // merge the wavefronts in wavefront order, one (head, d) per thread
+  const float l_tot = pair_sum(l);
+  __syncthreads();                          // everyone is done with its V tile: the merge buffer takes its place
+  float* sO = reinterpret_cast<float*>(sV);
+  if (n < GT) {
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 v = {o[db][q4 * 4], o[db][q4 * 4 + 1], o[db][q4 * 4 + 2], o[db][q4 * 4 + 3]};
+        *reinterpret_cast<f32x4*>(sO + (wave * GT + n) * OP + 32 * db + 8 * q4 + 4 * h) = v;
+      }
+    if (h == 0) {
+      sM[wave][n] = m;
+      sL[wave][n] = l_tot;
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < GT * D; idx += kThreads) {
+    const int hh = idx / D, d = idx % D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sM[w][hh]);
+    const float Mr = M == -INFINITY ? 0.f : M;
+    float Ls = 0.f, Os = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float wgt = sM[w][hh] == -INFINITY ? 0.f : exp2f(sM[w][hh] - Mr);
+      Ls = fmaf(sL[w][hh], wgt, Ls);
+      Os = fmaf(sO[(w * GT + hh) * OP + d], wgt, Os);
+    }
+    float* dst = p.part + ((long long)(b * p.Hq + head0 + hh) * (p.n_shared + p.n_head) + slot) * (D + 2);
+    dst[d] = Os;
+    if (d == 0) {
+      dst[D] = M;
+      dst[D + 1] = Ls;
+    }
+  }
+}
+
 // Streams the rows [begin, end) of a virtual row list for GT heads at once and leaves the merged
 // partial state of the workgroup in part[head][slot].  row_of maps a list position to a cache row
 // or -1.  Every thread of the workgroup must call it (it contains barriers).
@@ -108,6 +300,10 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
   // the lane groups, which own the rows for the softmax and the V side, through a wavefront-private LDS tile.
   // Otherwise every lane group forms its rows' dot products itself.
   constexpr bool kMfma = sizeof(T) == 2 && GT >= 2 && GT <= 8;
+  if constexpr (kMfma && kMmaValues) {
+    stream_rows_mma<D, GT>(p, b, head0, begin, end, row_of, mask_of, head_bits, slot, krows, vrows, row_stride);
+    return;
+  }
   constexpr int GPW = 64 / LPR;                     // lane groups (rows per pass) of a wavefront
   constexpr int U = kMfma ? 32 / GPW : kUnroll;     // rows per lane group and trip
   static_assert(U % kUnroll == 0, "a trip is consumed in chunks of kUnroll rows");
@@ -530,7 +726,7 @@ int group_tile(int G) {
 // batch 1).  Otherwise the shared rows only (plain decode; per-head lists, whose one-head workgroups need half
 // the registers and lose their occupancy inside a common kernel: 70 -> 84 us when fused).
 template <typename T, int D, int GT, bool GROUP>
-__global__ __launch_bounds__(kThreads) void decode_rows_kernel(DecodeParams p) {
+__global__ __launch_bounds__(kThreads, 2) void decode_rows_kernel(DecodeParams p) {
   const int units_s = p.B * p.Hkv * (p.G / GT);
   const int n_list = GROUP ? p.n_head * units_s : 0;
   const int i = blockIdx.x;
