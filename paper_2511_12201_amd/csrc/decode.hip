@@ -35,7 +35,6 @@ constexpr int kUnroll = 4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kMinRowsPerSlice = 64;  // rows of one pass of a workgroup (bf16, d = 128)
 constexpr int kMaxSlices = 256;
-constexpr bool kMmaValues = true;    // bf16 group kernels: P.V on the matrix cores too (stream_rows_mma)
 
 struct DecodeParams {
   const void* q;
@@ -295,43 +294,25 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
   constexpr int E = Elem<T>::kPer16B;
   constexpr int LPR = D / E;              // lanes per row
   constexpr int RPP = kThreads / LPR;     // lane groups = rows per pass
-  // bf16 with several heads per workgroup: the scores of 32 rows x GT heads are one chain of MFMAs per
-  // wavefront (K rows as the A operand straight from memory, the heads' queries as the B operand) and reach
-  // the lane groups, which own the rows for the softmax and the V side, through a wavefront-private LDS tile.
-  // Otherwise every lane group forms its rows' dot products itself.
-  constexpr bool kMfma = sizeof(T) == 2 && GT >= 2 && GT <= 8;
-  if constexpr (kMfma && kMmaValues) {
+  // bf16 with 2..8 heads per workgroup: both products on the matrix cores.  Otherwise (fp32, one head, more than
+  // 8 heads) every lane group forms its rows' dot products and weighted sums on the vector ALU.
+  if constexpr (sizeof(T) == 2 && GT >= 2 && GT <= 8) {
     stream_rows_mma<D, GT>(p, b, head0, begin, end, row_of, mask_of, head_bits, slot, krows, vrows, row_stride);
     return;
   }
-  constexpr int GPW = 64 / LPR;                     // lane groups (rows per pass) of a wavefront
-  constexpr int U = kMfma ? 32 / GPW : kUnroll;     // rows per lane group and trip
-  static_assert(U % kUnroll == 0, "a trip is consumed in chunks of kUnroll rows");
+  constexpr int U = kUnroll;              // rows per lane group and trip
   __shared__ float sM[GT][RPP], sL[GT][RPP];
   __shared__ float sO[RPP][D];
-  __shared__ __attribute__((aligned(16))) float sS[kMfma ? kThreads / 64 : 1][kMfma ? 32 : 1][8];
   const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const T* kbase = krows + c * E;
   const T* vbase = vrows + c * E;
   const float c2 = p.scale * kLog2e;
 
-  u32x4 qraw[kMfma ? 1 : GT];
-  bf16x8 qf[kMfma ? D / 16 : 1];
-  if constexpr (kMfma) {
-    const int n = lane & 31, h = lane >> 5;         // B operand: column n = head, 8 elements of the k chunk h
+  u32x4 qraw[GT];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) {
-      u32x4 raw = {0u, 0u, 0u, 0u};
-      if (n < GT)
-        raw = *reinterpret_cast<const u32x4*>(static_cast<const T*>(p.q) + (long long)(b * p.Hq + head0 + n) * D + ks * 16 + h * 8);
-      qf[ks] = __builtin_bit_cast(bf16x8, raw);
-    }
-  } else {
-#pragma unroll
-    for (int h = 0; h < GT; ++h)
-      qraw[h] = *reinterpret_cast<const u32x4*>(static_cast<const T*>(p.q) + (long long)(b * p.Hq + head0 + h) * D + c * E);
-  }
+  for (int h = 0; h < GT; ++h)
+    qraw[h] = *reinterpret_cast<const u32x4*>(static_cast<const T*>(p.q) + (long long)(b * p.Hq + head0 + h) * D + c * E);
   float m[GT], l[GT], acc[GT][E];
 #pragma unroll
   for (int h = 0; h < GT; ++h) {
@@ -377,103 +358,47 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
 
   // rows (and member bits) of a trip: list lookups, so they are fetched one trip ahead of the rows themselves --
   // a row's address depends on its list entry, and two dependent memory latencies per trip would otherwise add up
-  auto fetch_meta = [&](int it0, int (&row)[U], unsigned (&member)[U], int& krow) {
+  auto fetch_meta = [&](int it0, int (&row)[U], unsigned (&member)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      // MFMA: a wavefront owns 32 consecutive list positions, pass u covers GPW of them
-      const int it = kMfma ? it0 + wave * 32 + u * GPW + (grp % GPW) : it0 + u * RPP + grp;
+      const int it = it0 + u * RPP + grp;
       row[u] = it < end ? row_of(it) : -1;
       member[u] = (it < end && row[u] >= 0) ? (mask_of(it) & head_bits) : 0u;
       if (member[u] == 0u) row[u] = -1;                     // nobody wants it: not loaded
     }
-    krow = -1;
-    if constexpr (kMfma) {                                  // the K row this lane holds as MFMA A operand
-      const int itk = it0 + wave * 32 + (lane & 31);
-      krow = itk < end ? row_of(itk) : -1;
-      if (krow >= 0 && (mask_of(itk) & head_bits) == 0u) krow = -1;
-    }
   };
-  int row[U], krow;
+  int row[U];
   unsigned member[U];
-  if (begin < end) fetch_meta(begin, row, member, krow);
+  if (begin < end) fetch_meta(begin, row, member);
 
   for (int it0 = begin; it0 < end; it0 += RPP * U) {      // uniform trip count over the workgroup
-    u32x4 vraw[U];
-    int row_n[U], krow_n = -1;
+    u32x4 kraw[U], vraw[U];
+    int row_n[U];
     unsigned member_n[U];
-    if constexpr (kMfma) {
-      // K rows of the wavefront's block as the A operand: lane (r, h) holds elements 16 ks + 8 h .. + 7 of row r
-      const int r = lane & 31, h = lane >> 5;
-      bf16x8 kf[D / 16];
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        u32x4 raw = {0u, 0u, 0u, 0u};
-        if (krow >= 0) raw = *reinterpret_cast<const u32x4*>(krows + (long long)krow * row_stride + ks * 16 + h * 8);
-        kf[ks] = __builtin_bit_cast(bf16x8, raw);
+    for (int u = 0; u < U; ++u) {
+      kraw[u] = u32x4{0u, 0u, 0u, 0u};
+      vraw[u] = u32x4{0u, 0u, 0u, 0u};
+      if (row[u] >= 0) {
+        const long long off = (long long)row[u] * row_stride;
+        kraw[u] = *reinterpret_cast<const u32x4*>(kbase + off);
+        vraw[u] = *reinterpret_cast<const u32x4*>(vbase + off);
       }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        vraw[u] = u32x4{0u, 0u, 0u, 0u};
-        if (row[u] >= 0) vraw[u] = *reinterpret_cast<const u32x4*>(vbase + (long long)row[u] * row_stride);
-      }
-      if (it0 + RPP * U < end) fetch_meta(it0 + RPP * U, row_n, member_n, krow_n);
-      f32x16 sacc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
-      // accumulator register i of lane (n, h): row 8 (i / 4) + 4 h + i % 4 of the block, head n
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the previous trip's reads of the tile are done
-      if (r < 8) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sS[wave][8 * (i >> 2) + 4 * h + (i & 3)][r] = sacc[i];
-      }
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // same wavefront: LDS operations complete in order
-#pragma unroll
-      for (int half = 0; half < U / kUnroll; ++half) {
-        float s[GT][kUnroll];
-        u32x4 vpart[kUnroll];
-        unsigned mpart[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-          const int uu = half * kUnroll + u;
-          const float* srow = sS[wave][uu * GPW + (grp % GPW)];
-          const f32x4 lo = *reinterpret_cast<const f32x4*>(srow), hi = *reinterpret_cast<const f32x4*>(srow + 4);
-#pragma unroll
-          for (int hh = 0; hh < GT; ++hh) s[hh][u] = hh < 4 ? lo[hh] : hi[hh - 4];
-          vpart[u] = vraw[uu];
-          mpart[u] = member[uu];
-        }
-        consume(s, vpart, mpart);
-      }
-    } else {
-      u32x4 kraw[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        kraw[u] = u32x4{0u, 0u, 0u, 0u};
-        vraw[u] = u32x4{0u, 0u, 0u, 0u};
-        if (row[u] >= 0) {
-          const long long off = (long long)row[u] * row_stride;
-          kraw[u] = *reinterpret_cast<const u32x4*>(kbase + off);
-          vraw[u] = *reinterpret_cast<const u32x4*>(vbase + off);
-        }
-      }
-      if (it0 + RPP * U < end) fetch_meta(it0 + RPP * U, row_n, member_n, krow_n);
-      float s[GT][kUnroll];
-#pragma unroll
-      for (int h = 0; h < GT; ++h) {
-        if (!((head_bits >> h) & 1u)) continue;
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) s[h][u] = row_group_sum<LPR>(chunk_dot(qraw[h], kraw[u], (const T*)nullptr));
-      }
-      consume(s, vraw, member);
     }
+    if (it0 + RPP * U < end) fetch_meta(it0 + RPP * U, row_n, member_n);
+    float s[GT][kUnroll];
+#pragma unroll
+    for (int h = 0; h < GT; ++h) {
+      if (!((head_bits >> h) & 1u)) continue;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) s[h][u] = row_group_sum<LPR>(chunk_dot(qraw[h], kraw[u], (const T*)nullptr));
+    }
+    consume(s, vraw, member);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       row[u] = row_n[u];
       member[u] = member_n[u];
     }
-    krow = krow_n;
   }
 
   if (begin >= end) {                       // empty slice: mark it, the combine pass skips its output row
