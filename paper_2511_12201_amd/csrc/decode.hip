@@ -35,6 +35,7 @@ constexpr int kUnroll = 4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kMinRowsPerSlice = 64;  // rows of one pass of a workgroup (bf16, d = 128)
 constexpr int kMaxSlices = 256;
+constexpr int kRowBlocks = 768;        // workgroups a row-streaming launch aims for: three per CU
 
 struct DecodeParams {
   const void* q;
@@ -121,7 +122,9 @@ __device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, in
   // One LDS block per kernel whatever the list type: the instantiations for the different row_of / mask_of of a
   // kernel are alternatives of which a workgroup runs one.
   constexpr int kTileBytes = kWaves * 32 * PITCH;
-  unsigned char* sV = lds_block<kTileBytes + kWaves * (32 + 8 + 8) * 4>();
+  constexpr int QP = D * 2 + 16;             // bytes between the heads' queries in LDS
+  unsigned char* sV = lds_block<kTileBytes + kWaves * (32 + 8 + 8) * 4 + 8 * QP>();
+  unsigned char* sQ = sV + kTileBytes + kWaves * 48 * 4;
   unsigned (*sMem)[32] = reinterpret_cast<unsigned (*)[32]>(sV + kTileBytes);
   float (*sM)[8] = reinterpret_cast<float (*)[8]>(sV + kTileBytes + kWaves * 32 * 4);
   float (*sL)[8] = reinterpret_cast<float (*)[8]>(sV + kTileBytes + kWaves * 40 * 4);
@@ -130,14 +133,17 @@ __device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, in
   const float c2 = p.scale * kLog2e;
   unsigned char* tile = sV + wave * 32 * PITCH;
 
-  bf16x8 qf[D / 16];                         // B operand of the scores: column n = head, 8 elements of k chunk h
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
+  // The queries, B operand of the scores (column n = head, 8 elements of k chunk h), are re-read from LDS every
+  // trip: resident they cost 32 registers, a third wavefront per SIMD is worth more.  Columns beyond GT read
+  // zero rows or another head's row; the member words mask them either way.
+  for (int idx = threadIdx.x; idx < 8 * CPR; idx += kThreads) {
+    const int hh = idx / CPR, c = idx % CPR;
     u32x4 raw = {0u, 0u, 0u, 0u};
-    if (n < GT)
-      raw = *reinterpret_cast<const u32x4*>(static_cast<const u16*>(p.q) + (long long)(b * p.Hq + head0 + n) * D + ks * 16 + h * 8);
-    qf[ks] = __builtin_bit_cast(bf16x8, raw);
+    if (hh < GT) raw = *reinterpret_cast<const u32x4*>(static_cast<const u16*>(p.q) + (long long)(b * p.Hq + head0 + hh) * D + c * 8);
+    *reinterpret_cast<u32x4*>(sQ + hh * QP + c * 16) = raw;
   }
+  __syncthreads();
+  const unsigned char* qlane = sQ + (n & 7) * QP + h * 16;
   f32x16 o[NB];
 #pragma unroll
   for (int db = 0; db < NB; ++db)
@@ -181,7 +187,7 @@ __device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, in
 #pragma unroll
     for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
+    for (int ks = 0; ks < D / 16; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], *reinterpret_cast<const bf16x8*>(qlane + ks * 32), sacc, 0, 0, 0);
 #pragma unroll
     for (int j = 0; j < NVL; ++j)
       *reinterpret_cast<u32x4*>(tile + (j * RPI + lane / CPR) * PITCH + (lane % CPR) * 16) = vraw[j];
@@ -651,7 +657,7 @@ int group_tile(int G) {
 // batch 1).  Otherwise the shared rows only (plain decode; per-head lists, whose one-head workgroups need half
 // the registers and lose their occupancy inside a common kernel: 70 -> 84 us when fused).
 template <typename T, int D, int GT, bool GROUP>
-__global__ __launch_bounds__(kThreads, 2) void decode_rows_kernel(DecodeParams p) {
+__global__ __launch_bounds__(kThreads, 3) void decode_rows_kernel(DecodeParams p) {
   const int units_s = p.B * p.Hkv * (p.G / GT);
   const int n_list = GROUP ? p.n_head * units_s : 0;
   const int i = blockIdx.x;
@@ -726,7 +732,7 @@ Slices decode_slices(const omni_decode_desc* d, bool slim) {
   const long long shared_rows = slim ? (long long)d->cache_capacity - (d->vis_end - d->vis_begin) : d->cache_capacity;
   // two workgroups per CU: with more, the merge of a workgroup's lane groups and the slice combine weigh more
   // than the parallelism gains (plain decode at batch 1: 89 us with 1024 workgroups, 75 us with 512)
-  s.n_shared = slices_for(shared_rows, units, 512);
+  s.n_shared = slices_for(shared_rows, units, kRowBlocks);
   // only the active heads (typically a quarter) have rows to read, so aim higher
   s.n_head = slim ? slices_for(d->vis_end - d->vis_begin, d->batch * d->n_q_heads, 8192) : 0;
   return s;
@@ -837,7 +843,7 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
   p.n_head = s.n_head;
   if (grp_mask) {            // group lists: one workgroup serves all heads of a group, so fewer, longer slices do
     const int units = p.B * p.Hkv * (p.G / group_tile(p.G));
-    p.n_head = std::min(s.n_head, slices_for(d->vis_end - d->vis_begin, units, 512));
+    p.n_head = std::min(s.n_head, slices_for(d->vis_end - d->vis_begin, units, kRowBlocks));
   }
   p.scale = d->softmax_scale;
   p.tau = d->tau;
