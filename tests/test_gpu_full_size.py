@@ -107,6 +107,37 @@ def test_c3_64k_selection_and_forward_on_sampled_rows():
         assert np.all(np.isfinite(Lg[0, h, kept]))       # the sink key is selected, so every kept query sees a key
 
 
+def test_c3_64k_block_lists_in_place_equal_the_gathered_path():
+    """Block lists at the bench's granularity (256) on the 64k layer: the in-place kernel against expand + gather,
+    bit for bit, and sampled rows of it against the oracle."""
+    cfg = synth.C3_64K
+    c = FullCase.get(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    block = 256
+    nb = N // block
+    rng = np.random.default_rng(59)
+    nsel = int(0.6 * nb)
+    lists = [[np.sort(np.concatenate([[0], 1 + rng.choice(nb - 1, nsel - 1, replace=False)])).astype(np.int32)
+              for _ in range(H)]]
+    blk_idx, _ = lists_to_padded(lists, H, nb)
+    blk_budget = torch.tensor([nsel], dtype=torch.int32, device="cuda")
+    q_idx, q_cnt = lists_to_padded(c.q_lists, H, N)
+    O1, lse1 = ob.omni_block_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, blk_idx, blk_budget, block)
+    kv_idx, budget = ob.omni_expand_blocks(c.desc, blk_idx, blk_budget, block)
+    O2, lse2 = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, budget, kv_idx.shape[-1])
+    torch.cuda.synchronize()
+    assert torch.equal(O1.view(torch.int16), O2.view(torch.int16))
+    assert torch.equal(lse1.view(torch.int32), lse2.view(torch.int32))
+    tok = oc.expand_blocks(lists, block, N)
+    samples = [[_sample_queries(rng, c.q_lists[0][h], 3) for h in range(H)]]
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, samples, tok, cfg.causal, cfg.scale)
+    Og, Lg = to_host(O1), to_host(lse1)
+    for h in range(H):
+        rows = samples[0][h]
+        assert np.max(np.abs(Og[0, h, rows] - Oo[0, h, rows])) <= TOL
+        assert np.max(np.abs(Lg[0, h, rows] - Lo[0, h, rows])) <= 2e-3
+
+
 def test_c4_32k_backward_on_sampled_rows_and_sums_over_all_keys():
     cfg = synth.C4_TRAIN_32K
     c = FullCase.get(cfg)
@@ -208,3 +239,37 @@ def test_c5_131k_decode_step():
     assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= TOL
     Odo = oc.dense_decode(q, Kc, Vc, ctx, cfg.scale)
     assert np.max(np.abs(to_host(Od) - Odo)) <= TOL
+    # the same lists as group unions: gathered from the cache, from the compacted store, from the paged store
+    shape_only = torch.empty((batch, H, N, D), dtype=torch.bfloat16, device="meta")
+    ldesc = ob.make_layer_desc(shape_only, torch.empty((batch, Hkv, N, D), dtype=torch.bfloat16, device="meta"),
+                               cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset(ldesc, vis_idx, vis_cnt, b, _per_head=True)
+    u_max = int(grp_cnt.max().cpu())
+    grp_idx, grp_mask = grp_idx[:, :, :u_max].contiguous(), grp_mask[:, :, :u_max].contiguous()
+    Og, actg = ob.omni_slim_decode_grouped(desc, dq, dKc, dVc, dctx, dprobe, grp_idx, grp_mask, grp_cnt)
+    Kcomp, Vcomp = ob.omni_compact_cache(desc, dKc, dVc, grp_idx, grp_cnt)
+    page_rows = 256
+    need = ((grp_cnt + page_rows - 1) // page_rows).cpu().numpy()
+    n_pages = int(need.sum())
+    perm = np.random.default_rng(53).permutation(n_pages).astype(np.int32)
+    table = np.full((batch, Hkv, -(-u_max // page_rows)), -1, dtype=np.int32)
+    used = 0
+    for bb in range(batch):
+        for g in range(Hkv):
+            table[bb, g, : need[bb, g]] = perm[used: used + need[bb, g]]
+            used += int(need[bb, g])
+    Kpool = torch.empty(n_pages, page_rows, D, dtype=torch.bfloat16, device="cuda")
+    Vpool = torch.empty_like(Kpool)
+    pool = ob.make_page_pool(Kpool, Vpool, torch.from_numpy(table).cuda())
+    ob.omni_compact_cache_paged(desc, dKc, dVc, grp_idx, grp_cnt, pool)
+    dKc[:, :, cfg.vis_begin:cfg.vis_end] = float("nan")         # the visual rows of the cache are not needed any more
+    dVc[:, :, cfg.vis_begin:cfg.vis_end] = float("nan")
+    Oc, actc = ob.omni_slim_decode_compact(desc, dq, dKc, dVc, dctx, dprobe, Kcomp, Vcomp, grp_idx, grp_mask, grp_cnt)
+    Op, actp = ob.omni_slim_decode_paged(desc, dq, dKc, dVc, dctx, dprobe, pool, grp_idx, grp_mask, grp_cnt)
+    torch.cuda.synchronize()
+    for Ox, actx in ((Og, actg), (Oc, actc), (Op, actp)):
+        np.testing.assert_array_equal(to_host(actx), act)
+        got = to_host(Ox)
+        assert np.all(np.isfinite(got))
+        assert np.max(np.abs(got[same] - Oo[same])) <= TOL
+    assert torch.equal(Og.view(torch.int16), Oc.view(torch.int16)) and torch.equal(Oc.view(torch.int16), Op.view(torch.int16))
