@@ -15,12 +15,13 @@
 //    what turns fewer rows per head into fewer bytes from HBM, since the plain decode already
 //    shares every row between the heads of a group.
 //
-// A cache row is read by D*sizeof(T)/16 lanes (a lane group) with one 16-byte load for V, and for K
-// too where the lane group forms the row's dot products itself (fp32 inputs; one head per workgroup).
-// bf16 with several heads per workgroup: the scores of 32 rows x all heads are one chain of MFMAs per
-// wavefront, with the K rows loaded in fragment layout.  Every lane group keeps an online-softmax
-// state per head; groups, then slices, are merged with the usual (max, sum, weighted output) rule in
-// a fixed order, so results are bitwise reproducible.
+// bf16 with 2..8 heads per workgroup (stream_rows_mma): a wavefront takes 32 rows per trip and forms both
+// products on the matrix cores -- K rows loaded in fragment layout, V rows transposed through a
+// wavefront-private LDS tile, the online softmax in the accumulator layout.  Otherwise (fp32 inputs, one
+// head per workgroup) a cache row is read by D*sizeof(T)/16 lanes (a lane group) with one 16-byte load
+// each for K and V, and the lane group forms the row's dot products and weighted sums on the vector ALU.
+// Wavefronts (or lane groups), then slices, are merged with the usual (max, sum, weighted output) rule
+// in a fixed order, so results are bitwise reproducible.
 #include "common.h"
 #include "kernels.h"
 
