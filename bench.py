@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--only", choices=["train", "decode"],
                     help="run just the training-step or the decode extra and print its JSON (for profiling; the "
                          "headline line is the default run)")
+    ap.add_argument("--decode-steps", type=int, default=256, help="with --only decode: decode steps per mode")
+    ap.add_argument("--decode-modes", default="", help="with --only decode: comma-separated subset of "
+                    "slim,slim_grouped,slim_compact,slim_paged,dense (for counter runs; prints the times only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known HBM traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -80,7 +83,9 @@ def main():
         sys.exit(1)
     ob.load_library()
     if args.only:
-        fn = bench_train if args.only == "train" else (lambda *a: bench_decode(*a, batches=(1, 8)))
+        modes = tuple(m for m in args.decode_modes.split(",") if m) or DECODE_MODES
+        fn = bench_train if args.only == "train" else (
+            lambda *a: bench_decode(*a, n_steps=args.decode_steps, batches=(1, 8), modes=modes))
         print(json.dumps({args.only: fn(torch, ob, synth)}), flush=True)
         return
     cfg = synth.C3_64K if args.workload == "c3_64k" else synth.C2_16K
@@ -447,7 +452,10 @@ def bench_train(torch, ob, synth, steps: int = 5, per_head: bool = False):
     return res
 
 
-def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, batches=(1, 2, 4, 8)):
+DECODE_MODES = ("slim", "slim_grouped", "slim_compact", "slim_paged", "dense")
+
+
+def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, batches=(1, 2, 4, 8), modes=DECODE_MODES):
     """Decode with KV cache slimming on a 131072-token cache, batch 1..8, 256 steps each."""
     cfg = synth.C5_DECODE_131K
     layer = synth.make_layer(cfg)
@@ -520,7 +528,7 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
         pool = ob.make_page_pool(Kpool, Vpool, torch.from_numpy(table).cuda())
         ob.omni_compact_cache_paged(ddesc, Kc, Vc, g_idx_c, grp_cnt, pool)
         timing, ktime = {}, {}
-        for mode in ("slim", "slim_grouped", "slim_compact", "slim_paged", "dense"):
+        for mode in modes:
             ctx.fill_(N + 1)
             for _ in range(3):                                    # untimed warm-up of both entry points
                 ob.omni_slim_decode_grouped(ddesc, q_all[0], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act)
@@ -551,6 +559,11 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
             kms, kn = ob.profile_read("decode")                               # last 64 launches: row-streaming kernels only
             ktime[mode] = kms * 1e3 / max(1, kn)
             ob.profile_enable(False)
+        if set(modes) != set(DECODE_MODES):               # a counter run on some of the modes: times only
+            res["per_batch"][str(B)] = {f"{k}_us_per_token": round(v, 2) for k, v in ktime.items()}
+            del Kc, Vc, Kpool, Vpool, Kcomp, Vcomp
+            torch.cuda.empty_cache()
+            continue
         # K/V rows a step asks for (last step's activity).  Plain decode: every row once per KV group.  Slimmed
         # decode with per-head lists: every active head its own stored visual rows (heads of a group that store
         # the same row both ask for it), plus the non-visual rows once per group.  Grouped lists: the union over
