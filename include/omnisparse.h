@@ -483,17 +483,23 @@ int omni_profile_read(int kernel_id, float* total_ms /* host */, int* launches /
 /*
  * Diagnostic, host only: the work list the query-tile kernels (attention forward,
  * backward dQ) build on the device, computed by the same rule on the host.  Work item
- * = one tile of tile_rows (128 or 256) kept queries of a head; the items are handed
- * out longest first from one atomic counter, the cost of an item being the number of
+ * = one tile of tile_rows (128 or 256) kept queries of a head, its cost the number of
  * 64-key tiles it streams (estimated here from the position of the tile; the device
- * uses exact counts where it has them).  All pointers are HOST pointers.  q_cnt
- * [batch * n_q_heads] (null: every head keeps n_tokens rows), budget [batch] (null:
- * n_tokens); item_head / item_tile / item_cost [capacity] out, in hand-out order;
- * n_items out.  OMNI_ERR_WORKSPACE if capacity is too small (n_items is still written).
+ * uses exact counts where it has them).  queues = 1: one list, longest item first,
+ * handed out from one atomic counter.  queues = 8 (the sparse bf16 forward): one list
+ * per XCD -- whole heads are placed on queues, largest head first onto the least loaded
+ * queue; inside a queue head follows head, each longest item first; a workgroup takes
+ * from its XCD's queue and, once that is drained, from the queue with the most items left.  All pointers are
+ * HOST pointers.  q_cnt [batch * n_q_heads] (null: every head keeps n_tokens rows),
+ * budget [batch] (null: n_tokens); item_head / item_tile / item_cost [capacity] out,
+ * queue after queue in hand-out order; queue_end [8] out (nullable): queue q is the
+ * positions [queue_end[q-1], queue_end[q]); n_items out.  OMNI_ERR_WORKSPACE if
+ * capacity is too small (n_items is still written).
  */
 int omni_debug_work_list(const omni_layer_desc* desc, const int32_t* q_cnt, const int32_t* budget,
-                         int32_t b_cap, int32_t tile_rows, int32_t* item_head, int32_t* item_tile,
-                         int32_t* item_cost, int32_t capacity, int32_t* n_items);
+                         int32_t b_cap, int32_t tile_rows, int32_t queues, int32_t* item_head,
+                         int32_t* item_tile, int32_t* item_cost, int32_t capacity, int32_t* n_items,
+                         int32_t* queue_end);
 
 /*
  * Diagnostic: copy `bytes` (a positive multiple of 16) from src to dst, both DEVICE pointers

@@ -130,7 +130,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_debug_copy.argtypes = [vp, vp, sz, vp]
     lib.omni_debug_key_split_len.argtypes = [C.c_int]
     lib.omni_debug_mfma_rate.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
-    lib.omni_debug_work_list.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, i32, vp]   # same shape: three output arrays
+    lib.omni_debug_work_list.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, vp]   # same shape: three output arrays
     lib.omni_profile_read.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
     for name in EXPORTED:
         fn = getattr(lib, name)
@@ -197,8 +197,9 @@ def make_decode_desc(q: torch.Tensor, Kcache: torch.Tensor, vis_begin: int, vis_
     return d
 
 
-def debug_work_list(desc: LayerDesc, q_cnt=None, budget=None, b_cap: int = 1, tile_rows: int = 128):
-    """Host mirror of the device work list: (item_head[n], item_tile[n], item_cost[n]) in hand-out order."""
+def debug_work_list(desc: LayerDesc, q_cnt=None, budget=None, b_cap: int = 1, tile_rows: int = 128, queues: int = 1):
+    """Host mirror of the device work list: (item_head[n], item_tile[n], item_cost[n]) in hand-out order, queue after
+    queue; with queues > 1 also the end position of every queue."""
     import numpy as np
     lib = load_library()
     cap = desc.batch * desc.n_q_heads * ((desc.n_tokens + 127) // 128)
@@ -208,9 +209,12 @@ def debug_work_list(desc: LayerDesc, q_cnt=None, budget=None, b_cap: int = 1, ti
     n = C.c_int32(0)
     qc = None if q_cnt is None else np.ascontiguousarray(q_cnt, dtype=np.int32)
     bd = None if budget is None else np.ascontiguousarray(budget, dtype=np.int32)
+    qend = np.zeros(8, dtype=np.int32)
     _check(lib.omni_debug_work_list(C.byref(desc), None if qc is None else qc.ctypes.data,
-                                    None if bd is None else bd.ctypes.data, b_cap, tile_rows, head.ctypes.data,
-                                    tile.ctypes.data, cost.ctypes.data, cap, C.byref(n)))
+                                    None if bd is None else bd.ctypes.data, b_cap, tile_rows, queues, head.ctypes.data,
+                                    tile.ctypes.data, cost.ctypes.data, cap, C.byref(n), qend.ctypes.data))
+    if queues > 1:
+        return head[: n.value], tile[: n.value], cost[: n.value], qend
     return head[: n.value], tile[: n.value], cost[: n.value]
 
 

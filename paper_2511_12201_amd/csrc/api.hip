@@ -159,19 +159,22 @@ extern "C" {
 const char* omni_last_error(void) { return g_err; }
 
 int omni_debug_work_list(const omni_layer_desc* desc, const int32_t* q_cnt, const int32_t* budget, int32_t b_cap,
-                         int32_t tile_rows, int32_t* item_head, int32_t* item_tile, int32_t* item_cost, int32_t capacity,
-                         int32_t* n_items) {
+                         int32_t tile_rows, int32_t queues, int32_t* item_head, int32_t* item_tile, int32_t* item_cost,
+                         int32_t capacity, int32_t* n_items, int32_t* queue_end) {
   clear_error();
   CHECK(validate_layer(desc));
   REQUIRE_PTR(item_head); REQUIRE_PTR(item_tile); REQUIRE_PTR(item_cost); REQUIRE_PTR(n_items);
   if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
   if (tile_rows != 128 && tile_rows != 256) OMNI_FAIL(OMNI_ERR_INVALID, "tile_rows must be 128 or 256");
+  if (queues != 1 && queues != kSchedQueues) OMNI_FAIL(OMNI_ERR_INVALID, "queues must be 1 or %d", kSchedQueues);
   const int BH = desc->batch * desc->n_q_heads;
   std::vector<int> sched(sched_ints(BH, desc->n_tokens, tile_rows));
   sched_build_host(q_cnt, budget, desc->batch, desc->n_q_heads, desc->n_tokens, b_cap, desc->causal, tile_rows,
-                   sched.data());
+                   sched.data(), queues);
   const int items = sched[kSchedTotal];
   *n_items = items;
+  if (queue_end)
+    for (int q = 0; q < kSchedQueues; ++q) queue_end[q] = sched[kSchedEnd + q];
   if (items > capacity) OMNI_FAIL(OMNI_ERR_WORKSPACE, "work list has %d items, capacity is %d", items, capacity);
   const size_t order_off = sched_order_off(BH, desc->n_tokens, tile_rows);
   for (int it = 0; it < items; ++it) {

@@ -814,7 +814,12 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   constexpr bool kFast = sizeof(T) == 2;
   {
     p.order_off = sched_order_off(L.B * L.Hq, L.N, kFast ? kFastTileM : kTileM);
-    int rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kFastTileM : kTileM, w.qvis, w.sched, st);
+    // Per-head gathered K/V: one queue per XCD, so that the workgroups on a head share its tiles in that XCD's L2
+    // (16.2 -> 5.3 GB from beyond L2 per launch at 64k, at the same kernel time).  The dense baseline and the
+    // in-place block lists read one copy per KV group, which the heads of a group already share: splitting them
+    // over queues only costs (25.7 -> 25.9 ms dense).
+    int rc = run_schedule(L, q_cnt, budget, b_cap, kFast ? kFastTileM : kTileM, w.qvis, w.sched, st,
+                          kFast && sparse ? kSchedQueues : 1);
     if (rc != OMNI_OK) return rc;
   }
   {

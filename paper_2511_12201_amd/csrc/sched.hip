@@ -19,7 +19,6 @@ __global__ void sched_prefix_kernel(const int* __restrict__ q_cnt, int BH, int N
   }
   sched[kSchedPrefix + BH] = items;
   sched[kSchedTotal] = items;
-  sched[kSchedCounter] = 0;
 }
 
 struct ItemRef {
@@ -59,6 +58,128 @@ __global__ __launch_bounds__(256) void sched_cost_kernel(const int* __restrict__
   reinterpret_cast<unsigned long long*>(sched + keys_off)[id] = sched_key(cost, id);
 }
 
+// One workgroup: cost of every head, heads onto queues (largest first onto the least loaded queue), queue bounds,
+// and the queue and position of its head folded into every item's sort key.  queues <= 1 or too many heads: one
+// queue.  Everything the serial placement loop and the binary searches touch sits in LDS.
+constexpr int kAssignThreads = 1024;
+__global__ __launch_bounds__(kAssignThreads) void sched_assign_kernel(int BH, int queues, size_t keys_off, int* __restrict__ sched) {
+  __shared__ int sPrefix[kSchedMaxQueuedHeads + 1], sCost[kSchedMaxQueuedHeads], sOrder[kSchedMaxQueuedHeads],
+      sPlace[kSchedMaxQueuedHeads], sRankItems[kSchedMaxQueuedHeads], sRankPlace[kSchedMaxQueuedHeads], sShift;
+  __shared__ unsigned sRankCost[kSchedMaxQueuedHeads];
+  const int items_all = sched[kSchedTotal];
+  const bool queued = queues > 1 && BH <= kSchedMaxQueuedHeads;
+  if (!queued) {
+    if (threadIdx.x < kSchedQueues) {
+      sched[kSchedCursor + threadIdx.x] = threadIdx.x == 0 ? 0 : items_all;
+      sched[kSchedEnd + threadIdx.x] = items_all;
+    }
+    for (int bh = threadIdx.x; bh < BH; bh += kAssignThreads) sched[sched_head_place_off(BH) + bh] = 0;
+    return;                                               // the keys already carry place 0
+  }
+  unsigned long long* keys = reinterpret_cast<unsigned long long*>(sched + keys_off);
+  for (int bh = threadIdx.x; bh <= BH; bh += kAssignThreads) sPrefix[bh] = sched[kSchedPrefix + bh];
+  for (int bh = threadIdx.x; bh < BH; bh += kAssignThreads) sCost[bh] = 0;
+  __syncthreads();
+  // head costs: a wavefront's 64 consecutive items belong to one head most of the time.  kBatch key loads are in
+  // flight together (one workgroup walks the whole list: a load per trip would cost a memory latency per trip).
+  constexpr int kBatch = 8;
+  for (int base = (threadIdx.x & ~63); base < items_all; base += kBatch * kAssignThreads) {
+    unsigned long long kv[kBatch];
+#pragma unroll
+    for (int e = 0; e < kBatch; ++e) {
+      const int id = base + e * kAssignThreads + (threadIdx.x & 63);
+      kv[e] = id < items_all ? keys[id] : 0ull;
+    }
+#pragma unroll
+    for (int e = 0; e < kBatch; ++e) {
+      const int id = base + e * kAssignThreads + (threadIdx.x & 63);
+      int bh = -1, c = 0;
+      if (id < items_all) {
+        bh = item_of(sPrefix, BH, id).bh;
+        c = (int)((kv[e] >> 32) & 0xffffu);
+      }
+      const int first = __shfl(bh, 0, 64);
+      if (__all(bh == first || bh < 0)) {
+        c = wave_sum(c);
+        if ((threadIdx.x & 63) == 0 && first >= 0) atomicAdd(&sCost[first], c);
+      } else if (bh >= 0) {
+        atomicAdd(&sCost[bh], c);
+      }
+    }
+  }
+  __syncthreads();
+  for (int bh = threadIdx.x; bh < BH; bh += kAssignThreads) {       // rank of a head: cost descending, index ascending
+    const int mine = sCost[bh];
+    int r = 0;
+    for (int j = 0; j < BH; ++j) r += (sCost[j] > mine || (sCost[j] == mine && j < bh)) ? 1 : 0;
+    sOrder[r] = bh;
+  }
+  __syncthreads();
+  // cost and item count in rank order, so that the serial placement loop reads LDS sequentially
+  if (threadIdx.x == 0) {
+    long long total = 0;
+    for (int bh = 0; bh < BH; ++bh) total += sCost[bh];
+    sShift = sched_cost_shift(total);
+  }
+  __syncthreads();
+  for (int r = threadIdx.x; r < BH; r += kAssignThreads) {
+    const int bh = sOrder[r];
+    sRankCost[r] = (unsigned)(sCost[bh] >> sShift) << 3;
+    sRankItems[r] = sPrefix[bh + 1] - sPrefix[bh];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned load[kSchedQueues];               // load << 3 | queue: the least loaded queue is one unsigned minimum
+    int heads[kSchedQueues], items[kSchedQueues];
+#pragma unroll
+    for (int q = 0; q < kSchedQueues; ++q) load[q] = q < queues ? (unsigned)q : 0xffffffffu, heads[q] = 0, items[q] = 0;
+    for (int n = 0; n < BH; ++n) {
+      unsigned m = load[0];
+#pragma unroll
+      for (int r = 1; r < kSchedQueues; ++r) m = min(m, load[r]);
+      const int q = (int)(m & 7u);
+      const unsigned c = sRankCost[n];
+      const int ni = sRankItems[n];
+#pragma unroll
+      for (int r = 0; r < kSchedQueues; ++r)               // compile-time indices keep the arrays in registers
+        if (r == q) {
+          sRankPlace[n] = (r << 16) | heads[r];
+          heads[r] += 1;
+          load[r] += c;
+          items[r] += ni;
+        }
+    }
+    int start = 0;
+#pragma unroll
+    for (int q = 0; q < kSchedQueues; ++q) {
+      sched[kSchedCursor + q] = start;
+      start += items[q];
+      sched[kSchedEnd + q] = start;
+    }
+  }
+  __syncthreads();
+  for (int r = threadIdx.x; r < BH; r += kAssignThreads) sPlace[sOrder[r]] = sRankPlace[r];
+  __syncthreads();
+  for (int bh = threadIdx.x; bh < BH; bh += kAssignThreads) {
+    sched[sched_head_place_off(BH) + bh] = sPlace[bh];
+    sched[sched_head_cost_off(BH) + bh] = sCost[bh];
+  }
+  for (int base = threadIdx.x; base < items_all; base += kBatch * kAssignThreads) {
+    unsigned long long kv[kBatch];
+#pragma unroll
+    for (int e = 0; e < kBatch; ++e) {
+      const int id = base + e * kAssignThreads;
+      kv[e] = id < items_all ? keys[id] : 0ull;
+    }
+#pragma unroll
+    for (int e = 0; e < kBatch; ++e) {
+      const int id = base + e * kAssignThreads;
+      if (id < items_all)
+        keys[id] = sched_key((int)((kv[e] >> 32) & 0xffffu), id, (unsigned)sPlace[item_of(sPrefix, BH, id).bh]);
+    }
+  }
+}
+
 // kRankLanes threads per item id: its rank among the keys (all distinct) is its place in the hand-out order
 constexpr int kRankLanes = 4;
 constexpr int kRankItems = 256 / kRankLanes;                // items per workgroup
@@ -93,7 +214,7 @@ __global__ __launch_bounds__(256) void sched_rank_kernel(int BH, size_t keys_off
 }  // namespace
 
 int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap, int tile_m, const int* qvis, int* sched,
-                 hipStream_t st) {
+                 hipStream_t st, int queues) {
   const int BH = L.B * L.Hq;
   if (BH >= 65536 || cdiv(L.N, tile_m) >= 65536) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "work list: too many heads or tiles");
   const size_t cap = sched_cap(BH, L.N, tile_m);
@@ -104,6 +225,8 @@ int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap,
   hipLaunchKernelGGL(sched_cost_kernel, dim3(blocks), dim3(256), 0, st, q_cnt, budget, qvis, L.bph, BH, L.Hq, L.N, b_cap, L.causal,
                      tile_m, keys_off, sched);
   OMNI_LAUNCH_CHECK();
+  hipLaunchKernelGGL(sched_assign_kernel, dim3(1), dim3(kAssignThreads), 0, st, BH, queues, keys_off, sched);
+  OMNI_LAUNCH_CHECK();
   hipLaunchKernelGGL(sched_rank_kernel, dim3((unsigned)cdiv(cap, (size_t)kRankItems)), dim3(256), 0, st, BH, keys_off, order_off,
                      sched);
   OMNI_LAUNCH_CHECK();
@@ -111,26 +234,30 @@ int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap,
 }
 
 void sched_build_host(const int* q_cnt, const int* budget, int B, int Hq, int N, int b_cap, int causal, int tile_m,
-                      int* sched) {
+                      int* sched, int queues) {
   const int BH = B * Hq;
   int items = 0;
-  std::vector<unsigned long long> keys;
-  std::vector<int> packed;
+  std::vector<int> costs, packed;
   for (int bh = 0; bh < BH; ++bh) {
     const int nq = q_cnt ? q_cnt[bh] : N;
     const int nt = nq > 0 ? (nq + tile_m - 1) / tile_m : 0;
     int nk = budget ? budget[bh / Hq] : N;
     nk = nk < 0 ? 0 : (nk > b_cap ? b_cap : nk);
     sched[kSchedPrefix + bh] = items;
+    sched[sched_head_cost_off(BH) + bh] = 0;
     for (int tq = 0; tq < nt; ++tq) {
-      keys.push_back(sched_key(sched_estimate(tq, nt, nk, causal), items + tq));
+      costs.push_back(sched_estimate(tq, nt, nk, causal));
+      sched[sched_head_cost_off(BH) + bh] += costs.back();
       packed.push_back((int)(((unsigned)bh << 16) | (unsigned)tq));
     }
     items += nt;
   }
   sched[kSchedPrefix + BH] = items;
   sched[kSchedTotal] = items;
-  sched[kSchedCounter] = 0;
+  sched_assign_host(sched, BH, queues);
+  std::vector<unsigned long long> keys(items);
+  for (int id = 0; id < items; ++id)
+    keys[id] = sched_key(costs[id], id, (unsigned)sched[sched_head_place_off(BH) + (int)((unsigned)packed[id] >> 16)]);
   std::vector<int> idx(items);
   for (int i = 0; i < items; ++i) idx[i] = i;
   std::sort(idx.begin(), idx.end(), [&](int a, int b) { return keys[a] > keys[b]; });

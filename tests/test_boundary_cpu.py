@@ -195,3 +195,47 @@ def test_device_work_list_covers_every_query_tile_exactly_once(lib, q_cnt, budge
         nt = (counts[h] + tile_rows - 1) // tile_rows
         keys = nk if not causal else -(-nk * (t + 1) // nt)
         assert cst == -(-keys // 64)
+
+
+@pytest.mark.parametrize("q_cnt,budget,n_heads,n_tokens", [
+    ([65536] + [17000 + 13 * i for i in range(27)], [35000], 28, 65536),
+    ([1859, 500, 300, 0, 20, 129, 128, 1], [700], 8, 1859),
+    ([0, 0, 5, 0], [3], 4, 537),
+    ([400] * 3, [300], 3, 537),
+])
+def test_queued_work_list_places_whole_heads_and_balances_the_queues(lib, q_cnt, budget, n_heads, n_tokens):
+    """One list per XCD: every tile once, a head in one queue only and in one stretch of it, longest item first
+    inside a head, heads placed largest first onto the least loaded queue (checked by replaying that rule)."""
+    import numpy as np
+    tile_rows = 256
+    d = _desc(n_q_heads=n_heads, n_kv_heads=n_heads, n_tokens=n_tokens, vis_end=min(256, n_tokens), causal=1)
+    head, tile, cost, qend = ob.debug_work_list(d, q_cnt, budget, n_tokens, tile_rows, queues=8)
+    want = {(h, t) for h in range(n_heads) for t in range((q_cnt[h] + tile_rows - 1) // tile_rows)}
+    got = list(zip(head.tolist(), tile.tolist()))
+    assert len(got) == len(want) and set(got) == want
+    assert np.all(np.diff(qend) >= 0) and qend[-1] == len(got)
+    starts = np.concatenate([[0], qend[:-1]])
+    queue_of, loads, order_in_queue = {}, [], []
+    for q in range(8):
+        seg_h, seg_c = head[starts[q]:qend[q]], cost[starts[q]:qend[q]]
+        loads.append(int(seg_c.sum()))
+        heads_here = []
+        for h in seg_h.tolist():
+            if not heads_here or heads_here[-1] != h:
+                heads_here.append(h)
+        assert len(heads_here) == len(set(heads_here))            # a head is one contiguous stretch
+        for h in heads_here:
+            assert h not in queue_of
+            queue_of[h] = q
+            assert np.all(np.diff(seg_c[seg_h == h]) <= 0)       # longest item first inside the head
+        order_in_queue.append(heads_here)
+    # replay: heads by total cost (descending, lower index first among equals) onto the least loaded queue
+    total = {h: int(cost[head == h].sum()) for h in range(n_heads)}
+    sim_load, sim_order = [0] * 8, [[] for _ in range(8)]
+    for h in sorted(range(n_heads), key=lambda x: (-total[x], x)):
+        q = min(range(8), key=lambda r: (sim_load[r], r))
+        sim_load[q] += total[h]
+        if q_cnt[h] > 0:
+            sim_order[q].append(h)
+    assert sim_order == order_in_queue
+    assert loads == sim_load
