@@ -238,8 +238,10 @@ def main():
         # operands that toggle like data, where the clock is held down by the power limit
         tf_c, mhz_c = ob.debug_mfma_rate(False)
         tf_r, mhz_r = ob.debug_mfma_rate(True)
+        tf_d, mhz_d = ob.debug_mfma_rate(2)
         out["mfma_only_probe"] = {"constant_operands": {"TFLOP/s": round(tf_c, 1), "shader_MHz": round(mhz_c)},
-                                  "random_operands": {"TFLOP/s": round(tf_r, 1), "shader_MHz": round(mhz_r)}}
+                                  "random_operands": {"TFLOP/s": round(tf_r, 1), "shader_MHz": round(mhz_r)},
+                                  "random_operands_two_thirds_duty": {"TFLOP/s": round(tf_d, 1), "shader_MHz": round(mhz_d)}}
         out["roofline"]["frac_of_sustained_random_operand_rate"] = round(ach / tf_r, 4)
         try:
             out["block_granular_variant"] = bench_block_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, q_cnt,

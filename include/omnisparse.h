@@ -513,7 +513,9 @@ int omni_debug_copy(const void* src, void* dst, size_t bytes, void* stream);
  * Diagnostic: sustained rate of register-resident bf16 32x32x16 MFMAs on all compute units,
  * with constant operands (random_operands = 0) or pseudo-random ones (1); the second is
  * what power management leaves of the nominal matrix-core peak for operands that toggle
- * like real data.  Runs on the default stream and synchronises; allocates and frees a few
+ * like real data.  2: pseudo-random operands with the matrix cores idle a third of the time
+ * (all wavefronts sleep together after every 32 MFMAs) -- the clock it reaches tells whether
+ * the full-duty rate is set by the power limit.  Runs on the default stream and synchronises; allocates and frees a few
  * MiB.  Outputs are HOST pointers: TFLOP/s and the mean shader clock in MHz.
  */
 int omni_debug_mfma_rate(int random_operands, int iters, double* tflops /* host */, double* shader_mhz /* host */);

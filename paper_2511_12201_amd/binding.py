@@ -230,10 +230,11 @@ def debug_key_split_len(tiles: int):
     _check(load_library().omni_debug_key_split_len(int(tiles)))
 
 
-def debug_mfma_rate(random_operands: bool, iters: int = 40000):
-    """(TFLOP/s, shader MHz) of register-resident bf16 MFMAs with constant or pseudo-random operands."""
+def debug_mfma_rate(random_operands, iters: int = 40000):
+    """(TFLOP/s, shader MHz) of register-resident bf16 MFMAs: constant operands (0 / False), pseudo-random ones
+    (1 / True), or pseudo-random with the matrix cores idle a third of the time (2)."""
     tf, mhz = C.c_double(0), C.c_double(0)
-    _check(load_library().omni_debug_mfma_rate(1 if random_operands else 0, iters, C.byref(tf), C.byref(mhz)))
+    _check(load_library().omni_debug_mfma_rate(int(random_operands), iters, C.byref(tf), C.byref(mhz)))
     return tf.value, mhz.value
 
 

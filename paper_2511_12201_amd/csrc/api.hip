@@ -207,7 +207,8 @@ int omni_debug_mfma_rate(int random_operands, int iters, double* tflops, double*
   clear_error();
   REQUIRE_PTR(tflops); REQUIRE_PTR(shader_mhz);
   if (iters < 1 || iters > (1 << 22)) OMNI_FAIL(OMNI_ERR_INVALID, "iters must be in [1, 2^22]");
-  return run_mfma_rate(random_operands ? 1 : 0, iters, tflops, shader_mhz);
+  if (random_operands < 0 || random_operands > 2) OMNI_FAIL(OMNI_ERR_INVALID, "random_operands must be 0, 1 or 2");
+  return run_mfma_rate(random_operands, iters, tflops, shader_mhz);
 }
 
 int omni_profile_enable(int on) {

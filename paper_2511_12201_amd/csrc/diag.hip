@@ -5,7 +5,9 @@
 //  * mfma_rate_kernel: register-resident bf16 32x32x16 MFMAs and nothing else, with constant or
 //    with pseudo-random operands.  The sustained rate with random operands is what the chip's
 //    power management leaves of the nominal matrix-core peak for operands that toggle like real
-//    data; the attention kernels are priced against both figures.
+//    data; the attention kernels are priced against both figures.  A third mode idles the matrix cores a
+//    third of the time (all wavefronts of a workgroup sleep together after every 32 MFMAs): if the clock then
+//    rises, the full-duty rate is set by the power limit and not by a fixed clock.
 #include "common.h"
 #include "kernels.h"
 
@@ -59,6 +61,10 @@ __global__ __launch_bounds__(512, 2) void mfma_rate_kernel(float* sink, long lon
       c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(f + 2) % kRateFrags], b[f], c2, 0, 0, 0);
       c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(f + 3) % kRateFrags], b[f], c3, 0, 0, 0);
     }
+    if (RANDOM == 2) {                         // 2 x 32 MFMAs x 32 cycles per SIMD, then 17 x 64 idle cycles: 65 % duty
+      __syncthreads();
+      __builtin_amdgcn_s_sleep(17);
+    }
     if (RANDOM && (it & 63) == 63) {           // keep the accumulators finite
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -103,7 +109,8 @@ int run_mfma_rate(int random_operands, int iters, double* tflops, double* shader
   (void)hipEventCreate(&e0);
   (void)hipEventCreate(&e1);
   auto launch = [&](int n) {
-    if (random_operands) hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(blocks), dim3(threads), 0, 0, sink, clocks, n);
+    if (random_operands == 2) hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(blocks), dim3(threads), 0, 0, sink, clocks, n);
+    else if (random_operands) hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(blocks), dim3(threads), 0, 0, sink, clocks, n);
     else hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(blocks), dim3(threads), 0, 0, sink, clocks, n);
   };
   launch(16);
