@@ -632,6 +632,29 @@ def test_block_attention_in_place_equals_gathered_path_and_oracle(cfg, block, fr
     assert np.max(np.abs(to_host(lse1)[fin] - Lo[fin])) <= 2e-2
 
 
+def test_sparse_forward_with_more_heads_than_the_queued_scheduler_places():
+    """Batch 150 x 8 heads = 1200 (batch, head) pairs: above 1024 the work list falls back to one queue.  Every batch
+    entry holds the same sequence, so every one must give the oracle's output for it."""
+    cfg = CFG_BF16_64.scaled(name="bf16_d64_many", n_q_heads=8, n_kv_heads=2, frames=2, tok_per_frame=100, n_text=21, seed=13)
+    c = case_for(cfg)
+    N, H, B = cfg.n_tokens, cfg.n_q_heads, 150
+    dQ, dK, dV = (x.expand(B, -1, -1, -1).contiguous() for x in (c.dQ, c.dK, c.dV))
+    desc = ob.make_layer_desc(dQ, dK, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    b = len(c.o_kvidx[0][0])
+    q_idx, q_cnt = lists_to_padded([c.o_qidx[0]] * B, H, N)
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])] * B, H, b)
+    budget = torch.full((B,), b, dtype=torch.int32, device="cuda")
+    O, lse = ob.omni_sparse_attn_fwd(desc, dQ, dK, dV, q_idx, q_cnt, kv_idx, budget, b)
+    torch.cuda.synchronize()
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, [list(c.o_kvidx[0])], cfg.causal, cfg.scale)
+    Og, Lg = to_host(O), to_host(lse)
+    assert np.max(np.abs(Og - Oo)) <= TOL_OUT["bf16"]                 # broadcasts over the batch
+    fin = np.isfinite(Lo[0])
+    assert np.array_equal(np.isfinite(Lg), np.broadcast_to(fin, Lg.shape))
+    assert np.max(np.abs(Lg[:, fin] - Lo[0][fin])) <= 2e-3
+    assert np.array_equal(Og[0], Og[-1]) and np.array_equal(Og[0], Og[B // 2])
+
+
 # ------------------------------------------------------------------ attention backward
 
 def _run_fwd_bwd(c, q_lists, kv_lists, dO_np, desc=None):
