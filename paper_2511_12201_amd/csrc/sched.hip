@@ -67,14 +67,16 @@ __global__ __launch_bounds__(kAssignThreads) void sched_assign_kernel(int BH, in
       sPlace[kSchedMaxQueuedHeads], sRankItems[kSchedMaxQueuedHeads], sRankPlace[kSchedMaxQueuedHeads], sShift;
   __shared__ unsigned sRankCost[kSchedMaxQueuedHeads];
   const int items_all = sched[kSchedTotal];
-  const bool queued = queues > 1 && BH <= kSchedMaxQueuedHeads;
-  if (!queued) {
+  auto one_queue = [&]() {                                // the keys already carry place 0
     if (threadIdx.x < kSchedQueues) {
       sched[kSchedCursor + threadIdx.x] = threadIdx.x == 0 ? 0 : items_all;
       sched[kSchedEnd + threadIdx.x] = items_all;
     }
     for (int bh = threadIdx.x; bh < BH; bh += kAssignThreads) sched[sched_head_place_off(BH) + bh] = 0;
-    return;                                               // the keys already carry place 0
+  };
+  if (queues <= 1 || BH > kSchedMaxQueuedHeads) {
+    one_queue();
+    return;
   }
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(sched + keys_off);
   for (int bh = threadIdx.x; bh <= BH; bh += kAssignThreads) sPrefix[bh] = sched[kSchedPrefix + bh];
@@ -119,9 +121,13 @@ __global__ __launch_bounds__(kAssignThreads) void sched_assign_kernel(int BH, in
   if (threadIdx.x == 0) {
     long long total = 0;
     for (int bh = 0; bh < BH; ++bh) total += sCost[bh];
-    sShift = sched_cost_shift(total);
+    sShift = sched_queues_pay(total, sCost[sOrder[0]], queues) ? sched_cost_shift(total) : -1;
   }
   __syncthreads();
+  if (sShift < 0) {                                       // a head too large for a queue of its own: one list
+    one_queue();
+    return;
+  }
   for (int r = threadIdx.x; r < BH; r += kAssignThreads) {
     const int bh = sOrder[r];
     sRankCost[r] = (unsigned)(sCost[bh] >> sShift) << 3;

@@ -202,6 +202,7 @@ def test_device_work_list_covers_every_query_tile_exactly_once(lib, q_cnt, budge
     ([1859, 500, 300, 0, 20, 129, 128, 1], [700], 8, 1859),
     ([0, 0, 5, 0], [3], 4, 537),
     ([400] * 3, [300], 3, 537),
+    ([900 + 37 * i for i in range(24)], [1500], 24, 1859),
 ])
 def test_queued_work_list_places_whole_heads_and_balances_the_queues(lib, q_cnt, budget, n_heads, n_tokens):
     """One list per XCD: every tile once, a head in one queue only and in one stretch of it, longest item first
@@ -214,6 +215,11 @@ def test_queued_work_list_places_whole_heads_and_balances_the_queues(lib, q_cnt,
     got = list(zip(head.tolist(), tile.tolist()))
     assert len(got) == len(want) and set(got) == want
     assert np.all(np.diff(qend) >= 0) and qend[-1] == len(got)
+    total = {h: int(cost[head == h].sum()) for h in range(n_heads)}
+    if 2 * max(total.values()) * 8 > 3 * sum(total.values()):
+        # one head outweighs 1.5 fair shares of a queue: one longest-first list after all
+        assert np.all(qend == len(got)) and np.all(np.diff(cost) <= 0)
+        return
     starts = np.concatenate([[0], qend[:-1]])
     queue_of, loads, order_in_queue = {}, [], []
     for q in range(8):
@@ -230,7 +236,6 @@ def test_queued_work_list_places_whole_heads_and_balances_the_queues(lib, q_cnt,
             assert np.all(np.diff(seg_c[seg_h == h]) <= 0)       # longest item first inside the head
         order_in_queue.append(heads_here)
     # replay: heads by total cost (descending, lower index first among equals) onto the least loaded queue
-    total = {h: int(cost[head == h].sum()) for h in range(n_heads)}
     sim_load, sim_order = [0] * 8, [[] for _ in range(8)]
     for h in sorted(range(n_heads), key=lambda x: (-total[x], x)):
         q = min(range(8), key=lambda r: (sim_load[r], r))
