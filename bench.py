@@ -561,6 +561,27 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
             kms, kn = ob.profile_read("decode")                               # last 64 launches: row-streaming kernels only
             ktime[mode] = kms * 1e3 / max(1, kn)
             ob.profile_enable(False)
+        # the same call replayed from a captured HIP graph (rows kernel + slice combine back to back, no host in
+        # between): what a serving loop pays per token and layer once its step is captured
+        graph_us = {}
+        if set(modes) == set(DECODE_MODES):
+            def replay_us(fn):
+                fn()
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    fn()
+                g.replay()
+                torch.cuda.synchronize()
+                ev0.record()
+                for _ in range(64):
+                    g.replay()
+                ev1.record()
+                torch.cuda.synchronize()
+                return ev0.elapsed_time(ev1) * 1e3 / 64
+            graph_us["slim_grouped"] = replay_us(lambda: ob.omni_slim_decode_grouped(
+                ddesc, q_all[0], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act))
+            graph_us["dense"] = replay_us(lambda: ob.omni_dense_decode(ddesc, q_all[0], Kc, Vc, ctx, O))
         if set(modes) != set(DECODE_MODES):               # a counter run on some of the modes: times only
             res["per_batch"][str(B)] = {f"{k}_us_per_token": round(v, 2) for k, v in ktime.items()}
             del Kc, Vc, Kpool, Vpool, Kcomp, Vcomp
@@ -598,6 +619,7 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
             "kv_store_bytes": {"full_cache": int(rows_dense * row_bytes),
                                "compacted": int(int(grp_cnt.sum().cpu()) * (row_bytes + 8) + B * Hkv * n_text * row_bytes)},
             "python_loop_us_per_token": {k: round(v, 1) for k, v in timing.items()},
+            "hip_graph_us_per_token": {k: round(v, 1) for k, v in graph_us.items()},
             "active_head_fraction_last_step": round(float(a.mean()), 4),
             "rows_requested_vs_dense": {"slim": round(rows_head / rows_dense, 4), "slim_grouped": round(rows_union / rows_dense, 4)},
             "GBps_of_requested_rows": {"slim": gbps(rows_head, ktime["slim"]), "slim_grouped": gbps(rows_union, ktime["slim_grouped"]),

@@ -793,6 +793,54 @@ def test_prefill_step_replays_from_a_hip_graph():
         assert torch.isfinite(scratch)
 
 
+def test_decode_step_replays_from_a_hip_graph():
+    """A decode step (context length advanced on the device, then the group-list call) captured once and replayed
+    with a new query and a longer context each time: every replay equals the eager call on the same inputs."""
+    cfg, batch = CFG_BF16, 2
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    H = cfg.n_q_heads
+    b = len(c.o_kvidx[0][0])
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])] * batch, H, b)
+    budget = torch.full((batch,), b, dtype=torch.int32, device="cuda")
+    ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                               cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset(ldesc, kv_idx, budget, b)
+    dKc, dVc = (to_device(x, cfg.dtype) for x in (Kc, Vc))
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    rng = np.random.default_rng(61)
+    queries = [to_device(synth.round_to_bf16((q * (1.0 + 0.1 * k) + 0.05 * rng.standard_normal(q.shape)).astype(np.float32)),
+                         cfg.dtype) for k in range(3)]
+    q_static = queries[0].clone()
+    ctx0 = torch.from_numpy(ctx).cuda() - 4                    # four rows short of what the cache holds
+    ctx_static = ctx0.clone()
+    desc = ob.make_decode_desc(q_static, dKc, cfg.vis_begin, cfg.vis_end, 0.08)
+    O, act = torch.empty_like(q_static), torch.empty(batch, H, dtype=torch.uint8, device="cuda")
+
+    def step():
+        ctx_static.add_(1)
+        ob.omni_slim_decode_grouped(desc, q_static, dKc, dVc, ctx_static, dprobe, grp_idx, grp_mask, grp_cnt, O, act)
+
+    step()                                    # the workspace exists before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    ctx_static.copy_(ctx0)
+    for k in range(3):
+        q_static.copy_(queries[k])
+        O.zero_()
+        scratch = torch.randn(1 << 20, device="cuda").sum()      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want_ctx = ctx0 + (k + 1)
+        assert torch.equal(ctx_static, want_ctx)
+        O_e, act_e = ob.omni_slim_decode_grouped(desc, queries[k], dKc, dVc, want_ctx, dprobe, grp_idx, grp_mask, grp_cnt)
+        torch.cuda.synchronize()
+        assert torch.equal(O, O_e) and torch.equal(act, act_e), f"replay {k}"
+        assert torch.isfinite(scratch)
+
+
 # ------------------------------------------------------------------ batch > 1
 
 CFG_B2 = synth.C2_16K.scaled(name="bf16_batch2", batch=2, frames=4, tok_per_frame=252, n_text=70, n_q_heads=8, n_kv_heads=2,
