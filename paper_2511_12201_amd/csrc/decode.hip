@@ -101,7 +101,7 @@ __device__ __forceinline__ unsigned char* lds_block() {
 // bf16, 2..8 heads per workgroup: both products of a row block on the matrix cores.  A wavefront owns 32
 // consecutive list positions per trip and nothing in the loop is shared between wavefronts (no barriers):
 //  * S^T = K . q^T: the K rows are the A operand straight from memory (lane = row), the heads' queries the B
-//    operand (columns beyond GT are zero: the matrix cores are idle anyway).  Lane (n, h) of the accumulator
+//    operand (columns beyond GT are padding that the member words mask: the matrix cores are idle anyway).  Lane (n, h) of the accumulator
 //    then holds head n's scores of 16 of the 32 rows, so the online softmax is per-lane arithmetic plus one
 //    exchange with lane n + 32, and the weights are a B operand as they stand.
 //  * O^T += V^T . P^T: V rows go to a wavefront-private LDS tile as they come from memory (whole rows, coalesced)
