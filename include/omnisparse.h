@@ -368,7 +368,8 @@ int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q,
  * omni_expand_blocks turns ascending block lists blk_idx [batch, n_q_heads, blk_cap]
  * (blk_budget [batch] entries used) into ascending token lists kv_idx [batch,
  * n_q_heads, b_cap] and writes budget [batch] = min(blk_budget, blk_cap) * block; the
- * tokens a partial last block lacks become pad entries that no query ever sees.
+ * tokens a partial last block lacks become pad entries that no query ever sees under
+ * the causal mask (without it n_tokens must be a multiple of block).
  * b_cap must be >= blk_cap * block to hold every list.
  */
 int omni_block_scores(const omni_layer_desc* desc, const void* Q, const void* K, int32_t block,

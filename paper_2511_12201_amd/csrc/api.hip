@@ -462,6 +462,8 @@ int omni_expand_blocks(const omni_layer_desc* desc, const int32_t* blk_idx, cons
   REQUIRE_PTR(blk_idx); REQUIRE_PTR(blk_budget); REQUIRE_PTR(kv_idx); REQUIRE_PTR(budget);
   if (blk_cap < 1 || block < 1 || b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "blk_cap, block and b_cap must be >= 1");
   if ((long long)blk_cap * block > b_cap) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= blk_cap * block");
+  if (!desc->causal && desc->n_tokens % block)     // the pad entries of a partial last block are hidden by the causal mask only
+    OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "without the causal mask n_tokens must be a multiple of block");
   return run_expand_blocks(make_layer(desc), blk_idx, blk_budget, blk_cap, block, kv_idx, budget, b_cap,
                            static_cast<hipStream_t>(stream));
 }

@@ -140,6 +140,8 @@ def test_argument_errors(lib):
     assert ba(cap=4096, block=64) == -2
     assert ba(_desc(dtype=ob.OMNI_F32)) == -2 and "bf16" in ob.last_error()
     assert ba(_desc(causal=0), block=128) == -2
+    assert lib.omni_expand_blocks(C.byref(_desc(causal=0)), FAKE, FAKE, 3, 128, FAKE, FAKE, 384, None) == -2
+    assert lib.omni_expand_blocks(C.byref(d), FAKE, FAKE, 3, 128, FAKE, FAKE, 383, None) == -1
     assert ob.workspace_bytes(ob.CALL_BLOCK_ATTN_FWD, d, 5 * 64) > 0
     with pytest.raises(ob.OmniError):
         ob.workspace_bytes(ob.CALL_BLOCK_ATTN_FWD, d, 100)
