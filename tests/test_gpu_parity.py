@@ -661,6 +661,33 @@ def test_sparse_forward_with_more_heads_than_the_queued_scheduler_places():
     assert np.array_equal(Og[0], Og[-1]) and np.array_equal(Og[0], Og[B // 2])
 
 
+def test_block_attention_in_place_edge_budgets():
+    """Block budget 0: every kept query sees no key (zero output, lse = -inf).  A budget above blk_cap is clamped to
+    it.  Both as the gathered path does it."""
+    cfg = CFG_BF16
+    c = case_for(cfg)
+    N, H, block = cfg.n_tokens, cfg.n_q_heads, 128
+    nb = math.ceil(N / block)
+    cap = 5
+    rng = np.random.default_rng(71)
+    lists = [[np.sort(rng.choice(nb, cap, replace=False)).astype(np.int32) for _ in range(H)]]
+    blk_idx, _ = lists_to_padded(lists, H, cap)
+    q_idx, q_cnt = lists_to_padded(c.o_qidx, H, N)
+    zero = torch.zeros(1, dtype=torch.int32, device="cuda")
+    O0, lse0 = ob.omni_block_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, blk_idx, zero, block)
+    torch.cuda.synchronize()
+    assert not to_host(O0).any() and np.all(to_host(lse0) == -np.inf)
+    big = torch.full((1,), cap + 7, dtype=torch.int32, device="cuda")
+    O1, lse1 = ob.omni_block_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, blk_idx, big, block)
+    kv_idx, budget = ob.omni_expand_blocks(c.desc, blk_idx, big, block)
+    O2, lse2 = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, budget, kv_idx.shape[-1])
+    torch.cuda.synchronize()
+    assert int(to_host(budget)[0]) == cap * block
+    assert torch.equal(O1.view(torch.int16), O2.view(torch.int16)) and torch.equal(lse1.view(torch.int32), lse2.view(torch.int32))
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, oc.expand_blocks(lists, block, N), cfg.causal, cfg.scale)
+    assert np.max(np.abs(to_host(O1) - Oo)) <= TOL_OUT["bf16"]
+
+
 # ------------------------------------------------------------------ attention backward
 
 def _run_fwd_bwd(c, q_lists, kv_lists, dO_np, desc=None):
