@@ -60,9 +60,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3_64k", choices=["c3_64k", "c2_16k"])
     ap.add_argument("--no-extras", action="store_true", help="skip dense baseline / oracle timing")
-    ap.add_argument("--only", choices=["train", "decode"],
-                    help="run just the training-step or the decode extra and print its JSON (for profiling; the "
-                         "headline line is the default run)")
+    ap.add_argument("--only", choices=["train", "decode", "mfma"],
+                    help="run just the training-step extra, the decode extra or the matrix-core rate probe and print "
+                         "its JSON (for profiling; the headline line is the default run)")
     ap.add_argument("--decode-steps", type=int, default=256, help="with --only decode: decode steps per mode")
     ap.add_argument("--decode-modes", default="", help="with --only decode: comma-separated subset of "
                     "slim,slim_grouped,slim_compact,slim_paged,dense (for counter runs; prints the times only)")
@@ -82,6 +82,9 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(1)
     ob.load_library()
+    if args.only == "mfma":
+        print(json.dumps({"mfma_only_probe": mfma_probe(ob, repeats=3)}), flush=True)
+        return
     if args.only:
         modes = tuple(m for m in args.decode_modes.split(",") if m) or DECODE_MODES
         fn = bench_train if args.only == "train" else (
@@ -236,12 +239,8 @@ def main():
         del Od
         # what the matrix cores sustain with nothing else running: nominal (constant operands) and with
         # operands that toggle like data, where the clock is held down by the power limit
-        tf_c, mhz_c = ob.debug_mfma_rate(False)
-        tf_r, mhz_r = ob.debug_mfma_rate(True)
-        tf_d, mhz_d = ob.debug_mfma_rate(2)
-        out["mfma_only_probe"] = {"constant_operands": {"TFLOP/s": round(tf_c, 1), "shader_MHz": round(mhz_c)},
-                                  "random_operands": {"TFLOP/s": round(tf_r, 1), "shader_MHz": round(mhz_r)},
-                                  "random_operands_two_thirds_duty": {"TFLOP/s": round(tf_d, 1), "shader_MHz": round(mhz_d)}}
+        out["mfma_only_probe"] = mfma_probe(ob)
+        tf_r = out["mfma_only_probe"]["random_operands"]["TFLOP/s"]
         out["roofline"]["frac_of_sustained_random_operand_rate"] = round(ach / tf_r, 4)
         try:
             out["block_granular_variant"] = bench_block_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, q_cnt,
@@ -452,6 +451,18 @@ def bench_train(torch, ob, synth, steps: int = 5, per_head: bool = False):
            "bwd_issued_gemm_tflops": round(16.0 * D * valid / (bwd_ms * 1e-3) / 1e12, 2) if bwd_ms else None,
            "fwd_algorithmic_tflops": round(4.0 * D * valid / (kern["attn_fwd"] * 1e-3) / 1e12, 2)}
     return res
+
+
+def mfma_probe(ob, repeats: int = 1):
+    """Register-resident bf16 MFMAs and nothing else: constant operands, pseudo-random operands, and pseudo-random
+    operands with the matrix cores idle a third of the time.  With repeats > 1 every mode's runs are listed."""
+    names = ("constant_operands", "random_operands", "random_operands_two_thirds_duty")
+    runs = {n: [] for n in names}
+    for _ in range(repeats):
+        for mode, n in enumerate(names):
+            tf, mhz = ob.debug_mfma_rate(mode)
+            runs[n].append({"TFLOP/s": round(tf, 1), "shader_MHz": round(mhz)})
+    return {n: (v[0] if repeats == 1 else v) for n, v in runs.items()}
 
 
 DECODE_MODES = ("slim", "slim_grouped", "slim_compact", "slim_paged", "dense")
