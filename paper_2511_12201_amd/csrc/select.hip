@@ -173,10 +173,23 @@ __device__ void radix_select_block(const float* __restrict__ x, int lo, int hi, 
     sh.sum_above = 0;
   }
   __syncthreads();
+  // The four passes count only: the 64-bit mass atomics are the slow half of a histogram pass, and the mass of the
+  // k largest is one plain sweep once the cut is known (fixed point: the order of the additions does not matter).
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    radix_histogram(x, lo, hi, shift, sh, with_sum);
+    radix_histogram(x, lo, hi, shift, sh, false);
     if (threadIdx.x < 64) radix_pick_bin(sh, shift, false);     // k <= matching count: always found
+    __syncthreads();
+  }
+  if (with_sum) {
+    const unsigned cut = sh.prefix;
+    unsigned long long local = 0;
+    for (int j = lo + threadIdx.x; j < hi; j += blockDim.x) {
+      const float v = x[j];
+      if (float_key(v) > cut) local += to_fixed(v);
+    }
+    local = wave_sum(local);
+    if (lane_id() == 0 && local) atomicAdd(&sh.sum_above, local);
     __syncthreads();
   }
   if (threadIdx.x == 0) {
