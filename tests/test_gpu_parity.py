@@ -923,6 +923,57 @@ def test_two_sequences_in_a_batch_have_their_own_sets_budgets_and_gradients(budg
     assert np.all(np.abs(bg - want_bud["budget"]) <= np.maximum(2, (2e-3 * want_bud["budget"]).astype(np.int64)))
 
 
+def test_two_sequences_of_different_lengths_in_one_padded_batch():
+    """Sequences of 1859 and 1060 tokens, own visual ranges, in tensors padded to 1859 rows (NaN in the padding).
+    Selection runs per sequence on a batch-1 descriptor that points into the padded tensors (strides are explicit) and
+    gives the bits it gives on the sequence alone; attention forward and backward run once over the padded batch:
+    the lists carry the lengths."""
+    cfa = CFG_BF16
+    cfb = CFG_BF16.scaled(name="bf16_d128_short", frames=5, tok_per_frame=200, n_text=60, seed=77)
+    ca, cb = case_for(cfa), case_for(cfb)
+    Na, Nb, H, Hkv, D = cfa.n_tokens, cfb.n_tokens, cfa.n_q_heads, cfa.n_kv_heads, cfa.head_dim
+    assert Nb < Na
+    nan = float("nan")
+    Q = torch.full((2, H, Na, D), nan, dtype=torch.bfloat16, device="cuda")
+    K = torch.full((2, Hkv, Na, D), nan, dtype=torch.bfloat16, device="cuda")
+    V = torch.full_like(K, nan)
+    Q[0], K[0], V[0] = ca.dQ[0], ca.dK[0], ca.dV[0]
+    Q[1, :, :Nb], K[1, :, :Nb], V[1, :, :Nb] = cb.dQ[0], cb.dK[0], cb.dV[0]
+    # selection of the short sequence through a view of the padded tensors
+    desc_b = ob.make_layer_desc(Q[1:2, :, :Nb], K[1:2, :, :Nb], cfb.vis_begin, cfb.vis_end, cfb.sink_index, cfb.causal)
+    sel_view = ob.omni_prefill_select(desc_b, Q[1:2, :, :Nb], K[1:2, :, :Nb], cb.q_mode, cb.q_param, cb.recall_p, cb.probe_block, 0)
+    sel_own = ob.omni_prefill_select(cb.desc, cb.dQ, cb.dK, cb.q_mode, cb.q_param, cb.recall_p, cb.probe_block, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(sel_view.q_cnt, sel_own.q_cnt) and torch.equal(sel_view.budget.budget, sel_own.budget.budget)
+    assert torch.equal(sel_view.q_idx, sel_own.q_idx)
+    bb = int(sel_own.budget.budget[0])
+    assert torch.equal(sel_view.kv_idx[..., :bb], sel_own.kv_idx[..., :bb])
+    # attention over the padded batch on the oracle's sets of each sequence
+    b_cap = max(len(ca.o_kvidx[0][0]), len(cb.o_kvidx[0][0]))
+    q_idx, q_cnt = lists_to_padded([ca.o_qidx[0], cb.o_qidx[0]], H, Na)
+    kv_idx, _ = lists_to_padded([list(ca.o_kvidx[0]), list(cb.o_kvidx[0])], H, b_cap)
+    budget = torch.tensor([len(ca.o_kvidx[0][0]), len(cb.o_kvidx[0][0])], dtype=torch.int32, device="cuda")
+    desc = ob.make_layer_desc(Q, K, cfa.vis_begin, cfa.vis_end, cfa.sink_index, cfa.causal)
+    dOa = synth.round_to_bf16(0.5 * synth.make_grad_output(cfa))
+    dOb = synth.round_to_bf16(0.5 * synth.make_grad_output(cfb))
+    dO = torch.full_like(Q, nan)
+    dO[0] = to_device(dOa, "bf16")[0]
+    dO[1, :, :Nb] = to_device(dOb, "bf16")[0]
+    O, lse = ob.omni_sparse_attn_fwd(desc, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap)
+    dQ, dK, dV = ob.omni_sparse_attn_bwd(desc, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap)
+    torch.cuda.synchronize()
+    for c, cfg, n, i, dO_np in ((ca, cfa, Na, 0, dOa), (cb, cfb, Nb, 1, dOb)):
+        kv_lists = [list(c.o_kvidx[0])]
+        Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+        _check_fwd(c, to_host(O[i:i + 1, :, :n]), to_host(lse[i:i + 1, :, :n]), Oo, Lo)
+        want = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO_np, c.o_qidx, kv_lists, cfg.causal, cfg.scale)
+        _check_grads(cfg, (dQ[i:i + 1, :, :n], dK[i:i + 1, :, :n], dV[i:i + 1, :, :n]), want, c.o_qidx, kv_lists)
+    # the padding of the short sequence: zero output and zero gradients, never NaN
+    for x in (O, dQ, dK, dV):
+        assert not to_host(x[1, :, Nb:]).any()
+    assert np.all(to_host(lse[1, :, Nb:]) == -np.inf)
+
+
 # ------------------------------------------------------------------ strides
 
 @pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
