@@ -1007,6 +1007,45 @@ def test_token_major_memory_layout_gives_the_same_bits(cfg):
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("cfg,batch", [(CFG_BF16, 2), (CFG_F32, 2)], ids=lambda x: getattr(x, "name", str(x)))
+def test_decode_on_a_token_major_cache_gives_the_same_bits(cfg, batch):
+    """The KV cache as [batch, token, head, dim] in memory (viewed head-major): every decode call reads it through
+    the descriptor's strides and gives the head-major cache's result bit for bit."""
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    H = cfg.n_q_heads
+    b = len(c.o_kvidx[0][0])
+    kv_idx, _ = lists_to_padded([list(c.o_kvidx[0])] * batch, H, b)
+    budget = torch.full((batch,), b, dtype=torch.int32, device="cuda")
+    ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                               cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    grp_idx, grp_mask, grp_cnt = ob.omni_group_subset(ldesc, kv_idx, budget, b)
+    vis_idx, vis_cnt = ob.omni_visual_subset(ldesc, kv_idx, budget, b)
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    K2, V2 = tm(dKc), tm(dVc)
+    assert K2.stride(1) == cfg.head_dim and K2.stride(2) == cfg.n_kv_heads * cfg.head_dim
+    dctx = torch.from_numpy(ctx).cuda()
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    d1 = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, 0.08)
+    d2 = ob.make_decode_desc(dq, K2, cfg.vis_begin, cfg.vis_end, 0.08)
+
+    def run(desc, Kx, Vx):
+        out = [ob.omni_slim_decode(desc, dq, Kx, Vx, dctx, dprobe, vis_idx, vis_cnt, vis_idx.shape[-1])[0],
+               ob.omni_slim_decode_grouped(desc, dq, Kx, Vx, dctx, dprobe, grp_idx, grp_mask, grp_cnt)[0],
+               ob.omni_dense_decode(desc, dq, Kx, Vx, dctx)]
+        Kcomp, Vcomp = ob.omni_compact_cache(desc, Kx, Vx, grp_idx, grp_cnt)
+        out.append(ob.omni_slim_decode_compact(desc, dq, Kx, Vx, dctx, dprobe, Kcomp, Vcomp, grp_idx, grp_mask, grp_cnt)[0])
+        torch.cuda.synchronize()
+        return out, Kcomp
+
+    o1, kc1 = run(d1, dKc, dVc)
+    o2, kc2 = run(d2, K2, V2)
+    for x, y in zip(o1, o2):
+        assert torch.equal(x, y)
+    n = int(grp_cnt.min())
+    assert torch.equal(kc1[:, :, :n], kc2[:, :, :n])
+
+
 # ------------------------------------------------------------------ visual tokens in the middle of the sequence
 
 @pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
