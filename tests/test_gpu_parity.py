@@ -874,6 +874,43 @@ def test_decode_step_replays_from_a_hip_graph():
         assert torch.isfinite(scratch)
 
 
+def test_calls_on_two_streams_with_their_own_workspaces():
+    """Every call is ordered by its stream only and keeps its scratch in the caller's workspace: a prefill step and a
+    training step issued on two streams at once (default priority, one workspace each) give what they give alone."""
+    ca, cb = case_for(CFG_BF16), case_for(CFG_BF16_64)
+    Na, Nb = CFG_BF16.n_tokens, CFG_BF16_64.n_tokens
+    dOb = to_device(synth.round_to_bf16(0.5 * synth.make_grad_output(CFG_BF16_64)), "bf16")
+
+    def step_a(ws):
+        sel = ob.omni_prefill_select(ca.desc, ca.dQ, ca.dK, ca.q_mode, ca.q_param, ca.recall_p, ca.probe_block, 0, ws=ws)
+        return ob.omni_sparse_attn_fwd(ca.desc, ca.dQ, ca.dK, ca.dV, sel.q_idx, sel.q_cnt, sel.kv_idx, sel.budget.budget, Na,
+                                       ws=ws)
+
+    def step_b(ws):
+        sel = ob.omni_prefill_select(cb.desc, cb.dQ, cb.dK, cb.q_mode, cb.q_param, cb.recall_p, cb.probe_block, 2, ws=ws)
+        O, lse = ob.omni_sparse_attn_fwd(cb.desc, cb.dQ, cb.dK, cb.dV, sel.q_idx, sel.q_cnt, sel.kv_idx, sel.budget.budget,
+                                         Nb, ws=ws, _per_head=True)
+        return ob.omni_sparse_attn_bwd(cb.desc, cb.dQ, cb.dK, cb.dV, O, dOb, lse, sel.q_idx, sel.q_cnt, sel.kv_idx,
+                                       sel.budget.budget, Nb, ws=ws, _per_head=True)
+
+    wa, wb = ob.Workspace(), ob.Workspace()
+    alone_a, alone_b = step_a(wa), step_b(wb)
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(3):
+        with torch.cuda.stream(sa):
+            got_a = step_a(wa)
+        with torch.cuda.stream(sb):
+            got_b = step_b(wb)
+        with torch.cuda.stream(sa):
+            got_a2 = step_a(wa)
+        torch.cuda.synchronize()
+        for x, y in zip(alone_a + alone_b, got_a + got_b):
+            assert torch.equal(x, y)
+        for x, y in zip(alone_a, got_a2):
+            assert torch.equal(x, y)
+
+
 # ------------------------------------------------------------------ batch > 1
 
 CFG_B2 = synth.C2_16K.scaled(name="bf16_batch2", batch=2, frames=4, tok_per_frame=252, n_text=70, n_q_heads=8, n_kv_heads=2,
