@@ -19,6 +19,10 @@ __global__ void sched_prefix_kernel(const int* __restrict__ q_cnt, int BH, int N
   }
   sched[kSchedPrefix + BH] = items;
   sched[kSchedTotal] = items;
+  for (int q = 0; q < kSchedQueues; ++q) {                 // one list; sched_assign_kernel cuts it into queues if asked to
+    sched[kSchedCursor + q] = q == 0 ? 0 : items;
+    sched[kSchedEnd + q] = items;
+  }
 }
 
 struct ItemRef {
@@ -231,8 +235,10 @@ int run_schedule(const Layer& L, const int* q_cnt, const int* budget, int b_cap,
   hipLaunchKernelGGL(sched_cost_kernel, dim3(blocks), dim3(256), 0, st, q_cnt, budget, qvis, L.bph, BH, L.Hq, L.N, b_cap, L.causal,
                      tile_m, keys_off, sched);
   OMNI_LAUNCH_CHECK();
-  hipLaunchKernelGGL(sched_assign_kernel, dim3(1), dim3(kAssignThreads), 0, st, BH, queues, keys_off, sched);
-  OMNI_LAUNCH_CHECK();
+  if (queues > 1 && BH <= kSchedMaxQueuedHeads) {
+    hipLaunchKernelGGL(sched_assign_kernel, dim3(1), dim3(kAssignThreads), 0, st, BH, queues, keys_off, sched);
+    OMNI_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL(sched_rank_kernel, dim3((unsigned)cdiv(cap, (size_t)kRankItems)), dim3(256), 0, st, BH, keys_off, order_off,
                      sched);
   OMNI_LAUNCH_CHECK();
