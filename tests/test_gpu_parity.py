@@ -638,6 +638,34 @@ def test_block_attention_in_place_equals_gathered_path_and_oracle(cfg, block, fr
     assert np.max(np.abs(to_host(lse1)[fin] - Lo[fin])) <= 2e-2
 
 
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
+def test_block_lists_train_through_their_token_lists(cfg):
+    """Training on block lists: expanded to token lists they go through the same forward and backward, and the
+    gradients are the oracle's for those sets (pad entries of a partial last block collect nothing)."""
+    c = case_for(cfg)
+    N, H, block = cfg.n_tokens, cfg.n_q_heads, 64
+    nb = math.ceil(N / block)
+    nsel = max(2, nb // 2)
+    rng = np.random.default_rng(83)
+    lists = [[np.sort(np.concatenate([[0, nb - 1], 1 + rng.choice(nb - 2, nsel - 2, replace=False)])).astype(np.int32)
+              for _ in range(H)]]
+    blk_idx, _ = lists_to_padded(lists, H, nsel)
+    blk_budget = torch.tensor([nsel], dtype=torch.int32, device="cuda")
+    kv_idx, budget = ob.omni_expand_blocks(c.desc, blk_idx, blk_budget, block)
+    q_idx, q_cnt = lists_to_padded(c.o_qidx, H, N)
+    dO_np = synth.make_grad_output(cfg)
+    if cfg.dtype == "bf16":
+        dO_np = synth.round_to_bf16(0.5 * dO_np)
+    dO = to_device(dO_np, cfg.dtype)
+    b_cap = kv_idx.shape[-1]
+    O, lse = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, kv_idx, budget, b_cap)
+    grads = ob.omni_sparse_attn_bwd(c.desc, c.dQ, c.dK, c.dV, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap)
+    torch.cuda.synchronize()
+    tok = oc.expand_blocks(lists, block, N)
+    want = oc.sparse_attn_bwd(c.Q, c.K, c.V, dO_np, c.o_qidx, tok, cfg.causal, cfg.scale)
+    _check_grads(cfg, grads, want, c.o_qidx, tok)
+
+
 def test_sparse_forward_with_more_heads_than_the_queued_scheduler_places():
     """Batch 150 x 8 heads = 1200 (batch, head) pairs: above 1024 the work list falls back to one queue.  Every batch
     entry holds the same sequence, so every one must give the oracle's output for it."""
