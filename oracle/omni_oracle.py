@@ -255,9 +255,22 @@ def kurtosis(a_f32):
     return np.where(m2 > 0, r, -2.0)
 
 
+FLATTEST_TIE_REL = 1e-9
+
+
 def flattest_head(kurt):
-    """Head with the smallest kurtosis (lowest index among equals).  [B]."""
-    return np.argmin(kurt, axis=-1).astype(np.int32)
+    """Head with the smallest kurtosis (budget equation: arg-min over heads).  [B].
+
+    The paper does not say which head wins among equals.  Heads whose kurtosis
+    lies within FLATTEST_TIE_REL (relative) of the smallest count as tied and the
+    lowest index wins.  The window matters for vectors of two or three scores,
+    where the statistic is the same constant for every head (-2 and -1.5) and an
+    exact arg-min would be decided by the rounding of the moment sums.
+    """
+    kurt = np.asarray(kurt, dtype=np.float64)
+    lo = kurt.min(axis=-1, keepdims=True)
+    tied = kurt <= lo + FLATTEST_TIE_REL * np.abs(lo)
+    return np.argmax(tied, axis=-1).astype(np.int32)
 
 
 def budget_of(a_head_f32, recall_p: float, n_queries: int) -> int:
@@ -406,7 +419,7 @@ def sparse_attn_fwd(Q, K, V, q_idx, kv_idx, causal: bool, scale: float):
     return O, L
 
 
-def sparse_attn_bwd(Q, K, V, dO, q_idx, kv_idx, causal: bool, scale: float):
+def sparse_attn_bwd(Q, K, V, dO, q_idx, kv_idx, causal: bool, scale: float, O=None):
     """Gradient of sparse_attn_fwd w.r.t. Q, K, V with the index sets constant.
 
     The paper applies the same sparse attention in training and gives no
@@ -415,8 +428,15 @@ def sparse_attn_bwd(Q, K, V, dO, q_idx, kv_idx, causal: bool, scale: float):
     dS = P * (dP - rowsum(dO * O)), dQ = dS K * scale, dK = dS^T Q * scale.
     dK and dV add up over the query heads that share a KV head.  Rows that are
     not kept / not selected are 0.  Returns dQ [B,Hq,N,d], dK, dV [B,Hkv,N,d].
+
+    O [B,Hq,N,d], when given, is the forward's output as the layer stored it
+    (rounded to the layer's type) and is what rowsum(dO * O) reads, as in a
+    training step, where the backward is handed the stored output; without it
+    the unrounded product P V is used.
     """
     Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    if O is not None:
+        O = _f64(O)
     B, Hq, N, d = Q.shape
     Hkv = K.shape[1]
     G = _group(Hq, Hkv)
@@ -439,7 +459,7 @@ def sparse_attn_bwd(Q, K, V, dO, q_idx, kv_idx, causal: bool, scale: float):
             with np.errstate(divide="ignore", invalid="ignore"):
                 P = np.where(ok[:, None], P / l, 0.0)
             do = dO[b, i, qi] * ok[:, None]
-            o = P @ V[b, g, ki]
+            o = P @ V[b, g, ki] if O is None else O[b, i, qi]
             dP = do @ V[b, g, ki].T
             delta = (do * o).sum(axis=1, keepdims=True)
             dS = P * (dP - delta)

@@ -181,6 +181,32 @@ def test_backward_full_budget_matches_autograd_of_library_attention():
     np.testing.assert_allclose(dV, V.grad.numpy(), rtol=1e-9, atol=1e-12)
 
 
+def test_backward_with_a_stored_output_reads_it_in_the_row_sums_only():
+    """O handed in = what rowsum(dO * O) reads.  The exact output gives the plain gradient; an output off by E shifts
+    dS by -P * rowsum(dO * E) and nothing else (dV unchanged), checked with softmax rows from the library."""
+    B, Hq, Hkv, N, d = 1, 2, 1, 11, 4
+    Qn, Kn, Vn, dOn = (_rand(s, 60 + j) for j, s in enumerate([(B, Hq, N, d), (B, Hkv, N, d), (B, Hkv, N, d), (B, Hq, N, d)]))
+    full = _full_lists(B, Hq, N)
+    scale = 0.5
+    Oo, _ = oc.sparse_attn_fwd(Qn, Kn, Vn, full, full, True, scale)
+    plain = oc.sparse_attn_bwd(Qn, Kn, Vn, dOn, full, full, True, scale)
+    same = oc.sparse_attn_bwd(Qn, Kn, Vn, dOn, full, full, True, scale, O=Oo)
+    for x, y in zip(plain, same):
+        np.testing.assert_allclose(x, y, rtol=0, atol=1e-13)
+    E = 0.01 * _rand(Oo.shape, 70)
+    dQ, dK, dV = oc.sparse_attn_bwd(Qn, Kn, Vn, dOn, full, full, True, scale, O=Oo + E)
+    np.testing.assert_array_equal(dV, plain[2])
+    dK_want = plain[1].copy()
+    for i in range(Hq):
+        S = torch.tensor(Qn[0, i] @ Kn[0, 0].T * scale).masked_fill(~torch.tril(torch.ones(N, N, dtype=torch.bool)), float("-inf"))
+        P = torch.softmax(S, dim=1).numpy()
+        shift = -P * (dOn[0, i] * E[0, i]).sum(axis=1, keepdims=True)
+        np.testing.assert_allclose(dQ[0, i], plain[0][0, i] + shift @ Kn[0, 0] * scale, rtol=1e-10, atol=1e-13)
+        dK_want[0, 0] += shift.T @ Qn[0, i] * scale
+    np.testing.assert_allclose(dK, dK_want, rtol=1e-10, atol=1e-13)
+    assert np.abs(dK - plain[1]).max() > 1e-5
+
+
 def test_backward_matches_central_finite_differences():
     B, Hq, Hkv, N, d = 1, 2, 1, 9, 4
     rng = np.random.default_rng(40)

@@ -268,6 +268,22 @@ def test_flattest_head_is_argmin_with_lowest_index_on_ties_and_estimators_agree(
     assert oc.flattest_head(oc.kurtosis(np.stack([peak, flat])[None]))[0] == 1
 
 
+def test_flattest_head_ties_within_the_window_go_to_the_lowest_index():
+    # two and three scores: the statistic is -2 and -3/2 whatever the values (for deviations that sum to zero,
+    # sum c^4 = (sum c^2)^2 / 2 when there are three of them), so every head ties and head 0 is taken
+    rng = np.random.default_rng(77)
+    for n, const in ((2, -2.0), (3, -1.5)):
+        for _ in range(50):
+            a = rng.uniform(0.01, 3.0, (2, 6, n)).astype(np.float32)
+            k = oc.kurtosis(a)
+            np.testing.assert_allclose(k, const, rtol=0, atol=1e-12)
+            np.testing.assert_array_equal(oc.flattest_head(k), [0, 0])
+    # inside the window the lowest index wins, outside it the smaller value does
+    np.testing.assert_array_equal(oc.flattest_head(np.array([[1.0 + 5e-10, 1.0, 1.0 - 1e-12]])), [0])
+    np.testing.assert_array_equal(oc.flattest_head(np.array([[1.0 + 1e-6, 1.0, 1.0 + 1e-12]])), [1])
+    np.testing.assert_array_equal(oc.flattest_head(np.array([[-1.5 + 1e-6, -1.5 - 2e-16, -1.5]])), [1])
+
+
 # ------------------------------------------------------------------ budget
 
 def _brute_budget(a, p, n):
