@@ -469,6 +469,50 @@ def sparse_attn_bwd(Q, K, V, dO, q_idx, kv_idx, causal: bool, scale: float, O=No
     return dQ, dK, dV
 
 
+def sparse_attn_bwd_term_rss(Q, K, V, dO, q_idx, kv_idx, causal: bool, scale: float, O=None):
+    """Root of the sum of squares of the products that add up to each gradient element.
+
+    Every element of dQ, dK, dV is a sum of products (dS[n,k] K[k,e] scale over
+    the keys of a row; dS[n,k] Q[n,e] scale and P[n,k] dO[n,e] over the kept
+    queries of all heads of the group).  An implementation that rounds one
+    factor of each product to t bits is off by about 2^-t times this root (the
+    roundings are independent), whatever order it adds in, so the parity tests
+    scale their bar for reduced-precision arithmetic with it.  Same arguments
+    and same chain rule as sparse_attn_bwd; returns (rQ, rK, rV), shaped like
+    (dQ, dK, dV), all >= 0.
+    """
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    if O is not None:
+        O = _f64(O)
+    B, Hq, N, d = Q.shape
+    G = _group(Hq, K.shape[1])
+    sQ = np.zeros_like(Q)
+    sK = np.zeros_like(K)
+    sV = np.zeros_like(V)
+    for b in range(B):
+        for i in range(Hq):
+            qi = np.asarray(q_idx[b][i], dtype=np.int64)
+            ki = np.asarray(kv_idx[b][i], dtype=np.int64)
+            if qi.size == 0 or ki.size == 0:
+                continue
+            g = i // G
+            S = _masked_scores(Q[b, i, qi], K[b, g, ki], qi, ki, causal, scale)
+            m = S.max(axis=1, keepdims=True)
+            ok = np.isfinite(m[:, 0])
+            m = np.where(np.isfinite(m), m, 0.0)
+            P = np.exp(S - m)
+            l = P.sum(axis=1, keepdims=True)
+            with np.errstate(divide="ignore", invalid="ignore"):
+                P = np.where(ok[:, None], P / l, 0.0)
+            do = dO[b, i, qi] * ok[:, None]
+            o = P @ V[b, g, ki] if O is None else O[b, i, qi]
+            dS = P * (do @ V[b, g, ki].T - (do * o).sum(axis=1, keepdims=True))
+            sQ[b, i, qi] = ((dS ** 2) @ (K[b, g, ki] ** 2)) * scale ** 2
+            np.add.at(sK[b, g], ki, ((dS ** 2).T @ (Q[b, i, qi] ** 2)) * scale ** 2)
+            np.add.at(sV[b, g], ki, (P ** 2).T @ (do ** 2))
+    return np.sqrt(sQ), np.sqrt(sK), np.sqrt(sV)
+
+
 def visual_subset(kv_idx, vis_begin: int, vis_end: int):
     """The selected keys that are visual tokens, per head, ascending.
 

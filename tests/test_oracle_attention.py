@@ -207,6 +207,49 @@ def test_backward_with_a_stored_output_reads_it_in_the_row_sums_only():
     assert np.abs(dK - plain[1]).max() > 1e-5
 
 
+def test_term_root_sum_of_squares_of_the_gradient_elements():
+    """Pins of the tolerance helper: a gradient element that is one single product has root-sum-square |element|;
+    Cauchy-Schwarz bounds every element by sqrt(terms) times it; it is linear in |dO|; it is at most the sum of
+    absolute terms, which a brute-force loop over the products gives on a tiny case."""
+    B, Hq, Hkv, N, d = 1, 2, 1, 7, 3
+    Q, K, V, dO = (_rand(s, 80 + j) for j, s in enumerate([(B, Hq, N, d), (B, Hkv, N, d), (B, Hkv, N, d), (B, Hq, N, d)]))
+    # one kept query in one head: dK and dV elements are single products
+    q1, kv1 = [[np.array([5]), np.array([], dtype=np.int64)]], [[np.array([1, 4]), np.array([2])]]
+    g = oc.sparse_attn_bwd(Q, K, V, dO, q1, kv1, True, 0.7)
+    r = oc.sparse_attn_bwd_term_rss(Q, K, V, dO, q1, kv1, True, 0.7)
+    np.testing.assert_allclose(r[1], np.abs(g[1]), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(r[2], np.abs(g[2]), rtol=1e-12, atol=1e-15)
+    # one key: dQ elements are single products
+    q2, kv2 = [[np.array([2, 3, 6]), np.array([1, 6])]], [[np.array([0]), np.array([1])]]
+    g = oc.sparse_attn_bwd(Q, K, V, dO, q2, kv2, True, 0.7)
+    r = oc.sparse_attn_bwd_term_rss(Q, K, V, dO, q2, kv2, True, 0.7)
+    np.testing.assert_allclose(r[0], np.abs(g[0]), rtol=1e-12, atol=1e-15)
+    # general sets: brute force over the products of dK and dV
+    q3 = [[np.array([1, 2, 4, 6]), np.array([0, 3, 5, 6])]]
+    kv3 = [[np.array([0, 2, 3]), np.array([1, 2, 5, 6])]]
+    g = oc.sparse_attn_bwd(Q, K, V, dO, q3, kv3, True, 0.7)
+    r = oc.sparse_attn_bwd_term_rss(Q, K, V, dO, q3, kv3, True, 0.7)
+    O, L = oc.sparse_attn_fwd(Q, K, V, q3, kv3, True, 0.7)
+    sK, sV, nK = np.zeros_like(K), np.zeros_like(V), np.zeros_like(K)
+    for i in range(Hq):
+        for n in q3[0][i]:
+            delta = float(dO[0, i, n] @ O[0, i, n])
+            for k in kv3[0][i]:
+                if k > n:
+                    continue
+                p = math.exp(float(Q[0, i, n] @ K[0, 0, k]) * 0.7 - L[0, i, n])
+                ds = p * (float(dO[0, i, n] @ V[0, 0, k]) - delta)
+                sK[0, 0, k] += (ds * Q[0, i, n] * 0.7) ** 2
+                sV[0, 0, k] += (p * dO[0, i, n]) ** 2
+                nK[0, 0, k] += 1
+    np.testing.assert_allclose(r[1], np.sqrt(sK), rtol=1e-10, atol=1e-14)
+    np.testing.assert_allclose(r[2], np.sqrt(sV), rtol=1e-10, atol=1e-14)
+    assert np.all(np.abs(g[1]) <= np.sqrt(np.maximum(nK, 1)) * r[1] + 1e-12)
+    r3 = oc.sparse_attn_bwd_term_rss(Q, K, V, 3.0 * dO, q3, kv3, True, 0.7)
+    for x, y in zip(r, r3):
+        np.testing.assert_allclose(3.0 * x, y, rtol=1e-12)
+
+
 def test_backward_matches_central_finite_differences():
     B, Hq, Hkv, N, d = 1, 2, 1, 9, 4
     rng = np.random.default_rng(40)
