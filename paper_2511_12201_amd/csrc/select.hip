@@ -278,7 +278,8 @@ __global__ __launch_bounds__(kSelThreads) void radix_budget_kernel(const float* 
   __shared__ RadixShared sh;
   const int b = blockIdx.y;
   const int h = per_head ? (int)blockIdx.x : flattest[b];
-  const unsigned long long target = (unsigned long long)(target_mass * kFixScale);
+  // rounded up: the truncated element masses must never reach a target below the real one
+  const unsigned long long target = (unsigned long long)ceil(target_mass * kFixScale);
   const int r = radix_budget_block(a + ((long long)b * H + h) * N, N, target, sh);
   if (threadIdx.x == 0) out[per_head ? b * H + h : b] = r;
 }
@@ -342,15 +343,13 @@ __global__ __launch_bounds__(kSelThreads) void kurtosis_kernel(const float* __re
 __global__ void argmin_kernel(const double* __restrict__ kurt, int H, int* __restrict__ flattest) {
   const int b = blockIdx.x;
   if (threadIdx.x == 0) {
-    int best = 0;
+    // heads within 1e-9 (relative) of the smallest kurtosis tie and the lowest index wins: for two or
+    // three scores the statistic is one constant for every head and rounding would pick the head
     double v = kurt[b * H];
-    for (int h = 1; h < H; ++h) {
-      const double c = kurt[b * H + h];
-      if (c < v) {
-        v = c;
-        best = h;
-      }
-    }
+    for (int h = 1; h < H; ++h) v = fmin(v, kurt[b * H + h]);
+    const double bar = v + 1e-9 * fabs(v);
+    int best = 0;
+    while (best < H - 1 && !(kurt[b * H + best] <= bar)) ++best;
     flattest[b] = best;
   }
 }
