@@ -353,6 +353,29 @@ int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q,
                              void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * omni_slim_decode_grouped_static -- omni_slim_decode_grouped for callers that
+ * cannot allocate or carry a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments without ws / ws_bytes,
+ * same kernels, same output bits.  The partial softmax states go to a buffer the
+ * library holds in device memory (a file-scope __device__ array of
+ * omni_static_scratch_bytes() = 16 MiB, one copy on every GPU the library runs on,
+ * kept until the process ends).  The call allocates and frees nothing; the first
+ * call on a device looks the buffer's address up once.
+ * Errors: OMNI_ERR_WORKSPACE if the shape needs more scratch than the buffer holds
+ * (omni_workspace_bytes(OMNI_CALL_SLIM_DECODE, desc, 0) > omni_static_scratch_bytes());
+ * use omni_slim_decode_grouped then.  All calls on one GPU share the buffer: two
+ * calls that overlap in time on the same GPU (different streams or threads) race.
+ * Nothing of an earlier call's contents is relied on or needs clearing.
+ */
+int omni_slim_decode_grouped_static(const omni_decode_desc* desc, const void* q,
+                                    const void* Kcache, const void* Vcache, const int32_t* ctx_len,
+                                    const float* probe_keys,
+                                    const int32_t* grp_idx, const uint32_t* grp_mask,
+                                    const int32_t* grp_cnt, int32_t u_cap, void* O, uint8_t* active,
+                                    void* stream);
+size_t omni_static_scratch_bytes(void);
+
+/*
  * Block-granular variant of the KV selection -- Sec. "Block-wise probing and sparse
  * flash attention kernel" as the paper runs it: queries AND keys are mean-pooled in
  * blocks of `block` tokens, the pooled map gives one accumulated score per key block

@@ -32,6 +32,7 @@ EXPORTED = [
     "omni_visual_subset_per_head", "omni_prefill_select", "omni_compact_cache", "omni_slim_decode_compact",
     "omni_compact_cache_paged", "omni_slim_decode_paged",
     "omni_group_subset_per_head", "omni_debug_key_split_len",
+    "omni_slim_decode_grouped_static", "omni_static_scratch_bytes",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -122,6 +123,9 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_expand_blocks.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
     lib.omni_block_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.omni_slim_decode_grouped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.omni_slim_decode_grouped_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.omni_static_scratch_bytes.restype = sz
+    lib.omni_static_scratch_bytes.argtypes = []
     lib.omni_compact_cache.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.omni_slim_decode_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_compact_cache_paged.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
@@ -605,6 +609,21 @@ def omni_slim_decode_grouped(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe
                                         _ptr(probe_keys), _ptr(grp_idx), _ptr(grp_mask), _ptr(grp_cnt),
                                         grp_idx.shape[-1], _ptr(O), _ptr(active), _ptr(buf), buf.numel(), _stream()))
     return O, active
+
+
+def omni_slim_decode_grouped_static(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_mask, grp_cnt,
+                                    O, active):
+    """The grouped decode step on the library's built-in scratch buffer: no workspace, and O / active must be given
+    (nothing is allocated on this path)."""
+    lib = load_library()
+    _check(lib.omni_slim_decode_grouped_static(C.byref(desc), _ptr(q), _ptr(Kcache), _ptr(Vcache), _ptr(ctx_len),
+                                               _ptr(probe_keys), _ptr(grp_idx), _ptr(grp_mask), _ptr(grp_cnt),
+                                               grp_idx.shape[-1], _ptr(O), _ptr(active), _stream()))
+    return O, active
+
+
+def omni_static_scratch_bytes() -> int:
+    return int(load_library().omni_static_scratch_bytes())
 
 
 def omni_compact_cache(desc: DecodeDesc, Kcache, Vcache, grp_idx, grp_cnt, Kcomp=None, Vcomp=None):

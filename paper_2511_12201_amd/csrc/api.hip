@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -153,6 +154,44 @@ using namespace omni;
     int rc__ = (expr);         \
     if (rc__ != OMNI_OK) return rc__; \
   } while (0)
+
+// ---- library-owned scratch for the entry point that takes no workspace (omni_slim_decode_grouped_static)
+
+namespace omni {
+namespace {
+
+constexpr size_t kStaticScratchBytes = size_t(16) << 20;
+constexpr int kMaxDevices = 64;
+
+// One copy per GPU the library runs on, held until the process ends.  In host code the name below is only a
+// stand-in for the symbol: the memory is reached through the address hipGetSymbolAddress returns on each device.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static void* g_scratch_ptr[kMaxDevices];          // per device, filled on the first call on that device
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (nullptr + error message on failure).  No allocation.
+void* static_scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_error("static scratch: no current device (or device id >= %d)", kMaxDevices);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      set_error("static scratch: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+}  // namespace
+}  // namespace omni
 
 extern "C" {
 
@@ -594,6 +633,31 @@ int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q, const 
   if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
   if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
+  return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
+                    static_cast<hipStream_t>(stream));
+}
+
+size_t omni_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int omni_slim_decode_grouped_static(const omni_decode_desc* desc, const void* q, const void* Kcache,
+                                    const void* Vcache, const int32_t* ctx_len, const float* probe_keys,
+                                    const int32_t* grp_idx, const uint32_t* grp_mask, const int32_t* grp_cnt,
+                                    int32_t u_cap, void* O, uint8_t* active, void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(q); REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(ctx_len); REQUIRE_PTR(probe_keys);
+  REQUIRE_PTR(grp_idx); REQUIRE_PTR(grp_mask); REQUIRE_PTR(grp_cnt); REQUIRE_PTR(O); REQUIRE_PTR(active);
+  REQUIRE_ALIGNED(q); REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache);
+  if (u_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "u_cap must be >= 1");
+  if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
+  if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
+  const size_t need = decode_ws(desc);
+  if (need > kStaticScratchBytes)
+    OMNI_FAIL(OMNI_ERR_WORKSPACE, "this shape needs %zu bytes of scratch, the built-in buffer holds %zu: use "
+              "omni_slim_decode_grouped with a workspace", need, kStaticScratchBytes);
+  void* ws = static_scratch_of_current_device();
+  if (!ws) return OMNI_ERR_HIP;
+  // the kernels write every partial state they later read, so nothing of the previous call's contents is cleared
   return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
                     static_cast<hipStream_t>(stream));
 }
