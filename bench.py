@@ -65,7 +65,7 @@ def main():
                          "its JSON (for profiling; the headline line is the default run)")
     ap.add_argument("--decode-steps", type=int, default=256, help="with --only decode: decode steps per mode")
     ap.add_argument("--decode-modes", default="", help="with --only decode: comma-separated subset of "
-                    "slim,slim_grouped,slim_compact,slim_paged,dense (for counter runs; prints the times only)")
+                    "slim,slim_stateless,slim_grouped,slim_compact,slim_paged,dense (for counter runs; prints the times only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known HBM traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -465,7 +465,7 @@ def mfma_probe(ob, repeats: int = 1):
     return {n: (v[0] if repeats == 1 else v) for n, v in runs.items()}
 
 
-DECODE_MODES = ("slim", "slim_grouped", "slim_compact", "slim_paged", "dense")
+DECODE_MODES = ("slim", "slim_stateless", "slim_grouped", "slim_compact", "slim_paged", "dense")
 
 
 def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, batches=(1, 2, 4, 8), modes=DECODE_MODES):
@@ -514,6 +514,9 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
         O = torch.empty(B, Hq, D, dtype=torch.bfloat16, device="cuda")
         act = torch.empty(B, Hq, dtype=torch.uint8, device="cuda")
         ddesc = ob.make_decode_desc(q_all[0], Kc, cfg.vis_begin, cfg.vis_end, TAU)
+        # omni_slim_decode as a serving loop calls it: the lists are fixed at prefill (static_lists), so the call keeps
+        # them merged per KV group in its workspace; "slim_stateless" reads the per-head lists anew on every step
+        sdesc = ob.make_decode_desc(q_all[0], Kc, cfg.vis_begin, cfg.vis_end, TAU, static_lists=True)
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         # the compacted store: the rows of the group lists side by side (built once after prefill)
         u_max = int(grp_cnt.max().cpu())
@@ -546,6 +549,7 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
             for _ in range(3):                                    # untimed warm-up of both entry points
                 ob.omni_slim_decode_grouped(ddesc, q_all[0], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act)
                 ob.omni_slim_decode(ddesc, q_all[0], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
+                ob.omni_slim_decode(sdesc, q_all[0], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
                 ob.omni_dense_decode(ddesc, q_all[0], Kc, Vc, ctx, O)
             ctx.fill_(N)
             torch.cuda.synchronize()
@@ -556,6 +560,8 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
                 Vc[:, :, N + s] = v_new[s]
                 ctx += 1
                 if mode == "slim":
+                    ob.omni_slim_decode(sdesc, q_all[s], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
+                elif mode == "slim_stateless":
                     ob.omni_slim_decode(ddesc, q_all[s], Kc, Vc, ctx, probe_b, vis_idx, vis_cnt, b, O, act)
                 elif mode == "slim_grouped":
                     ob.omni_slim_decode_grouped(ddesc, q_all[s], Kc, Vc, ctx, probe_b, grp_idx, grp_mask, grp_cnt, O, act)
@@ -621,6 +627,7 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
             "slim_us_per_token": round(ktime["slim"], 2), "dense_us_per_token": round(ktime["dense"], 2),
             "speedup": round(ktime["dense"] / ktime["slim"], 3),
             "speedup_grouped": round(ktime["dense"] / ktime["slim_grouped"], 3),
+            "slim_stateless_us_per_token": round(ktime["slim_stateless"], 2),
             "slim_grouped_us_per_token": round(ktime["slim_grouped"], 2),
             "slim_compact_us_per_token": round(ktime["slim_compact"], 2),
             "slim_paged_us_per_token": round(ktime["slim_paged"], 2),

@@ -95,6 +95,12 @@ typedef struct {
   float softmax_scale;
   float tau;                   /* lazy/active threshold of the query-mask equation */
   int64_t kv_stride[3];        /* batch, head, token strides of the caches, in elements */
+  int32_t static_lists;        /* omni_slim_decode only.  1: the caller guarantees that vis_idx / vis_cnt keep their
+                                  contents from call to call for as long as the same workspace is passed (the lists
+                                  are fixed at prefill; Sec. "KV Cache Slimming").  The first call with a workspace
+                                  then merges the lists of every KV group into it (ascending union + membership
+                                  bits) and later calls read a stored row once per group, as
+                                  omni_slim_decode_grouped does.  0: the lists are read anew on every call. */
 } omni_decode_desc;
 
 /* Paged form of the compacted visual KV store (omni_compact_cache_paged,

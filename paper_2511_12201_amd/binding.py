@@ -53,6 +53,7 @@ class DecodeDesc(C.Structure):
         ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("cache_capacity", C.c_int32), ("vis_begin", C.c_int32), ("vis_end", C.c_int32), ("dtype", C.c_int32),
         ("softmax_scale", C.c_float), ("tau", C.c_float), ("kv_stride", C.c_int64 * 3),
+        ("static_lists", C.c_int32),
     ]
 
 
@@ -188,7 +189,7 @@ def make_layer_desc(Q: torch.Tensor, K: torch.Tensor, vis_begin: int, vis_end: i
 
 
 def make_decode_desc(q: torch.Tensor, Kcache: torch.Tensor, vis_begin: int, vis_end: int, tau: float,
-                     softmax_scale: float | None = None) -> DecodeDesc:
+                     softmax_scale: float | None = None, static_lists: bool = False) -> DecodeDesc:
     B, Hq, D = q.shape
     d = DecodeDesc()
     d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = B, Hq, Kcache.shape[1], D
@@ -198,6 +199,7 @@ def make_decode_desc(q: torch.Tensor, Kcache: torch.Tensor, vis_begin: int, vis_
     d.softmax_scale = softmax_scale if softmax_scale is not None else D ** -0.5
     d.tau = tau
     d.kv_stride = (C.c_int64 * 3)(*Kcache.stride()[:3])
+    d.static_lists = 1 if static_lists else 0
     return d
 
 

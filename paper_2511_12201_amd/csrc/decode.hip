@@ -108,8 +108,10 @@ __device__ __forceinline__ unsigned char* lds_block() {
 //    and are read back transposed, 2 bytes at a time, in the row order the accumulator layout dictates
 //    (k index 8 h + e of step s <-> row 16 s + 8 (e / 4) + 4 h + e % 4 on both operands).
 // Same contract as stream_rows below.
-template <int D, int GT, typename RowOf, typename MaskOf>
-__device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, int head0, int begin, int end,
+// The rows come as nsub successive stretches: prep(sub, begin, end) sets the list positions of stretch `sub`
+// (it may stage them in LDS and may contain barriers; every thread calls it).
+template <int D, int GT, typename RowOf, typename MaskOf, typename Prep>
+__device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, int head0, int nsub, Prep prep,
                                                 RowOf row_of, MaskOf mask_of, unsigned head_bits, int slot,
                                                 const u16* krows, const u16* vrows, long long row_stride) {
   constexpr int kWaves = kThreads / 64;
@@ -152,6 +154,11 @@ __device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, in
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
   float m = -INFINITY, l = 0.f;              // head n: running maximum (scaled), sum over this lane's rows
 
+  bool any_rows = false;
+  for (int sub = 0; sub < nsub; ++sub) {
+  int begin = 0, end = 0;
+  prep(sub, begin, end);
+  any_rows |= begin < end;
   // cache row and member word of list position it0 + 32 wave + n (both lane halves hold it); -1 / 0: nothing to read
   auto fetch_meta = [&](int it0, int& krow, unsigned& mem) {
     const int it = it0 + wave * 32 + n;
@@ -239,8 +246,9 @@ __device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, in
     krow = krow_n;
     mem = mem_n;
   }
+  }  // stretches
 
-  if (begin >= end) {                       // empty slice: mark it, the combine pass skips its output row
+  if (!any_rows) {                          // empty slice: mark it, the combine pass skips its output row
     if (threadIdx.x < GT) {
       float* dst = p.part + ((long long)(b * p.Hq + head0 + threadIdx.x) * (p.n_shared + p.n_head) + slot) * (D + 2);
       dst[D] = -INFINITY;
@@ -294,8 +302,8 @@ __device__ __forceinline__ void stream_rows_mma(const DecodeParams& p, int b, in
 // mask_of gives the heads (bit h = head0 + h) that attend the row; heads outside head_bits are skipped
 // altogether (a wave-uniform decision) and get an empty partial state.
 // krows / vrows point at row 0 of the (batch, KV head) the rows belong to; rows are row_stride elements apart.
-template <typename T, int D, int GT, typename RowOf, typename MaskOf>
-__device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g, int head0, int begin, int end,
+template <typename T, int D, int GT, typename RowOf, typename MaskOf, typename Prep>
+__device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g, int head0, int nsub, Prep prep,
                                             RowOf row_of, MaskOf mask_of, unsigned head_bits, int slot,
                                             const T* krows, const T* vrows, long long row_stride) {
   constexpr int E = Elem<T>::kPer16B;
@@ -304,7 +312,7 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
   // bf16 with 2..8 heads per workgroup: both products on the matrix cores.  Otherwise (fp32, one head, more than
   // 8 heads) every lane group forms its rows' dot products and weighted sums on the vector ALU.
   if constexpr (sizeof(T) == 2 && GT >= 2 && GT <= 8) {
-    stream_rows_mma<D, GT>(p, b, head0, begin, end, row_of, mask_of, head_bits, slot, krows, vrows, row_stride);
+    stream_rows_mma<D, GT>(p, b, head0, nsub, prep, row_of, mask_of, head_bits, slot, krows, vrows, row_stride);
     return;
   }
   constexpr int U = kUnroll;              // rows per lane group and trip
@@ -363,6 +371,11 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
     }
   };
 
+  bool any_rows = false;
+  for (int sub = 0; sub < nsub; ++sub) {
+  int begin = 0, end = 0;
+  prep(sub, begin, end);
+  any_rows |= begin < end;
   // rows (and member bits) of a trip: list lookups, so they are fetched one trip ahead of the rows themselves --
   // a row's address depends on its list entry, and two dependent memory latencies per trip would otherwise add up
   auto fetch_meta = [&](int it0, int (&row)[U], unsigned (&member)[U]) {
@@ -407,8 +420,9 @@ __device__ __forceinline__ void stream_rows(const DecodeParams& p, int b, int g,
       member[u] = member_n[u];
     }
   }
+  }  // stretches
 
-  if (begin >= end) {                       // empty slice: mark it, the combine pass skips its output row
+  if (!any_rows) {                          // empty slice: mark it, the combine pass skips its output row
     if (threadIdx.x < GT) {
       float* dst = p.part + ((long long)(b * p.Hq + head0 + threadIdx.x) * (p.n_shared + p.n_head) + slot) * (D + 2);
       dst[D] = -INFINITY;
@@ -462,7 +476,7 @@ __device__ __forceinline__ void decode_shared_rows(const DecodeParams& p, int sl
   int per = cdiv(total, p.n_shared);
   per = cdiv(per, RPP * kUnroll) * (RPP * kUnroll);
   const int begin = min(total, slice * per), end = min(total, begin + per);
-  stream_rows<T, D, GT>(p, b, g, g * p.G + chunk * GT, begin, end,
+  stream_rows<T, D, GT>(p, b, g, g * p.G + chunk * GT, 1, [&](int, int& b0_, int& e0_) { b0_ = begin; e0_ = end; },
                         [&](int it) { return it < n_lo ? it : hi0 + (it - n_lo); }, [](int) { return ~0u; },
                         (1u << GT) - 1u, slice, static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1],
                         static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1], p.ks[2]);
@@ -494,10 +508,10 @@ __device__ __forceinline__ void decode_head_rows(const DecodeParams& p, int slic
   per = cdiv(per, RPP * kUnroll) * (RPP * kUnroll);
   const int begin = min(total, slice * per), end = min(total, begin + per);
   const int* vlist = p.vis_idx + (long long)bh * p.b_cap;
-  stream_rows<T, D, 1>(p, b, g, i, begin, end,
+  stream_rows<T, D, 1>(p, b, g, i, 1, [&](int, int& b0_, int& e0_) { b0_ = begin; e0_ = end; },
                        [&](int it) {
                          const int r = vlist[it];
-                         return r < ctx ? r : -1;          // stored rows beyond the context are ignored
+                         return (unsigned)r < (unsigned)ctx ? r : -1;          // stored rows beyond the context are ignored
                        },
                        [](int) { return 1u; }, 1u, p.n_shared + slice,
                        static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1],
@@ -556,10 +570,10 @@ __device__ __forceinline__ void decode_group_rows(const DecodeParams& p, int sli
       for (int i = threadIdx.x; i < nslots; i += kThreads) sPages[i] = slot0 + i < p.pages_cap ? table[slot0 + i] : -1;
       __syncthreads();
     }
-    stream_rows<T, D, GT>(p, b, g, head0, begin, end,
+    stream_rows<T, D, GT>(p, b, g, head0, 1, [&](int, int& b0_, int& e0_) { b0_ = begin; e0_ = end; },
                           [&](int it) {
                             const int slot = it >> pshift;
-                            if (vlist[it] >= ctx || slot >= p.pages_cap) return -1;
+                            if ((unsigned)vlist[it] >= (unsigned)ctx || slot >= p.pages_cap) return -1;
                             const int page = staged ? sPages[slot - slot0] : table[slot];
                             return (unsigned)page < (unsigned)p.pool_pages ? (page << pshift) + (it & pmask) : -1;
                           },
@@ -569,18 +583,198 @@ __device__ __forceinline__ void decode_group_rows(const DecodeParams& p, int sli
   }
   if (p.Kcomp) {                 // the listed rows sit side by side in the compacted store: position = row
     const long long base = (long long)bg * p.b_cap * D;
-    stream_rows<T, D, GT>(p, b, g, head0, begin, end, [&](int it) { return vlist[it] < ctx ? it : -1; },
+    stream_rows<T, D, GT>(p, b, g, head0, 1, [&](int, int& b0_, int& e0_) { b0_ = begin; e0_ = end; },
+                          [&](int it) { return (unsigned)vlist[it] < (unsigned)ctx ? it : -1; },
                           [&](int it) { return mlist[it] >> shift; }, bits, p.n_shared + slice,
                           static_cast<const T*>(p.Kcomp) + base, static_cast<const T*>(p.Vcomp) + base, (long long)D);
     return;
   }
-  stream_rows<T, D, GT>(p, b, g, head0, begin, end,
+  stream_rows<T, D, GT>(p, b, g, head0, 1, [&](int, int& b0_, int& e0_) { b0_ = begin; e0_ = end; },
                         [&](int it) {
                           const int r = vlist[it];
-                          return r < ctx ? r : -1;
+                          return (unsigned)r < (unsigned)ctx ? r : -1;
                         },
                         [&](int it) { return mlist[it] >> shift; }, bits, p.n_shared + slice,
                         static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1],
+                        static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1], p.ks[2]);
+}
+
+// The per-head lists of a KV group merged on the fly (omni_slim_decode under grouped-query attention): slice `slice`
+// of unit `unit` owns a stretch of the visual token range and walks it kMergeSpan tokens at a time.  For every span
+// the active heads' list entries that fall into it are marked in an LDS bitmap (bit h of word t: head h stores
+// token t), the marked tokens are compacted, in ascending order, into an LDS list with their member words, and the
+// rows are streamed exactly as from a stored group list -- a row is loaded once, whichever of the heads store it.
+// Reading the lists costs 4 bytes per stored entry and active head, against 4 D bytes per row.
+constexpr int kMergeSpan = 1024;            // tokens of a span
+constexpr int kMergeWindow = kMergeSpan;    // list entries read per head and span: no more can fall into it
+
+// First positions of two ascending lists a0[0, n0), a1[0, n1) whose values are >= v, found together by one
+// wavefront (all lanes take part and get both results): 64 probes per list and round, the loads of both lists in
+// flight at once.  Three rounds for lists of up to 2^18 entries.  (More probes per round would save a round but
+// every probe is a cache line of its own: with a thousand workgroups searching seven lists each, 256 probes per
+// round move more bytes than the rows of the step.)
+__device__ __forceinline__ void wave_lower_bound2(const int* __restrict__ a0, int n0, const int* __restrict__ a1, int n1,
+                                                  int v, int& r0, int& r1) {
+  const int lane = threadIdx.x & 63;
+  const int* a[2] = {a0, a1};
+  int lo[2] = {0, 0}, hi[2] = {n0, n1};                 // the answers lie in [lo, hi]
+  for (;;) {
+    const bool last = hi[0] - lo[0] <= 64 && hi[1] - lo[1] <= 64;        // wave-uniform
+    int val[2], step[2];
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      step[w] = max(1, cdiv(hi[w] - lo[w], 64));
+      const int idx = lo[w] + lane * step[w];
+      val[w] = idx < hi[w] ? a[w][idx] : 0x7fffffff;
+    }
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      const int below = __popcll(__ballot(val[w] < v));  // probes ascend with the lane: those below v are a prefix
+      if (below == 0) {
+        hi[w] = lo[w];
+      } else {
+        const int nlo = lo[w] + (below - 1) * step[w] + 1;
+        hi[w] = min(hi[w], lo[w] + below * step[w]);
+        lo[w] = nlo;
+      }
+    }
+    if (last) break;                                    // the steps were 1: lo = hi = the answer
+  }
+  r0 = lo[0];
+  r1 = lo[1];
+}
+
+template <typename T, int D, int GT>
+__device__ __forceinline__ void decode_merged_rows(const DecodeParams& p, int slice, int unit) {
+  __shared__ unsigned sBits;
+  __shared__ int sCur[GT];                              // per head: first list entry not yet consumed
+  __shared__ int sCount;
+  __shared__ int sWaveSum[kThreads / 64];
+  __shared__ unsigned sWord[kMergeSpan];                // bitmap of a span, then the member words of its list
+  __shared__ int sTok[kMergeSpan];
+  const int chunks = p.G / GT;
+  const int chunk = unit % chunks, bg = unit / chunks;
+  const int b = bg / p.Hkv, g = bg % p.Hkv;
+  const int head0 = g * p.G + chunk * GT;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int ctx = min(p.ctx_len[b], p.cap);
+  const int vis_hi = min(p.v1, ctx);                    // stored rows beyond the context are ignored
+  const int span_tokens = max(0, vis_hi - p.v0);
+  const int per = cdiv(max(1, p.v1 - p.v0), p.n_head);   // tokens per slice
+  const int t_begin = p.v0 + min(span_tokens, slice * per), t_end = p.v0 + min(span_tokens, (slice + 1) * per);
+  const int nsub_all = cdiv(t_end - t_begin, kMergeSpan);
+  if (threadIdx.x == 0) sBits = 0u;
+  __syncthreads();
+  {
+    const float* pk = p.probe + ((long long)(b * p.Hkv + g) * 2) * D;
+    for (int h = wave; h < GT; h += kThreads / 64) {
+      const int i = head0 + h;
+      const T* qptr = static_cast<const T*>(p.q) + (long long)(b * p.Hq + i) * D;
+      float dot = 0.f;
+      for (int d = lane; d < D; d += 64) dot = fmaf(Elem<T>::load(qptr + d), pk[D + d] - pk[d], dot);
+      dot = wave_sum(dot);
+      if (lane == 0) {
+        const float score = 1.0f / (1.0f + expf(-dot * p.scale));
+        const int act = (i == 0 || score > p.tau) ? 1 : 0;
+        if (act) atomicOr(&sBits, 1u << h);
+        if (slice == 0 && p.active) p.active[b * p.Hq + i] = (unsigned char)act;
+      }
+    }
+  }
+  __syncthreads();
+  const unsigned bits = sBits;
+  const int nsub = bits ? nsub_all : 0;
+  // A wavefront looks after heads `wave` and `wave + 4` of the tile (GT <= 8), both at once; a head that is lazy,
+  // or beyond GT, is an empty list.
+  static_assert(GT <= 2 * (kThreads / 64), "two heads per wavefront");
+  const int* hlist[2];
+  int hcnt[2];
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    const int h = wave + w * (kThreads / 64);
+    const bool on = h < GT && ((bits >> h) & 1u) && nsub > 0;
+    const int bh = b * p.Hq + head0 + (h < GT ? h : 0);
+    hlist[w] = p.vis_idx + (long long)bh * p.b_cap;
+    hcnt[w] = on ? max(0, min(p.vis_cnt[bh], p.b_cap)) : 0;
+  }
+  if (nsub > 0) {                                       // where the lists enter the slice
+    int c0, c1;
+    wave_lower_bound2(hlist[0], hcnt[0], hlist[1], hcnt[1], t_begin, c0, c1);
+    if (lane == 0) {
+      if (wave < GT) sCur[wave] = c0;
+      if (wave + kThreads / 64 < GT) sCur[wave + kThreads / 64] = c1;
+    }
+  }
+  __syncthreads();
+  auto prep = [&](int sub, int& begin, int& end) {
+    const int t_lo = t_begin + sub * kMergeSpan, t_hi = min(t_end, t_lo + kMergeSpan);
+    __syncthreads();                                    // the previous span's list is no longer read
+    for (int t = threadIdx.x; t < kMergeSpan; t += kThreads) sWord[t] = 0u;
+    __syncthreads();
+    {
+      // ascending entries: those of this span are among the next kMergeWindow entries of a list.  The loads of both
+      // lists of the wavefront are issued before any is used.
+      constexpr int NK = kMergeWindow / 64;
+      int tok[2][NK], cur[2];
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const int h = wave + w * (kThreads / 64);
+        cur[w] = h < GT ? sCur[h] : 0;
+#pragma unroll
+        for (int k = 0; k < NK; ++k) {
+          const int e = cur[w] + k * 64 + lane;
+          tok[w][k] = e < hcnt[w] ? hlist[w][e] : 0x7fffffff;
+        }
+      }
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const int h = wave + w * (kThreads / 64);
+        if (hcnt[w] == 0) continue;                     // wave-uniform
+        int taken = 0;
+#pragma unroll
+        for (int k = 0; k < NK; ++k) {
+          const bool in = tok[w][k] < t_hi;
+          if (in && tok[w][k] >= t_lo) atomicOr(&sWord[tok[w][k] - t_lo], 1u << h);
+          taken += __popcll(__ballot(in));
+        }
+        if (lane == 0) sCur[h] = cur[w] + taken;
+      }
+    }
+    __syncthreads();
+    // compaction in token order: every thread owns kMergeSpan / kThreads consecutive words
+    constexpr int PER = kMergeSpan / kThreads;
+    unsigned w[PER];
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      w[j] = sWord[threadIdx.x * PER + j];
+      mine += w[j] != 0u;
+    }
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) sWaveSum[wave] = incl;
+    __syncthreads();                                    // every word is in registers: the list may take their place
+    int base = 0;
+    for (int k = 0; k < wave; ++k) base += sWaveSum[k];
+    if (threadIdx.x == kThreads - 1) sCount = base + incl;
+    int at = base + incl - mine;
+#pragma unroll
+    for (int j = 0; j < PER; ++j)
+      if (w[j] != 0u) {
+        sTok[at] = t_lo + threadIdx.x * PER + j;
+        sWord[at] = w[j];
+        ++at;
+      }
+    __syncthreads();
+    begin = 0;
+    end = sCount;
+  };
+  stream_rows<T, D, GT>(p, b, g, head0, nsub, prep, [&](int it) { return sTok[it]; }, [&](int it) { return sWord[it]; },
+                        bits, p.n_shared + slice, static_cast<const T*>(p.K) + b * p.ks[0] + g * p.ks[1],
                         static_cast<const T*>(p.V) + b * p.ks[0] + g * p.ks[1], p.ks[2]);
 }
 
@@ -652,19 +846,29 @@ int group_tile(int G) {
   return 1;
 }
 
-// One launch for the row streams of a step that share a register footprint.  GROUP: the group lists, then the
+constexpr int kNoLists = 0, kStoredGroupLists = 1, kMergedHeadLists = 2;
+
+// One launch for the row streams of a step that share a register footprint.  With lists (the stored group lists, or
+// the per-head lists of a group merged on the fly -- a kernel of its own, so that its bookkeeping does not cost the
+// stored-list kernel registers): the lists, then the
 // shared rows -- the list workgroups come first in the grid (they are the long ones) and the few shared
 // (non-visual) rows of a slimmed step fill in behind them instead of costing a launch of their own (11 us at
 // batch 1).  Otherwise the shared rows only (plain decode; per-head lists, whose one-head workgroups need half
 // the registers and lose their occupancy inside a common kernel: 70 -> 84 us when fused).
-template <typename T, int D, int GT, bool GROUP>
+template <typename T, int D, int GT, int LISTS>
 __global__ __launch_bounds__(kThreads, 3) void decode_rows_kernel(DecodeParams p) {
   const int units_s = p.B * p.Hkv * (p.G / GT);
-  const int n_list = GROUP ? p.n_head * units_s : 0;
+  const int n_list = LISTS ? p.n_head * units_s : 0;
   const int i = blockIdx.x;
-  if constexpr (GROUP) {
+  if constexpr (LISTS == kStoredGroupLists) {
     if (i < n_list) {
       decode_group_rows<T, D, GT>(p, i % p.n_head, i / p.n_head);
+      return;
+    }
+  }
+  if constexpr (LISTS == kMergedHeadLists) {
+    if (i < n_list) {
+      decode_merged_rows<T, D, GT>(p, i % p.n_head, i / p.n_head);
       return;
     }
   }
@@ -682,13 +886,20 @@ template <typename T, int D, int GT>
 void launch_rows(const DecodeParams& p, hipStream_t st) {
   const int units_s = p.B * p.Hkv * (p.G / GT);
   const int n_shared = p.n_shared * units_s;
+  // group lists, or per-head lists of a group of two or more heads (merged on the fly into the rows of the group)
   if (p.n_head > 0 && p.grp_mask) {
-    hipLaunchKernelGGL((decode_rows_kernel<T, D, GT, true>), dim3(n_shared + p.n_head * units_s), dim3(kThreads), 0, st, p);
+    hipLaunchKernelGGL((decode_rows_kernel<T, D, GT, kStoredGroupLists>), dim3(n_shared + p.n_head * units_s),
+                       dim3(kThreads), 0, st, p);
+    return;
+  }
+  if (p.n_head > 0 && GT >= 2) {
+    hipLaunchKernelGGL((decode_rows_kernel<T, D, GT, kMergedHeadLists>), dim3(n_shared + p.n_head * units_s),
+                       dim3(kThreads), 0, st, p);
     return;
   }
   if (p.n_head > 0)      // per-head lists: the long kernel first
     hipLaunchKernelGGL((decode_head_kernel<T, D>), dim3(p.n_head, p.B * p.Hq), dim3(kThreads), 0, st, p);
-  hipLaunchKernelGGL((decode_rows_kernel<T, D, GT, false>), dim3(n_shared), dim3(kThreads), 0, st, p);
+  hipLaunchKernelGGL((decode_rows_kernel<T, D, GT, kNoLists>), dim3(n_shared), dim3(kThreads), 0, st, p);
 }
 
 template <typename T, int D>
@@ -842,7 +1053,9 @@ int run_decode(const omni_decode_desc* d, const void* q, const void* K, const vo
   const Slices s = decode_slices(d, probe != nullptr);
   p.n_shared = s.n_shared;
   p.n_head = s.n_head;
-  if (grp_mask) {            // group lists: one workgroup serves all heads of a group, so fewer, longer slices do
+  if (grp_mask || (probe && group_tile(p.G) >= 2)) {
+    // group lists (stored, or merged on the fly from the per-head lists): one workgroup serves all heads of a
+    // group, so fewer, longer slices do
     const int units = p.B * p.Hkv * (p.G / group_tile(p.G));
     p.n_head = std::min(s.n_head, slices_for(d->vis_end - d->vis_begin, units, kRowBlocks));
   }

@@ -329,6 +329,60 @@ def test_grouped_slim_decode(cfg, batch):
     assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
 
 
+@pytest.mark.parametrize("cfg,batch", [(CFG_BF16, 1), (CFG_BF16, 3), (CFG_BF16_64, 2), (CFG_F32, 2)],
+                         ids=lambda x: getattr(x, "name", str(x)))
+def test_slim_decode_with_static_lists_keeps_the_merged_lists_in_its_workspace(cfg, batch):
+    """static_lists = 1: the first call with a workspace merges the per-head lists per KV group into it, later calls
+    reuse them.  Every call must give the bits of omni_slim_decode_grouped on the library's own group lists (and so
+    the oracle's result); other lists (another pointer), another decode call on the same workspace in between, and a
+    new workspace all make it merge again."""
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    tau = 0.08
+    H = cfg.n_q_heads
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    dctx = torch.from_numpy(ctx).cuda()
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    b_cap = max(len(v) for per in vis for v in per)
+    vis_idx, vis_cnt = lists_to_padded(vis, H, b_cap)
+    desc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau)
+    sdesc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau, static_lists=True)
+    assert ob.workspace_bytes(ob.CALL_SLIM_DECODE, sdesc) > ob.workspace_bytes(ob.CALL_SLIM_DECODE, desc)
+    view = torch.int16 if cfg.dtype == "bf16" else torch.int32
+
+    def grouped_reference(lists):
+        b = max(len(x) for per in lists for x in per)
+        kv_idx, cnt = lists_to_padded(lists, H, b)
+        ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                                   cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+        grp = ob.omni_group_subset_per_head(ldesc, kv_idx, cnt, b)
+        return ob.omni_slim_decode_grouped(desc, dq, dKc, dVc, dctx, dprobe, *grp, ws=ob.Workspace())
+
+    want_O, want_act = grouped_reference(vis)
+    Oo, acto, sc = oc.slim_decode(q, Kc, Vc, ctx, probe.astype(np.float32), vis, tau, cfg.vis_begin, cfg.vis_end, cfg.scale)
+    same = to_host(want_act) == acto
+    assert np.max(np.abs(to_host(want_O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
+    ws = ob.Workspace()
+    for _ in range(3):                                   # merge, then two calls on the stored lists
+        O, act = ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(O.view(view), want_O.view(view)) and torch.equal(act, want_act)
+    # the stateless call on the same workspace in between: the next static call merges again
+    O0, act0 = ob.omni_slim_decode(desc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws)
+    ws.bufs[ob.CALL_SLIM_DECODE].fill_(0xFF)             # whatever it left there
+    O, act = ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(O.view(view), want_O.view(view)) and torch.equal(act, want_act)
+    assert np.max(np.abs(to_host(O0)[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
+    # other lists in other tensors: every second entry of every head
+    thin = [[v[::2] for v in per] for per in vis]
+    t_idx, t_cnt = lists_to_padded(thin, H, b_cap)
+    want2_O, want2_act = grouped_reference(thin)
+    O, act = ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, t_idx, t_cnt, b_cap, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(O.view(view), want2_O.view(view)) and torch.equal(act, want2_act)
+    assert not torch.equal(O.view(view), want_O.view(view))
+
+
 @pytest.mark.parametrize("cfg,batch", [(CFG_BF16, 1), (CFG_BF16, 3), (CFG_BF16_64, 2), (CFG_F32, 2), (CFG_F32_128, 1)],
                          ids=lambda x: getattr(x, "name", str(x)))
 def test_compacted_cache_decode(cfg, batch):
