@@ -185,7 +185,10 @@ def main():
                    "step": "prefill_select (= score_queries + select_queries + kv_budget + select_kv) + sparse_attn_fwd"},
         "roofline": {"bound": "mfma", "kernel": "attn_fwd_bf16_kernel<128> (sparse)", "achieved": round(ach, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC.get(cfg.name), "kernel_ms": round(attn_ms, 4),
+                     "traffic": MEASURED_TRAFFIC.get(cfg.name),
+                     "traffic_source": "profiles/attn_fwd_c3_64k_hbm_traffic.txt (rocprofv3 counter runs of this command; "
+                                       "not measured in this run)",
+                     "kernel_ms": round(attn_ms, 4),
                      "achieved_on_issued_tiles": round(ach_issued, 2),
                      "frac_on_issued_tiles": round(ach_issued / PEAK_BF16_TFLOPS, 4)},
         "selection_ms": round(sel_ms, 4),
@@ -253,8 +256,24 @@ def main():
         except Exception as e:
             out["per_head_budget_variant"] = {"error": repr(e)}
         out["cpu_baseline"] = cpu_baseline(cfg, layer, q_lists, kv_lists, valid, ms_per_step)
-        del Q, K, V, O, dev, layer
+        del Q, K, V, O, dev
         torch.cuda.empty_cache()
+        # shared budget against per-head budgets over the recall target, on the bench's generator and on the
+        # configuration text's generator without the salience term and the sharpness of head 0 (synth `plain`)
+        try:
+            t0 = time.time()
+            plain_cfg = cfg.scaled(name=cfg.name + "_plain", plain=True)
+            out["recall_sweep"] = {
+                "what": "budget b/N, recall reached and ms per step (selection + sparse forward) for the paper's "
+                        "shared budget (flattest head), the largest per-head budget, and one budget per head; "
+                        "over-selection = shared budget minus the heads' own budgets, in percent of N (the paper "
+                        "reports about 5 at recall 0.2 and 20 at 0.8 between its flattest and sharpest heads)",
+                "bench_generator": bench_recall_sweep(torch, ob, synth, cfg, layer=layer),
+                "plain_generator": bench_recall_sweep(torch, ob, synth, plain_cfg)}
+            log(f"[bench] recall_sweep done in {time.time() - t0:.1f}s")
+        except Exception as e:
+            out["recall_sweep"] = {"error": repr(e)}
+        del layer
         for name, fn in (("train_step_32k", bench_train),
                          ("train_step_32k_per_head_budgets", lambda *a: bench_train(*a, per_head=True)),
                          ("decode_131k", bench_decode),
@@ -396,6 +415,61 @@ def bench_per_head_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, 
             "recall_min": round(float(res.recall.min().item()), 4),
             "flops_fraction_of_dense": round(valid / (Hq * N * (N + 1) // 2), 4),
             "attn_algorithmic_tflops": round(4.0 * cfg.head_dim * valid / (attn * 1e-3) / 1e12, 1)}
+
+
+RECALL_SWEEP = (0.2, 0.5, 0.8, 0.82, 0.95)
+
+
+def bench_recall_sweep(torch, ob, synth, cfg, steps: int = 5, layer=None):
+    """Shared budget against per-head budgets as a function of the recall target (the measurement of the paper's
+    paragraph on over-selection for sharp heads, its sparsity-difference figure): budgets, recall reached, and the
+    time of the whole step, for budget_mode 0 (flattest head, the paper's rule), 1 (largest per-head budget) and 2
+    (one budget per head)."""
+    layer = layer or synth.make_layer(cfg)
+    Q, K, V = (_upload(torch, synth, layer[k]) for k in "QKV")
+    N, Hq = cfg.n_tokens, cfg.n_q_heads
+    desc = ob.make_layer_desc(Q, K, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    O = torch.empty_like(Q)
+    lse = torch.empty(cfg.batch, Hq, N, dtype=torch.float32, device="cuda")
+    rows = []
+    for p in RECALL_SWEEP:
+        row = {"recall_target": p}
+        per_head_budgets = None
+        for mode, name in ((2, "per_head"), (0, "flattest_head"), (1, "max_over_heads")):
+            sel = None
+
+            def step():
+                nonlocal sel
+                sel = ob.omni_prefill_select(desc, Q, K, 0, TAU, p, PROBE_BLOCK, mode, N, out=sel)
+                ob.omni_sparse_attn_fwd(desc, Q, K, V, sel.q_idx, sel.q_cnt, sel.kv_idx, sel.budget.budget, N, O, lse,
+                                        _per_head=mode == 2)
+
+            step()
+            step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+            b = sel.budget.budget.cpu().numpy().reshape(-1).astype(np.float64)
+            r = {"ms_per_step": round(ms, 3), "recall_min": round(float(sel.budget.recall.min().item()), 4)}
+            if mode == 2:
+                per_head_budgets = b
+                r["budget_fraction_min_mean_max"] = [round(b.min() / N, 4), round(b.mean() / N, 4), round(b.max() / N, 4)]
+            else:
+                r["budget_fraction"] = round(b[0] / N, 4)
+                r["flattest_head"] = int(sel.budget.flattest.cpu()[0])
+                # keys selected beyond what the heads need themselves, in percent of the sequence: on average over
+                # the heads, and for the sharpest head (the figure's flattest-minus-sharpest sparsity difference)
+                r["over_selection_pct_of_N"] = {"mean_head": round(100 * (b[0] - per_head_budgets.mean()) / N, 2),
+                                                "sharpest_head": round(100 * (b[0] - per_head_budgets.min()) / N, 2)}
+                r["heads_below_target"] = int((sel.budget.recall.cpu().numpy() < p - 1e-6).sum())
+            row[name] = r
+        rows.append(row)
+    del Q, K, V, O, lse
+    torch.cuda.empty_cache()
+    return rows
 
 
 def bench_train(torch, ob, synth, steps: int = 5, per_head: bool = False):
@@ -684,8 +758,7 @@ def cpu_baseline(cfg, layer, q_lists, kv_lists, total_pairs, gpu_ms):
     return {"value": round(est_ms, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
             "sample": f"selection pipeline on query heads 0..{len(heads) - 1} ({t_sel:.1f}s, scaled x{cfg.n_q_heads / len(heads):g}) + "
                       f"sparse attention of {sample_q_total} kept queries of heads {att_heads} against their selected keys "
-                      f"({t_att:.1f}s, {sample_pairs} of {total_pairs} pairs, scaled by pairs)",
-            "gpu_speedup": round(est_ms / gpu_ms, 1)}
+                      f"({t_att:.1f}s, {sample_pairs} of {total_pairs} pairs, scaled by pairs)"}
 
 
 if __name__ == "__main__":

@@ -5,20 +5,21 @@
 //   P = exp(S - lse), dV = P^T dO, dP = dO V^T, dS = P (dP - delta),
 //   delta = rowsum(dO O), dQ = scale dS K, dK = scale dS^T Q.
 //
-// Deterministic two-kernel scheme, no floating-point atomics:
-//  * dkdv kernel: a workgroup owns 128 packed keys of one query head (32 per
-//    wavefront, K and V fragments resident in registers) and streams 64-query
-//    tiles of the kept rows through LDS.  S = Q K^T and dP = dO V^T are computed
-//    with queries on the accumulator rows, so that P and dS are already the B
-//    operands of dV^T = dO^T P and dK^T = Q^T dS; the A operands dO^T and Q^T come
-//    from the k-packed copies made by the pack pass.
-//  * dq kernel: a workgroup owns 128 kept queries (32 per wavefront) and streams
-//    64-key tiles, exactly like the forward: S^T = K Q^T, dP^T = V dO^T, and
-//    dQ^T = K^T dS^T with K^T from the k-packed copy of K.
-//  * a reduce kernel adds the per-query-head dK', dV' rows of a KV group into
-//    dK, dV in head order (position found by binary search in the ascending
-//    index list) and writes zeros for unselected tokens.
-// fp32 inputs run the same kernels on the fp32 32x32x2 MFMA with natural layouts.
+// Deterministic, no floating-point atomics.  bf16 (the measured path), three kernels in the forward's style
+// (8 wavefronts, LDS-DMA ring, position masks from the visible-prefix counts):
+//  * attn_bwd_dq_bf16_kernel: a work item is 256 kept queries of a head (32 per wavefront) from the forward's
+//    longest-first list; it streams 64-key tiles of K, V (natural) and K^T (k-packed): S^T = K Q^T,
+//    dP^T = V dO^T, dQ^T += K^T dS^T.
+//  * attn_bwd_key_bf16_kernel<D, MODE>: a workgroup owns 256 packed keys of a query head (32 per wavefront, K or V
+//    fragments resident) and streams 64-query tiles of the packed kept rows (Q, dO natural and k-packed, lse and
+//    delta by 4-byte LDS-DMA).  MODE 0 forms dK' = dS^T Q, MODE 1 dV' = P^T dO: two launches, because the resident
+//    fragments and accumulators of both do not fit two wavefronts per SIMD; S = Q K^T is computed in both.  Items
+//    (head, key tile, split) come from a list a small kernel compacts; a key tile seen by many query tiles is
+//    shared by up to four workgroups, each with a partial plane of its own.
+//  * attn_bwd_reduce_kernel adds the per-query-head dK', dV' rows (and split planes) of a KV group in a fixed order
+//    into dK, dV -- a head's row is found through an inverse slot map -- and writes zeros for unselected tokens.
+// fp32 inputs (the 1e-4 parity cases) keep the older register-staged pair attn_bwd_dkdv_kernel (128 keys per
+// workgroup, dK' and dV' together) / attn_bwd_dq_kernel on the fp32 32x32x2 MFMA with natural layouts.
 #include <algorithm>
 
 #include "common.h"

@@ -16,9 +16,16 @@
 //  * V is packed so that the A operand of O^T = V^T P^T is one 16-byte LDS read:
 //    [16-key group][half h][d][8 keys], key(group,h,j) = 16 group + 8 (j/4) + 4 h + j%4,
 //    which is the order in which the S^T accumulators hold the keys.
-//  * 256 threads = 4 wavefronts x 32 query rows; 64-key K/V tiles are double
-//    buffered in LDS, one barrier per tile; two workgroups fit a CU.
-//  * fp32 inputs take the same path with the fp32 32x32x2 MFMA (accuracy path).
+//  * bf16 (attn_fwd_bf16_kernel, the measured path): 512 threads = 8 wavefronts x
+//    32 query rows per work item of 256 kept queries; 64-key K/V tiles go from
+//    memory straight into a ring of four LDS stages (global_load_lds, hand-placed
+//    s_waitcnt), one barrier per tile; inside a wavefront the softmax of tile t
+//    runs under the MFMAs of tile t+1.  Work items come from a persistent,
+//    longest-first work list with one queue per XCD (sched.hip); causal masks are
+//    position compares against per-query visible-prefix counts (pack.hip).
+//  * fp32 inputs (attn_fwd_kernel, the accuracy path of the 1e-4 parity cases):
+//    256 threads = 4 wavefronts x 32 rows, fp32 32x32x2 MFMA, register-staged
+//    double buffer; not tuned.
 
 #include <type_traits>
 
