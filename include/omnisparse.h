@@ -69,7 +69,8 @@ typedef enum {
   OMNI_CALL_GROUP_SUBSET = 9,
   OMNI_CALL_BLOCK_SCORES = 10,
   OMNI_CALL_PREFILL_SELECT = 11,
-  OMNI_CALL_BLOCK_ATTN_FWD = 12
+  OMNI_CALL_BLOCK_ATTN_FWD = 12,
+  OMNI_CALL_BLOCK_ATTN_BWD = 13
 } omni_call_id;
 
 /* One attention layer during prefill / training.
@@ -429,6 +430,27 @@ int omni_block_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* 
                         int32_t block, void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * omni_block_attn_bwd -- gradients of omni_block_attn_fwd (the chain rule on the
+ * attention equation of Sec. "Preliminary" with the block lists constant, as in
+ * omni_sparse_attn_bwd; the paper trains with the same block-sparse attention, Sec.
+ * "Implementation Details"), again without a gathered copy: K and V (natural and
+ * k-packed K) are laid out once per KV head in token order and the kernels of
+ * omni_sparse_attn_bwd find tile t of a head's list through the same tile map.
+ * Same tiles in the same order, so dQ, dK, dV are bit for bit what
+ * omni_expand_blocks + omni_sparse_attn_bwd give.
+ * Arguments as in omni_block_attn_fwd and omni_sparse_attn_bwd (O, dO, lse in; dQ
+ * [batch, n_q_heads, n_tokens, head_dim], dK, dV [batch, n_kv_heads, n_tokens,
+ * head_dim] out, fully written); same limits as omni_block_attn_fwd.
+ * Workspace: OMNI_CALL_BLOCK_ATTN_BWD with param = blk_cap * block.
+ */
+int omni_block_attn_bwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                        const void* O, const void* dO, const float* lse,
+                        const int32_t* q_idx, const int32_t* q_cnt,
+                        const int32_t* blk_idx, const int32_t* blk_budget, int32_t blk_cap,
+                        int32_t block, void* dQ, void* dK, void* dV,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Baselines used by the reported metric (not part of the method): plain causal
  * / non-causal attention of the attention equation in Sec. "Preliminary" built
  * on the same tile engine, and plain decode attention over rows [0, ctx_len).
@@ -491,7 +513,7 @@ int omni_dense_decode(const omni_decode_desc* desc, const void* q,
  * descriptor (omni_layer_desc* for prefill calls, omni_decode_desc* for the two
  * decode calls).  `param` is the index capacity b_cap for the calls that take
  * one, the probe block for OMNI_CALL_KV_BUDGET and OMNI_CALL_PREFILL_SELECT,
- * blk_cap * block for OMNI_CALL_BLOCK_ATTN_FWD, and ignored otherwise.
+ * blk_cap * block for OMNI_CALL_BLOCK_ATTN_FWD and OMNI_CALL_BLOCK_ATTN_BWD, and ignored otherwise.
  * Returns 0 on invalid input (a valid call never needs 0 bytes). */
 size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param);
 

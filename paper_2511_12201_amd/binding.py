@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libomnisparse.so")
 OMNI_F32, OMNI_BF16 = 0, 1
 (CALL_SCORE_QUERIES, CALL_SELECT_QUERIES, CALL_KV_BUDGET, CALL_SELECT_KV, CALL_SPARSE_ATTN_FWD,
  CALL_SPARSE_ATTN_BWD, CALL_SLIM_DECODE, CALL_DENSE_ATTN_FWD, CALL_DENSE_DECODE, CALL_GROUP_SUBSET,
- CALL_BLOCK_SCORES, CALL_PREFILL_SELECT, CALL_BLOCK_ATTN_FWD) = range(13)
+ CALL_BLOCK_SCORES, CALL_PREFILL_SELECT, CALL_BLOCK_ATTN_FWD, CALL_BLOCK_ATTN_BWD) = range(14)
 
 EXPORTED = [
     "omni_score_queries", "omni_select_queries", "omni_kv_budget", "omni_budget_from_scores", "omni_select_kv",
@@ -27,7 +27,7 @@ EXPORTED = [
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
     "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
     "omni_group_subset", "omni_slim_decode_grouped", "omni_block_scores", "omni_expand_blocks",
-    "omni_block_attn_fwd",
+    "omni_block_attn_fwd", "omni_block_attn_bwd",
     "omni_select_kv_per_head", "omni_sparse_attn_fwd_per_head", "omni_sparse_attn_bwd_per_head",
     "omni_visual_subset_per_head", "omni_prefill_select", "omni_compact_cache", "omni_slim_decode_compact",
     "omni_compact_cache_paged", "omni_slim_decode_paged",
@@ -123,6 +123,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_block_scores.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
     lib.omni_expand_blocks.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
     lib.omni_block_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.omni_block_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.omni_slim_decode_grouped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.omni_slim_decode_grouped_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.omni_static_scratch_bytes.restype = sz
@@ -572,6 +573,22 @@ def omni_block_attn_fwd(desc: LayerDesc, Q, K, V, q_idx, q_cnt, blk_idx, blk_bud
                                    _ptr(blk_budget), blk_cap, block, _ptr(O), _ptr(lse), _ptr(buf), buf.numel(),
                                    _stream()))
     return O, lse
+
+
+def omni_block_attn_bwd(desc: LayerDesc, Q, K, V, O, dO, lse, q_idx, q_cnt, blk_idx, blk_budget, block: int,
+                        dQ=None, dK=None, dV=None, ws: Workspace | None = None):
+    """Gradients of omni_block_attn_fwd on the same block lists, again without a gathered K/V copy."""
+    lib = load_library()
+    ws = ws or default_workspace()
+    blk_cap = blk_idx.shape[-1]
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    buf = ws.get(CALL_BLOCK_ATTN_BWD, desc, blk_cap * block)
+    _check(lib.omni_block_attn_bwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(q_idx),
+                                   _ptr(q_cnt), _ptr(blk_idx), _ptr(blk_budget), blk_cap, block, _ptr(dQ), _ptr(dK),
+                                   _ptr(dV), _ptr(buf), buf.numel(), _stream()))
+    return dQ, dK, dV
 
 
 def omni_group_subset(desc: LayerDesc, kv_idx, budget, b_cap: int, u_cap: int | None = None,

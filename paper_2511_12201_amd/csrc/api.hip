@@ -355,6 +355,9 @@ size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param) {
     case OMNI_CALL_BLOCK_ATTN_FWD:
       if (param < 64 || param % 64) { set_error("blk_cap * block must be a positive multiple of 64"); return 0; }
       return attn_fwd_blocks_ws(L, param);
+    case OMNI_CALL_BLOCK_ATTN_BWD:
+      if (param < 64 || param % 64) { set_error("blk_cap * block must be a positive multiple of 64"); return 0; }
+      return attn_bwd_blocks_ws(L, param);
     default: set_error("unknown call id %d", call_id); return 0;
   }
 }
@@ -599,6 +602,30 @@ int omni_block_attn_fwd(const omni_layer_desc* desc, const void* Q, const void* 
   const Layer L = make_layer(desc);
   CHECK(check_ws(ws, ws_bytes, attn_fwd_blocks_ws(L, blk_cap * block)));
   return run_attn_fwd_blocks(L, Q, K, V, q_idx, q_cnt, blk_idx, blk_budget, blk_cap, block, O, lse, ws,
+                             static_cast<hipStream_t>(stream));
+}
+
+int omni_block_attn_bwd(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, const void* O,
+                        const void* dO, const float* lse, const int32_t* q_idx, const int32_t* q_cnt,
+                        const int32_t* blk_idx, const int32_t* blk_budget, int32_t blk_cap, int32_t block, void* dQ,
+                        void* dK, void* dV, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(V); REQUIRE_PTR(O); REQUIRE_PTR(dO); REQUIRE_PTR(lse);
+  REQUIRE_PTR(q_idx); REQUIRE_PTR(q_cnt); REQUIRE_PTR(blk_idx); REQUIRE_PTR(blk_budget);
+  REQUIRE_PTR(dQ); REQUIRE_PTR(dK); REQUIRE_PTR(dV);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K); REQUIRE_ALIGNED(V); REQUIRE_ALIGNED(O); REQUIRE_ALIGNED(dO);
+  REQUIRE_ALIGNED(dQ); REQUIRE_ALIGNED(dK); REQUIRE_ALIGNED(dV);
+  if (desc->dtype != OMNI_BF16) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "omni_block_attn_bwd runs in bf16 only");
+  if (blk_cap < 1 || block < 1) OMNI_FAIL(OMNI_ERR_INVALID, "blk_cap and block must be >= 1");
+  if (block % 64) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "block must be a multiple of 64 (the kernels' key tile)");
+  if ((long long)blk_cap * block > attn_bwd_blocks_max_keys())
+    OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "blk_cap * block above %d", attn_bwd_blocks_max_keys());
+  if (!desc->causal && desc->n_tokens % block)
+    OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "without the causal mask n_tokens must be a multiple of block");
+  const Layer L = make_layer(desc);
+  CHECK(check_ws(ws, ws_bytes, attn_bwd_blocks_ws(L, blk_cap * block)));
+  return run_attn_bwd_blocks(L, Q, K, V, O, dO, lse, q_idx, q_cnt, blk_idx, blk_budget, blk_cap, block, dQ, dK, dV, ws,
                              static_cast<hipStream_t>(stream));
 }
 

@@ -65,6 +65,11 @@ struct BwdParams {
   int split_len;        // query tiles per split, at least
   long long plane;      // floats between the partial-gradient planes of two splits
   int* klist;           // work list of the key kernels: [0], [1] counters (dV, dK kernel), [2] items, [4..] items
+  // In-place block lists (TILEMAP kernels): Kn, Vn, Kt hold every KV head once, in token order ([B*Hkv, npad_kv, D]),
+  // and tile t of a head's key list is tile tile_map[bh * tile_stride + t] of its KV head's copy.
+  const int* tile_map;
+  int tile_stride;
+  int npad_kv;          // rows per (head) buffer of Kn / Vn / Kt: npad for the gathered copies
 };
 
 // first position in ascending a[0,n) with a[pos] >= v
@@ -586,7 +591,9 @@ constexpr int kDqThreads = kDqWaves * 64;
 constexpr int kDqTileM = kDqWaves * 32;
 constexpr int kDqStages = 3;
 
-template <int D>
+constexpr int kBwdMaxMapTiles = 2048;               // key tiles of one head in the in-place variant (128k tokens)
+
+template <int D, bool TILEMAP>
 __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdParams p) {
   typedef u16 T;
   constexpr int CH = D / 8;                          // 16-byte chunks per natural row
@@ -599,6 +606,7 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kDqStages * kStageBytes];
   __shared__ int sBound[2];
   __shared__ int sItem;
+  __shared__ int sTileMap[TILEMAP ? kBwdMaxMapTiles : 1];
 
   const Layer& L = p.L;
   const int lane = lane_id();
@@ -639,6 +647,11 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
   __syncthreads();
   const int n_full_tiles = sBound[0] / kTileN;
   const int ntiles = cdiv(sBound[1], kTileN);
+  if constexpr (TILEMAP) {                                   // this item's share of the head's tile map
+    const int* tm = p.tile_map + (long long)bh * p.tile_stride;
+    for (int t = threadIdx.x; t < ntiles; t += kDqThreads) sTileMap[t] = tm[t];
+    __syncthreads();
+  }
 
   const int qpos = pos_first + wave * 32 + ln;
   const bool qvalid = qpos < nq;
@@ -670,13 +683,16 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
 
-  const T* kn = static_cast<const T*>(p.Kn) + (long long)bh * p.npad * D;
-  const T* vn = static_cast<const T*>(p.Vn) + (long long)bh * p.npad * D;
-  const T* kt = static_cast<const T*>(p.Kt) + (long long)bh * p.npad * D;
+  const int bhx = TILEMAP ? b * L.Hkv + i / L.G : bh;
+  const T* kn = static_cast<const T*>(p.Kn) + (long long)bhx * p.npad_kv * D;
+  const T* vn = static_cast<const T*>(p.Vn) + (long long)bhx * p.npad_kv * D;
+  const T* kt = static_cast<const T*>(p.Kt) + (long long)bhx * p.npad_kv * D;
   auto issue_part = [&](int t, int part) {
     const int op = part / LPH, j = part % LPH;
     const unsigned dst = lds_base + (unsigned)(t % kDqStages) * kStageBytes + op * kOpBytes + (j * kDqWaves + wave) * 1024;
-    const long long tile_off = (long long)t * kTileN * D;
+    // where tile t of the key list lives (wave-uniform: the tile base stays in scalar registers)
+    const int src = TILEMAP ? __builtin_amdgcn_readfirstlane(sTileMap[t]) : t;
+    const long long tile_off = (long long)src * kTileN * D;
     if (op == 0) gload_lds16(kn + tile_off, ngoff[j], dst);
     else if (op == 1) gload_lds16(vn + tile_off, ngoff[j], dst);
     else gload_lds16(kt + tile_off, pgoff[j], dst);
@@ -860,7 +876,7 @@ __global__ __launch_bounds__(1024) void key_list_kernel(BwdParams p, long long n
   }
 }
 
-template <int D, int MODE>
+template <int D, int MODE, bool TILEMAP>
 __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdParams p) {
   typedef u16 T;
   constexpr int CH = D / 8;
@@ -918,8 +934,14 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
   const int q_begin = q_first + sp * per_split;             // this workgroup's query tiles: [q_begin, q_begin + n)
 
   // resident K (and V) fragments: B operands, lane = key column
-  const T* krow = static_cast<const T*>(p.Kn) + ((long long)bh * p.npad + slot) * D;
-  const T* vrow = static_cast<const T*>(p.Vn) + ((long long)bh * p.npad + slot) * D;
+  long long kv_row = (long long)bh * p.npad + slot;
+  if constexpr (TILEMAP) {           // the slot's row inside its KV head's token-ordered copy (slots past the map: masked)
+    const int t = slot / kTileN;
+    const int src = t < p.tile_stride ? p.tile_map[(long long)bh * p.tile_stride + t] : 0;
+    kv_row = (long long)(b * L.Hkv + (bh % L.Hq) / L.G) * p.npad_kv + (long long)src * kTileN + slot % kTileN;
+  }
+  const T* krow = static_cast<const T*>(p.Kn) + kv_row * D;
+  const T* vrow = static_cast<const T*>(p.Vn) + kv_row * D;
   bf16x8 kf[D / 16], vf[MODE == 0 ? D / 16 : 1];
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) {
@@ -1185,6 +1207,14 @@ struct BwdWs {
   float *lse2c, *deltac, *dKp, *dVp;
   int* sched;
   int *qvis, *kfirst, *inv, *klist;
+  int *kidx_kv, *vbudget, *tile_map;      // in-place block lists only
+};
+
+// Block lists walked in place (omni_block_attn_bwd): ascending block ids per head, one budget per batch item.
+struct BlockLists {
+  const int* blk_idx;
+  const int* blk_budget;
+  int blk_cap, block;
 };
 
 constexpr int kKeyHeadGroup = 7;
@@ -1194,14 +1224,17 @@ size_t key_list_slots(const Layer& L, int npad) {
   return (size_t)cdiv(L.B * L.Hq, kKeyHeadGroup) * kKeyHeadGroup * (npad / kKeyTile) * kKeyMaxSplits;
 }
 
-BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
+// npad_kv > 0: Kn, Vn, Kt hold every KV head once ([B*Hkv, npad_kv, D], the in-place block lists) instead of one
+// gathered copy per query head; cap_tiles = key tiles of a head's list then.
+BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad, int npad_kv = 0, int cap_tiles = 0) {
   BwdWs w;
   const size_t es = dtype == OMNI_BF16 ? 2 : 4;
   const size_t BH = (size_t)L.B * L.Hq;
   const size_t krows = BH * npad, qrows = BH * nqpad;
-  w.Kn = a.take<unsigned char>(krows * L.D * es);
-  w.Vn = a.take<unsigned char>(krows * L.D * es);
-  w.Kt = a.take<unsigned char>(dtype == OMNI_BF16 ? krows * L.D * es : 16);
+  const size_t kvrows = npad_kv > 0 ? (size_t)L.B * L.Hkv * npad_kv : krows;
+  w.Kn = a.take<unsigned char>(kvrows * L.D * es);
+  w.Vn = a.take<unsigned char>(kvrows * L.D * es);
+  w.Kt = a.take<unsigned char>(dtype == OMNI_BF16 ? kvrows * L.D * es : 16);
   w.Qt = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
   w.dOt = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
   w.Qn = a.take<unsigned char>(dtype == OMNI_BF16 ? qrows * L.D * es : 16);
@@ -1217,6 +1250,9 @@ BwdWs carve_bwd(Arena& a, const Layer& L, int dtype, int npad, int nqpad) {
   w.kfirst = a.take<int>(dtype == OMNI_BF16 ? krows : 4);
   w.inv = a.take<int>(BH * L.N);
   w.klist = a.take<int>(kKeyListHeader + key_list_slots(L, npad));
+  w.kidx_kv = a.take<int>(npad_kv > 0 ? kvrows : 4);
+  w.vbudget = a.take<int>(L.B);
+  w.tile_map = a.take<int>(npad_kv > 0 ? BH * cap_tiles : 4);
   return w;
 }
 
@@ -1234,18 +1270,38 @@ int bwd_nqpad(const Layer& L) {
   return n;
 }
 
-template <typename T, int D>
+int bwd_npad_kv(const Layer& L) { return (int)align_up(L.N, kTileN); }
+
+// BLOCKS (bf16 only): kv_idx / budget / b_cap are ignored and the key lists are the block lists `blk`, walked in place.
+template <typename T, int D, bool BLOCKS>
 int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, const void* O, const void* dO,
                const float* lse, const int* q_idx, const int* q_cnt, const int* kv_idx, const int* budget, int b_cap,
-               void* dQ, void* dK, void* dV, void* ws, hipStream_t st) {
+               void* dQ, void* dK, void* dV, void* ws, hipStream_t st, const BlockLists* blk = nullptr) {
   constexpr int dt = sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32;
+  static_assert(!BLOCKS || sizeof(T) == 2, "block lists run in bf16");
   Arena a(ws);
-  const int npad = bwd_npad(b_cap), nqpad = bwd_nqpad(L);
-  BwdWs w = carve_bwd(a, L, dt, npad, nqpad);
-  int rc = run_pack_kv(L, dt, K, V, 1, kv_idx, b_cap, budget, b_cap, npad, kKeyTile, w.Kn, w.Vn,
-                       dt == OMNI_BF16 ? w.Kt : nullptr,
-                       nullptr, w.kidx, st);
-  if (rc != OMNI_OK) return rc;
+  const int cap_keys = BLOCKS ? blk->blk_cap * blk->block : b_cap;
+  const int npad = bwd_npad(cap_keys), nqpad = bwd_nqpad(L);
+  const int npad_kv = BLOCKS ? bwd_npad_kv(L) : 0;
+  BwdWs w = carve_bwd(a, L, dt, npad, nqpad, npad_kv, cap_keys / kTileN);
+  int rc;
+  if constexpr (BLOCKS) {
+    // K, V (natural) and K (k-packed) of every KV head once, in token order: shared by the heads of a group
+    rc = run_pack_kv(L, dt, K, V, 0, nullptr, L.N, nullptr, L.N, npad_kv, kTileN, w.Kn, w.Vn, w.Kt, nullptr, w.kidx_kv, st);
+    if (rc != OMNI_OK) return rc;
+    // token lists of the selected blocks (causal bounds, the reduction's slot map), rows npad apart, and the tile map
+    rc = run_expand_blocks(L, blk->blk_idx, blk->blk_budget, blk->blk_cap, blk->block, w.kidx, w.vbudget, npad, st);
+    if (rc != OMNI_OK) return rc;
+    rc = run_tile_map(L, blk->blk_idx, blk->blk_budget, blk->blk_cap, blk->block, npad_kv / kTileN - 1, w.tile_map, st);
+    if (rc != OMNI_OK) return rc;
+    kv_idx = w.kidx;
+    budget = w.vbudget;
+    b_cap = npad;                             // the lists' row pitch; their lengths are in vbudget
+  } else {
+    rc = run_pack_kv(L, dt, K, V, 1, kv_idx, b_cap, budget, b_cap, npad, kKeyTile, w.Kn, w.Vn,
+                     dt == OMNI_BF16 ? w.Kt : nullptr, nullptr, w.kidx, st);
+    if (rc != OMNI_OK) return rc;
+  }
   rc = run_pack_q(L, dt, Q, O, dO, lse, q_idx, q_cnt, nqpad, w.Qt, w.dOt, dt == OMNI_BF16 ? w.Qn : nullptr,
                   dt == OMNI_BF16 ? w.dOn : nullptr, w.lse2c, w.deltac, st);
   if (rc != OMNI_OK) return rc;
@@ -1281,6 +1337,9 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   p.sched = w.sched;
   p.qvis = w.qvis;
   p.kfirst = w.kfirst;
+  p.tile_map = w.tile_map;
+  p.tile_stride = cap_keys / kTileN;
+  p.npad_kv = BLOCKS ? npad_kv : npad;
   constexpr bool kFast = sizeof(T) == 2;
   if constexpr (kFast) {
     rc = run_visible_counts(L, q_idx, q_cnt, w.kidx, budget, b_cap, npad, w.qvis, w.kfirst, st);
@@ -1303,9 +1362,9 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
       hipLaunchKernelGGL(key_list_kernel, dim3(1), dim3(1024), 0, st, p, (long long)key_list_slots(L, npad));
       OMNI_LAUNCH_CHECK();
       const unsigned key_wgs = (unsigned)persistent_grid() / 2;       // one workgroup per CU (its LDS ring fills it)
-      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 1>), dim3(key_wgs), dim3(kKeyThreads), 0, st, p);
+      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 1, BLOCKS>), dim3(key_wgs), dim3(kKeyThreads), 0, st, p);
       OMNI_LAUNCH_CHECK();
-      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 0>), dim3(key_wgs), dim3(kKeyThreads), 0, st, p);
+      hipLaunchKernelGGL((attn_bwd_key_bf16_kernel<D, 0, BLOCKS>), dim3(key_wgs), dim3(kKeyThreads), 0, st, p);
     } else {
       hipLaunchKernelGGL((attn_bwd_dkdv_kernel<T, D>), dim3(npad / kBwdKeys, L.B * L.Hq), dim3(kThreads), 0, st, p);
     }
@@ -1314,7 +1373,7 @@ int launch_bwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   {
     ProfScope prof__(kProfBwdDq, st);
     if constexpr (kFast)
-      hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), dim3(persistent_grid() / 2), dim3(kDqThreads), 0, st, p);
+      hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D, BLOCKS>), dim3(persistent_grid() / 2), dim3(kDqThreads), 0, st, p);
     else
       hipLaunchKernelGGL((attn_bwd_dq_kernel<T, D>), dim3(persistent_grid() / 2), dim3(kThreads), 0, st, p);
     OMNI_LAUNCH_CHECK();
@@ -1351,12 +1410,29 @@ int run_attn_bwd(const Layer& L, int dtype, const void* Q, const void* K, const 
                  const int* budget, int b_cap, void* dQ, void* dK, void* dV, void* ws, hipStream_t st) {
   if (dtype == OMNI_BF16) {
     if (L.D == 128)
-      return launch_bwd<u16, 128>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
-    return launch_bwd<u16, 64>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
+      return launch_bwd<u16, 128, false>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
+    return launch_bwd<u16, 64, false>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
   }
   if (L.D == 128)
-    return launch_bwd<float, 128>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
-  return launch_bwd<float, 64>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
+    return launch_bwd<float, 128, false>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
+  return launch_bwd<float, 64, false>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, kv_idx, budget, b_cap, dQ, dK, dV, ws, st);
+}
+
+int attn_bwd_blocks_max_keys() { return kBwdMaxMapTiles * kTileN; }
+
+size_t attn_bwd_blocks_ws(const Layer& L, int cap_keys) {
+  Arena a(nullptr);
+  carve_bwd(a, L, OMNI_BF16, bwd_npad(cap_keys), bwd_nqpad(L), bwd_npad_kv(L), cap_keys / kTileN);
+  return a.used();
+}
+
+int run_attn_bwd_blocks(const Layer& L, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                        const float* lse, const int* q_idx, const int* q_cnt, const int* blk_idx, const int* blk_budget,
+                        int blk_cap, int block, void* dQ, void* dK, void* dV, void* ws, hipStream_t st) {
+  const BlockLists blk{blk_idx, blk_budget, blk_cap, block};
+  if (L.D == 128)
+    return launch_bwd<u16, 128, true>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, nullptr, nullptr, 0, dQ, dK, dV, ws, st, &blk);
+  return launch_bwd<u16, 64, true>(L, Q, K, V, O, dO, lse, q_idx, q_cnt, nullptr, nullptr, 0, dQ, dK, dV, ws, st, &blk);
 }
 
 }  // namespace omni

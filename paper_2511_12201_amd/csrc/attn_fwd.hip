@@ -943,6 +943,15 @@ size_t attn_fwd_blocks_ws(const Layer& L, int cap_keys) {
 
 int attn_fwd_blocks_max_keys() { return kMaxMapTiles * kTileN; }
 
+int run_tile_map(const Layer& L, const int* blk_idx, const int* blk_budget, int blk_cap, int block, int last_tile,
+                 int* tile_map, hipStream_t st) {
+  const int tpb = block / kTileN;
+  hipLaunchKernelGGL(tile_map_kernel, dim3(cdiv(blk_cap * tpb, 256), L.B * L.Hq), dim3(256), 0, st, blk_idx, blk_budget,
+                     L.Hq, blk_cap, tpb, last_tile, tile_map);
+  OMNI_LAUNCH_CHECK();
+  return OMNI_OK;
+}
+
 int run_attn_fwd_blocks(const Layer& L, const void* Q, const void* K, const void* V, const int* q_idx, const int* q_cnt,
                         const int* blk_idx, const int* blk_budget, int blk_cap, int block, void* O, float* lse,
                         void* ws, hipStream_t st) {

@@ -55,6 +55,9 @@ int run_attn_fwd(const Layer& L, int dtype, const void* Q, const void* K, const 
 
 // bf16 only, block % 64 == 0: the forward pass on block lists without a gathered copy of K/V per query head
 int attn_fwd_blocks_max_keys();
+// tile_map[bh, t] = tile of the KV head's token-ordered K/V copy that holds tile t of the head's block list
+int run_tile_map(const Layer& L, const int* blk_idx, const int* blk_budget, int blk_cap, int block, int last_tile,
+                 int* tile_map, hipStream_t st);
 size_t attn_fwd_blocks_ws(const Layer& L, int cap_keys);   // cap_keys = blk_cap * block
 int run_attn_fwd_blocks(const Layer& L, const void* Q, const void* K, const void* V, const int* q_idx, const int* q_cnt,
                         const int* blk_idx, const int* blk_budget, int blk_cap, int block, void* O, float* lse,
@@ -65,6 +68,12 @@ size_t attn_bwd_ws(const Layer& L, int dtype, int b_cap);
 int run_attn_bwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const void* O,
                  const void* dO, const float* lse, const int* q_idx, const int* q_cnt, const int* kv_idx,
                  const int* budget, int b_cap, void* dQ, void* dK, void* dV, void* ws, hipStream_t st);
+// the same on block lists walked in place (bf16): K/V of every KV head once, tiles found through a tile map
+int attn_bwd_blocks_max_keys();
+size_t attn_bwd_blocks_ws(const Layer& L, int cap_keys);   // cap_keys = blk_cap * block
+int run_attn_bwd_blocks(const Layer& L, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                        const float* lse, const int* q_idx, const int* q_cnt, const int* blk_idx, const int* blk_budget,
+                        int blk_cap, int block, void* dQ, void* dK, void* dV, void* ws, hipStream_t st);
 
 void set_key_split_len(int tiles);   // attn_bwd.hip; <= 0 restores the default
 

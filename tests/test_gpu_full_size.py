@@ -210,6 +210,32 @@ def test_c4_32k_backward_on_sampled_rows_and_sums_over_all_keys():
         assert not gQ[0, h, ~kept].any()
 
 
+def test_c4_32k_block_lists_backward_in_place_equals_the_gathered_path():
+    """Block lists at the bench's granularity (256) on the 32k training layer: the backward that walks them in place
+    against expand + gather, bit for bit (the gathered path is checked against the oracle above)."""
+    cfg = synth.C4_TRAIN_32K
+    c = FullCase.get(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    block = 256
+    nb = N // block
+    rng = np.random.default_rng(61)
+    nsel = int(0.6 * nb)
+    lists = [[np.sort(np.concatenate([[0], 1 + rng.choice(nb - 1, nsel - 1, replace=False)])).astype(np.int32)
+              for _ in range(H)]]
+    blk_idx, _ = lists_to_padded(lists, H, nb)
+    blk_budget = torch.tensor([nsel], dtype=torch.int32, device="cuda")
+    q_idx, q_cnt = lists_to_padded(c.q_lists, H, N)
+    dO = to_device(synth.make_grad_output(cfg), cfg.dtype)
+    O, lse = ob.omni_block_attn_fwd(c.desc, c.dQ, c.dK, c.dV, q_idx, q_cnt, blk_idx, blk_budget, block)
+    g1 = ob.omni_block_attn_bwd(c.desc, c.dQ, c.dK, c.dV, O, dO, lse, q_idx, q_cnt, blk_idx, blk_budget, block)
+    kv_idx, budget = ob.omni_expand_blocks(c.desc, blk_idx, blk_budget, block)
+    g2 = ob.omni_sparse_attn_bwd(c.desc, c.dQ, c.dK, c.dV, O, dO, lse, q_idx, q_cnt, kv_idx, budget, kv_idx.shape[-1])
+    torch.cuda.synchronize()
+    for name, x, y in zip(("dQ", "dK", "dV"), g1, g2):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16)), name
+    assert float(g1[1].float().abs().max()) > 0
+
+
 def test_c5_131k_decode_step():
     """One decode step on the 131072-token cache: seeded per-head lists of the bench's budget fraction (the
     oracle's own selection at this length takes a minute; the decode kernels do not care where a list came from)."""

@@ -682,6 +682,42 @@ def test_block_attention_in_place_equals_gathered_path_and_oracle(cfg, block, fr
     assert np.max(np.abs(to_host(lse1)[fin] - Lo[fin])) <= 2e-2
 
 
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_BF16_64, CFG_BF16_NC], ids=lambda c: c.name)
+@pytest.mark.parametrize("block,frac", [(64, 0.4), (128, 0.5), (256, 1.0), (192, 0.3)])
+@pytest.mark.parametrize("split_len", [0, 2])
+def test_block_attention_backward_in_place_equals_gathered_path_and_oracle(cfg, block, frac, split_len):
+    """The backward pass that walks block lists inside one token-ordered copy of K/V per KV head: bit-for-bit the
+    gradients of expanding the lists to tokens and gathering, and within the gradient bar of the oracle.  split_len 2
+    forces the long-context path of the key kernels (a key tile shared by several workgroups)."""
+    c = case_for(cfg)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    if not cfg.causal and N % block:
+        pytest.skip("without the causal mask the call wants whole blocks")
+    nb = math.ceil(N / block)
+    nsel = max(1, int(round(frac * nb)))
+    rng = np.random.default_rng(2000 + block)
+    lists = [[np.sort(rng.choice(nb, nsel, replace=False)).astype(np.int32) for _ in range(H)]]
+    lists[0][0] = np.sort(np.concatenate([rng.choice(nb - 1, nsel - 1, replace=False), [nb - 1]])).astype(np.int32)
+    blk_idx, _ = lists_to_padded(lists, H, nb)
+    blk_budget = torch.tensor([nsel], dtype=torch.int32, device="cuda")
+    q_idx, q_cnt = lists_to_padded(c.o_qidx, H, N)
+    tok = oc.expand_blocks(lists, block, N)
+    dO_np = synth.make_grad_output(cfg)
+    O_st, lse_o, want = oracle_train(oc, cfg.dtype, c.Q, c.K, c.V, dO_np, c.o_qidx, tok, cfg.causal, cfg.scale)
+    O, lse, dO = to_device(O_st, cfg.dtype), torch.from_numpy(lse_o).cuda(), to_device(dO_np, cfg.dtype)
+    kv_idx, budget = ob.omni_expand_blocks(c.desc, blk_idx, blk_budget, block)
+    ob.debug_key_split_len(split_len)
+    try:
+        g1 = ob.omni_block_attn_bwd(c.desc, c.dQ, c.dK, c.dV, O, dO, lse, q_idx, q_cnt, blk_idx, blk_budget, block)
+        g2 = ob.omni_sparse_attn_bwd(c.desc, c.dQ, c.dK, c.dV, O, dO, lse, q_idx, q_cnt, kv_idx, budget, kv_idx.shape[-1])
+        torch.cuda.synchronize()
+    finally:
+        ob.debug_key_split_len(0)
+    for name, x, y in zip(("dQ", "dK", "dV"), g1, g2):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16)), name
+    _check_grads(cfg, g1, want, c.o_qidx, tok)
+
+
 @pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
 def test_block_lists_train_through_their_token_lists(cfg):
     """Training on block lists: expanded to token lists they go through the same forward and backward, and the
