@@ -220,6 +220,35 @@ int omni_prefill_select(const omni_layer_desc* desc, const void* Q, const void* 
                         void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * omni_prefill_select_varlen -- omni_prefill_select for sequences of different
+ * lengths in one padded batch: sequence b occupies rows [0, seq_tokens[b]) of its
+ * slab of Q and K, its visual tokens are [seq_vis_begin[b], seq_vis_end[b]), and
+ * everything the selection computes for it (probe keys, scores, kept queries,
+ * accumulated key scores, kurtosis, flattest head, budget, recall, key lists) is
+ * what omni_prefill_select gives on that sequence alone, bit for bit.  desc
+ * describes the padded batch (n_tokens = the padded length; its vis_begin / vis_end
+ * are not used; sink_index is common and must lie inside every sequence).
+ *   seq_tokens, seq_vis_begin, seq_vis_end: [batch] i32, HOST pointers, read
+ *   before the call returns.
+ * Outputs have the padded batch's shapes ([batch, n_q_heads, n_tokens] for scores,
+ * q_idx and key_scores, as omni_sparse_attn_fwd / _bwd take them); rows and list
+ * entries beyond a sequence's length / counts are unspecified.  The kernels of a
+ * sequence are sized to that sequence and are launched sequence after sequence on
+ * the caller's stream.  Padding rows of Q and K are never read.
+ * Workspace: OMNI_CALL_PREFILL_SELECT with param = probe_block (as for the padded
+ * length; one sequence uses it at a time).
+ */
+int omni_prefill_select_varlen(const omni_layer_desc* desc, const void* Q, const void* K,
+                               const int32_t* seq_tokens, const int32_t* seq_vis_begin,
+                               const int32_t* seq_vis_end,
+                               int q_mode, float q_param, float recall_p, int probe_block,
+                               int budget_mode,
+                               float* probe_keys, float* scores, int32_t* q_idx, int32_t* q_cnt,
+                               float* key_scores, double* kurtosis, int32_t* flattest,
+                               int32_t* budget, float* recall, int32_t* kv_idx, int32_t b_cap,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/*
  * omni_select_kv -- same section, key-mask equation (value mask = key mask).
  * Per head the min(budget, b_cap) keys of largest key_scores; when several keys
  * share the cut value those of lower token index are taken.

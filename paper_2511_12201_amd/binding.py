@@ -27,7 +27,7 @@ EXPORTED = [
     "omni_dense_attn_fwd", "omni_dense_decode", "omni_workspace_bytes", "omni_last_error", "omni_version",
     "omni_profile_enable", "omni_profile_read", "omni_debug_work_list", "omni_debug_copy", "omni_debug_mfma_rate",
     "omni_group_subset", "omni_slim_decode_grouped", "omni_block_scores", "omni_expand_blocks",
-    "omni_block_attn_fwd", "omni_block_attn_bwd",
+    "omni_block_attn_fwd", "omni_block_attn_bwd", "omni_prefill_select_varlen",
     "omni_select_kv_per_head", "omni_sparse_attn_fwd_per_head", "omni_sparse_attn_bwd_per_head",
     "omni_visual_subset_per_head", "omni_prefill_select", "omni_compact_cache", "omni_slim_decode_compact",
     "omni_compact_cache_paged", "omni_slim_decode_paged",
@@ -107,6 +107,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_budget_from_scores.argtypes = [vp, vp, f32, C.c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_prefill_select.argtypes = [vp, vp, vp, C.c_int, f32, f32, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                         vp, i32, vp, sz, vp]
+    lib.omni_prefill_select_varlen.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int, f32, f32, C.c_int, C.c_int, vp, vp, vp, vp,
+                                               vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.omni_select_kv.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
     lib.omni_visual_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.omni_select_kv_per_head.argtypes = lib.omni_select_kv.argtypes
@@ -386,6 +388,37 @@ def omni_prefill_select(desc: LayerDesc, Q, K, q_mode: int, q_param: float, reca
                                    _ptr(out.probe_keys), _ptr(out.scores), _ptr(out.q_idx), _ptr(out.q_cnt),
                                    _ptr(r.key_scores), _ptr(r.kurtosis), _ptr(r.flattest), _ptr(r.budget),
                                    _ptr(r.recall), _ptr(out.kv_idx), b_cap, _ptr(buf), buf.numel(), _stream()))
+    return out
+
+
+def omni_prefill_select_varlen(desc: LayerDesc, Q, K, seq_tokens, seq_vis_begin, seq_vis_end, q_mode: int, q_param: float,
+                               recall_p: float, probe_block: int = 256, budget_mode: int = 0, b_cap: int | None = None,
+                               ws: Workspace | None = None) -> SelectionResult:
+    """Fused selection of a padded batch of sequences with their own lengths and visual ranges (host int sequences)."""
+    lib = load_library()
+    ws = ws or default_workspace()
+    dev = Q.device
+    B, H, Hkv, N, D = desc.batch, desc.n_q_heads, desc.n_kv_heads, desc.n_tokens, desc.head_dim
+    b_cap = N if b_cap is None else b_cap
+    f32, i32 = torch.float32, torch.int32
+    bud = BudgetResult(
+        torch.empty(B, H, N, dtype=f32, device=dev), torch.empty(B, H, dtype=torch.float64, device=dev),
+        torch.empty(B, dtype=i32, device=dev), torch.empty((B, H) if budget_mode == 2 else (B,), dtype=i32, device=dev),
+        torch.empty(B, H, dtype=f32, device=dev))
+    out = SelectionResult(
+        torch.empty(B, Hkv, 2, D, dtype=f32, device=dev), torch.empty(B, H, N, dtype=f32, device=dev),
+        torch.empty(B, H, N, dtype=i32, device=dev), torch.empty(B, H, dtype=i32, device=dev), bud,
+        torch.empty(B, H, b_cap, dtype=i32, device=dev))
+    arr = lambda x: (C.c_int32 * B)(*[int(v) for v in x])
+    n_arr, v0_arr, v1_arr = arr(seq_tokens), arr(seq_vis_begin), arr(seq_vis_end)
+    one = LayerDesc.from_buffer_copy(desc)
+    one.batch = 1
+    buf = ws.get(CALL_PREFILL_SELECT, one, probe_block)
+    _check(lib.omni_prefill_select_varlen(C.byref(desc), _ptr(Q), _ptr(K), n_arr, v0_arr, v1_arr, q_mode, q_param, recall_p,
+                                          probe_block, budget_mode, _ptr(out.probe_keys), _ptr(out.scores), _ptr(out.q_idx),
+                                          _ptr(out.q_cnt), _ptr(bud.key_scores), _ptr(bud.kurtosis), _ptr(bud.flattest),
+                                          _ptr(bud.budget), _ptr(bud.recall), _ptr(out.kv_idx), b_cap, _ptr(buf), buf.numel(),
+                                          _stream()))
     return out
 
 

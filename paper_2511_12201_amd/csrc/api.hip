@@ -87,6 +87,7 @@ Layer make_layer(const omni_layer_desc* d) {
   L.G = L.Hq / L.Hkv;
   L.D = d->head_dim;
   L.N = d->n_tokens;
+  L.ld = d->n_tokens;
   L.v0 = d->vis_begin;
   L.v1 = d->vis_end;
   L.sink = d->sink_index;
@@ -442,6 +443,66 @@ int omni_prefill_select(const omni_layer_desc* desc, const void* Q, const void* 
   // the recall pass already finds each head's cut for its budget: the key lists are compacted from it
   CHECK(run_budget_stats(L, key_scores, recall_p, budget_mode, kurtosis, flattest, budget, recall, ws_stats, st, b_cap));
   return run_select_kv_from_stats(L, key_scores, ws_stats, b_cap, kv_idx, ws_sel, st);
+}
+
+int omni_prefill_select_varlen(const omni_layer_desc* desc, const void* Q, const void* K, const int32_t* seq_tokens,
+                               const int32_t* seq_vis_begin, const int32_t* seq_vis_end, int q_mode, float q_param,
+                               float recall_p, int probe_block, int budget_mode, float* probe_keys, float* scores,
+                               int32_t* q_idx, int32_t* q_cnt, float* key_scores, double* kurtosis, int32_t* flattest,
+                               int32_t* budget, float* recall, int32_t* kv_idx, int32_t b_cap, void* ws,
+                               size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(seq_tokens); REQUIRE_PTR(seq_vis_begin); REQUIRE_PTR(seq_vis_end);
+  REQUIRE_PTR(probe_keys); REQUIRE_PTR(scores); REQUIRE_PTR(q_idx); REQUIRE_PTR(q_cnt);
+  REQUIRE_PTR(key_scores); REQUIRE_PTR(kurtosis); REQUIRE_PTR(flattest); REQUIRE_PTR(budget); REQUIRE_PTR(recall);
+  REQUIRE_PTR(kv_idx);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K);
+  if (q_mode != 0 && q_mode != 1) OMNI_FAIL(OMNI_ERR_INVALID, "mode must be 0 (threshold) or 1 (top fraction)");
+  if (!std::isfinite(q_param)) OMNI_FAIL(OMNI_ERR_INVALID, "param must be finite");
+  if (q_mode == 1 && !(q_param > 0.f && q_param <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "top fraction must be in (0, 1]");
+  if (!(recall_p > 0.f && recall_p <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "recall_p must be in (0, 1]");
+  if (probe_block < 1) OMNI_FAIL(OMNI_ERR_INVALID, "probe_block must be >= 1");
+  if (budget_mode < 0 || budget_mode > 2) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0, 1 or 2");
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  for (int b = 0; b < desc->batch; ++b) {
+    const int n = seq_tokens[b], v0 = seq_vis_begin[b], v1 = seq_vis_end[b];
+    if (n < 1 || n > desc->n_tokens) OMNI_FAIL(OMNI_ERR_INVALID, "sequence %d: need 1 <= seq_tokens <= n_tokens", b);
+    if (!(v0 >= 0 && v0 < v1 && v1 <= n)) OMNI_FAIL(OMNI_ERR_INVALID, "sequence %d: need 0 <= vis_begin < vis_end <= seq_tokens", b);
+    if (desc->sink_index >= n) OMNI_FAIL(OMNI_ERR_INVALID, "sequence %d: sink_index beyond the sequence", b);
+  }
+  Layer Lmax = make_layer(desc);
+  Lmax.B = 1;
+  Lmax.bph = budget_mode == 2;
+  CHECK(check_ws(ws, ws_bytes, prefill_select_ws(Lmax, desc->dtype, probe_block)));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t es = desc->dtype == OMNI_BF16 ? 2 : 4;
+  const long long Hq = desc->n_q_heads, Hkv = desc->n_kv_heads, Np = desc->n_tokens, D = desc->head_dim;
+  for (int b = 0; b < desc->batch; ++b) {
+    // the sequence as a layer of its own inside the padded tensors: its length and visual range, the batch's row
+    // pitch; every kernel is sized to the sequence, and the result is bit for bit what the sequence gives alone
+    Layer L = Lmax;
+    L.N = seq_tokens[b];
+    L.v0 = seq_vis_begin[b];
+    L.v1 = seq_vis_end[b];
+    const char* Qb = static_cast<const char*>(Q) + (size_t)b * desc->q_stride[0] * es;
+    const char* Kb = static_cast<const char*>(K) + (size_t)b * desc->kv_stride[0] * es;
+    float* probe_b = probe_keys + b * Hkv * 2 * D;
+    float* scores_b = scores + b * Hq * Np;
+    float* a_b = key_scores + b * Hq * Np;
+    int32_t* budget_b = budget + (budget_mode == 2 ? b * Hq : b);
+    char* ws_score = static_cast<char*>(ws);
+    char* ws_probe = ws_score + align_up(score_queries_ws(L), 256);
+    char* ws_stats = ws_probe + align_up(probe_ws(L, desc->dtype, probe_block), 256);
+    char* ws_sel = ws_stats + align_up(budget_stats_ws(L), 256);
+    CHECK(run_probe_keys(L, desc->dtype, Kb, probe_b, ws_score, st));
+    CHECK(run_probe(L, desc->dtype, Qb, Kb, probe_block, a_b, ws_probe, st, probe_b, scores_b));
+    CHECK(run_select_queries(L, scores_b, q_mode, q_param, q_idx + b * Hq * Np, q_cnt + b * Hq, ws_sel, st));
+    CHECK(run_budget_stats(L, a_b, recall_p, budget_mode, kurtosis + b * Hq, flattest + b, budget_b, recall + b * Hq,
+                           ws_stats, st, b_cap));
+    CHECK(run_select_kv_from_stats(L, a_b, ws_stats, b_cap, kv_idx + b * Hq * b_cap, ws_sel, st));
+  }
+  return OMNI_OK;
 }
 
 int omni_budget_from_scores(const omni_layer_desc* desc, const float* key_scores, float recall_p, int budget_mode,

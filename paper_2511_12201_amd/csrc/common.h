@@ -53,6 +53,8 @@ int check_ws(const void* ws, size_t have, size_t need);
 // Plain-data copy of the descriptor with derived fields, passed to kernels by value.
 struct Layer {
   int B, Hq, Hkv, G, D, N;
+  int ld;                        // elements between the heads' rows of the caller's [B,Hq,.] score and query-index arrays:
+                                 // N, or the padded length when the layer is one sequence of a padded batch
   int v0, v1, sink;
   int causal;
   int bph;                       // 1: the budget array holds one key count per head [B,Hq], 0: one per batch item [B]

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kThreads) void pool_queries_kernel(const T* __restr
     float diff[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) diff[e] = pk[D + c * E + e] - pk[c * E + e];
-    float* out = scores + (long long)bh * L.N;
+    float* out = scores + (long long)bh * L.ld;
     constexpr int kRowsInFlight = 4;                       // loads of this many rows per lane group are issued together
     for (int rb = row_begin; rb < row_end; rb += RPP * kRowsInFlight) {   // uniform trip count: shuffles need every lane
       u32x4 raw[kRowsInFlight];
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void probe_f32_kernel(const float* __rest
         colacc[kb][r] = v;
       }
     if (ln == 0) {
-      float* dst = a_out + (long long)bh * L.N;
+      float* dst = a_out + (long long)bh * L.ld;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -511,7 +511,7 @@ __global__ __launch_bounds__(kThreads, 2) void probe_bf16_kernel(const u16* __re
       if (jb == nrb - 1) {                         // last row block of this head: reduce over its rows and store
         const float total = half_wave_reduce_scatter(colacc, ln);
         const int key = k0 + (ln >> 4) * 32 + 8 * ((ln & 15) >> 2) + 4 * h + (ln & 3);
-        if (key < L.N) a_out[(long long)(bh0 + jh) * L.N + key] = total;
+        if (key < L.N) a_out[(long long)(bh0 + jh) * L.ld + key] = total;
 #pragma unroll
         for (int r = 0; r < 32; ++r) colacc[r] = 0.f;
       }

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void score_queries_kernel(const T* __rest
 #pragma unroll
   for (int e = 0; e < E; ++e) diff[e] = pk[D + c * E + e] - pk[c * E + e];
   const T* base = Q + b * L.qs[0] + i * L.qs[1];
-  float* out = scores + (long long)bh * L.N;
+  float* out = scores + (long long)bh * L.ld;
   const int row_begin = blockIdx.x * rows_per_block;
   const int row_end = min(L.N, row_begin + rows_per_block);
   for (int rb = row_begin; rb < row_end; rb += RPP) {      // uniform trip count: shuffles need every lane

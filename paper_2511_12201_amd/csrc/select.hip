@@ -272,7 +272,7 @@ __global__ __launch_bounds__(kSelThreads) void radix_select_kernel(const float* 
 }
 
 // grid: (H or 1, B).  Budget of head h (or of the flattest head when per_head == 0).
-__global__ __launch_bounds__(kSelThreads) void radix_budget_kernel(const float* __restrict__ a, int N, int H,
+__global__ __launch_bounds__(kSelThreads) void radix_budget_kernel(const float* __restrict__ a, int N, int ld, int H,
                                                                   const int* __restrict__ flattest, int per_head,
                                                                   double target_mass, int* __restrict__ out) {
   __shared__ RadixShared sh;
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(kSelThreads) void radix_budget_kernel(const float* 
   const int h = per_head ? (int)blockIdx.x : flattest[b];
   // rounded up: the truncated element masses must never reach a target below the real one
   const unsigned long long target = (unsigned long long)ceil(target_mass * kFixScale);
-  const int r = radix_budget_block(a + ((long long)b * H + h) * N, N, target, sh);
+  const int r = radix_budget_block(a + ((long long)b * H + h) * ld, N, target, sh);
   if (threadIdx.x == 0) out[per_head ? b * H + h : b] = r;
 }
 
@@ -294,11 +294,11 @@ __global__ void max_over_heads_kernel(const int* __restrict__ per_head, int H, i
 }
 
 // grid: B*H.  Excess kurtosis m4/m2^2 - 3 in fp64 with a fixed reduction tree.
-__global__ __launch_bounds__(kSelThreads) void kurtosis_kernel(const float* __restrict__ a, int N,
+__global__ __launch_bounds__(kSelThreads) void kurtosis_kernel(const float* __restrict__ a, int N, int ld,
                                                               double* __restrict__ kurt) {
   __shared__ double red[2][kSelThreads / 64];
   __shared__ double mean_sh;
-  const float* x = a + (long long)blockIdx.x * N;
+  const float* x = a + (long long)blockIdx.x * ld;
   const int w = threadIdx.x >> 6;
   double s = 0.0;
 #pragma unroll 8
@@ -375,14 +375,14 @@ __device__ __forceinline__ void classify(const KeepRule& r, int h, int n, float 
 }
 
 // grid: (nchunk, B*H).  Per chunk: number of always-kept and of cut-valued elements.
-__global__ __launch_bounds__(kChunkThreads) void chunk_count_kernel(const float* __restrict__ x, int N, int H,
+__global__ __launch_bounds__(kChunkThreads) void chunk_count_kernel(const float* __restrict__ x, int N, int ld, int H,
                                                                    KeepRule rule, const unsigned* __restrict__ thr_tab,
                                                                    int nchunk, int* __restrict__ cnt_keep,
                                                                    int* __restrict__ cnt_eq) {
   __shared__ int red[2][kChunkThreads / 64];
   const int bh = blockIdx.y, h = bh % H;
   const unsigned thr = rule.use_table ? thr_tab[bh] : rule.thr_scalar;
-  const float* row = x + (long long)bh * N;
+  const float* row = x + (long long)bh * ld;
   const int base = blockIdx.x * kChunk + threadIdx.x * kPerThread;
   int ck = 0, ce = 0;
 #pragma unroll
@@ -449,7 +449,7 @@ __global__ void chunk_scan_kernel(int nchunk, KeepRule rule, const int* __restri
 }
 
 // grid: (nchunk, B*H).  Writes the kept indices of the chunk, ascending, at their global rank.
-__global__ __launch_bounds__(kChunkThreads) void chunk_write_kernel(const float* __restrict__ x, int N, int H,
+__global__ __launch_bounds__(kChunkThreads) void chunk_write_kernel(const float* __restrict__ x, int N, int ld, int H,
                                                                    KeepRule rule, const unsigned* __restrict__ thr_tab,
                                                                    const int* __restrict__ need_tab, int nchunk,
                                                                    const int* __restrict__ off_keep,
@@ -459,7 +459,7 @@ __global__ __launch_bounds__(kChunkThreads) void chunk_write_kernel(const float*
   const int bh = blockIdx.y, h = bh % H;
   const unsigned thr = rule.use_table ? thr_tab[bh] : rule.thr_scalar;
   const int need = rule.use_table ? need_tab[bh] : 0;
-  const float* row = x + (long long)bh * N;
+  const float* row = x + (long long)bh * ld;
   const int base = blockIdx.x * kChunk + threadIdx.x * kPerThread;
   bool al[kPerThread], eq[kPerThread];
   int ck = 0, ce = 0;
@@ -530,16 +530,16 @@ __global__ void visual_subset_kernel(const int* __restrict__ kv_idx, const int* 
   if (threadIdx.x == 0) vis_cnt[bh] = cnt;
 }
 
-int compact(const float* x, int BH, int N, int H, const KeepRule& rule, const unsigned* thr, const int* need,
+int compact(const float* x, int BH, int N, int ld, int H, const KeepRule& rule, const unsigned* thr, const int* need,
             int* cnt_keep, int* cnt_eq, int* out, int out_stride, int* total_out, hipStream_t st) {
   const int nchunk = cdiv(N, kChunk);
-  hipLaunchKernelGGL(chunk_count_kernel, dim3(nchunk, BH), dim3(kChunkThreads), 0, st, x, N, H, rule, thr, nchunk,
+  hipLaunchKernelGGL(chunk_count_kernel, dim3(nchunk, BH), dim3(kChunkThreads), 0, st, x, N, ld, H, rule, thr, nchunk,
                      cnt_keep, cnt_eq);
   OMNI_LAUNCH_CHECK();
   hipLaunchKernelGGL(chunk_scan_kernel, dim3(BH), dim3(64), 0, st, nchunk, rule, need, cnt_keep, cnt_eq, total_out,
                      out_stride);
   OMNI_LAUNCH_CHECK();
-  hipLaunchKernelGGL(chunk_write_kernel, dim3(nchunk, BH), dim3(kChunkThreads), 0, st, x, N, H, rule, thr, need, nchunk,
+  hipLaunchKernelGGL(chunk_write_kernel, dim3(nchunk, BH), dim3(kChunkThreads), 0, st, x, N, ld, H, rule, thr, need, nchunk,
                      cnt_keep, cnt_eq, out, out_stride);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
@@ -591,11 +591,11 @@ int run_select_queries(const Layer& L, const float* scores, int mode, float para
     long long want = (long long)std::ceil((double)param * (double)n_vis);
     if (want < 0) want = 0;
     if (want > n_vis) want = n_vis;
-    hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, scores, L.N, L.Hq, L.v0, L.v1,
+    hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, scores, L.ld, L.Hq, L.v0, L.v1,
                        (int)want, (const int*)nullptr, 0, 0, 1, w.thr, w.need, (float*)nullptr, 1.f);
     OMNI_LAUNCH_CHECK();
   }
-  return compact(scores, BH, L.N, L.Hq, rule, w.thr, w.need, w.cnt_keep, w.cnt_eq, q_idx, L.N, q_cnt, st);
+  return compact(scores, BH, L.N, L.ld, L.Hq, rule, w.thr, w.need, w.cnt_keep, w.cnt_eq, q_idx, L.ld, q_cnt, st);
 }
 
 int run_select_kv(const Layer& L, const float* key_scores, const int* budget, int b_cap, int* kv_idx, void* ws,
@@ -603,7 +603,7 @@ int run_select_kv(const Layer& L, const float* key_scores, const int* budget, in
   Arena a(ws);
   SelWs w = carve_select(a, L);
   const int BH = L.B * L.Hq;
-  hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, 0, L.N, 0, budget,
+  hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.ld, L.Hq, 0, L.N, 0, budget,
                      L.bph, b_cap, 0, w.thr, w.need, (float*)nullptr, 1.f);
   OMNI_LAUNCH_CHECK();
   KeepRule rule;
@@ -612,7 +612,7 @@ int run_select_kv(const Layer& L, const float* key_scores, const int* budget, in
   rule.keep_all_head0 = 0;
   rule.use_table = 1;
   rule.thr_scalar = 0;
-  return compact(key_scores, BH, L.N, L.Hq, rule, w.thr, w.need, w.cnt_keep, w.cnt_eq, kv_idx, b_cap, nullptr, st);
+  return compact(key_scores, BH, L.N, L.ld, L.Hq, rule, w.thr, w.need, w.cnt_keep, w.cnt_eq, kv_idx, b_cap, nullptr, st);
 }
 
 size_t budget_stats_ws(const Layer& L) {
@@ -631,27 +631,27 @@ int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, in
   unsigned* thr = a.take<unsigned>(BH);
   int* need = a.take<int>(BH);
   int* per_head = a.take<int>(BH);
-  hipLaunchKernelGGL(kurtosis_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.N, kurt);
+  hipLaunchKernelGGL(kurtosis_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.N, L.ld, kurt);
   OMNI_LAUNCH_CHECK();
   hipLaunchKernelGGL(argmin_kernel, dim3(L.B), dim3(64), 0, st, kurt, L.Hq, flattest);
   OMNI_LAUNCH_CHECK();
   const double target = (double)recall_p * (double)L.N;
   if (budget_mode == 2) {                      // every head its own budget, written straight to budget[B,Hq]
-    hipLaunchKernelGGL(radix_budget_kernel, dim3(L.Hq, L.B), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, flattest,
+    hipLaunchKernelGGL(radix_budget_kernel, dim3(L.Hq, L.B), dim3(kSelThreads), 0, st, key_scores, L.N, L.ld, L.Hq, flattest,
                        1, target, budget);
     OMNI_LAUNCH_CHECK();
   } else if (budget_mode == 0) {
-    hipLaunchKernelGGL(radix_budget_kernel, dim3(1, L.B), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, flattest, 0,
+    hipLaunchKernelGGL(radix_budget_kernel, dim3(1, L.B), dim3(kSelThreads), 0, st, key_scores, L.N, L.ld, L.Hq, flattest, 0,
                        target, budget);
     OMNI_LAUNCH_CHECK();
   } else {
-    hipLaunchKernelGGL(radix_budget_kernel, dim3(L.Hq, L.B), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, flattest,
+    hipLaunchKernelGGL(radix_budget_kernel, dim3(L.Hq, L.B), dim3(kSelThreads), 0, st, key_scores, L.N, L.ld, L.Hq, flattest,
                        1, target, per_head);
     OMNI_LAUNCH_CHECK();
     hipLaunchKernelGGL(max_over_heads_kernel, dim3(L.B), dim3(64), 0, st, per_head, L.Hq, budget);
     OMNI_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.N, L.Hq, 0, L.N, 0, budget,
+  hipLaunchKernelGGL(radix_select_kernel, dim3(BH), dim3(kSelThreads), 0, st, key_scores, L.ld, L.Hq, 0, L.N, 0, budget,
                      budget_mode == 2 ? 1 : 0, std::min(k_cap, L.N), 0, thr, need, recall, (float)L.N);
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
@@ -673,7 +673,7 @@ int run_select_kv_from_stats(const Layer& L, const float* key_scores, void* stat
   rule.keep_all_head0 = 0;
   rule.use_table = 1;
   rule.thr_scalar = 0;
-  return compact(key_scores, BH, L.N, L.Hq, rule, thr, need, w.cnt_keep, w.cnt_eq, kv_idx, b_cap, nullptr, st);
+  return compact(key_scores, BH, L.N, L.ld, L.Hq, rule, thr, need, w.cnt_keep, w.cnt_eq, kv_idx, b_cap, nullptr, st);
 }
 
 // ---- union of the stored visual rows over the heads of a KV group, with a membership bit per head

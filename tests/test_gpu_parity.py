@@ -1154,6 +1154,63 @@ def test_two_sequences_of_different_lengths_in_one_padded_batch():
     assert np.all(to_host(lse[1, :, Nb:]) == -np.inf)
 
 
+@pytest.mark.parametrize("budget_mode", [0, 2])
+def test_selection_of_a_padded_batch_in_one_call_with_per_sequence_lengths(budget_mode):
+    """omni_prefill_select_varlen on three sequences (1859, 1060 and 537 tokens, own visual ranges) padded to 1859 rows
+    with NaN: every output of a sequence is bit for bit what omni_prefill_select gives on the sequence alone, and the
+    attention call consumes the batch's lists as they are."""
+    cfa = CFG_BF16
+    cfb = CFG_BF16.scaled(name="bf16_d128_short", frames=5, tok_per_frame=200, n_text=60, seed=77)
+    cfc = CFG_BF16.scaled(name="bf16_d128_shorter", frames=5, tok_per_frame=100, n_text=37, seed=78)
+    cases = [case_for(cfa), case_for(cfb), case_for(cfc)]
+    cfgs = [cfa, cfb, cfc]
+    Np, H, Hkv, D = cfa.n_tokens, cfa.n_q_heads, cfa.n_kv_heads, cfa.head_dim
+    nan = float("nan")
+    Q = torch.full((3, H, Np, D), nan, dtype=torch.bfloat16, device="cuda")
+    K = torch.full((3, Hkv, Np, D), nan, dtype=torch.bfloat16, device="cuda")
+    V = torch.full_like(K, nan)
+    for i, (c, cfg) in enumerate(zip(cases, cfgs)):
+        n = cfg.n_tokens
+        Q[i, :, :n], K[i, :, :n], V[i, :, :n] = c.dQ[0], c.dK[0], c.dV[0]
+    desc = ob.make_layer_desc(Q, K, cfa.vis_begin, cfa.vis_end, cfa.sink_index, cfa.causal)
+    ca = cases[0]
+    sel = ob.omni_prefill_select_varlen(desc, Q, K, [c.n_tokens for c in cfgs], [c.vis_begin for c in cfgs],
+                                        [c.vis_end for c in cfgs], ca.q_mode, ca.q_param, ca.recall_p, ca.probe_block,
+                                        budget_mode)
+    torch.cuda.synchronize()
+    ph = budget_mode == 2
+    for i, (c, cfg) in enumerate(zip(cases, cfgs)):
+        n = cfg.n_tokens
+        own = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, budget_mode,
+                                     ws=ob.Workspace())
+        torch.cuda.synchronize()
+        assert torch.equal(sel.probe_keys[i], own.probe_keys[0])
+        assert torch.equal(sel.scores[i, :, :n], own.scores[0])
+        assert torch.equal(sel.budget.key_scores[i, :, :n], own.budget.key_scores[0])
+        assert torch.equal(sel.budget.kurtosis[i], own.budget.kurtosis[0])
+        assert torch.equal(sel.budget.flattest[i], own.budget.flattest[0])
+        assert torch.equal(sel.budget.budget[i], own.budget.budget[0])
+        assert torch.equal(sel.budget.recall[i], own.budget.recall[0])
+        assert torch.equal(sel.q_cnt[i], own.q_cnt[0])
+        cnt, bud = to_host(own.q_cnt)[0], to_host(own.budget.budget)[0]
+        for h in range(H):
+            assert torch.equal(sel.q_idx[i, h, : cnt[h]], own.q_idx[0, h, : cnt[h]])
+            bh = int(bud[h] if ph else bud)
+            assert torch.equal(sel.kv_idx[i, h, :bh], own.kv_idx[0, h, :bh])
+    # attention over the padded batch straight from the batch's lists; the shortest sequence against the oracle
+    O, lse = ob.omni_sparse_attn_fwd(desc, Q, K, V, sel.q_idx, sel.q_cnt, sel.kv_idx, sel.budget.budget, Np, _per_head=ph)
+    torch.cuda.synchronize()
+    i, c, cfg = 2, cases[2], cfgs[2]
+    n = cfg.n_tokens
+    q_lists = [padded_to_lists(sel.q_idx[i:i + 1], sel.q_cnt[i:i + 1])[0]]
+    bud = to_host(sel.budget.budget)[i]
+    kv = to_host(sel.kv_idx)[i]
+    kv_lists = [[kv[h, : int(bud[h] if ph else bud)] for h in range(H)]]
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, q_lists, kv_lists, cfg.causal, cfg.scale)
+    _check_fwd(c, to_host(O[i:i + 1, :, :n]), to_host(lse[i:i + 1, :, :n]), Oo, Lo)
+    assert not to_host(O[i, :, n:]).any() and np.all(to_host(lse[i, :, n:]) == -np.inf)
+
+
 # ------------------------------------------------------------------ strides
 
 @pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
