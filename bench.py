@@ -60,7 +60,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3_64k", choices=["c3_64k", "c2_16k"])
     ap.add_argument("--no-extras", action="store_true", help="skip dense baseline / oracle timing")
-    ap.add_argument("--only", choices=["train", "decode", "mfma"],
+    ap.add_argument("--only", choices=["train", "decode", "mfma", "dense"],
                     help="run just the training-step extra, the decode extra or the matrix-core rate probe and print "
                          "its JSON (for profiling; the headline line is the default run)")
     ap.add_argument("--decode-steps", type=int, default=256, help="with --only decode: decode steps per mode")
@@ -84,6 +84,9 @@ def main():
     ob.load_library()
     if args.only == "mfma":
         print(json.dumps({"mfma_only_probe": mfma_probe(ob, repeats=3)}), flush=True)
+        return
+    if args.only == "dense":
+        print(json.dumps({"dense": bench_dense(torch, ob, synth)}), flush=True)
         return
     if args.only:
         modes = tuple(m for m in args.decode_modes.split(",") if m) or DECODE_MODES
@@ -415,6 +418,28 @@ def bench_per_head_variant(torch, ob, cfg, desc, Q, K, V, probe, scores, q_idx, 
             "recall_min": round(float(res.recall.min().item()), 4),
             "flops_fraction_of_dense": round(valid / (Hq * N * (N + 1) // 2), 4),
             "attn_algorithmic_tflops": round(4.0 * cfg.head_dim * valid / (attn * 1e-3) / 1e12, 1)}
+
+
+def bench_dense(torch, ob, synth, reps: int = 3):
+    """The dense baseline alone (omni_dense_attn_fwd on the 64k layer), for counter runs."""
+    cfg = synth.C3_64K
+    layer = synth.make_layer(cfg)
+    Q, K, V = (_upload(torch, synth, layer[k]) for k in "QKV")
+    desc = ob.make_layer_desc(Q, K, cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    O = torch.empty_like(Q)
+    lse = torch.empty(cfg.batch, cfg.n_q_heads, cfg.n_tokens, dtype=torch.float32, device="cuda")
+    ob.omni_dense_attn_fwd(desc, Q, K, V, O, lse)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(reps):
+        ob.omni_dense_attn_fwd(desc, Q, K, V, O, lse)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / reps
+    pairs = cfg.n_q_heads * cfg.n_tokens * (cfg.n_tokens + 1) // 2
+    return {"workload": "c3_64k dense causal attention", "ms": round(ms, 4),
+            "tflops": round(4.0 * cfg.head_dim * pairs / (ms * 1e-3) / 1e12, 2)}
 
 
 RECALL_SWEEP = (0.2, 0.5, 0.8, 0.82, 0.95)
