@@ -211,6 +211,31 @@ def main():
                                           "frac": round(pool_bytes / kern["pool_q"] / 1e6 / PEAK_HBM_GBS, 4)}
 
     if not args.no_extras:
+        # the same step through omni_sparse_prefill (key lists formed inside the attention's gather: one launch and one
+        # pass over the lists fewer), outputs bit-identical; interleaved with the two-call step so that both see the
+        # same clocks
+        O1, lse1 = torch.empty_like(O), torch.empty_like(lse)
+
+        def one_call():
+            ob.omni_sparse_prefill(desc, Q, K, V, 0, TAU, RECALL_P, PROBE_BLOCK, 0, b_cap, out=sel, O=O1, lse=lse1)
+
+        t_two = t_one = 0.0
+        for fn in (step, one_call):
+            for _ in range(args.warmup):
+                fn()
+        for _ in range(2):
+            for which, fn in ((0, step), (1, one_call)):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    fn()
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - t0) * 1e3 / args.steps / 2
+                t_two, t_one = (t_two + dt, t_one) if which == 0 else (t_two, t_one + dt)
+        out["one_call_step"] = {"what": "omni_sparse_prefill: selection + gather + attention in one call",
+                                "ms_per_step": round(t_one, 4), "two_call_ms_per_step_same_session": round(t_two, 4),
+                                "output_bit_identical": bool(torch.equal(O1, O) and torch.equal(lse1, lse))}
+        del O1, lse1
         # the same step replayed from a captured HIP graph (no call of it allocates, synchronises or memsets):
         # what the launch gaps between its ~25 kernels cost
         try:

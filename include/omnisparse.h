@@ -220,6 +220,35 @@ int omni_prefill_select(const omni_layer_desc* desc, const void* Q, const void* 
                         void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * omni_sparse_prefill -- a whole prefill step in one call: omni_prefill_select
+ * followed by omni_sparse_attn_fwd (the _per_head forms when budget_mode is 2),
+ * i.e. Sec. "Query Selection", Sec. "KV Selection" and the sparse attention of
+ * Sec. "Preliminary" under the two masks.  Every output (the selection's arrays,
+ * O and lse) is bit-identical to what the two calls write.  What the fusion
+ * changes is the hand-over between them: the kernel that gathers each head's
+ * selected K and V rows into the attention's tile layout forms the key lists
+ * itself, from the accumulated key scores and the head's cut (key-mask
+ * equation), and writes kv_idx on the way; the list is neither written by a
+ * pass of its own nor read back.
+ * Arguments: as in omni_prefill_select, then V, O and lse as in
+ * omni_sparse_attn_fwd.
+ * Workspace: omni_sparse_prefill_workspace_bytes(desc, probe_block, b_cap)
+ * (the two calls' workspaces one after the other); 0 with a message in
+ * omni_last_error on invalid arguments.
+ */
+size_t omni_sparse_prefill_workspace_bytes(const omni_layer_desc* desc, int32_t probe_block,
+                                           int32_t b_cap);
+int omni_sparse_prefill(const omni_layer_desc* desc, const void* Q, const void* K, const void* V,
+                        int q_mode, float q_param,
+                        float recall_p, int probe_block, int budget_mode,
+                        float* probe_keys, float* scores, int32_t* q_idx, int32_t* q_cnt,
+                        float* key_scores, double* kurtosis, int32_t* flattest,
+                        int32_t* budget, float* recall,
+                        int32_t* kv_idx, int32_t b_cap,
+                        void* O, float* lse,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
  * omni_prefill_select_varlen -- omni_prefill_select for sequences of different
  * lengths in one padded batch: sequence b occupies rows [0, seq_tokens[b]) of its
  * slab of Q and K, its visual tokens are [seq_vis_begin[b], seq_vis_end[b]), and

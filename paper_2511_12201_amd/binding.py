@@ -33,6 +33,7 @@ EXPORTED = [
     "omni_compact_cache_paged", "omni_slim_decode_paged",
     "omni_group_subset_per_head", "omni_debug_key_split_len",
     "omni_slim_decode_grouped_static", "omni_static_scratch_bytes",
+    "omni_sparse_prefill", "omni_sparse_prefill_workspace_bytes",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -107,6 +108,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_budget_from_scores.argtypes = [vp, vp, f32, C.c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_prefill_select.argtypes = [vp, vp, vp, C.c_int, f32, f32, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                         vp, i32, vp, sz, vp]
+    lib.omni_sparse_prefill.argtypes = [vp, vp, vp, vp, C.c_int, f32, f32, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp,
+                                        vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.omni_sparse_prefill_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.omni_sparse_prefill_workspace_bytes.restype = sz
     lib.omni_prefill_select_varlen.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int, f32, f32, C.c_int, C.c_int, vp, vp, vp, vp,
                                                vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.omni_select_kv.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
@@ -389,6 +394,52 @@ def omni_prefill_select(desc: LayerDesc, Q, K, q_mode: int, q_param: float, reca
                                    _ptr(r.key_scores), _ptr(r.kurtosis), _ptr(r.flattest), _ptr(r.budget),
                                    _ptr(r.recall), _ptr(out.kv_idx), b_cap, _ptr(buf), buf.numel(), _stream()))
     return out
+
+
+CALL_SPARSE_PREFILL_WS = -1      # key of the binding's workspace pool only; the library sizes this call by a function
+
+
+def omni_sparse_prefill(desc: LayerDesc, Q, K, V, q_mode: int, q_param: float, recall_p: float, probe_block: int = 256,
+                        budget_mode: int = 0, b_cap: int | None = None, out: SelectionResult | None = None, O=None,
+                        lse=None, ws: Workspace | None = None):
+    """Selection and sparse attention forward of a prefill step in one call: (SelectionResult, O, lse)."""
+    lib = load_library()
+    ws = ws or default_workspace()
+    dev = Q.device
+    B, H, Hkv, N, D = desc.batch, desc.n_q_heads, desc.n_kv_heads, desc.n_tokens, desc.head_dim
+    b_cap = N if b_cap is None else b_cap
+    f32, i32 = torch.float32, torch.int32
+    if out is None:
+        bud = BudgetResult(
+            torch.empty(B, H, N, dtype=f32, device=dev), torch.empty(B, H, dtype=torch.float64, device=dev),
+            torch.empty(B, dtype=i32, device=dev),
+            torch.empty((B, H) if budget_mode == 2 else (B,), dtype=i32, device=dev),
+            torch.empty(B, H, dtype=f32, device=dev))
+        out = SelectionResult(
+            torch.empty(B, Hkv, 2, D, dtype=f32, device=dev), torch.empty(B, H, N, dtype=f32, device=dev),
+            torch.empty(B, H, N, dtype=i32, device=dev), torch.empty(B, H, dtype=i32, device=dev), bud,
+            torch.empty(B, H, b_cap, dtype=i32, device=dev))
+    _budget_shape_ok(desc, out.budget.budget, budget_mode == 2)
+    if out.kv_idx.shape[-1] != b_cap:
+        raise ValueError("kv_idx must be [batch, n_q_heads, b_cap]")
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty(B, H, N, dtype=f32, device=dev)
+    need = lib.omni_sparse_prefill_workspace_bytes(C.byref(desc), probe_block, b_cap)
+    if need == 0:
+        raise OmniError(-1, last_error())
+    buf = ws.bufs.get(CALL_SPARSE_PREFILL_WS)
+    if buf is None or buf.numel() < need:
+        buf = torch.empty(need, dtype=torch.uint8, device=ws.device)
+        ws.bufs[CALL_SPARSE_PREFILL_WS] = buf
+    r = out.budget
+    _check(lib.omni_sparse_prefill(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), q_mode, q_param, recall_p, probe_block,
+                                   budget_mode, _ptr(out.probe_keys), _ptr(out.scores), _ptr(out.q_idx), _ptr(out.q_cnt),
+                                   _ptr(r.key_scores), _ptr(r.kurtosis), _ptr(r.flattest), _ptr(r.budget),
+                                   _ptr(r.recall), _ptr(out.kv_idx), b_cap, _ptr(O), _ptr(lse), _ptr(buf), buf.numel(),
+                                   _stream()))
+    return out, O, lse
 
 
 def omni_prefill_select_varlen(desc: LayerDesc, Q, K, seq_tokens, seq_vis_begin, seq_vis_end, q_mode: int, q_param: float,

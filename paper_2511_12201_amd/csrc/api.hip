@@ -445,6 +445,53 @@ int omni_prefill_select(const omni_layer_desc* desc, const void* Q, const void* 
   return run_select_kv_from_stats(L, key_scores, ws_stats, b_cap, kv_idx, ws_sel, st);
 }
 
+size_t omni_sparse_prefill_workspace_bytes(const omni_layer_desc* desc, int32_t probe_block, int32_t b_cap) {
+  clear_error();
+  if (validate_layer(desc) != OMNI_OK) return 0;
+  if (probe_block < 1) { set_error("probe_block must be >= 1"); return 0; }
+  if (b_cap < 1) { set_error("b_cap must be >= 1"); return 0; }
+  const Layer L = make_layer(desc);
+  return align_up(prefill_select_ws(L, desc->dtype, probe_block), 256) + attn_fwd_ws(L, desc->dtype, b_cap, true);
+}
+
+int omni_sparse_prefill(const omni_layer_desc* desc, const void* Q, const void* K, const void* V, int q_mode,
+                        float q_param, float recall_p, int probe_block, int budget_mode, float* probe_keys,
+                        float* scores, int32_t* q_idx, int32_t* q_cnt, float* key_scores, double* kurtosis,
+                        int32_t* flattest, int32_t* budget, float* recall, int32_t* kv_idx, int32_t b_cap, void* O,
+                        float* lse, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_layer(desc));
+  REQUIRE_PTR(Q); REQUIRE_PTR(K); REQUIRE_PTR(V); REQUIRE_PTR(probe_keys); REQUIRE_PTR(scores); REQUIRE_PTR(q_idx);
+  REQUIRE_PTR(q_cnt); REQUIRE_PTR(key_scores); REQUIRE_PTR(kurtosis); REQUIRE_PTR(flattest); REQUIRE_PTR(budget);
+  REQUIRE_PTR(recall); REQUIRE_PTR(kv_idx); REQUIRE_PTR(O); REQUIRE_PTR(lse);
+  REQUIRE_ALIGNED(Q); REQUIRE_ALIGNED(K); REQUIRE_ALIGNED(V); REQUIRE_ALIGNED(O);
+  if (q_mode != 0 && q_mode != 1) OMNI_FAIL(OMNI_ERR_INVALID, "mode must be 0 (threshold) or 1 (top fraction)");
+  if (!std::isfinite(q_param)) OMNI_FAIL(OMNI_ERR_INVALID, "param must be finite");
+  if (q_mode == 1 && !(q_param > 0.f && q_param <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "top fraction must be in (0, 1]");
+  if (!(recall_p > 0.f && recall_p <= 1.f)) OMNI_FAIL(OMNI_ERR_INVALID, "recall_p must be in (0, 1]");
+  if (probe_block < 1) OMNI_FAIL(OMNI_ERR_INVALID, "probe_block must be >= 1");
+  if (budget_mode < 0 || budget_mode > 2) OMNI_FAIL(OMNI_ERR_INVALID, "budget_mode must be 0, 1 or 2");
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  Layer L = make_layer(desc);
+  L.bph = budget_mode == 2;
+  const size_t sel_bytes = align_up(prefill_select_ws(L, desc->dtype, probe_block), 256);
+  CHECK(check_ws(ws, ws_bytes, sel_bytes + attn_fwd_ws(L, desc->dtype, b_cap, true)));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws_score = static_cast<char*>(ws);
+  char* ws_probe = ws_score + align_up(score_queries_ws(L), 256);
+  char* ws_stats = ws_probe + align_up(probe_ws(L, desc->dtype, probe_block), 256);
+  char* ws_sel = ws_stats + align_up(budget_stats_ws(L), 256);
+  char* ws_fwd = static_cast<char*>(ws) + sel_bytes;
+  CHECK(run_probe_keys(L, desc->dtype, K, probe_keys, ws_score, st));
+  CHECK(run_probe(L, desc->dtype, Q, K, probe_block, key_scores, ws_probe, st, probe_keys, scores));
+  CHECK(run_select_queries(L, scores, q_mode, q_param, q_idx, q_cnt, ws_sel, st));
+  CHECK(run_budget_stats(L, key_scores, recall_p, budget_mode, kurtosis, flattest, budget, recall, ws_stats, st, b_cap));
+  // the chunk counts of the key lists; the lists themselves come out of the attention's gather
+  SelectSource src;
+  CHECK(run_select_kv_counts(L, key_scores, ws_stats, b_cap, kv_idx, ws_sel, &src, st));
+  return run_attn_fwd(L, desc->dtype, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws_fwd, true, st, &src);
+}
+
 int omni_prefill_select_varlen(const omni_layer_desc* desc, const void* Q, const void* K, const int32_t* seq_tokens,
                                const int32_t* seq_vis_begin, const int32_t* seq_vis_end, int q_mode, float q_param,
                                float recall_p, int probe_block, int budget_mode, float* probe_keys, float* scores,

@@ -570,13 +570,17 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  // running maximum from a finished S tile, rescale of the accumulators if it grew
-  float mc = 0.f;                              // (running maximum, 0 if none yet) * c2
+  // Reference value of the softmax from a finished S tile.  m_run is the value the weights are taken against, not
+  // the exact running maximum: it moves (and the accumulators are rescaled) only when some row of the wavefront
+  // exceeds it by more than kRescaleSlack in the exponent, so a weight is at most 2^kRescaleSlack and the rescale
+  // is rare.  Output and log-sum-exp do not depend on the reference value beyond rounding.
+  float mc = 0.f;                              // (reference value, 0 if none yet) * c2
+  constexpr float kRescaleSlack = 6.0f;
   auto update_max = [&](float mloc) {
     mloc = pair_max(mloc);
-    const float m_new = fmaxf(m_run, mloc);
-    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-    if (__any(m_new > m_run)) {
+    if (__any(mloc > m_run + kRescaleSlack / c2)) {
+      const float m_new = fmaxf(m_run, mloc);
+      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = fast_exp2((m_run - m_ref) * c2);
       l_run *= alpha;
 #pragma unroll
@@ -584,8 +588,8 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
       m_run = m_new;
+      mc = m_ref * c2;
     }
-    mc = m_ref * c2;
   };
   auto mask_tile = [&](f32x16 (&sn)[2], int t) {
     const int rel = qvisible - t * kTileN;     // keys of this tile at positions >= rel are hidden (pad rows too)
@@ -775,7 +779,7 @@ FwdWs carve_fwd(Arena& a, const Layer& L, int dtype, int heads, int npad, bool s
 template <typename T, int D>
 int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, const int* q_idx, const int* q_cnt,
                const int* kv_idx, const int* budget, int b_cap, void* O, float* lse, void* ws, bool sparse,
-               hipStream_t st) {
+               hipStream_t st, const SelectSource* sel) {
   Arena a(ws);
   const int heads = sparse ? L.Hq : L.Hkv;
   const int npad = fwd_npad(sparse ? b_cap : L.N);
@@ -784,7 +788,8 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
     const int dt = sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32;
     // bf16: K natural + V k-packed; fp32: both natural
     int rc = run_pack_kv(L, dt, K, V, sparse ? 1 : 0, kv_idx, b_cap, budget, b_cap, npad, kTileN, w.Kp,
-                         dt == OMNI_BF16 ? nullptr : w.Vp, nullptr, dt == OMNI_BF16 ? w.Vp : nullptr, w.kidx, st);
+                         dt == OMNI_BF16 ? nullptr : w.Vp, nullptr, dt == OMNI_BF16 ? w.Vp : nullptr, w.kidx, st,
+                         sparse ? sel : nullptr);
     if (rc != OMNI_OK) return rc;
   }
   if (sparse) {
@@ -968,15 +973,15 @@ size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse) {
 
 int run_attn_fwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const int* q_idx,
                  const int* q_cnt, const int* kv_idx, const int* budget, int b_cap, void* O, float* lse, void* ws,
-                 bool sparse, hipStream_t st) {
+                 bool sparse, hipStream_t st, const SelectSource* sel) {
   if (dtype == OMNI_BF16) {
     if (L.D == 128)
-      return launch_fwd<u16, 128>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st);
-    return launch_fwd<u16, 64>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st);
+      return launch_fwd<u16, 128>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st, sel);
+    return launch_fwd<u16, 64>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st, sel);
   }
   if (L.D == 128)
-    return launch_fwd<float, 128>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st);
-  return launch_fwd<float, 64>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st);
+    return launch_fwd<float, 128>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st, sel);
+  return launch_fwd<float, 64>(L, Q, K, V, q_idx, q_cnt, kv_idx, budget, b_cap, O, lse, ws, sparse, st, sel);
 }
 
 }  // namespace omni

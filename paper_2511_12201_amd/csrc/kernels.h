@@ -22,6 +22,23 @@ int run_budget_stats(const Layer& L, const float* key_scores, float recall_p, in
                      int* flattest, int* budget, float* recall, void* ws, hipStream_t st, int k_cap = 0x7fffffff);
 int run_select_kv_from_stats(const Layer& L, const float* key_scores, void* stats_ws, int b_cap, int* kv_idx,
                              void* ws, hipStream_t st);
+// The key lists as the packing kernel can form them itself: the scores, each head's cut (threshold key and number of
+// cut-valued elements to take) and, per chunk of kSelectChunk elements, how many kept elements precede it.  out
+// receives the lists ([B*Hq, out_stride], what run_select_kv_from_stats writes).
+constexpr int kSelectChunk = 1024;
+struct SelectSource {
+  const float* x;          // [B*Hq, ld]
+  int ld, nchunk;
+  const unsigned* thr;     // [B*Hq]
+  const int* need;         // [B*Hq]
+  const int* off_keep;     // [B*Hq, nchunk] exclusive counts of elements above the cut
+  const int* off_eq;       // [B*Hq, nchunk] exclusive counts of elements at the cut
+  int* out;
+  int out_stride;
+};
+// the counting half of run_select_kv_from_stats: fills *src (pointers into the two workspaces), writes no list
+int run_select_kv_counts(const Layer& L, const float* key_scores, void* stats_ws, int b_cap, int* kv_idx, void* ws,
+                         SelectSource* src, hipStream_t st);
 int run_visual_subset(const Layer& L, const int* kv_idx, const int* budget, int b_cap, int* vis_idx, int* vis_cnt,
                       hipStream_t st);
 size_t group_subset_ws(const Layer& L);
@@ -35,9 +52,10 @@ int run_probe(const Layer& L, int dtype, const void* Q, const void* K, int pb, f
               hipStream_t st, const float* probe_keys = nullptr, float* scores = nullptr);
 
 // pack.hip (outputs that are nullptr are skipped; Kt / Vt / Qt / dOt exist for bf16 only)
+// sel not null (per_q_head only, src_idx ignored): the kernel forms the lists from *sel and writes them to sel->out
 int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per_q_head, const int* src_idx,
                 int idx_stride, const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt,
-                void* Vt, int* kidx, hipStream_t st);
+                void* Vt, int* kidx, hipStream_t st, const SelectSource* sel = nullptr);
 int run_pack_q(const Layer& L, int dtype, const void* Q, const void* O, const void* dO, const float* lse,
                const int* q_idx, const int* q_cnt, int nqpad, void* Qt, void* dOt, void* Qn, void* dOn, float* lse2c,
                float* deltac, hipStream_t st);
@@ -49,9 +67,10 @@ int run_visible_counts(const Layer& L, const int* q_idx, const int* q_cnt, const
 
 // attn_fwd.hip
 size_t attn_fwd_ws(const Layer& L, int dtype, int b_cap, bool sparse);
+// sel not null: kv_idx is an output, formed from *sel by the packing kernel (sparse only)
 int run_attn_fwd(const Layer& L, int dtype, const void* Q, const void* K, const void* V, const int* q_idx,
                  const int* q_cnt, const int* kv_idx, const int* budget, int b_cap, void* O, float* lse, void* ws,
-                 bool sparse, hipStream_t st);
+                 bool sparse, hipStream_t st, const SelectSource* sel = nullptr);
 
 // bf16 only, block % 64 == 0: the forward pass on block lists without a gathered copy of K/V per query head
 int attn_fwd_blocks_max_keys();

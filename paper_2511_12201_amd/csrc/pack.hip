@@ -40,14 +40,83 @@ __device__ __forceinline__ void transpose8x8_store(const u32x4 (&in)[8], u16* ds
   }
 }
 
+// The list entries [p0, p1) of head bh, formed from the key scores and the head's cut instead of read from a list
+// (Eq. 5: the keys above the cut, and the first `need` of those at the cut, in index order).  The chunk offsets say
+// which chunks of kSelectChunk scores hold those ranks; they are classified and ranked again here, as the list
+// writer of the selection does.  Workgroup-uniform control flow; sIdx must hold the pad index beforehand.
+__device__ __forceinline__ void select_tile_entries(const SelectSource& sel, int bh, int N, int p0, int p1, int* sIdx) {
+  static_assert(kSelectChunk == 4 * kThreads, "four scores per thread");
+  __shared__ int wsum[2][kThreads / 64];
+  const unsigned thr = sel.thr[bh];
+  const int need = sel.need[bh];
+  const int* ok = sel.off_keep + (long long)bh * sel.nchunk;
+  const int* oe = sel.off_eq + (long long)bh * sel.nchunk;
+  const float* row = sel.x + (long long)bh * sel.ld;
+  // last chunk whose first rank is <= p0 (the first ranks are non-decreasing and chunk 0 starts at rank 0)
+  int c0 = -1;
+  for (int cb = 0; cb < sel.nchunk; cb += kThreads) {
+    const int c = cb + threadIdx.x;
+    c0 += __syncthreads_count(c < sel.nchunk && ok[c] + min(oe[c], need) <= p0);
+  }
+  const int lane = lane_id(), w = threadIdx.x >> 6;
+  for (int c = c0; c < sel.nchunk; ++c) {
+    if (ok[c] + min(oe[c], need) >= p1) break;
+    const int base = c * kSelectChunk + threadIdx.x * 4;
+    bool al[4], eq[4];
+    int ck = 0, ce = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      al[e] = false;
+      eq[e] = false;
+      if (base + e < N) {
+        const unsigned key = float_key(row[base + e]);
+        al[e] = key > thr;
+        eq[e] = key == thr;
+      }
+      ck += al[e];
+      ce += eq[e];
+    }
+    int sk = ck, se = ce;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int tk = __shfl_up(sk, o, 64);
+      const int te = __shfl_up(se, o, 64);
+      if (lane >= o) {
+        sk += tk;
+        se += te;
+      }
+    }
+    if (lane == 63) {
+      wsum[0][w] = sk;
+      wsum[1][w] = se;
+    }
+    __syncthreads();
+    int pk = ok[c] + sk - ck, pe = oe[c] + se - ce;
+    for (int i = 0; i < w; ++i) {
+      pk += wsum[0][i];
+      pe += wsum[1][i];
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (al[e] || (eq[e] && pe < need)) {
+        const int pos = pk + min(pe, need);
+        if (pos >= p0 && pos < p1) sIdx[pos - p0] = base + e;
+      }
+      pk += al[e];
+      pe += eq[e];
+    }
+    __syncthreads();
+  }
+}
+
 // grid: (npad/64, BHx)
-template <typename T, int D>
+template <typename T, int D, bool SELECT>
 __global__ __launch_bounds__(kThreads) void pack_kv_kernel(const T* __restrict__ K, const T* __restrict__ V, Layer L,
                                                           int per_q_head, const int* __restrict__ src_idx,
                                                           int idx_stride, const int* __restrict__ budget, int b_cap,
                                                           int npad, int pad_to, T* __restrict__ Kn, T* __restrict__ Vn,
                                                           T* __restrict__ Kt, T* __restrict__ Vt,
-                                                          int* __restrict__ kidx) {
+                                                          int* __restrict__ kidx, SelectSource sel) {
   constexpr bool kBf16 = sizeof(T) == 2;
   constexpr int E = Elem<T>::kPer16B;
   constexpr int CPR = D / E;
@@ -58,12 +127,25 @@ __global__ __launch_bounds__(kThreads) void pack_kv_kernel(const T* __restrict__
   const int g = per_q_head ? hx / L.G : hx;
   const int nkeys = budget ? min(budget[per_q_head ? budget_slot(L.bph, b, bhx) : b], b_cap) : L.N;
   if (tile * kTileN >= (int)align_up((size_t)max(nkeys, 0), (size_t)pad_to)) return;   // consumers read whole pad_to-slot groups
-  if (threadIdx.x < kTileN) {
-    const int p = tile * kTileN + threadIdx.x;
-    int id = kPadKeyIndex;
-    if (p < nkeys) id = src_idx ? src_idx[(long long)bhx * idx_stride + p] : p;
-    sIdx[threadIdx.x] = id;
-    kidx[(long long)bhx * npad + p] = id;
+  if constexpr (SELECT) {
+    const int p0 = tile * kTileN;
+    if (threadIdx.x < kTileN) sIdx[threadIdx.x] = kPadKeyIndex;
+    __syncthreads();
+    if (p0 < nkeys) select_tile_entries(sel, bhx, L.N, p0, min(p0 + kTileN, nkeys), sIdx);
+    __syncthreads();
+    if (threadIdx.x < kTileN) {
+      const int p = p0 + threadIdx.x, id = sIdx[threadIdx.x];
+      kidx[(long long)bhx * npad + p] = id;
+      if (p < nkeys) sel.out[(long long)bhx * sel.out_stride + p] = id;
+    }
+  } else {
+    if (threadIdx.x < kTileN) {
+      const int p = tile * kTileN + threadIdx.x;
+      int id = kPadKeyIndex;
+      if (p < nkeys) id = src_idx ? src_idx[(long long)bhx * idx_stride + p] : p;
+      sIdx[threadIdx.x] = id;
+      kidx[(long long)bhx * npad + p] = id;
+    }
   }
   __syncthreads();
   const T* kbase = K + b * L.ks[0] + g * L.ks[1];
@@ -194,13 +276,21 @@ __global__ __launch_bounds__(kThreads) void pack_q_kernel(const T* __restrict__ 
 template <typename T, int D>
 int launch_pack_kv(const Layer& L, const void* K, const void* V, int per_q_head, const int* src_idx, int idx_stride,
                    const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt, void* Vt,
-                   int* kidx, hipStream_t st) {
+                   int* kidx, hipStream_t st, const SelectSource* sel) {
   const int heads = per_q_head ? L.Hq : L.Hkv;
   ProfScope prof__(kProfPack, st);
-  hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kTileN, L.B * heads), dim3(kThreads), 0, st,
-                     static_cast<const T*>(K), static_cast<const T*>(V), L, per_q_head, src_idx, idx_stride, budget,
-                     b_cap, npad, pad_to, static_cast<T*>(Kn), static_cast<T*>(Vn), static_cast<T*>(Kt), static_cast<T*>(Vt),
-                     kidx);
+  if (sel) {
+    if (!per_q_head || !budget) return OMNI_ERR_INVALID;
+    hipLaunchKernelGGL((pack_kv_kernel<T, D, true>), dim3(npad / kTileN, L.B * heads), dim3(kThreads), 0, st,
+                       static_cast<const T*>(K), static_cast<const T*>(V), L, per_q_head, src_idx, idx_stride, budget,
+                       b_cap, npad, pad_to, static_cast<T*>(Kn), static_cast<T*>(Vn), static_cast<T*>(Kt),
+                       static_cast<T*>(Vt), kidx, *sel);
+  } else {
+    hipLaunchKernelGGL((pack_kv_kernel<T, D, false>), dim3(npad / kTileN, L.B * heads), dim3(kThreads), 0, st,
+                       static_cast<const T*>(K), static_cast<const T*>(V), L, per_q_head, src_idx, idx_stride, budget,
+                       b_cap, npad, pad_to, static_cast<T*>(Kn), static_cast<T*>(Vn), static_cast<T*>(Kt),
+                       static_cast<T*>(Vt), kidx, SelectSource{});
+  }
   OMNI_LAUNCH_CHECK();
   return OMNI_OK;
 }
@@ -264,19 +354,19 @@ int run_visible_counts(const Layer& L, const int* q_idx, const int* q_cnt, const
 
 int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per_q_head, const int* src_idx,
                 int idx_stride, const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt,
-                void* Vt, int* kidx, hipStream_t st) {
+                void* Vt, int* kidx, hipStream_t st, const SelectSource* sel) {
   if (dtype == OMNI_BF16) {
     if (L.D == 128)
       return launch_pack_kv<u16, 128>(L, K, V, per_q_head, src_idx, idx_stride, budget, b_cap, npad, pad_to, Kn, Vn, Kt,
-                                      Vt, kidx, st);
+                                      Vt, kidx, st, sel);
     return launch_pack_kv<u16, 64>(L, K, V, per_q_head, src_idx, idx_stride, budget, b_cap, npad, pad_to, Kn, Vn, Kt, Vt,
-                                   kidx, st);
+                                   kidx, st, sel);
   }
   if (L.D == 128)
     return launch_pack_kv<float, 128>(L, K, V, per_q_head, src_idx, idx_stride, budget, b_cap, npad, pad_to, Kn, Vn,
-                                      nullptr, nullptr, kidx, st);
+                                      nullptr, nullptr, kidx, st, sel);
   return launch_pack_kv<float, 64>(L, K, V, per_q_head, src_idx, idx_stride, budget, b_cap, npad, pad_to, Kn, Vn,
-                                   nullptr, nullptr, kidx, st);
+                                   nullptr, nullptr, kidx, st, sel);
 }
 
 int run_pack_q(const Layer& L, int dtype, const void* Q, const void* O, const void* dO, const float* lse,

@@ -21,7 +21,7 @@ namespace omni {
 namespace {
 
 constexpr int kSelThreads = 1024;
-constexpr int kChunk = 1024;          // elements per compaction workgroup
+constexpr int kChunk = kSelectChunk;    // elements per compaction workgroup
 constexpr int kChunkThreads = 256;
 constexpr int kPerThread = kChunk / kChunkThreads;
 constexpr double kFixScale = 1099511627776.0;   // 2^40
@@ -674,6 +674,39 @@ int run_select_kv_from_stats(const Layer& L, const float* key_scores, void* stat
   rule.use_table = 1;
   rule.thr_scalar = 0;
   return compact(key_scores, BH, L.N, L.ld, L.Hq, rule, thr, need, w.cnt_keep, w.cnt_eq, kv_idx, b_cap, nullptr, st);
+}
+
+int run_select_kv_counts(const Layer& L, const float* key_scores, void* stats_ws, int b_cap, int* kv_idx, void* ws,
+                         SelectSource* src, hipStream_t st) {
+  Arena sa(stats_ws);
+  const int BH = L.B * L.Hq;
+  const unsigned* thr = sa.take<unsigned>(BH);
+  const int* need = sa.take<int>(BH);
+  Arena a(ws);
+  SelWs w = carve_select(a, L);
+  KeepRule rule;
+  rule.lo = 0;
+  rule.hi = L.N;
+  rule.keep_all_head0 = 0;
+  rule.use_table = 1;
+  rule.thr_scalar = 0;
+  const int nchunk = cdiv(L.N, kChunk);
+  hipLaunchKernelGGL(chunk_count_kernel, dim3(nchunk, BH), dim3(kChunkThreads), 0, st, key_scores, L.N, L.ld, L.Hq, rule,
+                     thr, nchunk, w.cnt_keep, w.cnt_eq);
+  OMNI_LAUNCH_CHECK();
+  hipLaunchKernelGGL(chunk_scan_kernel, dim3(BH), dim3(64), 0, st, nchunk, rule, need, w.cnt_keep, w.cnt_eq,
+                     (int*)nullptr, b_cap);
+  OMNI_LAUNCH_CHECK();
+  src->x = key_scores;
+  src->ld = L.ld;
+  src->nchunk = nchunk;
+  src->thr = thr;
+  src->need = need;
+  src->off_keep = w.cnt_keep;
+  src->off_eq = w.cnt_eq;
+  src->out = kv_idx;
+  src->out_stride = b_cap;
+  return OMNI_OK;
 }
 
 // ---- union of the stored visual rows over the heads of a KV group, with a membership bit per head

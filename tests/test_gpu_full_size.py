@@ -88,7 +88,14 @@ def test_c3_64k_selection_and_forward_on_sampled_rows():
         rows = samples[0][h]
         assert np.max(np.abs(Og[0, h, rows] - Oo[0, h, rows])) <= TOL, f"free-running attention, head {h}"
         assert np.max(np.abs(Lg[0, h, rows] - Lo[0, h, rows])) <= 2e-3
-    del Of, lsef
+    # the same step as one call (key lists formed inside the attention's gather): every output bit for bit
+    one, O1, lse1 = ob.omni_sparse_prefill(c.desc, c.dQ, c.dK, c.dV, 0, TAU, RECALL_P, PROBE_BLOCK, 0, N)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, Of) and torch.equal(lse1, lsef)
+    assert torch.equal(one.scores, sel.scores) and torch.equal(one.budget.key_scores, sel.budget.key_scores)
+    assert torch.equal(one.budget.budget, sel.budget.budget) and torch.equal(one.q_cnt, sel.q_cnt)
+    assert torch.equal(one.kv_idx[0, :, :bg], sel.kv_idx[0, :, :bg])
+    del Of, lsef, one, O1, lse1
 
     # attention on the oracle's sets (b_cap = N as in the bench), sampled rows against the oracle
     q_idx, q_cnt = lists_to_padded(c.q_lists, H, N)

@@ -597,6 +597,91 @@ def test_fused_selection_call_with_a_capacity_below_the_budget():
     np.testing.assert_allclose(to_host(f.budget.recall)[0], mass, atol=1e-6)
 
 
+def _same_selection(f, g, cfg, budget_mode):
+    assert torch.equal(f.probe_keys, g.probe_keys) and torch.equal(f.scores, g.scores) and torch.equal(f.q_cnt, g.q_cnt)
+    for a, b in zip(padded_to_lists(f.q_idx, f.q_cnt), padded_to_lists(g.q_idx, g.q_cnt)):
+        for x, y in zip(a, b):
+            np.testing.assert_array_equal(x, y)
+    fb, gb = f.budget, g.budget
+    assert torch.equal(fb.key_scores, gb.key_scores) and torch.equal(fb.kurtosis, gb.kurtosis)
+    assert torch.equal(fb.flattest, gb.flattest) and torch.equal(fb.budget, gb.budget) and torch.equal(fb.recall, gb.recall)
+    cap = f.kv_idx.shape[-1]
+    bud = to_host(gb.budget).reshape(cfg.batch, -1)
+    got, want = to_host(f.kv_idx), to_host(g.kv_idx)
+    for b in range(cfg.batch):
+        for h in range(cfg.n_q_heads):
+            n = min(int(bud[b, h if budget_mode == 2 else 0]), cap)
+            np.testing.assert_array_equal(got[b, h, :n], want[b, h, :n], err_msg=f"kv list, batch {b} head {h}")
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("budget_mode", [0, 1, 2])
+def test_prefill_step_in_one_call_writes_what_selection_and_attention_write(cfg, budget_mode):
+    """omni_sparse_prefill (key lists formed inside the attention's gather) against omni_prefill_select followed by
+    omni_sparse_attn_fwd: every output bit for bit; and the output against the oracle on the lists it returned."""
+    c = case_for(cfg)
+    N = cfg.n_tokens
+    g = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, budget_mode)
+    Og, Lg = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, g.q_idx, g.q_cnt, g.kv_idx, g.budget.budget, N,
+                                     _per_head=budget_mode == 2)
+    torch.cuda.synchronize()
+    f, O, lse = ob.omni_sparse_prefill(c.desc, c.dQ, c.dK, c.dV, c.q_mode, c.q_param, c.recall_p, c.probe_block,
+                                       budget_mode)
+    torch.cuda.synchronize()
+    _same_selection(f, g, cfg, budget_mode)
+    assert torch.equal(O, Og)
+    assert torch.equal(lse, Lg)
+    bud = to_host(f.budget.budget).reshape(cfg.batch, -1)
+    kv = to_host(f.kv_idx)
+    kv_lists = [[kv[b, h, : int(bud[b, h if budget_mode == 2 else 0])] for h in range(cfg.n_q_heads)]
+                for b in range(cfg.batch)]
+    Oo, Lo = oc.sparse_attn_fwd(c.Q, c.K, c.V, padded_to_lists(f.q_idx, f.q_cnt), kv_lists, cfg.causal, cfg.scale)
+    _check_fwd(c, to_host(O), to_host(lse), Oo, Lo)
+
+
+@pytest.mark.parametrize("cap", [1, 63, 64, 200, 777])
+def test_prefill_step_in_one_call_with_a_capacity_below_the_budget(cap):
+    cfg = CFG_BF16
+    c = case_for(cfg)
+    g = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0, b_cap=cap)
+    Og, Lg = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, g.q_idx, g.q_cnt, g.kv_idx, g.budget.budget, cap)
+    torch.cuda.synchronize()
+    f, O, lse = ob.omni_sparse_prefill(c.desc, c.dQ, c.dK, c.dV, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0,
+                                       b_cap=cap)
+    torch.cuda.synchronize()
+    _same_selection(f, g, cfg, 0)
+    assert torch.equal(O, Og) and torch.equal(lse, Lg)
+    n = min(cap, int(to_host(f.budget.budget)[0]))
+    want = oc.select_kv(to_host(f.budget.key_scores), [n])
+    np.testing.assert_array_equal(to_host(f.kv_idx)[0, :, :n], want[0])
+
+
+def test_prefill_step_in_one_call_on_tied_key_scores():
+    """Key scores with many equal values at the cut: the lists formed inside the gather take the first of them in index
+    order, as omni_select_kv does.  Ties are made by giving groups of tokens the same key and query rows."""
+    cfg = CFG_BF16
+    c = case_for(cfg)
+    N = cfg.n_tokens
+    K2 = c.K.copy()
+    Q2 = c.Q.copy()
+    for n in range(8, N - 8, 8):                       # tokens n .. n+3 share their key rows
+        K2[:, :, n + 1:n + 4] = K2[:, :, n:n + 1]
+    dK2, dQ2 = to_device(K2, cfg.dtype), to_device(Q2, cfg.dtype)
+    for mode in (0, 2):
+        g = ob.omni_prefill_select(c.desc, dQ2, dK2, c.q_mode, c.q_param, 0.6, c.probe_block, mode)
+        Og, Lg = ob.omni_sparse_attn_fwd(c.desc, dQ2, dK2, c.dV, g.q_idx, g.q_cnt, g.kv_idx, g.budget.budget, N,
+                                         _per_head=mode == 2)
+        f, O, lse = ob.omni_sparse_prefill(c.desc, dQ2, dK2, c.dV, c.q_mode, c.q_param, 0.6, c.probe_block, mode)
+        torch.cuda.synchronize()
+        _same_selection(f, g, cfg, mode)
+        assert torch.equal(O, Og) and torch.equal(lse, Lg)
+        a = to_host(g.budget.key_scores)[0]
+        bud = to_host(g.budget.budget).reshape(-1)
+        cut_ties = [int(np.sum(a[h] == np.sort(a[h])[::-1][int(bud[h if mode == 2 else 0]) - 1]))
+                    for h in range(cfg.n_q_heads)]
+        assert max(cut_ties) >= 2, "the input was meant to put equal scores at the cut"
+
+
 # ------------------------------------------------------------------ block-granular KV selection
 
 @pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
@@ -1053,6 +1138,11 @@ def test_calls_on_two_streams_with_their_own_workspaces():
 
 CFG_B2 = synth.C2_16K.scaled(name="bf16_batch2", batch=2, frames=4, tok_per_frame=252, n_text=70, n_q_heads=8, n_kv_heads=2,
                              seed=23)
+
+
+@pytest.mark.parametrize("budget_mode", [0, 2])
+def test_prefill_step_in_one_call_on_a_batch_of_two(budget_mode):
+    test_prefill_step_in_one_call_writes_what_selection_and_attention_write(CFG_B2, budget_mode)
 
 
 @pytest.mark.parametrize("budget_mode", [0, 2])
