@@ -101,7 +101,10 @@ typedef struct {
                                   are fixed at prefill; Sec. "KV Cache Slimming").  The first call with a workspace
                                   then merges the lists of every KV group into it (ascending union + membership
                                   bits) and later calls read a stored row once per group, as
-                                  omni_slim_decode_grouped does.  0: the lists are read anew on every call. */
+                                  omni_slim_decode_grouped does.  Which heads are active is still decided on every
+                                  call.  0: the lists are read anew on every call; such a call (like any other decode
+                                  call on that workspace) also discards lists merged earlier, which is how a caller
+                                  that refills the same list buffers tells the library so. */
 } omni_decode_desc;
 
 /* Paged form of the compacted visual KV store (omni_compact_cache_paged,
