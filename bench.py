@@ -321,7 +321,8 @@ def main():
         for name, fn in (("train_step_32k", bench_train),
                          ("train_step_32k_per_head_budgets", lambda *a: bench_train(*a, per_head=True)),
                          ("decode_131k", bench_decode),
-                         ("decode_131k_per_head_budgets", lambda *a: bench_decode(*a, per_head=True, batches=(1, 8)))):
+                         ("decode_131k_per_head_budgets", lambda *a: bench_decode(*a, per_head=True, batches=(1, 8))),
+                         ("decode_131k_plain_generator", lambda *a: bench_decode(*a, batches=(1, 8), plain=True))):
             try:
                 t0 = time.time()
                 out[name] = fn(torch, ob, synth)
@@ -608,9 +609,12 @@ def mfma_probe(ob, repeats: int = 1):
 DECODE_MODES = ("slim", "slim_stateless", "slim_grouped", "slim_compact", "slim_paged", "dense")
 
 
-def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, batches=(1, 2, 4, 8), modes=DECODE_MODES):
+def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, batches=(1, 2, 4, 8), modes=DECODE_MODES,
+                 plain: bool = False):
     """Decode with KV cache slimming on a 131072-token cache, batch 1..8, 256 steps each."""
     cfg = synth.C5_DECODE_131K
+    if plain:             # the generator without the salience term: the heads of a group pick less alike
+        cfg = cfg.scaled(name=cfg.name + "_plain", plain=True)
     layer = synth.make_layer(cfg)
     Q, K, V = (_upload(torch, synth, layer[k]) for k in "QKV")
     N, Hq, Hkv, D = cfg.n_tokens, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
@@ -779,8 +783,11 @@ def bench_decode(torch, ob, synth, n_steps: int = 256, per_head: bool = False, b
             "python_loop_us_per_token": {k: round(v, 1) for k, v in timing.items()},
             "hip_graph_us_per_token": {k: round(v, 1) for k, v in graph_us.items()},
             "active_head_fraction_last_step": round(float(a.mean()), 4),
-            "rows_requested_vs_dense": {"slim": round(rows_head / rows_dense, 4), "slim_grouped": round(rows_union / rows_dense, 4)},
-            "GBps_of_requested_rows": {"slim": gbps(rows_head, ktime["slim"]), "slim_grouped": gbps(rows_union, ktime["slim_grouped"]),
+            # rows the lists name: per head (a row stored by several active heads of a group counted for each) and as
+            # the group's union, which is what every slimmed variant reads (omni_slim_decode merges the heads' lists)
+            "rows_requested_vs_dense": {"per_head_lists": round(rows_head / rows_dense, 4),
+                                        "group_union": round(rows_union / rows_dense, 4)},
+            "GBps_of_requested_rows": {"slim": gbps(rows_union, ktime["slim"]), "slim_grouped": gbps(rows_union, ktime["slim_grouped"]),
                                        "dense": gbps(rows_dense, ktime["dense"])},
             "dense_frac_of_hbm_peak": round(rows_dense * row_bytes / (ktime["dense"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)}
         del Kc, Vc, Kpool, Vpool, Kcomp, Vcomp
