@@ -139,14 +139,23 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ob.profile_enable(True)
+    # the timed region: HIP events around the dominant kernel only (an event pair costs a few microseconds on the
+    # stream; the other kernels are timed in a pass of their own below)
+    ob.profile_enable(True, ["attn_fwd"])
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     kern = {}
-    for name in ("attn_fwd", "pack_kv", "clear_out", "pool_q", "probe_lse", "probe_sum", "score"):
+    ms, n = ob.profile_read("attn_fwd")
+    kern["attn_fwd"] = ms / n
+    others = ("pack_kv", "clear_out", "pool_q", "probe_lse", "probe_sum", "score")
+    ob.profile_enable(True, others)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    for name in others:
         ms, n = ob.profile_read(name)
         if n:
             kern[name] = ms / n

@@ -582,7 +582,10 @@ size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param);
  * Kernel timing for benchmarks (not part of the method).  While enabled, the
  * library records a HIP event pair on the call's stream around each launch of
  * the kernels listed below (at most 64 launches per kernel; later ones are not
- * recorded).  omni_profile_enable() resets the records; omni_profile_read()
+ * recorded).  omni_profile_enable(mask): 0 switches the timing off, a negative
+ * value times every listed kernel, otherwise bit k of mask switches kernel_id k
+ * on (an event pair costs a few microseconds on the stream: time one kernel
+ * inside a region whose wall clock matters).  It also resets the records; omni_profile_read()
  * waits for the recorded launches and returns their summed duration in
  * milliseconds and their number.  Not thread safe.  kernel_id: 0 attention
  * forward main kernel, 1 K/V pack (gather), 2 output clear, 3 query pooling,
@@ -590,7 +593,7 @@ size_t omni_workspace_bytes(int call_id, const void* desc, int32_t param);
  * scoring, 7 backward dK/dV kernel, 8 backward dQ kernel, 9 backward
  * scatter-reduce, 10 decode partial kernel, 11 selection kernels.
  */
-int omni_profile_enable(int on);
+int omni_profile_enable(int mask);
 int omni_profile_read(int kernel_id, float* total_ms /* host */, int* launches /* host */);
 
 /*

@@ -252,8 +252,12 @@ def debug_mfma_rate(random_operands, iters: int = 40000):
     return tf.value, mhz.value
 
 
-def profile_enable(on: bool):
-    _check(load_library().omni_profile_enable(1 if on else 0))
+def profile_enable(on: bool, kernels=None):
+    """Kernel timing on (every kernel of PROF_KERNELS, or only the named ones) or off; resets the records."""
+    mask = 0
+    if on:
+        mask = -1 if kernels is None else sum(1 << PROF_KERNELS[k] for k in kernels)
+    _check(load_library().omni_profile_enable(mask))
 
 
 def profile_read(kernel: str):

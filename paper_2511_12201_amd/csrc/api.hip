@@ -108,10 +108,10 @@ struct ProfEntry {
   int created, used;
 };
 static ProfEntry g_prof[kProfCount];
-static bool g_prof_on = false;
+static unsigned g_prof_mask = 0;     // bit k: kernel id k is timed
 
 void prof_begin(int id, hipStream_t st) {
-  if (!g_prof_on) return;
+  if (!(g_prof_mask >> id & 1u)) return;
   ProfEntry& e = g_prof[id];
   if (e.used >= kProfSlots) return;
   if (e.used >= e.created) {
@@ -121,7 +121,7 @@ void prof_begin(int id, hipStream_t st) {
   (void)hipEventRecord(e.start[e.used], st);
 }
 void prof_end(int id, hipStream_t st) {
-  if (!g_prof_on) return;
+  if (!(g_prof_mask >> id & 1u)) return;
   ProfEntry& e = g_prof[id];
   if (e.used >= e.created || e.used >= kProfSlots) return;
   (void)hipEventRecord(e.stop[e.used], st);
@@ -295,9 +295,9 @@ int omni_debug_mfma_rate(int random_operands, int iters, double* tflops, double*
   return run_mfma_rate(random_operands, iters, tflops, shader_mhz);
 }
 
-int omni_profile_enable(int on) {
+int omni_profile_enable(int mask) {
   clear_error();
-  g_prof_on = on != 0;
+  g_prof_mask = mask < 0 ? ~0u : (unsigned)mask;
   for (int i = 0; i < kProfCount; ++i) g_prof[i].used = 0;
   return OMNI_OK;
 }
