@@ -331,7 +331,12 @@ int omni_group_subset_per_head(const omni_layer_desc* desc, const int32_t* kv_id
  * For head i and kept query n: softmax over {k in kv_idx[i] : k <= n} (all of
  * kv_idx[i] when not causal) of q_n . k_k * scale, times V.  Queries that are
  * not kept, and kept queries with no admissible key, get an all-zero output row
- * and lse = -inf.  bf16 inputs: bf16 MFMA with fp32 accumulation and softmax.
+ * and lse = -inf.  bf16 inputs: Q K^T on the bf16 matrix cores, softmax in fp32,
+ * the weights rounded to f16 and multiplied with V on the f16 matrix cores (fp32
+ * accumulation); V is converted to f16 on the way, which is exact for magnitudes
+ * in [2^-14, 65504]; larger magnitudes saturate at 65504, smaller ones keep an
+ * absolute accuracy of 3e-8.  The dense baseline and the block-list calls share
+ * the kernel and the limit.
  *   q_idx/q_cnt as written by omni_select_queries, kv_idx/budget as written by
  *   omni_select_kv / omni_kv_budget (both index lists ascending); the effective
  *   number of keys per head is min(budget[batch], b_cap).

@@ -16,6 +16,11 @@
 //  * V is packed so that the A operand of O^T = V^T P^T is one 16-byte LDS read:
 //    [16-key group][half h][d][8 keys], key(group,h,j) = 16 group + 8 (j/4) + 4 h + j%4,
 //    which is the order in which the S^T accumulators hold the keys.
+//  * bf16 inputs, second product in f16: S^T = K Q^T runs on the bf16 matrix cores; the weights are rounded to
+//    f16 (11 significant bits against bf16's 8, same matrix-core rate) and multiplied with V converted to f16 by
+//    the pack pass (exact for magnitudes in [2^-14, 65504]; beyond that V saturates, below it keeps 3e-8 absolute).
+//    The normaliser is the sum of the weights as rounded, so a row that one key dominates returns that key's V row
+//    whatever value the weights are taken against, and the log-sum-exp is off by at most 2^-11 relative in the sum.
 //  * bf16 (attn_fwd_bf16_kernel, the measured path): 512 threads = 8 wavefronts x
 //    32 query rows per work item of 256 kept queries; 64-key K/V tiles go from
 //    memory straight into a ring of four LDS stages (global_load_lds, hand-placed
@@ -543,7 +548,6 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   constexpr int kAhead = 2;                  // fragment reads run this many MFMAs ahead
   static_assert(32 % NQK == 0 && 32 % NPV == 0 && 16 % NPV == 0, "chunking of the vector work");
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  union PFrag { bf16x8 v[4]; bf16x2 h[16]; };
 
   auto kfrag = [&](const unsigned char* sk, int c) {
     const int kb = c % 2, ks = c / 2;
@@ -551,7 +555,7 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   };
   auto vfrag = [&](const unsigned char* sv, int c) {
     const int t16 = c / NB, db = c % NB;
-    return *reinterpret_cast<const bf16x8*>(sv + vlane_b + (t16 * 2 * D + db * 32) * 16);
+    return *reinterpret_cast<const f16x8*>(sv + vlane_b + (t16 * 2 * D + db * 32) * 16);
   };
 
   // S^T of tile t alone (first tile of an item)
@@ -608,18 +612,64 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
     return mloc;
   };
 
+  // Steps that do not follow the maximum (below) call this when a weight left the safe range: the reference value
+  // moves to the maximum of the tile at hand, the accumulators are rescaled, and the tile's weights are formed again.
+  union PFrag { f16x8 v[4]; f16x2 h[16]; };
+  // acc + both halves of pk, one instruction each: the sum of the weights exactly as the matrix cores get them
+  auto add_halves = [](float acc, f16x2 pk) {
+    asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "+v"(acc) : "v"(pk));
+    asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(acc) : "v"(pk));
+    return acc;
+  };
+  auto refit = [&](const f32x16 (&sc)[2], PFrag& pf, float& lsum) {
+    float mloc = sc[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) mloc = fmaxf(fmaxf(sc[kb][r], sc[kb][r + 1]), mloc);
+    mloc = pair_max(mloc);
+    const float m_new = fmaxf(m_run, mloc);
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = fast_exp2((m_run - m_ref) * c2);
+    l_run *= alpha;
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    m_run = m_new;
+    mc = m_ref * c2;
+    lsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 32; r += 2) {
+      f32x2 pv;
+      pv[0] = fast_exp2(fmaf(sc[r / 16][r % 16], c2, -mc));
+      pv[1] = fast_exp2(fmaf(sc[r / 16][r % 16 + 1], c2, -mc));
+      const f16x2 pk = __builtin_convertvector(pv, f16x2);
+      pf.h[r / 2] = pk;
+      lsum = add_halves(lsum, pk);
+    }
+  };
+
   // One pipeline step: P(t) from sc, O += V(t) P(t); if there is a tile t+1: S(t+1) into sn and its maximum.
   // `steady` steps are the ones with t + 3 < ntiles: they always have a next tile and always prefetch,
   // so the step is straight-line code and the fences keep the interleaving as written.
-  auto step = [&](auto steady, f32x16 (&sc)[2], f32x16 (&sn)[2], int t) {
+  // `follow` steps scan S(t+1) for its maximum and move the reference value by the slack rule.  Once every row of
+  // the wavefront has a reference value (a finite one: it has seen a key), the steady steps stop following: a
+  // reference value that is the maximum of some of the row's logits can only be too low, never too high, so a weight
+  // that underflows is below 2^-126 of the row's largest and does not matter, and one that grows past kHuge shows in
+  // the tile's sum of weights, which is there anyway -- then refit() moves the reference.  That takes the maximum
+  // scan and its bookkeeping (a sixth of the step's vector instructions) out of the loop.
+  constexpr float kHuge = 16384.f;                 // 2^14: a weight stays inside the f16 range
+  auto step = [&](auto steady, auto follows, f32x16 (&sc)[2], f32x16 (&sn)[2], int t) {
     constexpr bool kSteady = decltype(steady)::value;
+    constexpr bool kFollow = decltype(follows)::value;
     const bool has_next = kSteady || t + 1 < ntiles;
     const int pre = (kSteady || t + 3 < ntiles) ? t + 3 : -1;
     const unsigned char* sk = smem + ((t + 1) % kStages) * kStageBytes;
     const unsigned char* sv = smem + (t % kStages) * kStageBytes + kKBytes;
     PFrag pf;
     float lsum = 0.f;
-    bf16x8 vf[kAhead];
+    f16x8 vf[kAhead];
     constexpr int EQ = 32 / NQK;             // S elements turned into P per QK MFMA
     auto softmax_chunk = [&](int c) {
 #pragma unroll
@@ -628,9 +678,9 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
         f32x2 pv;
         pv[0] = fast_exp2(fmaf(sc[r / 16][r % 16], c2, -mc));
         pv[1] = fast_exp2(fmaf(sc[r / 16][r % 16 + 1], c2, -mc));
-        const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
+        const f16x2 pk = __builtin_convertvector(pv, f16x2);
         pf.h[r / 2] = pk;
-        lsum += pv[0] + pv[1];                 // fp32 sum of the unrounded weights: lse stays exact to fp32
+        lsum = add_halves(lsum, pk);           // the weights as rounded: numerator and normaliser agree
       }
     };
     if (has_next) {
@@ -657,6 +707,9 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
 #pragma unroll
       for (int c = 0; c < NQK; ++c) softmax_chunk(c);
     }
+    // (also in the following steps: the first one after a stretch that did not follow forms its weights against
+    // the reference value that stretch left behind)
+    if (__any(lsum > kHuge)) refit(sc, pf, lsum);
     l_run += lsum;
     __builtin_amdgcn_s_setprio(0);
     float mloc = -INFINITY;
@@ -665,12 +718,14 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
     for (int c = 0; c < NPV; ++c) {
       const int t16 = c / NB, db = c % NB;
       __builtin_amdgcn_sched_barrier(0);
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c % kAhead], pf.v[t16], o[db], 0, 0, 0);
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[c % kAhead], pf.v[t16], o[db], 0, 0, 0);
       if (c + kAhead < NPV) vf[c % kAhead] = vfrag(sv, c + kAhead);
+      if constexpr (kFollow) {
 #pragma unroll
-      for (int e = 0; e < EV; e += 2) {
-        const int r = c * EV + e;
-        mloc = fmaxf(fmaxf(sn[r / 16][r % 16], sn[r / 16][r % 16 + 1]), mloc);
+        for (int e = 0; e < EV; e += 2) {
+          const int r = c * EV + e;
+          mloc = fmaxf(fmaxf(sn[r / 16][r % 16], sn[r / 16][r % 16 + 1]), mloc);
+        }
       }
       if (c * LPH % NPV == 0 && (kSteady || pre >= 0)) issue_part(pre, LPH + c * LPH / NPV);
     }
@@ -680,7 +735,7 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
     __builtin_amdgcn_s_setprio(1);
     if (has_next) {
       if (t + 1 >= n_full_tiles) mloc = mask_tile(sn, t + 1);
-      update_max(mloc);
+      if constexpr (kFollow) update_max(mloc);
     }
   };
 
@@ -717,13 +772,17 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
       update_max(mloc);
     }
     int t = 0;
+    for (; t + 4 < ntiles && __any(m_run == -INFINITY); t += 2) {   // some row has not seen a key yet
+      step(std::true_type{}, std::true_type{}, sa, sb, t);
+      step(std::true_type{}, std::true_type{}, sb, sa, t + 1);
+    }
     for (; t + 4 < ntiles; t += 2) {
-      step(std::true_type{}, sa, sb, t);
-      step(std::true_type{}, sb, sa, t + 1);
+      step(std::true_type{}, std::false_type{}, sa, sb, t);
+      step(std::true_type{}, std::false_type{}, sb, sa, t + 1);
     }
     for (; t < ntiles; t += 2) {
-      step(std::false_type{}, sa, sb, t);
-      if (t + 1 < ntiles) step(std::false_type{}, sb, sa, t + 1);
+      step(std::false_type{}, std::true_type{}, sa, sb, t);
+      if (t + 1 < ntiles) step(std::false_type{}, std::true_type{}, sb, sa, t + 1);
     }
   }
 
@@ -786,7 +845,7 @@ int launch_fwd(const Layer& L, const void* Q, const void* K, const void* V, cons
   FwdWs w = carve_fwd(a, L, sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32, heads, npad, sparse);
   {
     const int dt = sizeof(T) == 2 ? OMNI_BF16 : OMNI_F32;
-    // bf16: K natural + V k-packed; fp32: both natural
+    // bf16: K natural + V k-packed and converted to f16; fp32: both natural
     int rc = run_pack_kv(L, dt, K, V, sparse ? 1 : 0, kv_idx, b_cap, budget, b_cap, npad, kTileN, w.Kp,
                          dt == OMNI_BF16 ? nullptr : w.Vp, nullptr, dt == OMNI_BF16 ? w.Vp : nullptr, w.kidx, st,
                          sparse ? sel : nullptr);

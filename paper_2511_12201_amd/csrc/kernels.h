@@ -51,7 +51,7 @@ size_t probe_ws(const Layer& L, int dtype, int pb);
 int run_probe(const Layer& L, int dtype, const void* Q, const void* K, int pb, float* key_scores, void* ws,
               hipStream_t st, const float* probe_keys = nullptr, float* scores = nullptr);
 
-// pack.hip (outputs that are nullptr are skipped; Kt / Vt / Qt / dOt exist for bf16 only)
+// pack.hip (outputs that are nullptr are skipped; Kt / Vt / Qt / dOt exist for bf16 only; Vt holds f16 values)
 // sel not null (per_q_head only, src_idx ignored): the kernel forms the lists from *sel and writes them to sel->out
 int run_pack_kv(const Layer& L, int dtype, const void* K, const void* V, int per_q_head, const int* src_idx,
                 int idx_stride, const int* budget, int b_cap, int npad, int pad_to, void* Kn, void* Vn, void* Kt,

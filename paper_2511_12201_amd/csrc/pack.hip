@@ -7,7 +7,9 @@
 // with slot(group,h,j) = 16 group + 8 (j/4) + 4 h + j%4 -- the order in which a
 // 32x32 MFMA accumulator holds its rows -- so that the operand of a GEMM that
 // contracts over the slots is one 16-byte LDS read per lane.  fp32 inputs only
-// use the natural layout (the fp32 MFMA takes one element per lane).
+// use the natural layout (the fp32 MFMA takes one element per lane).  The k-packed
+// V (the forward's operand; the backward does not use it) is written in f16: the
+// forward multiplies its f16-rounded weights with it.
 //
 // pack_q: for the backward pass, the kept rows of Q and dO in the k-packed
 // layout (contraction over queries) and, for bf16, also as contiguous natural
@@ -22,6 +24,20 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
+
+// Eight bf16 values as f16.  Every bf16 value of magnitude in [2^-14, 65504] is an f16 value (8 significant bits
+// into 11); smaller ones land on the f16 subnormal grid (absolute error below 3e-8), larger ones saturate at 65504
+// (the conversion rounds towards zero, which never produces an infinity from a finite value).
+__device__ __forceinline__ u32x4 bf16x8_to_f16x8(const u32x4& x) {
+  u32x4 r;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float lo = __uint_as_float(x[j] << 16), hi = __uint_as_float(x[j] & 0xffff0000u);
+    const auto pk = __builtin_amdgcn_cvt_pkrtz(lo, hi);
+    r[j] = __builtin_bit_cast(unsigned, pk);
+  }
+  return r;
+}
 
 // 8 rows x 8 bf16 (one 16-byte chunk per row) -> 8 columns x 8 rows, written as 8 x 16 bytes
 __device__ __forceinline__ void transpose8x8_store(const u32x4 (&in)[8], u16* dst) {
@@ -185,6 +201,7 @@ __global__ __launch_bounds__(kThreads) void pack_kv_kernel(const T* __restrict__
         const int id = sIdx[16 * grp + 8 * (j >> 2) + 4 * h + (j & 3)];
         in[j] = zero;
         if (id != kPadKeyIndex) in[j] = *reinterpret_cast<const u32x4*>(src + (long long)id * L.ks[2] + dc * 8);
+        if (which) in[j] = bf16x8_to_f16x8(in[j]);     // the forward multiplies its weights and V in f16
       }
       transpose8x8_store(in, reinterpret_cast<u16*>(dst_t) + tile_off + ((grp * 2 + h) * D + dc * 8) * 8);
     }

@@ -222,6 +222,70 @@ def test_sparse_attn_fwd_edge_sets(cfg):
         assert np.all(lse[0, 1] == -np.inf)
 
 
+def _plain_bf16_layer(seed, N, H, Hkv, d):
+    rng = np.random.default_rng(seed)
+    mk = lambda *shape: synth.round_to_bf16(rng.standard_normal(shape).astype(np.float32))
+    return mk(1, H, N, d), mk(1, Hkv, N, d), mk(1, Hkv, N, d)
+
+
+@pytest.mark.parametrize("ramp", [3.0, 12.0, 40.0])
+def test_forward_when_the_logits_keep_rising_along_the_key_list(ramp):
+    """Keys whose logits grow with their index by up to `ramp` per 64-key tile in the exponent's base-2 units, and
+    jump up and down around that trend: whatever value the kernel takes the weights of a row against early on is far
+    too low later (by more than the f16 and, for the steepest ramp, the fp32 range), so the path that moves it and
+    forms a tile's weights again has to run, many times per row.  Every query is kept, causal and not."""
+    N, H, Hkv, d = 1536, 4, 2, 128
+    Q, K, V = _plain_bf16_layer(77, N, H, Hkv, d)
+    u = np.zeros(d, dtype=np.float32)
+    u[:8] = 1.0
+    scale = 1.0 / math.sqrt(d)
+    # q.u = 8 a and k_n.u = 8 g(n) on top of the noise, u a unit step on 8 coordinates: logit trend 8 a g(n) scale nats
+    a = 2.0
+    rng = np.random.default_rng(78)
+    g = (ramp * math.log(2.0) / 64.0) * np.arange(N) / (8 * a * scale) + rng.choice([0.0, 0.5, -0.5], N)
+    Q = synth.round_to_bf16(Q * 0.25 + a * u)
+    K = synth.round_to_bf16(K * 0.25 + g[None, None, :, None].astype(np.float32) * u)
+    dQ, dK, dV = (to_device(x, "bf16") for x in (Q, K, V))
+    full = [[np.arange(N, dtype=np.int32) for _ in range(H)]]
+    q_idx, q_cnt = lists_to_padded(full, H, N)
+    budget = torch.full((1,), N, dtype=torch.int32, device="cuda")
+    for causal in (True, False):
+        desc = ob.make_layer_desc(dQ, dK, 1, N - 8, 0, causal, scale)
+        O, lse = ob.omni_sparse_attn_fwd(desc, dQ, dK, dV, q_idx, q_cnt, q_idx, budget, N)
+        O2, lse2 = ob.omni_dense_attn_fwd(desc, dQ, dK, dV)
+        torch.cuda.synchronize()
+        Oo, Lo = oc.dense_attention(Q, K, V, causal, scale)
+        for got_o, got_l in ((O, lse), (O2, lse2)):
+            assert np.max(np.abs(to_host(got_o) - Oo)) <= TOL_OUT["bf16"]
+            assert np.max(np.abs(to_host(got_l) - Lo)) <= 2e-3 * max(1.0, float(np.max(np.abs(Lo))) / 64)
+
+
+@pytest.mark.parametrize("vscale", [2.0 ** -12, 1.0, 2.0 ** 13])
+def test_forward_value_range(vscale):
+    """The second product runs in f16: V is converted exactly inside [2^-14, 65504].  Outputs follow V's scale with the
+    same relative accuracy there; beyond it V saturates at 65504, which the last case pins against the oracle on the
+    clamped values."""
+    N, H, Hkv, d = 640, 4, 2, 64
+    Q, K, V = _plain_bf16_layer(91, N, H, Hkv, d)
+    V = synth.round_to_bf16(V * np.float32(vscale))
+    scale = 1.0 / math.sqrt(d)
+    dQ, dK = to_device(Q, "bf16"), to_device(K, "bf16")
+    desc = ob.make_layer_desc(dQ, dK, 1, N - 8, 0, True, scale)
+    O, _ = ob.omni_dense_attn_fwd(desc, dQ, dK, to_device(V, "bf16"))
+    torch.cuda.synchronize()
+    Oo, _ = oc.dense_attention(Q, K, V, True, scale)
+    assert np.max(np.abs(to_host(O) - Oo)) <= TOL_OUT["bf16"] * vscale + 2e-7
+    if vscale > 1:
+        Vbig = V.copy()
+        Vbig[0, :, 5::7, 3] = 3.0e5                     # beyond the f16 range: taken as 65504
+        O, _ = ob.omni_dense_attn_fwd(desc, dQ, dK, to_device(Vbig, "bf16"))
+        torch.cuda.synchronize()
+        Oc, _ = oc.dense_attention(Q, K, np.minimum(Vbig, 65504.0), True, scale)
+        got = to_host(O)
+        assert np.all(np.isfinite(got))
+        assert np.max(np.abs(got - Oc)) <= TOL_OUT["bf16"] * vscale + 2.0 ** -8 * 65504
+
+
 @pytest.mark.parametrize("cfg", ALL_CFGS, ids=lambda c: c.name)
 @pytest.mark.parametrize("causal", [True, False])
 def test_dense_attn_fwd_and_full_budget_sparse_equal_dense_definition(cfg, causal):
