@@ -56,8 +56,9 @@ def pair_counts(q_lists, kv_lists, causal: bool, tile_m: int = 128, tile_n: int 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps before the timed ones (the clocks of the first few steps under load are lower)")
     ap.add_argument("--workload", default="c3_64k", choices=["c3_64k", "c2_16k"])
     ap.add_argument("--no-extras", action="store_true", help="skip dense baseline / oracle timing")
     ap.add_argument("--only", choices=["train", "decode", "mfma", "dense"],
