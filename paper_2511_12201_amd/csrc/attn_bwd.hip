@@ -22,6 +22,8 @@
 // workgroup, dK' and dV' together) / attn_bwd_dq_kernel on the fp32 32x32x2 MFMA with natural layouts.
 #include <algorithm>
 
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 #include "sched.h"
@@ -733,23 +735,28 @@ __global__ __launch_bounds__(kDqThreads, 2) void attn_bwd_dq_bf16_kernel(BwdPara
       if (c % (NA / (2 * LPH)) == 0 && pre >= 0) issue_part(pre, c / (NA / (2 * LPH)));      // K and V parts of tile t+2
     }
     __builtin_amdgcn_sched_barrier(0);
-    // dS^T = P^T (dP^T - delta); the lane's query fixes lse and delta, the register fixes the key
-    const int rel = masked ? qvisible - t * kTileN : 0x7fffffff;
+    // dS^T = P^T (dP^T - delta); the lane's query fixes lse and delta, the register fixes the key.  Only the tiles
+    // at the causal diagonal of the item pay for the position compares (a wavefront-uniform branch).
     bf16x8 fc[kAhead];
 #pragma unroll
     for (int c = 0; c < kAhead; ++c) fc[c] = cfrag(c);
     bf16x8 dsf[4];
+    auto weights = [&](auto with_mask) {
+      const int rel = qvisible - t * kTileN;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+      for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float pv = fast_exp2(fmaf(s[kb][r], c2, -lse2r));
-        if (kb * 32 + 8 * (r >> 2) + (r & 3) >= rel) pv = 0.f;
-        dp[kb][r] = pv * (dp[kb][r] - deltar);
+        for (int r = 0; r < 16; ++r) {
+          float pv = fast_exp2(fmaf(s[kb][r], c2, -lse2r));
+          if (decltype(with_mask)::value && kb * 32 + 8 * (r >> 2) + (r & 3) >= rel) pv = 0.f;
+          dp[kb][r] = pv * (dp[kb][r] - deltar);
+        }
+        dsf[kb * 2] = pack8(dp[kb], 0);
+        dsf[kb * 2 + 1] = pack8(dp[kb], 8);
       }
-      dsf[kb * 2] = pack8(dp[kb], 0);
-      dsf[kb * 2 + 1] = pack8(dp[kb], 8);
-    }
+    };
+    if (masked) weights(std::true_type{});
+    else weights(std::false_type{});
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       const int t16 = c / NB, db = c % NB;
@@ -1012,7 +1019,7 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
 
   auto compute_tile = [&](int u, int pre, bool masked) {
     const unsigned char* st = smem + (u % kStages) * kStageBytes;
-    const int rel = masked ? first_h - (q_begin + u) * kKeyQ : -0x7fffffff;   // query positions below rel do not see this key
+    const int rel = first_h - (q_begin + u) * kKeyQ;                 // query positions below rel do not see this key
     auto cfrag = [&](int c) {
       const int t16 = c / NB, db = c % NB;
       return *reinterpret_cast<const bf16x8*>(st + (NOPS - 1) * kOpBytes + plane_b + (t16 * 2 * D + db * 32) * 16);
@@ -1041,22 +1048,27 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
       }
       __builtin_amdgcn_sched_barrier(0);
       if (qb == 0 && pre >= 0) issue_small(pre);
-      // accumulator rows are queries 8 (r/4) + 4 h + r%4 of this block, the column is this lane's key
+      // accumulator rows are queries 8 (r/4) + 4 h + r%4 of this block, the column is this lane's key; only the
+      // query tiles at the causal diagonal of the key tile pay for the position compares (wavefront-uniform branch)
+      auto weights = [&](auto with_mask) {
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int qo = qb * 32 + 8 * q4 + 4 * h;
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + qo * 4);
-        f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
-        if (MODE == 0) d4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + 256 + qo * 4);
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int qo = qb * 32 + 8 * q4 + 4 * h;
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + qo * 4);
+          f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+          if (MODE == 0) d4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + 256 + qo * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = q4 * 4 + e;
-          float pv = fast_exp2(fmaf(s[r], c2, -l4[e]));
-          if (qb * 32 + 8 * q4 + e < rel) pv = 0.f;
-          s[r] = MODE == 0 ? pv * (dp[r] - d4[e]) : pv;
+          for (int e = 0; e < 4; ++e) {
+            const int r = q4 * 4 + e;
+            float pv = fast_exp2(fmaf(s[r], c2, -l4[e]));
+            if (decltype(with_mask)::value && qb * 32 + 8 * q4 + e < rel) pv = 0.f;
+            s[r] = MODE == 0 ? pv * (dp[r] - d4[e]) : pv;
+          }
+          if (MODE == 0) __builtin_amdgcn_sched_barrier(0);    // one quad of lse / delta values in registers at a time
         }
-        if (MODE == 0) __builtin_amdgcn_sched_barrier(0);    // one quad of lse / delta values in registers at a time
-      }
+      };
+      if (masked) weights(std::true_type{});
+      else weights(std::false_type{});
       // P (or dS) of these 32 queries as two B operands of 16 queries each, then their share of the update
       bf16x8 bfrag[2];
       bfrag[0] = pack8(s, 0);
