@@ -1024,14 +1024,13 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
       const int t16 = c / NB, db = c % NB;
       return *reinterpret_cast<const bf16x8*>(st + (NOPS - 1) * kOpBytes + plane_b + (t16 * 2 * D + db * 32) * 16);
     };
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      // chunk c of phase A: k-step ks, operand (0: Q for S, 1: dO for dP)
+    // phase A of query block qb: S^T (and dP^T) of its 32 queries; under(c) is vector work placed behind MFMA c
+    auto phase_a = [&](int qb, f32x16& s, f32x16& dp, auto under) {
+      // chunk c: k-step ks, operand (0: Q for S, 1: dO for dP)
       auto afrag = [&](int c) {
         const int which = MODE == 0 ? c % 2 : 0, ks = MODE == 0 ? c / 2 : c;
         return *reinterpret_cast<const bf16x8*>(st + which * kOpBytes + qb * (32 * CH * 16) + krow_b + ((ks << 5) ^ khx));
       };
-      f32x16 s, dp;
       bf16x8 fa[kAhead];
 #pragma unroll
       for (int c = 0; c < kAhead; ++c) fa[c] = afrag(c);
@@ -1042,34 +1041,31 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
         if (which == 0) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c % kAhead], kf[ks], ks == 0 ? zero16 : s, 0, 0, 0);
         else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c % kAhead], vf[MODE == 0 ? ks : 0], ks == 0 ? zero16 : dp, 0, 0, 0);
         if (c + kAhead < NA) fa[c % kAhead] = afrag(c + kAhead);
+        under(c);
         // natural operand parts of the tile to prefetch: NOPS - 1 operands x LPH parts over 2 * NA MFMAs
         constexpr int kParts = (NOPS - 1) * LPH, kEvery = 2 * NA / kParts;
         if ((qb * NA + c) % kEvery == 0 && pre >= 0) issue_part(pre, (qb * NA + c) / kEvery);
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (qb == 0 && pre >= 0) issue_small(pre);
-      // accumulator rows are queries 8 (r/4) + 4 h + r%4 of this block, the column is this lane's key; only the
-      // query tiles at the causal diagonal of the key tile pay for the position compares (wavefront-uniform branch)
-      auto weights = [&](auto with_mask) {
+    };
+    // weights (MODE 1) or dS (MODE 0) of four queries of block qb, in place: accumulator rows are queries
+    // 8 (r/4) + 4 h + r%4 of the block, the column is this lane's key.  Only the query tiles at the causal diagonal
+    // of the key tile pay for the position compares (with_mask; a wavefront-uniform choice).
+    auto quad = [&](auto with_mask, int qb, f32x16& s, const f32x16& dp, int q4) {
+      const int qo = qb * 32 + 8 * q4 + 4 * h;
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + qo * 4);
+      f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+      if (MODE == 0) d4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + 256 + qo * 4);
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int qo = qb * 32 + 8 * q4 + 4 * h;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + qo * 4);
-          f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
-          if (MODE == 0) d4 = *reinterpret_cast<const f32x4*>(st + kSmallOff + 256 + qo * 4);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = q4 * 4 + e;
-            float pv = fast_exp2(fmaf(s[r], c2, -l4[e]));
-            if (decltype(with_mask)::value && qb * 32 + 8 * q4 + e < rel) pv = 0.f;
-            s[r] = MODE == 0 ? pv * (dp[r] - d4[e]) : pv;
-          }
-          if (MODE == 0) __builtin_amdgcn_sched_barrier(0);    // one quad of lse / delta values in registers at a time
-        }
-      };
-      if (masked) weights(std::true_type{});
-      else weights(std::false_type{});
-      // P (or dS) of these 32 queries as two B operands of 16 queries each, then their share of the update
+      for (int e = 0; e < 4; ++e) {
+        const int r = q4 * 4 + e;
+        float pv = fast_exp2(fmaf(s[r], c2, -l4[e]));
+        if (decltype(with_mask)::value && qb * 32 + 8 * q4 + e < rel) pv = 0.f;
+        s[r] = MODE == 0 ? pv * (dp[r] - d4[e]) : pv;
+      }
+    };
+    // phase C of block qb: its P (or dS), as two B operands of 16 queries each, into the update
+    auto phase_c = [&](int qb, const f32x16& s, auto under) {
       bf16x8 bfrag[2];
       bfrag[0] = pack8(s, 0);
       bfrag[1] = pack8(s, 8);
@@ -1082,10 +1078,42 @@ __global__ __launch_bounds__(kKeyThreads, 2) void attn_bwd_key_bf16_kernel(BwdPa
         __builtin_amdgcn_sched_barrier(0);
         acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[c % kAhead], bfrag[c / NB], acc[db], 0, 0, 0);
         if (c + kAhead < NC / 2) fc[c % kAhead] = cfrag(cc + kAhead);
+        under(c);
         if (cc % (NC / LPH) == 0 && pre >= 0) issue_part(pre, (NOPS - 1) * LPH + cc / (NC / LPH));   // k-packed operand parts
       }
-      __builtin_amdgcn_sched_barrier(0);       // keep the two query blocks apart: their accumulators would double up
-    }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto nothing = [](int) {};
+    auto run = [&](auto with_mask) {
+      if constexpr (MODE == 1) {
+        // dV': the weights of a block run on the vector ALU under the matrix-core work of the other block -- S of
+        // block 1 over the weights of block 0, the update of block 0 over the weights of block 1 (a quad of queries
+        // behind every second MFMA).  Two S accumulators are live at once; this kernel has the registers for it.
+        static_assert(MODE != 1 || (NA == 2 * 4 || NA == 4) && NC / 2 >= 4, "a quad per MFMA or per two");
+        constexpr int kPerA = NA / 4, kPerC = (NC / 2) / 4;
+        f32x16 s0, s1, none;
+        phase_a(0, s0, none, nothing);
+        if (pre >= 0) issue_small(pre);
+        phase_a(1, s1, none, [&](int c) { if (c % kPerA == 0) quad(with_mask, 0, s0, none, c / kPerA); });
+        phase_c(0, s0, [&](int c) { if (c % kPerC == 0 && c / kPerC < 4) quad(with_mask, 1, s1, none, c / kPerC); });
+        phase_c(1, s1, nothing);
+      } else {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          f32x16 s, dp;
+          phase_a(qb, s, dp, nothing);
+          if (qb == 0 && pre >= 0) issue_small(pre);
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            quad(with_mask, qb, s, dp, q4);
+            __builtin_amdgcn_sched_barrier(0);    // one quad of lse / delta values in registers at a time
+          }
+          phase_c(qb, s, nothing);                // the two blocks stay apart: their accumulators would double up
+        }
+      }
+    };
+    if (masked) run(std::true_type{});
+    else run(std::false_type{});
   };
 
   // Ring of kStages buffers, one barrier per tile: at the top of step u the tiles up to u + kStages - 2 have
