@@ -195,7 +195,10 @@ def main():
         "config": {"workload": f"{cfg.name}: 1 layer, batch 1, {Hq} q heads / {cfg.n_kv_heads} kv heads, head_dim {D}, "
                                f"N={N} ({cfg.frames} frames x {cfg.tok_per_frame} visual + {cfg.n_text} text), causal, "
                                f"tau={TAU}, recall p={RECALL_P}, probe block {PROBE_BLOCK}",
-                   "step": "prefill_select (= score_queries + select_queries + kv_budget + select_kv) + sparse_attn_fwd"},
+                   "step": "prefill_select (= score_queries + select_queries + kv_budget + select_kv) + sparse_attn_fwd",
+                   "arithmetic": "bf16 inputs; Q.K^T on the bf16 matrix cores, softmax in fp32, weights rounded to f16 and "
+                                 "multiplied with V (converted from bf16 to f16, exact inside +-65504) on the f16 matrix "
+                                 "cores, fp32 accumulation"},
         "roofline": {"bound": "mfma", "kernel": "attn_fwd_bf16_kernel<128> (sparse)", "achieved": round(ach, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(cfg.name),
