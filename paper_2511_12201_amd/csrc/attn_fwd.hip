@@ -536,8 +536,9 @@ __global__ __launch_bounds__(kFastThreads, 2) void attn_fwd_bf16_kernel(FwdParam
   };
 
   // Software pipeline over key tiles.  While the matrix cores compute S(t+1)^T = K(t+1) . Q^T the
-  // same wavefront turns S(t) into P(t) on the vector ALU (exp2, row sum, bf16 pack); while they
-  // accumulate O^T += V(t)^T . P(t)^T it scans S(t+1) for the running maximum.  Each MFMA is followed
+  // same wavefront turns S(t) into P(t) on the vector ALU (exp2, f16 pack, row sum); while they
+  // accumulate O^T += V(t)^T . P(t)^T it scans S(t+1) for the running maximum (in the steps that follow
+  // it; see `step`).  Each MFMA is followed
   // in program order by its share of the vector work and a scheduling fence, so the hardware always
   // has independent vector instructions to issue under a running MFMA.  Without this the two
   // wavefronts of a SIMD, which the per-tile barrier keeps in step, are in their softmax phases at
