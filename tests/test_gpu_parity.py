@@ -260,6 +260,34 @@ def test_forward_when_the_logits_keep_rising_along_the_key_list(ramp):
             assert np.max(np.abs(to_host(got_l) - Lo)) <= 2e-3 * max(1.0, float(np.max(np.abs(Lo))) / 64)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_forward_returns_the_value_row_of_a_key_that_dominates(causal):
+    """Every query's own key beats all others by more than 40 in the exponent: the softmax is one-hot to any working
+    precision, so the output row is that key's V row -- bit for bit, whatever value the kernel takes the weights
+    against and however it rounds them, because numerator and normaliser carry the same rounded weight."""
+    N, H, Hkv, d = 1536, 4, 4, 128
+    _, K, V = _plain_bf16_layer(55, N, H, Hkv, d)
+    scale = 1.0 / math.sqrt(d)
+    Q = synth.round_to_bf16(10.0 * K)                       # q_n . k_n scale ~ 113; q_n . k_m scale below 50
+    S = np.einsum("hnd,hmd->hnm", Q[0].astype(np.float64), K[0].astype(np.float64)) * scale
+    own = np.diagonal(S, axis1=1, axis2=2)
+    off = S - 1e9 * np.eye(N)[None]
+    if causal:
+        off = np.where(np.tril(np.ones((N, N), bool))[None], off, -np.inf)
+    assert np.min(own - off.max(-1)) > 40 * math.log(2.0) + 1          # the construction holds
+    dQ, dK, dV = (to_device(x, "bf16") for x in (Q, K, V))
+    desc = ob.make_layer_desc(dQ, dK, 1, N - 8, 0, causal, scale)
+    O, lse = ob.omni_dense_attn_fwd(desc, dQ, dK, dV)
+    full = [[np.arange(N, dtype=np.int32) for _ in range(H)]]
+    q_idx, q_cnt = lists_to_padded(full, H, N)
+    budget = torch.full((1,), N, dtype=torch.int32, device="cuda")
+    O2, _ = ob.omni_sparse_attn_fwd(desc, dQ, dK, dV, q_idx, q_cnt, q_idx, budget, N)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(O), V)
+    np.testing.assert_array_equal(to_host(O2), V)
+    np.testing.assert_allclose(to_host(lse)[0], own, rtol=2e-6, atol=1e-4)
+
+
 @pytest.mark.parametrize("vscale", [2.0 ** -12, 1.0, 2.0 ** 13])
 def test_forward_value_range(vscale):
     """The second product runs in f16: V is converted exactly inside [2^-14, 65504].  Outputs follow V's scale with the
