@@ -1104,7 +1104,8 @@ def test_sparse_attn_bwd_with_key_tiles_shared_between_workgroups(cfg, split_len
         assert torch.equal(x, y)
 
 
-def test_prefill_step_replays_from_a_hip_graph():
+@pytest.mark.parametrize("one_call", [False, True], ids=["two_calls", "one_call"])
+def test_prefill_step_replays_from_a_hip_graph(one_call):
     """No call of the step allocates, synchronises or clears memory from the host, so a caller may capture it.
     Replays are interleaved with eager work and each one must reproduce the eager result bit for bit."""
     cfg = CFG_BF16
@@ -1118,6 +1119,10 @@ def test_prefill_step_replays_from_a_hip_graph():
     O, lse = torch.empty_like(eager_O), torch.empty_like(eager_lse)
 
     def step():
+        if one_call:
+            ob.omni_sparse_prefill(c.desc, c.dQ, c.dK, c.dV, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0, out=sel,
+                                   O=O, lse=lse)
+            return
         ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, c.probe_block, 0, out=sel)
         ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, sel.q_idx, sel.q_cnt, sel.kv_idx, sel.budget.budget, N, O, lse)
 
