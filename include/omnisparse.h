@@ -96,15 +96,12 @@ typedef struct {
   float softmax_scale;
   float tau;                   /* lazy/active threshold of the query-mask equation */
   int64_t kv_stride[3];        /* batch, head, token strides of the caches, in elements */
-  int32_t static_lists;        /* omni_slim_decode only.  1: the caller guarantees that vis_idx / vis_cnt keep their
-                                  contents from call to call for as long as the same workspace is passed (the lists
-                                  are fixed at prefill; Sec. "KV Cache Slimming").  The first call with a workspace
-                                  then merges the lists of every KV group into it (ascending union + membership
-                                  bits) and later calls read a stored row once per group, as
-                                  omni_slim_decode_grouped does.  Which heads are active is still decided on every
-                                  call.  0: the lists are read anew on every call; such a call (like any other decode
-                                  call on that workspace) also discards lists merged earlier, which is how a caller
-                                  that refills the same list buffers tells the library so. */
+  int32_t static_lists;        /* omni_slim_decode / omni_slim_decode_prepare only.  1: the lists are fixed after
+                                  prefill (Sec. "KV Cache Slimming") and omni_slim_decode_prepare has merged them
+                                  per KV group into the workspace that omni_slim_decode is given; the call reads
+                                  a stored row once per group, as omni_slim_decode_grouped does, and ignores the
+                                  contents of vis_idx / vis_cnt.  Which heads are active is still decided on every
+                                  call.  0: the lists are read anew on every call. */
 } omni_decode_desc;
 
 /* Paged form of the compacted visual KV store (omni_compact_cache_paged,
@@ -388,6 +385,25 @@ int omni_slim_decode(const omni_decode_desc* desc, const void* q,
                      const int32_t* vis_idx, const int32_t* vis_cnt, int32_t b_cap,
                      void* O, uint8_t* active,
                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * omni_slim_decode_prepare -- once after prefill, and again whenever the lists
+ * change: merges the per-head lists of every KV group (ascending union with a
+ * membership bit per head, as omni_group_subset builds it from kv_idx) into the
+ * workspace, behind the partial states of the decode call.  The omni_slim_decode
+ * calls that follow with static_lists = 1, the same shapes and this workspace then
+ * read every stored row once per group.  The merged lists live in the caller's
+ * memory and nowhere else: between this call and the decode calls that rely on it
+ * no other call may be given the workspace (the stateless omni_slim_decode and the
+ * other decode calls write their partial states over it), and a workspace that was
+ * freed and allocated again has to be prepared again.  desc must have
+ * static_lists = 1.  Groups wider than 32 heads have no membership word: the call
+ * does nothing and omni_slim_decode reads the per-head lists.
+ * Workspace: OMNI_CALL_SLIM_DECODE for this descriptor (it includes the lists).
+ */
+int omni_slim_decode_prepare(const omni_decode_desc* desc,
+                             const int32_t* vis_idx, const int32_t* vis_cnt, int32_t b_cap,
+                             void* ws, size_t ws_bytes, void* stream);
 
 /*
  * omni_visual_subset -- helper for the hand-over from prefill to decode

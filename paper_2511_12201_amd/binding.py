@@ -33,7 +33,7 @@ EXPORTED = [
     "omni_compact_cache_paged", "omni_slim_decode_paged",
     "omni_group_subset_per_head", "omni_debug_key_split_len",
     "omni_slim_decode_grouped_static", "omni_static_scratch_bytes",
-    "omni_sparse_prefill", "omni_sparse_prefill_workspace_bytes",
+    "omni_sparse_prefill", "omni_sparse_prefill_workspace_bytes", "omni_slim_decode_prepare",
 ]
 
 PROF_KERNELS = {"attn_fwd": 0, "pack_kv": 1, "clear_out": 2, "pool_q": 3, "probe_lse": 4, "probe_sum": 5,
@@ -124,6 +124,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.omni_sparse_attn_fwd_per_head.argtypes = lib.omni_sparse_attn_fwd.argtypes
     lib.omni_sparse_attn_bwd_per_head.argtypes = lib.omni_sparse_attn_bwd.argtypes
     lib.omni_slim_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.omni_slim_decode_prepare.argtypes = [vp, vp, vp, i32, vp, sz, vp]
     lib.omni_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.omni_group_subset.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, sz, vp]
     lib.omni_group_subset_per_head.argtypes = lib.omni_group_subset.argtypes
@@ -606,6 +607,14 @@ def omni_slim_decode(desc: DecodeDesc, q, Kcache, Vcache, ctx_len, probe_keys, v
                                 _ptr(vis_idx), _ptr(vis_cnt), b_cap, _ptr(O), _ptr(active), _ptr(buf), buf.numel(),
                                 _stream()))
     return O, active
+
+
+def omni_slim_decode_prepare(desc: DecodeDesc, vis_idx, vis_cnt, b_cap: int, ws: Workspace | None = None):
+    """Merge the per-head lists per KV group into the workspace the omni_slim_decode calls with static_lists get."""
+    ws = ws or default_workspace()
+    buf = ws.get(CALL_SLIM_DECODE, desc)
+    _check(load_library().omni_slim_decode_prepare(C.byref(desc), _ptr(vis_idx), _ptr(vis_cnt), b_cap, _ptr(buf),
+                                                   buf.numel(), _stream()))
 
 
 def block_level_desc(desc: LayerDesc, block: int) -> LayerDesc:

@@ -5,7 +5,6 @@
 #include <cstdio>
 #include <cstring>
 #include <mutex>
-#include <unordered_map>
 #include <vector>
 
 #include "common.h"
@@ -163,6 +162,33 @@ using namespace omni;
 namespace omni {
 namespace {
 
+// Where omni_slim_decode_prepare keeps the merged lists: behind the partial states of the decode call.
+struct StaticLists {
+  int* grp_idx;         // [B, Hkv, nv]
+  unsigned* grp_mask;   // [B, Hkv, nv]
+  int* grp_cnt;         // [B, Hkv]
+  void* scratch;        // of the merge
+  int nv;
+  Layer L;              // the shapes the merge kernels take
+};
+
+size_t static_lists_bytes(const omni_decode_desc* d);
+
+StaticLists carve_static_lists(const omni_decode_desc* d, void* ws) {
+  StaticLists m;
+  m.nv = d->vis_end - d->vis_begin;
+  const size_t pairs = (size_t)d->batch * d->n_kv_heads;
+  Arena a(static_cast<unsigned char*>(ws) + decode_ws(d));
+  m.grp_idx = a.take<int>(pairs * m.nv);
+  m.grp_mask = a.take<unsigned>(pairs * m.nv);
+  m.grp_cnt = a.take<int>(pairs);
+  m.L = Layer{};
+  m.L.B = d->batch; m.L.Hq = d->n_q_heads; m.L.Hkv = d->n_kv_heads; m.L.G = m.L.Hq / m.L.Hkv; m.L.D = d->head_dim;
+  m.L.N = d->cache_capacity; m.L.v0 = d->vis_begin; m.L.v1 = d->vis_end; m.L.bph = 1;
+  m.scratch = a.take<unsigned char>(group_subset_ws(m.L));
+  return m;
+}
+
 // Bytes behind the partial states: grp_idx, grp_mask [B, Hkv, nv], grp_cnt [B, Hkv], the merge's own scratch.
 size_t static_lists_bytes(const omni_decode_desc* d) {
   if (!d->static_lists || d->n_q_heads / d->n_kv_heads > 32) return 0;
@@ -175,26 +201,6 @@ size_t static_lists_bytes(const omni_decode_desc* d) {
   L.B = d->batch; L.Hq = d->n_q_heads; L.Hkv = d->n_kv_heads; L.v0 = d->vis_begin; L.v1 = d->vis_end;
   a.take<unsigned char>(group_subset_ws(L));
   return a.used();
-}
-
-// Which lists a workspace holds merged (host side: the device contents cannot be inspected without a synchronisation).
-struct MergedKey {
-  const void* vis_idx;
-  const void* vis_cnt;
-  int b_cap, B, Hq, Hkv, v0, v1, device;
-  bool operator==(const MergedKey& o) const {
-    return vis_idx == o.vis_idx && vis_cnt == o.vis_cnt && b_cap == o.b_cap && B == o.B && Hq == o.Hq && Hkv == o.Hkv &&
-           v0 == o.v0 && v1 == o.v1 && device == o.device;
-  }
-};
-std::mutex g_merged_mutex;
-std::unordered_map<const void*, MergedKey> g_merged;    // workspace pointer -> lists merged into it
-
-// Any other decode call that is handed the workspace may write over the merged lists (its partial states can be
-// larger): what the workspace held is forgotten.
-void forget_merged(const void* ws) {
-  std::lock_guard<std::mutex> lock(g_merged_mutex);
-  if (!g_merged.empty()) g_merged.erase(ws);
 }
 
 }  // namespace
@@ -798,36 +804,26 @@ int omni_slim_decode(const omni_decode_desc* desc, const void* q, const void* Kc
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc) + lists_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (lists_bytes) {
-    // The lists do not change between calls (the caller's promise): merge them per KV group once, into the
-    // workspace behind the partial states, and run every step on the merged lists.
-    const int nv = desc->vis_end - desc->vis_begin;
-    const size_t pairs = (size_t)desc->batch * desc->n_kv_heads;
-    Arena a(static_cast<unsigned char*>(ws) + decode_ws(desc));
-    int* grp_idx = a.take<int>(pairs * nv);
-    unsigned* grp_mask = a.take<unsigned>(pairs * nv);
-    int* grp_cnt = a.take<int>(pairs);
-    Layer L{};
-    L.B = desc->batch; L.Hq = desc->n_q_heads; L.Hkv = desc->n_kv_heads; L.G = L.Hq / L.Hkv; L.D = desc->head_dim;
-    L.N = desc->cache_capacity; L.v0 = desc->vis_begin; L.v1 = desc->vis_end; L.bph = 1;
-    void* scratch = a.take<unsigned char>(group_subset_ws(L));
-    int dev = -1;
-    OMNI_HIP_CHECK(hipGetDevice(&dev));
-    const MergedKey key{vis_idx, vis_cnt, b_cap, L.B, L.Hq, L.Hkv, L.v0, L.v1, dev};
-    bool fresh;
-    {
-      std::lock_guard<std::mutex> lock(g_merged_mutex);
-      auto it = g_merged.find(ws);
-      fresh = it != g_merged.end() && it->second == key;
-      if (!fresh) {
-        if (g_merged.size() > 4096) g_merged.clear();
-        g_merged[ws] = key;
-      }
-    }
-    if (!fresh) CHECK(run_group_subset(L, vis_idx, vis_cnt, b_cap, grp_idx, grp_mask, grp_cnt, nv, scratch, st));
-    return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, nv, O, active, ws, st);
+    // the lists as omni_slim_decode_prepare left them in the workspace, merged per KV group
+    StaticLists m = carve_static_lists(desc, ws);
+    return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, m.grp_idx, m.grp_cnt, m.grp_mask, m.nv, O, active, ws, st);
   }
-  forget_merged(ws);
   return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, vis_idx, vis_cnt, nullptr, b_cap, O, active, ws, st);
+}
+
+int omni_slim_decode_prepare(const omni_decode_desc* desc, const int32_t* vis_idx, const int32_t* vis_cnt, int32_t b_cap,
+                             void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  CHECK(validate_decode(desc));
+  REQUIRE_PTR(vis_idx); REQUIRE_PTR(vis_cnt);
+  if (b_cap < 1) OMNI_FAIL(OMNI_ERR_INVALID, "b_cap must be >= 1");
+  if (!desc->static_lists) OMNI_FAIL(OMNI_ERR_INVALID, "omni_slim_decode_prepare is for descriptors with static_lists = 1");
+  const size_t lists_bytes = static_lists_bytes(desc);
+  CHECK(check_ws(ws, ws_bytes, decode_ws(desc) + lists_bytes));
+  if (!lists_bytes) return OMNI_OK;      // groups wider than the membership word: the decode call reads the per-head lists
+  StaticLists m = carve_static_lists(desc, ws);
+  return run_group_subset(m.L, vis_idx, vis_cnt, b_cap, m.grp_idx, m.grp_mask, m.grp_cnt, m.nv, m.scratch,
+                          static_cast<hipStream_t>(stream));
 }
 
 int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q, const void* Kcache, const void* Vcache,
@@ -843,7 +839,6 @@ int omni_slim_decode_grouped(const omni_decode_desc* desc, const void* q, const 
   if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
   if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
-  forget_merged(ws);
   return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
                     static_cast<hipStream_t>(stream));
 }
@@ -899,7 +894,6 @@ int omni_slim_decode_compact(const omni_decode_desc* desc, const void* q, const 
   if (desc->n_q_heads / desc->n_kv_heads > 32) OMNI_FAIL(OMNI_ERR_UNSUPPORTED, "more than 32 query heads per KV head");
   if (!std::isfinite(desc->tau)) OMNI_FAIL(OMNI_ERR_INVALID, "tau must be finite");
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
-  forget_merged(ws);
   return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
                     static_cast<hipStream_t>(stream), Kcomp, Vcomp);
 }
@@ -951,7 +945,6 @@ int omni_slim_decode_paged(const omni_decode_desc* desc, const void* q, const vo
   PagePool pp;
   CHECK(validate_pool(pool, u_cap, &pp));
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
-  forget_merged(ws);
   return run_decode(desc, q, Kcache, Vcache, ctx_len, probe_keys, grp_idx, grp_cnt, grp_mask, u_cap, O, active, ws,
                     static_cast<hipStream_t>(stream), pool->K, pool->V, &pp);
 }
@@ -963,7 +956,6 @@ int omni_dense_decode(const omni_decode_desc* desc, const void* q, const void* K
   REQUIRE_PTR(q); REQUIRE_PTR(Kcache); REQUIRE_PTR(Vcache); REQUIRE_PTR(ctx_len); REQUIRE_PTR(O);
   REQUIRE_ALIGNED(q); REQUIRE_ALIGNED(Kcache); REQUIRE_ALIGNED(Vcache);
   CHECK(check_ws(ws, ws_bytes, decode_ws(desc)));
-  forget_merged(ws);
   return run_decode(desc, q, Kcache, Vcache, ctx_len, nullptr, nullptr, nullptr, nullptr, 1, O, nullptr, ws,
                     static_cast<hipStream_t>(stream));
 }

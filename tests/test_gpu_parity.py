@@ -423,11 +423,11 @@ def test_grouped_slim_decode(cfg, batch):
 
 @pytest.mark.parametrize("cfg,batch", [(CFG_BF16, 1), (CFG_BF16, 3), (CFG_BF16_64, 2), (CFG_F32, 2)],
                          ids=lambda x: getattr(x, "name", str(x)))
-def test_slim_decode_with_static_lists_keeps_the_merged_lists_in_its_workspace(cfg, batch):
-    """static_lists = 1: the first call with a workspace merges the per-head lists per KV group into it, later calls
-    reuse them.  Every call must give the bits of omni_slim_decode_grouped on the library's own group lists (and so
-    the oracle's result); other lists (another pointer), another decode call on the same workspace in between, and a
-    new workspace all make it merge again."""
+def test_slim_decode_with_static_lists_reads_the_lists_merged_by_the_prepare_call(cfg, batch):
+    """static_lists = 1: omni_slim_decode_prepare merges the per-head lists per KV group into the workspace and the
+    decode calls that follow read them there.  Every call must give the bits of omni_slim_decode_grouped on the
+    library's own group lists (and so the oracle's result), whatever the list arguments then hold; preparing again
+    with other lists switches to those."""
     c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
     tau = 0.08
     H = cfg.n_q_heads
@@ -454,25 +454,76 @@ def test_slim_decode_with_static_lists_keeps_the_merged_lists_in_its_workspace(c
     same = to_host(want_act) == acto
     assert np.max(np.abs(to_host(want_O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
     ws = ob.Workspace()
-    for _ in range(3):                                   # merge, then two calls on the stored lists
-        O, act = ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws)
+    ws.get(ob.CALL_SLIM_DECODE, sdesc).fill_(0xFF)       # whatever the workspace held before
+    ob.omni_slim_decode_prepare(sdesc, vis_idx, vis_cnt, b_cap, ws=ws)
+    poison_idx, poison_cnt = torch.full_like(vis_idx, -7), torch.zeros_like(vis_cnt)
+    for args in ((vis_idx, vis_cnt), (poison_idx, poison_cnt), (vis_idx, vis_cnt)):   # the decode calls read the workspace
+        O, act = ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, *args, b_cap, ws=ws)
         torch.cuda.synchronize()
         assert torch.equal(O.view(view), want_O.view(view)) and torch.equal(act, want_act)
-    # the stateless call on the same workspace in between: the next static call merges again
-    O0, act0 = ob.omni_slim_decode(desc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws)
-    ws.bufs[ob.CALL_SLIM_DECODE].fill_(0xFF)             # whatever it left there
-    O, act = ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws)
-    torch.cuda.synchronize()
-    assert torch.equal(O.view(view), want_O.view(view)) and torch.equal(act, want_act)
-    assert np.max(np.abs(to_host(O0)[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
-    # other lists in other tensors: every second entry of every head
+    # other lists: every second entry of every head
     thin = [[v[::2] for v in per] for per in vis]
     t_idx, t_cnt = lists_to_padded(thin, H, b_cap)
     want2_O, want2_act = grouped_reference(thin)
+    ob.omni_slim_decode_prepare(sdesc, t_idx, t_cnt, b_cap, ws=ws)
     O, act = ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, t_idx, t_cnt, b_cap, ws=ws)
     torch.cuda.synchronize()
     assert torch.equal(O.view(view), want2_O.view(view)) and torch.equal(act, want2_act)
     assert not torch.equal(O.view(view), want_O.view(view))
+    # the stateless call needs no preparation and gives the oracle's result too
+    O0, act0 = ob.omni_slim_decode(desc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ob.Workspace())
+    torch.cuda.synchronize()
+    assert np.max(np.abs(to_host(O0)[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
+    with pytest.raises(ob.OmniError):
+        ob.omni_slim_decode_prepare(desc, vis_idx, vis_cnt, b_cap, ws=ws)      # not a static_lists descriptor
+
+
+@pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
+@pytest.mark.parametrize("case", ["all_lazy", "all_active", "empty_lists", "short_context", "one_row"])
+def test_decode_degenerate_cases(cfg, case):
+    """The decode step at its corners, on the per-head call (stateless and with static lists) and the group-list call:
+    every head but head 0 lazy; every head active; heads that stored no visual row; a context that ends inside the
+    visual range (listed rows at or beyond it do not exist yet); a context of one row."""
+    batch = 2
+    c, q, Kc, Vc, ctx, probe, vis = _decode_case(cfg, batch)
+    H = cfg.n_q_heads
+    tau = {"all_lazy": 0.9999, "all_active": -1.0}.get(case, 0.08)
+    if case == "empty_lists":
+        vis = [[v[:0] if (h % 3) else v for h, v in enumerate(per)] for per in vis]
+        vis[1] = [v[:0] for v in vis[1]]                     # the second sequence stored nothing at all
+    if case == "short_context":
+        ctx = np.array([cfg.vis_begin + (cfg.vis_end - cfg.vis_begin) // 2, cfg.vis_begin + 3], dtype=np.int32)
+    if case == "one_row":
+        ctx = np.array([1, 1], dtype=np.int32)
+    dq, dKc, dVc = (to_device(x, cfg.dtype) for x in (q, Kc, Vc))
+    dctx = torch.from_numpy(ctx).cuda()
+    dprobe = torch.from_numpy(probe.astype(np.float32)).cuda()
+    b_cap = max(1, max(len(v) for per in vis for v in per))
+    vis_idx, vis_cnt = lists_to_padded(vis, H, b_cap)
+    Oo, acto, sc = oc.slim_decode(q, Kc, Vc, ctx, probe.astype(np.float32), vis, tau, cfg.vis_begin, cfg.vis_end, cfg.scale)
+    if case == "all_lazy":
+        assert acto[:, 1:].sum() == 0 and acto[:, 0].all()
+    if case == "all_active":
+        assert acto.all()
+    ldesc = ob.make_layer_desc(c.dQ.expand(batch, -1, -1, -1).contiguous(), c.dK.expand(batch, -1, -1, -1).contiguous(),
+                               cfg.vis_begin, cfg.vis_end, cfg.sink_index, cfg.causal)
+    grp = ob.omni_group_subset_per_head(ldesc, vis_idx, vis_cnt, b_cap)
+    desc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau)
+    sdesc = ob.make_decode_desc(dq, dKc, cfg.vis_begin, cfg.vis_end, tau, static_lists=True)
+    ws_a, ws_b = ob.Workspace(), ob.Workspace()
+    ob.omni_slim_decode_prepare(sdesc, vis_idx, vis_cnt, b_cap, ws=ws_b)
+    results = [ob.omni_slim_decode(desc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws_a),
+               ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws_b),
+               ob.omni_slim_decode_grouped(desc, dq, dKc, dVc, dctx, dprobe, *grp)]
+    torch.cuda.synchronize()
+    clear = np.abs(sc - tau) > 1e-5
+    for O, act in results:
+        act = to_host(act)
+        np.testing.assert_array_equal(act[clear], acto[clear])
+        same = act == acto
+        got = to_host(O)
+        assert np.all(np.isfinite(got))
+        assert np.max(np.abs(got[same] - Oo[same])) <= TOL_OUT[cfg.dtype]
 
 
 @pytest.mark.parametrize("cfg,batch", [(CFG_BF16, 1), (CFG_BF16, 3), (CFG_BF16_64, 2), (CFG_F32, 2), (CFG_F32_128, 1)],
