@@ -82,3 +82,29 @@ def test_prefill_path_on_a_seeded_random_shape(cfg):
                                         _per_head=mode == 2)
         torch.cuda.synchronize()
         _check_grads(cfg, grads, wantg, c.o_qidx, kv_lists)
+
+
+@pytest.mark.parametrize("cfg", _shapes() + _tiny_shapes(), ids=lambda c: f"{c.name}-N{c.n_tokens}-H{c.n_q_heads}x{c.n_kv_heads}-d{c.head_dim}-{c.dtype}")
+def test_one_call_prefill_step_on_a_seeded_random_shape(cfg):
+    """omni_sparse_prefill (key lists formed inside the gather) against omni_prefill_select + omni_sparse_attn_fwd on
+    every shape of the spread, one token to a few thousand: all outputs bit for bit, also with a capacity below N."""
+    pb = [32, 64, 100, 256][cfg.seed % 4]
+    c = Case.get(cfg, probe_block=pb) if cfg.structured else Case.get(cfg, q_mode=1, q_param=0.3, probe_block=pb)
+    N, H = cfg.n_tokens, cfg.n_q_heads
+    for mode, cap in ((0, N), (2, N), (0, max(1, N // 3))):
+        g = ob.omni_prefill_select(c.desc, c.dQ, c.dK, c.q_mode, c.q_param, c.recall_p, pb, mode, b_cap=cap)
+        Og, Lg = ob.omni_sparse_attn_fwd(c.desc, c.dQ, c.dK, c.dV, g.q_idx, g.q_cnt, g.kv_idx, g.budget.budget, cap,
+                                         _per_head=mode == 2)
+        f, O, lse = ob.omni_sparse_prefill(c.desc, c.dQ, c.dK, c.dV, c.q_mode, c.q_param, c.recall_p, pb, mode, b_cap=cap)
+        torch.cuda.synchronize()
+        assert torch.equal(f.scores, g.scores) and torch.equal(f.q_cnt, g.q_cnt)
+        assert torch.equal(f.budget.key_scores, g.budget.key_scores) and torch.equal(f.budget.budget, g.budget.budget)
+        assert torch.equal(f.budget.recall, g.budget.recall) and torch.equal(f.budget.flattest, g.budget.flattest)
+        bud = to_host(g.budget.budget).reshape(cfg.batch, -1)
+        got, want = to_host(f.kv_idx), to_host(g.kv_idx)
+        for h in range(H):
+            n = min(int(bud[0, h if mode == 2 else 0]), cap)
+            np.testing.assert_array_equal(got[0, h, :n], want[0, h, :n], err_msg=f"mode {mode} cap {cap} head {h}")
+        view = torch.int16 if cfg.dtype == "bf16" else torch.int32
+        assert torch.equal(O.view(view), Og.view(view)), f"mode {mode} cap {cap}"
+        assert torch.equal(lse, Lg)
