@@ -515,6 +515,22 @@ def test_decode_degenerate_cases(cfg, case):
     results = [ob.omni_slim_decode(desc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws_a),
                ob.omni_slim_decode(sdesc, dq, dKc, dVc, dctx, dprobe, vis_idx, vis_cnt, b_cap, ws=ws_b),
                ob.omni_slim_decode_grouped(desc, dq, dKc, dVc, dctx, dprobe, *grp)]
+    # the compacted store and its paged form (pages of 32 rows handed out in order) on the same group lists
+    grp_idx, grp_mask, grp_cnt = grp
+    Kcomp, Vcomp = ob.omni_compact_cache(desc, dKc, dVc, grp_idx, grp_cnt)
+    page_rows, pages_cap = 32, -(-grp_idx.shape[-1] // 32)
+    need = -(-to_host(grp_cnt) // page_rows)
+    table = np.full((batch, cfg.n_kv_heads, pages_cap), -1, dtype=np.int32)
+    nxt = 0
+    for bb in range(batch):
+        for g in range(cfg.n_kv_heads):
+            table[bb, g, : need[bb, g]] = np.arange(nxt, nxt + need[bb, g])
+            nxt += int(need[bb, g])
+    Kpool = torch.full((max(nxt, 1), page_rows, cfg.head_dim), float("nan"), dtype=dKc.dtype, device="cuda")
+    pool = ob.make_page_pool(Kpool, torch.full_like(Kpool, float("nan")), torch.from_numpy(table).cuda())
+    ob.omni_compact_cache_paged(desc, dKc, dVc, grp_idx, grp_cnt, pool)
+    results.append(ob.omni_slim_decode_compact(desc, dq, dKc, dVc, dctx, dprobe, Kcomp, Vcomp, grp_idx, grp_mask, grp_cnt))
+    results.append(ob.omni_slim_decode_paged(desc, dq, dKc, dVc, dctx, dprobe, pool, grp_idx, grp_mask, grp_cnt))
     torch.cuda.synchronize()
     clear = np.abs(sc - tau) > 1e-5
     for O, act in results:
