@@ -1635,3 +1635,49 @@ def test_decode_with_other_group_sizes(G, hkv, d):
         same = act == acto
         assert np.max(np.abs(to_host(O)[same] - Oo[same])) <= TOL_OUT[cfg.dtype], name
     assert np.max(np.abs(to_host(Od) - oc.dense_decode(q, Kc, Vc, ctx, cfg.scale))) <= TOL_OUT[cfg.dtype]
+
+
+# ------------------------------------------------------------------ odd layouts of the visual range and the sink
+
+@pytest.mark.parametrize("layout", ["all_visual", "sink_not_first", "two_visual_tokens", "text_on_both_sides",
+                                    "visual_at_the_end"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_selection_and_attention_on_odd_layouts(layout, dtype):
+    """Where the visual tokens and the sink sit is the caller's business: the whole sequence visual (the sink inside
+    the range), a sink that is not token 0, a visual range of two tokens, text on both sides, visual tokens up to the
+    last position.  Scores, kept queries, key scores, budgets and lists against the oracle (lists on the GPU's own
+    score arrays, bit for bit), then attention on those sets."""
+    N, H, Hkv, d = 700, 6, 2, 64
+    v0, v1, sink = {"all_visual": (0, N, 0), "sink_not_first": (9, 600, 5), "two_visual_tokens": (300, 302, 0),
+                    "text_on_both_sides": (200, 450, 0), "visual_at_the_end": (64, N, 0)}[layout]
+    rng = np.random.default_rng(300 + sorted(["all_visual", "sink_not_first", "two_visual_tokens", "text_on_both_sides",
+                                              "visual_at_the_end"]).index(layout))
+    mk = lambda *shape: rng.standard_normal(shape).astype(np.float32)
+    Q, K, V = mk(1, H, N, d), mk(1, Hkv, N, d), mk(1, Hkv, N, d)
+    K[0, :, sink] *= 1.5
+    if dtype == "bf16":
+        Q, K, V = (synth.round_to_bf16(x) for x in (Q, K, V))
+    scale = d ** -0.5
+    dQ, dK, dV = (to_device(x, dtype) for x in (Q, K, V))
+    desc = ob.make_layer_desc(dQ, dK, v0, v1, sink, True, scale)
+    tau, p, pb = 0.45, 0.8, 64
+    for mode in (0, 2):
+        sel, O, lse = ob.omni_sparse_prefill(desc, dQ, dK, dV, 0, tau, p, pb, mode)
+        torch.cuda.synchronize()
+        probe = oc.probe_keys(K, v0, v1, sink)
+        o_scores = oc.score_queries(Q, probe, scale)
+        s_gpu, a_gpu = to_host(sel.scores), to_host(sel.budget.key_scores)
+        assert np.max(np.abs(s_gpu - o_scores)) <= 2e-5
+        o_a = oc.pooled_key_scores(Q, K, pb, True, scale)
+        assert np.max(np.abs(a_gpu - o_a)) <= 1e-4 * o_a.max()
+        got_q = padded_to_lists(sel.q_idx, sel.q_cnt)
+        kv_lists = check_selection_on_gpu_scores(oc, s_gpu, a_gpu, got_q, to_host(sel.budget.flattest),
+                                                 to_host(sel.budget.budget), to_host(sel.kv_idx), 0, tau, p, mode, v0, v1)
+        kept = sum(len(x) for x in got_q[0])
+        assert H * (N - (v1 - v0)) <= kept <= H * N                  # non-visual queries are always kept
+        assert len(got_q[0][0]) == N                                 # head 0 keeps every query
+        Oo, Lo = oc.sparse_attn_fwd(Q, K, V, got_q, kv_lists, True, scale)
+        assert np.max(np.abs(to_host(O) - Oo)) <= TOL_OUT[dtype]
+        fin = np.isfinite(Lo)
+        assert np.array_equal(np.isfinite(to_host(lse)), fin)
+        assert np.max(np.abs(to_host(lse)[fin] - Lo[fin])) <= (1e-4 if dtype == "f32" else 2e-3)
