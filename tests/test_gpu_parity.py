@@ -1465,6 +1465,45 @@ def test_selection_of_a_padded_batch_in_one_call_with_per_sequence_lengths(budge
     assert not to_host(O[i, :, n:]).any() and np.all(to_host(lse[i, :, n:]) == -np.inf)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_padded_batch_with_sequences_of_two_tokens_and_of_the_full_length(dtype):
+    """omni_prefill_select_varlen at its corners: a sequence of two tokens (sink + one visual token), one of 65, one
+    that fills the padded length; NaN in the padding.  Per sequence bit for bit the single-sequence call."""
+    Np, H, Hkv, d = 333, 4, 2, 64
+    lens, v0s, v1s = [2, 65, Np], [1, 3, 10], [2, 60, Np - 20]
+    rng = np.random.default_rng(4242)
+    mk = lambda *shape: rng.standard_normal(shape).astype(np.float32)
+    Qh, Kh = mk(3, H, Np, d), mk(3, Hkv, Np, d)
+    if dtype == "bf16":
+        Qh, Kh = synth.round_to_bf16(Qh), synth.round_to_bf16(Kh)
+    for i, n in enumerate(lens):
+        Qh[i, :, n:], Kh[i, :, n:] = np.nan, np.nan
+    Q, K = to_device(Qh, dtype), to_device(Kh, dtype)
+    desc = ob.make_layer_desc(Q, K, 1, 2, 0, True)
+    for mode in (0, 2):
+        sel = ob.omni_prefill_select_varlen(desc, Q, K, lens, v0s, v1s, 1, 0.5, 0.7, 32, mode)
+        torch.cuda.synchronize()
+        for i, n in enumerate(lens):
+            Qi, Ki = Q[i:i + 1, :, :n].contiguous(), K[i:i + 1, :, :n].contiguous()
+            di = ob.make_layer_desc(Qi, Ki, v0s[i], v1s[i], 0, True)
+            own = ob.omni_prefill_select(di, Qi, Ki, 1, 0.5, 0.7, 32, mode, ws=ob.Workspace())
+            torch.cuda.synchronize()
+            assert torch.equal(sel.scores[i, :, :n], own.scores[0]) and torch.equal(sel.q_cnt[i], own.q_cnt[0])
+            assert torch.equal(sel.budget.key_scores[i, :, :n], own.budget.key_scores[0])
+            assert torch.equal(sel.budget.budget[i], own.budget.budget[0])
+            assert torch.equal(sel.budget.flattest[i], own.budget.flattest[0])
+            cnt, bud = to_host(own.q_cnt)[0], to_host(own.budget.budget)[0]
+            for h in range(H):
+                assert torch.equal(sel.q_idx[i, h, : cnt[h]], own.q_idx[0, h, : cnt[h]])
+                bh = int(bud[h] if mode == 2 else bud)
+                assert 1 <= bh <= n
+                assert torch.equal(sel.kv_idx[i, h, :bh], own.kv_idx[0, h, :bh])
+            # and the single-sequence call against the oracle's selection on its own score arrays
+            check_selection_on_gpu_scores(oc, to_host(own.scores), to_host(own.budget.key_scores),
+                                          padded_to_lists(own.q_idx, own.q_cnt), to_host(own.budget.flattest),
+                                          to_host(own.budget.budget), to_host(own.kv_idx), 1, 0.5, 0.7, mode, v0s[i], v1s[i])
+
+
 # ------------------------------------------------------------------ strides
 
 @pytest.mark.parametrize("cfg", [CFG_BF16, CFG_F32], ids=lambda c: c.name)
