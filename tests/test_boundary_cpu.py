@@ -170,6 +170,72 @@ def test_argument_errors(lib):
     assert ob.last_error() == ""
 
 
+def test_argument_errors_of_the_fused_and_batched_calls(lib):
+    """omni_sparse_prefill, omni_prefill_select_varlen, omni_block_attn_bwd, omni_slim_decode_prepare and the decode
+    call without workspace refuse bad arguments before any launch."""
+    d = _desc()
+    sp = lambda **kw: lib.omni_sparse_prefill(
+        C.byref(d), FAKE, FAKE, kw.get("V", FAKE), kw.get("q_mode", 0), kw.get("q_param", 0.08), kw.get("p", 0.95),
+        kw.get("pb", 256), kw.get("mode", 0), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, kw.get("cap", 300),
+        kw.get("O", FAKE), FAKE, FAKE, kw.get("ws", 1 << 32), None)
+    assert sp(mode=3) == -1 and sp(q_mode=2) == -1 and sp(p=1.5) == -1 and sp(pb=0) == -1 and sp(cap=0) == -1
+    assert sp(V=None) == -1 and "null" in ob.last_error()
+    assert sp(O=None) == -1
+    assert sp(ws=1024) == -3 and "too small" in ob.last_error()
+    need = lib.omni_sparse_prefill_workspace_bytes(C.byref(d), 256, 300)
+    assert need > ob.workspace_bytes(ob.CALL_PREFILL_SELECT, d, 256) + ob.workspace_bytes(ob.CALL_SPARSE_ATTN_FWD, d, 300) - 256
+    assert lib.omni_sparse_prefill_workspace_bytes(C.byref(d), 0, 300) == 0 and "probe_block" in ob.last_error()
+    assert lib.omni_sparse_prefill_workspace_bytes(C.byref(d), 256, 0) == 0
+    assert lib.omni_sparse_prefill_workspace_bytes(C.byref(_desc(head_dim=96)), 256, 300) == 0
+    # per-sequence lengths: host arrays, checked against the padded length, the visual range and the sink
+    arr = lambda *v: (C.c_int32 * len(v))(*v)
+    d2 = _desc(batch=2)
+    vl = lambda n, v0, v1, **kw: lib.omni_prefill_select_varlen(
+        C.byref(d2), FAKE, FAKE, n, v0, v1, 0, 0.08, 0.95, 256, kw.get("mode", 0), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+        FAKE, FAKE, FAKE, 300, FAKE, kw.get("ws", 1 << 32), None)
+    assert vl(arr(300, 301), arr(1, 1), arr(200, 200)) == -1 and "seq_tokens" in ob.last_error()
+    assert vl(arr(300, 0), arr(1, 1), arr(200, 200)) == -1
+    assert vl(arr(300, 100), arr(1, 1), arr(200, 101)) == -1 and "vis_begin" in ob.last_error()
+    assert vl(arr(300, 100), arr(1, 50), arr(200, 50)) == -1
+    assert vl(None, arr(1, 1), arr(200, 50)) == -1
+    assert vl(arr(300, 100), arr(1, 1), arr(200, 50), mode=5) == -1
+    assert vl(arr(300, 100), arr(1, 1), arr(200, 50), ws=64) == -3
+    d3 = _desc(batch=2, sink_index=120)
+    assert lib.omni_prefill_select_varlen(C.byref(d3), FAKE, FAKE, arr(300, 100), arr(1, 1), arr(200, 50), 0, 0.08, 0.95, 256, 0,
+                                          FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 300, FAKE, 1 << 32,
+                                          None) == -1 and "sink_index" in ob.last_error()
+    # backward on block lists: as the forward
+    bb = lambda dd_=d, **kw: lib.omni_block_attn_bwd(
+        C.byref(dd_), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, kw.get("blk", FAKE), FAKE, kw.get("cap", 4),
+        kw.get("block", 64), FAKE, FAKE, kw.get("dV", FAKE), FAKE, kw.get("ws", 1 << 32), None)
+    assert bb(block=100) == -2 and bb(cap=0) == -1 and bb(blk=None) == -1 and bb(dV=None) == -1 and bb(ws=16) == -3
+    assert bb(_desc(dtype=ob.OMNI_F32)) == -2 and bb(_desc(causal=0), block=128) == -2
+    assert ob.workspace_bytes(ob.CALL_BLOCK_ATTN_BWD, d, 5 * 64) > 0
+    # decode: the prepare call wants a descriptor with static_lists, whose workspace holds the merged lists too
+    dd = ob.DecodeDesc()
+    dd.batch, dd.n_q_heads, dd.n_kv_heads, dd.head_dim, dd.cache_capacity = 2, 4, 2, 128, 1000
+    dd.vis_begin, dd.vis_end, dd.dtype, dd.softmax_scale, dd.tau = 0, 900, ob.OMNI_BF16, 0.088, 0.08
+    dd.kv_stride = (C.c_int64 * 3)(2 * 1000 * 128, 1000 * 128, 128)
+    plain = ob.workspace_bytes(ob.CALL_SLIM_DECODE, dd)
+    assert lib.omni_slim_decode_prepare(C.byref(dd), FAKE, FAKE, 64, FAKE, 1 << 30, None) == -1
+    assert "static_lists" in ob.last_error()
+    dd.static_lists = 1
+    with_lists = ob.workspace_bytes(ob.CALL_SLIM_DECODE, dd)
+    assert with_lists >= plain + 2 * 2 * 900 * 8
+    assert lib.omni_slim_decode_prepare(C.byref(dd), None, FAKE, 64, FAKE, 1 << 30, None) == -1
+    assert lib.omni_slim_decode_prepare(C.byref(dd), FAKE, FAKE, 0, FAKE, 1 << 30, None) == -1
+    assert lib.omni_slim_decode_prepare(C.byref(dd), FAKE, FAKE, 64, FAKE, plain, None) == -3
+    assert lib.omni_slim_decode(C.byref(dd), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, FAKE, FAKE, FAKE, plain, None) == -3
+    dd.static_lists = 2
+    assert lib.omni_slim_decode_prepare(C.byref(dd), FAKE, FAKE, 64, FAKE, 1 << 30, None) == -1
+    dd.static_lists = 0
+    assert lib.omni_static_scratch_bytes() == 16 << 20
+    assert lib.omni_slim_decode_grouped_static(C.byref(dd), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 64, FAKE,
+                                               FAKE, None) == -1
+    assert lib.omni_slim_decode_grouped_static(C.byref(dd), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE,
+                                               FAKE, None) == -1
+
+
 @pytest.mark.parametrize("q_cnt,budget,n_heads,n_tokens,causal", [
     ([1859, 500, 300, 0, 20, 129, 128, 1], [700], 8, 1859, 1),
     (None, None, 8, 1859, 1),
